@@ -1,0 +1,200 @@
+"""TEST INFRASTRUCTURE: Python face of the fp64 CPU parity oracle (``hyena_oracle.c``).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import
+this package.  It imports nothing from the HIP package and shares no code with it.
+
+What it computes (paper Sec. 2.1 Eq. 1, Sec. 2.2 filter grouping, Sec. 3.1 Eq. 2):
+``y[b,t,c] = q[b,t,c] * sum_{j<l_h, j<=t} h[c // d_g, j] * k[b,t-j,c] * v[b,t-j,c]`` in fp64, inputs
+widened exactly from the bits handed over (fp64, fp32 or bf16).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hyena_oracle.c")
+_SO = os.path.join(_HERE, "liboracle.so")
+
+F64, F32, BF16 = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (+OpenMP) next to its source; returns the .so path."""
+    stale = not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _SO + ".%d.tmp" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", tmp, _SRC]
+        )
+        os.replace(tmp, _SO)
+    return _SO
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        lib.oracle_num_threads.restype = ci
+        lib.oracle_causal_conv.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, ci, ci]
+        lib.oracle_gated_conv.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci]
+        lib.oracle_gated_conv_points.argtypes = [vp, vp, vp, vp, vp, i64, vp] + [i64] * 5 + [ci, ci]
+        lib.oracle_chain_points.argtypes = [vp] * 8 + [i64, vp] + [i64] * 7 + [ci, ci]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _arr(x):
+    """Return (contiguous numpy array, dtype code) holding exactly the bits of ``x``.
+
+    Accepts numpy float64/float32 arrays, numpy uint16 arrays (taken as bf16 bit patterns) and CPU
+    torch tensors of dtype float64/float32/bfloat16.
+    """
+    if not isinstance(x, np.ndarray):
+        import torch
+
+        if not isinstance(x, torch.Tensor):
+            raise TypeError("oracle input must be a numpy array or a CPU torch tensor")
+        if x.device.type != "cpu":
+            raise ValueError("oracle inputs live on the host")
+        x = x.contiguous()
+        if x.dtype == torch.bfloat16:
+            x = x.view(torch.int16).numpy().view(np.uint16)
+        elif x.dtype in (torch.float32, torch.float64):
+            x = x.numpy()
+        else:
+            raise TypeError("unsupported tensor dtype %s" % x.dtype)
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.float64:
+        return x, F64
+    if x.dtype == np.float32:
+        return x, F32
+    if x.dtype == np.uint16:
+        return x, BF16
+    raise TypeError("unsupported array dtype %s" % x.dtype)
+
+
+def _same(*codes):
+    if len(set(codes)) != 1:
+        raise TypeError("activation arrays must share one dtype")
+    return codes[0]
+
+
+def _filt(h, n_filters, lh=None):
+    h = np.ascontiguousarray(h)
+    if h.dtype not in (np.float64, np.float32):
+        raise TypeError("filters are float32 or float64")
+    if h.ndim != 2 or h.shape[0] != n_filters or (lh is not None and h.shape[1] != lh):
+        raise ValueError("filter array must be [D // group, l_h]; got %s" % (h.shape,))
+    return h, (F64 if h.dtype == np.float64 else F32)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _ok(rc, what):
+    if rc != 0:
+        raise ValueError("%s rejected its arguments (code %d)" % (what, rc))
+
+
+def causal_conv(x, h, group: int = 1) -> np.ndarray:
+    """Featurizer convolution (Eq. 1 lines 1-3 with Eq. 2): y = h * x per channel, no gating."""
+    xa, xd = _arr(x)
+    B, L, D = xa.shape
+    ha, hd = _filt(h, D // group if group > 0 and D % group == 0 else -1)
+    y = np.empty((B, L, D), dtype=np.float64)
+    _ok(_load().oracle_causal_conv(_ptr(xa), _ptr(ha), _ptr(y), B, L, D, ha.shape[1], group, xd, hd),
+        "oracle_causal_conv")
+    return y
+
+
+def gated_conv(q, k, v, h, group: int = 1) -> np.ndarray:
+    """Hyena-SE / Hyena-MR inner operator: y = q (.) (h * (k (.) v)) (Eq. 1 last line, Eq. 2)."""
+    qa, qd = _arr(q)
+    ka, kd = _arr(k)
+    va, vd = _arr(v)
+    xd = _same(qd, kd, vd)
+    if not (qa.shape == ka.shape == va.shape) or qa.ndim != 3:
+        raise ValueError("q, k, v must share one [B, L, D] shape")
+    B, L, D = qa.shape
+    ha, hd = _filt(h, D // group if group > 0 and D % group == 0 else -1)
+    y = np.empty((B, L, D), dtype=np.float64)
+    _ok(_load().oracle_gated_conv(_ptr(qa), _ptr(ka), _ptr(va), _ptr(ha), _ptr(y), B, L, D,
+                                  ha.shape[1], group, xd, hd), "oracle_gated_conv")
+    return y
+
+
+def _points(pts, n_dims=3):
+    p = np.ascontiguousarray(np.asarray(pts, dtype=np.int64))
+    if p.ndim != 2 or p.shape[1] != n_dims:
+        raise ValueError("points are an [n, 3] array of (b, t, c)")
+    return p
+
+
+def gated_conv_points(q, k, v, h, pts, group: int = 1) -> np.ndarray:
+    """``gated_conv`` evaluated only at the listed (b, t, c) outputs."""
+    qa, qd = _arr(q)
+    ka, kd = _arr(k)
+    va, vd = _arr(v)
+    xd = _same(qd, kd, vd)
+    B, L, D = qa.shape
+    ha, hd = _filt(h, D // group if group > 0 and D % group == 0 else -1)
+    p = _points(pts)
+    out = np.empty(p.shape[0], dtype=np.float64)
+    _ok(_load().oracle_gated_conv_points(_ptr(qa), _ptr(ka), _ptr(va), _ptr(ha), _ptr(p), p.shape[0],
+                                         _ptr(out), B, L, D, ha.shape[1], group, xd, hd),
+        "oracle_gated_conv_points")
+    return out
+
+
+def chain(q, k, v, hq, hk, hv, h, group: int = 1, feat_group: int = 1) -> np.ndarray:
+    """Operator chain of Eq. 1 minus the dense projections: featurize q, k, v, then the gated inner
+    convolution; intermediates stay in fp64 (composition of the two functions above)."""
+    qf = causal_conv(q, hq, feat_group)
+    kf = causal_conv(k, hk, feat_group)
+    vf = causal_conv(v, hv, feat_group)
+    return gated_conv(qf, kf, vf, h, group)
+
+
+def chain_points(q, k, v, hq, hk, hv, h, pts, group: int = 1, feat_group: int = 1) -> np.ndarray:
+    """``chain`` evaluated only at the listed (b, t, c) outputs (nested sums written out in C)."""
+    qa, qd = _arr(q)
+    ka, kd = _arr(k)
+    va, vd = _arr(v)
+    xd = _same(qd, kd, vd)
+    B, L, D = qa.shape
+    nf = D // feat_group if feat_group > 0 and D % feat_group == 0 else -1
+    hqa, d1 = _filt(hq, nf)
+    hka, d2 = _filt(hk, nf, hqa.shape[1])
+    hva, d3 = _filt(hv, nf, hqa.shape[1])
+    ha, d4 = _filt(h, D // group if group > 0 and D % group == 0 else -1)
+    hd = _same(d1, d2, d3, d4)
+    p = _points(pts)
+    out = np.empty(p.shape[0], dtype=np.float64)
+    _ok(_load().oracle_chain_points(_ptr(qa), _ptr(ka), _ptr(va), _ptr(hqa), _ptr(hka), _ptr(hva),
+                                    _ptr(ha), _ptr(p), p.shape[0], _ptr(out), B, L, D, hqa.shape[1],
+                                    feat_group, ha.shape[1], group, xd, hd), "oracle_chain_points")
+    return out
+
+
+def rel_err(y, y_ref) -> float:
+    """Acceptance metric: max|y - y_ref| / max|y_ref| over the whole tensor."""
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    den = float(np.max(np.abs(y_ref))) if y_ref.size else 0.0
+    num = float(np.max(np.abs(y - y_ref))) if y_ref.size else 0.0
+    if den == 0.0:
+        return 0.0 if num == 0.0 else float("inf")
+    return num / den
