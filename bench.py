@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Throughput of the Hyena-SE / Hyena-MR forward path on one MI355X, against the HBM roofline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4]
+
+A step is one pass of the hot path over one synthetic batch that already sits in HBM:
+  c1  Hyena-SE  bf16 B1 L8192   D4096 lh7            hyena_se_fwd            (default; the headline case)
+  c2  Hyena-MR  bf16 B1 L8192   D4096 lh128 group16  hyena_mr_fwd
+  c3  Hyena-MR  bf16 B1 L131072 D4096 lh128 group16  hyena_mr_fwd
+  c4  chain     bf16 B4 L32768  D4096                hyena_featurize3_fwd + hyena_mr_fwd
+Successive steps rotate through several independent input/output sets so that every launch streams from
+HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
+Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded slice of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "Hyena-SE/MR fwd tokens/s at D=4096; achieved HBM GB/s and MFMA % of peak"
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle slice")
+    ap.add_argument("--also", default="c2", help="comma list of further workloads to time briefly (c1 only)")
+    return ap.parse_args()
+
+
+def upload(w, torch):
+    d = {}
+    for key in ("q", "k", "v"):
+        d[key] = w[key].cuda()
+    for key in ("h", "hq", "hk", "hv"):
+        if key in w:
+            d[key] = torch.from_numpy(w[key]).cuda()
+    return d
+
+
+class Workload:
+    """Device-resident rotating buffer sets plus the step function of one configuration."""
+
+    def __init__(self, name, nsets, torch, pkg, synth):
+        self.name, self.torch, self.pkg = name, torch, pkg
+        self.cfg = synth.config(name)
+        c = self.cfg
+        self.n_out = c["B"] * c["L"] * c["D"]
+        self.tokens = c["B"] * c["L"]
+        bytes_set = self.n_out * 2 * (4 if c["kind"] != "chain" else 7)
+        if nsets <= 0:
+            nsets = max(1, min(6, int((1.5 * 2 ** 30) // bytes_set) + 1))
+        self.host0 = None
+        self.sets = []
+        for i in range(nsets):
+            w = synth.make(name, variant=i)
+            if i == 0:
+                self.host0 = w
+            d = upload(w, torch)
+            d["y"] = torch.empty_like(d["q"])
+            if c["kind"] == "chain":
+                d["f"] = tuple(torch.empty_like(d["q"]) for _ in range(3))
+            self.sets.append(d)
+        self.i = 0
+        self.ev = []
+
+    def main_kernel(self, d):
+        c, pkg = self.cfg, self.pkg
+        if c["kind"] == "se":
+            pkg.hyena_se_fwd(d["q"], d["k"], d["v"], d["h"], c["group"], out=d["y"])
+        elif c["kind"] == "mr":
+            pkg.hyena_mr_fwd(d["q"], d["k"], d["v"], d["h"], c["group"], out=d["y"])
+        else:
+            pkg.hyena_mr_fwd(d["f"][0], d["f"][1], d["f"][2], d["h"], c["group"], out=d["y"])
+
+    def step(self, timed=False):
+        d = self.sets[self.i % len(self.sets)]
+        self.i += 1
+        if self.cfg["kind"] == "chain":
+            self.pkg.hyena_featurize3_fwd(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"],
+                                          self.cfg["feat_group"], out=d["f"])
+        if timed:
+            e0 = self.torch.cuda.Event(enable_timing=True)
+            e1 = self.torch.cuda.Event(enable_timing=True)
+            e0.record()
+            self.main_kernel(d)
+            e1.record()
+            self.ev.append((e0, e1))
+        else:
+            self.main_kernel(d)
+
+    def run(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        self.ev = []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(timed=True)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kern_ms = [a.elapsed_time(b) for a, b in self.ev]
+        return wall, kern_ms
+
+    # algorithmic work of the dominant kernel per launch
+    def algo_bytes(self):
+        return 8.0 * self.n_out  # bf16: q, k, v read once, y written once
+
+    def algo_flops(self):
+        return (2.0 * self.cfg["lh"] + 2.0) * self.n_out
+
+
+def cpu_baseline(wl, target_s, np, oracle):
+    """Time the fp64 oracle on the first rows of buffer set 0 (all channels), sized for ~target_s seconds."""
+    w, c = wl.host0, wl.cfg
+    L = c["L"]
+
+    def run(rows):
+        q, k, v = (w[key][:1, :rows].contiguous() for key in ("q", "k", "v"))
+        t0 = time.perf_counter()
+        if c["kind"] == "chain":
+            y = oracle.chain(q, k, v, w["hq"], w["hk"], w["hv"], w["h"], group=c["group"], feat_group=c["feat_group"])
+        else:
+            y = oracle.gated_conv(q, k, v, w["h"], group=c["group"])
+        return time.perf_counter() - t0, y
+
+    probe_rows = min(L, 128)
+    t_probe, _ = run(probe_rows)
+    rows = int(min(L, max(probe_rows, probe_rows * target_s / max(t_probe, 1e-4))))
+    t, y = run(rows)
+    return {
+        "value": rows / t, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "first %d of %d time steps of batch item 0, all %d channels, fp64, %.1f s" % (rows, L, c["D"], t),
+    }, rows, y
+
+
+def measure(name, args, torch, pkg, synth, steps, warmup):
+    wl = Workload(name, args.sets, torch, pkg, synth)
+    wall, kern_ms = wl.run(steps, warmup)
+    avg_ms = sum(kern_ms) / len(kern_ms)
+    med_ms = sorted(kern_ms)[len(kern_ms) // 2]
+    res = {
+        "tokens_per_s": wl.tokens * steps / wall,
+        "ms_per_step": 1e3 * wall / steps,
+        "kernel_ms_avg": avg_ms, "kernel_ms_median": med_ms, "kernel_ms_min": min(kern_ms),
+        "hbm_gbs": wl.algo_bytes() / (avg_ms * 1e-3) / 1e9,
+        "tflops_algorithmic": wl.algo_flops() / (avg_ms * 1e-3) / 1e12,
+        "sets": len(wl.sets),
+    }
+    return wl, res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X; --gpus %d is not supported (this build has no multi-GPU path)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2503_01868_amd as pkg
+    from paper_2503_01868_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup)
+    cfg = wl.cfg
+    kernel = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_mr_fwd"}[cfg["kind"]]
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(args.workload, {}).get("bytes_per_launch")
+
+    out = {
+        "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s bf16 B=%d L=%d D=%d lh=%d group=%d" % (
+            args.workload, {"se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurize x3 + Hyena-MR"}[cfg["kind"]],
+            cfg["B"], cfg["L"], cfg["D"], cfg["lh"], cfg["group"]), "buffer_sets": res["sets"]},
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": res["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": res["hbm_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel_ms_avg": res["kernel_ms_avg"], "kernel_ms_median": res["kernel_ms_median"],
+                     "kernel_ms_min": res["kernel_ms_min"], "algorithmic_bytes_per_launch": wl.algo_bytes()},
+    }
+    if cfg["kind"] != "se":
+        out["mfma"] = {"tflops_algorithmic": res["tflops_algorithmic"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                       "frac": res["tflops_algorithmic"] / MFMA_BF16_PEAK_TFLOPS}
+
+    if not args.no_cpu_baseline:
+        import oracle
+
+        base, rows, y_ref = cpu_baseline(wl, args.cpu_seconds, np, oracle)
+        out["cpu_baseline"] = base
+        # the slice the oracle just computed doubles as an end-of-run parity check of buffer set 0
+        d = wl.sets[0]
+        wl.i = 0
+        wl.step()
+        torch.cuda.synchronize()
+        got = d["y"][:1, :rows].float().cpu().numpy().astype(np.float64)
+        out["parity_rel_err"] = oracle.rel_err(got, y_ref)
+
+    if args.workload == "c1" and args.also:
+        del wl
+        torch.cuda.empty_cache()
+        out["also"] = {}
+        for name in [s for s in args.also.split(",") if s]:
+            wl2, r2 = measure(name, args, torch, pkg, synth, max(10, args.steps // 4), max(3, args.warmup // 4))
+            r2["hbm_frac"] = r2["hbm_gbs"] / HBM_PEAK_GBS
+            r2["mfma_frac_algorithmic"] = r2["tflops_algorithmic"] / MFMA_BF16_PEAK_TFLOPS
+            out["also"][name] = r2
+            del wl2
+            torch.cuda.empty_cache()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,111 @@
+/*
+ * hyena.h -- C ABI of the MI355X (gfx950) forward kernels for the StripedHyena 2 short and medium
+ * gated causal convolutions (Hyena-SE and Hyena-MR) and their featurizer convolutions.
+ *
+ * Common conventions for every entry point
+ *   - Activations are dense [B, L, D] row-major tensors with the channel index D contiguous; element
+ *     type is given by `dtype` (HY_F32: IEEE binary32, HY_BF16: bfloat16).
+ *   - Filters are fp32 for both dtypes, [D / group, lh] row-major, tap index contiguous; tap 0
+ *     multiplies the current sample and tap j the sample j steps in the past (the FIR definition of
+ *     Sec. 3.1, Eq. 2).  Channel c uses filter c / group (contiguous groups, Sec. 2.2).
+ *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned; outputs must not alias
+ *     inputs.  The library allocates nothing, keeps no state between calls besides the tuning
+ *     options below, launches on `hip_stream` (a hipStream_t, NULL = default stream) and never
+ *     synchronises.
+ *   - Left boundary: zero padding, separately for each batch item (terms with t - j < 0 vanish).
+ *   - Errors: a status code is returned, nothing is thrown and nothing aborts.  All argument checks
+ *     run before the first HIP call, so they work on a machine without a GPU.  B, L or D equal to 0
+ *     is a valid empty problem and returns HY_OK without launching.
+ */
+#ifndef HYENA_H
+#define HYENA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum hy_status {
+    HY_OK = 0,
+    HY_ERR_NULL = 1,        /* a required pointer is NULL */
+    HY_ERR_SHAPE = 2,       /* negative size, lh < 1, group < 1, or D not a multiple of group */
+    HY_ERR_DTYPE = 3,       /* dtype is not one of hy_dtype */
+    HY_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned, or an output aliases an input */
+    HY_ERR_UNSUPPORTED = 5, /* valid problem, but no kernel in this build handles it */
+    HY_ERR_LAUNCH = 6       /* the HIP runtime reported an error at launch */
+} hy_status;
+
+typedef enum hy_dtype { HY_F32 = 0, HY_BF16 = 1 } hy_dtype;
+
+/*
+ * Hyena-SE inner operator, forward (Sec. 2.1 Eq. 1 last line without the dense M; Algorithm 1 with
+ * both optional gates on; FIR sum of Sec. 3.1 Eq. 2):
+ *     y[b,t,c] = q[b,t,c] * sum_{j=0}^{min(lh-1,t)} h[c/group, j] * k[b,t-j,c] * v[b,t-j,c]
+ * Meant for short filters (the paper runs lh = 4..7, always below 14): a fused streaming stencil on
+ * the vector ALUs, fp32 arithmetic, one rounding at the store.  Any lh >= 1 is accepted; long
+ * filters fall to a slower general kernel.  q,k,v,y: [B,L,D] of `dtype`; h: fp32 [D/group, lh].
+ */
+hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
+                       int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype,
+                       void *hip_stream);
+
+/*
+ * Hyena-MR inner operator, forward: same formula as hyena_se_fwd, meant for filters of length in
+ * the hundreds shared by groups of channels (paper default lh = 128, group = 16).  For HY_BF16 with
+ * group a multiple of 16, D a multiple of 64 and lh <= 257 the convolution is evaluated as the
+ * block-Toeplitz contraction of Sec. 3.1 (hat y_n = sum_k H_k hat x_{n-k}) on bf16 matrix cores with
+ * fp32 accumulation: u = k*v is rounded once to bf16, h is rounded once to bf16, the output is
+ * rounded once at the store.  Every other valid combination (HY_F32, other group sizes, longer
+ * filters) runs a general fp32 vector-ALU kernel.
+ */
+hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
+                       int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype,
+                       void *hip_stream);
+
+/*
+ * Featurizer convolution, forward (Sec. 2.1 Eq. 1, first three lines: the short explicit filters
+ * h_T, h_H, h_K applied to the projected q, k, v; no gating):
+ *     y[b,t,c] = sum_{j=0}^{min(lh-1,t)} h[c/group, j] * x[b,t-j,c]
+ * x,y: [B,L,D] of `dtype`; h: fp32 [D/group, lh].
+ */
+hy_status hyena_featurize_fwd(const void *x, const float *h, void *y, int64_t B, int64_t L,
+                              int64_t D, int32_t lh, int32_t group, hy_dtype dtype,
+                              void *hip_stream);
+
+/*
+ * The three featurizer convolutions of Eq. 1 in one launch: qo = hq * q, ko = hk * k, vo = hv * v,
+ * each as hyena_featurize_fwd.  All six tensors share one shape and dtype, the three filters share
+ * lh and group.
+ */
+hy_status hyena_featurize3_fwd(const void *q, const void *k, const void *v, const float *hq,
+                               const float *hk, const float *hv, void *qo, void *ko, void *vo,
+                               int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group,
+                               hy_dtype dtype, void *hip_stream);
+
+/*
+ * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16) with the same launch
+ * shape as the streaming kernels.  Used to measure the practical HBM ceiling and to calibrate
+ * hardware byte counters; not part of the operator.
+ */
+hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip_stream);
+
+/*
+ * Tuning knobs (process-wide, not thread-safe; 0 restores the built-in choice).  Names:
+ *   "se_vec"   channels per lane in the SE / featurizer stencil (1, 2, 4 or 8)
+ *   "se_rows"  time steps each lane walks (tile length in t)
+ *   "mr_rows"  time steps per workgroup in the MR kernel (multiple of 32)
+ * Unknown names return HY_ERR_UNSUPPORTED.  Results never depend on these, only speed.
+ */
+hy_status hyena_set_option(const char *name, int32_t value);
+
+/* Static, NUL-terminated description of a status code. */
+const char *hyena_status_string(hy_status s);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t hyena_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYENA_H */

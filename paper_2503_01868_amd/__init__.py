@@ -1,1 +1,16 @@
-"""MI355X-native forward kernels for the Hyena-SE / Hyena-MR gated causal convolutions."""
+"""MI355X-native forward kernels for the Hyena-SE / Hyena-MR gated causal convolutions.
+
+``binding`` exposes the C ABI of ``libhyena.so`` under the same names; ``synth`` draws the seeded
+benchmark inputs; ``build`` compiles the library.
+"""
+from .binding import (  # noqa: F401
+    HyenaError,
+    hyena_featurize3_fwd,
+    hyena_featurize_fwd,
+    hyena_mr_fwd,
+    hyena_se_fwd,
+    hyena_stream_copy,
+    set_option,
+    status_string,
+    version,
+)

@@ -1,0 +1,172 @@
+"""Thin ctypes binding of the C ABI declared in ``include/hyena.h``.
+
+Argument marshalling only: every step of the operators runs inside ``libhyena.so``.  PyTorch supplies
+device memory and the HIP stream.  There is no CPU or PyTorch fallback: if the library is missing and
+cannot be built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+HY_OK = 0
+HY_F32, HY_BF16 = 0, 1
+
+_lib = None
+
+
+class HyenaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__("%s failed: %s (status %d)" % (what, status_string(code), code))
+
+
+def lib() -> ctypes.CDLL:
+    """Load ``libhyena.so`` from the package directory (building it first only if it is absent)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build_library()
+        L = ctypes.CDLL(_build.LIB)
+        vp, i64, i32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int
+        conv_args = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_se_fwd.argtypes = conv_args
+        L.hyena_mr_fwd.argtypes = conv_args
+        L.hyena_featurize_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_featurize3_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
+        L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
+        for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd",
+                     "hyena_stream_copy", "hyena_set_option"):
+            getattr(L, name).restype = ci
+        L.hyena_status_string.argtypes = [ci]
+        L.hyena_status_string.restype = ctypes.c_char_p
+        L.hyena_version.argtypes = []
+        L.hyena_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().hyena_status_string(int(code)).decode()
+
+
+def version() -> int:
+    return int(lib().hyena_version())
+
+
+def set_option(name: str, value: int) -> None:
+    rc = lib().hyena_set_option(name.encode(), int(value))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_set_option(%s)" % name)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return HY_F32
+    if t.dtype == torch.bfloat16:
+        return HY_BF16
+    raise TypeError("activations must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check_act(name: str, t: torch.Tensor, ref: torch.Tensor | None = None) -> None:
+    if not isinstance(t, torch.Tensor) or t.device.type != "cuda":
+        raise ValueError("%s must be a tensor on the GPU" % name)
+    if t.dim() != 3 or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous [B, L, D] tensor" % name)
+    if ref is not None and (t.shape != ref.shape or t.dtype != ref.dtype or t.device != ref.device):
+        raise ValueError("%s must match the shape, dtype and device of the first activation" % name)
+
+
+def _check_filter(name: str, h: torch.Tensor, x: torch.Tensor, group: int) -> int:
+    if not isinstance(h, torch.Tensor) or h.device != x.device or h.dtype != torch.float32:
+        raise ValueError("%s must be a float32 tensor on the same GPU" % name)
+    if h.dim() != 2 or not h.is_contiguous() or group < 1 or x.shape[2] % group != 0 or h.shape[0] != x.shape[2] // group:
+        raise ValueError("%s must be a contiguous [D // group, l_h] tensor" % name)
+    return int(h.shape[1])
+
+
+def _stream(x: torch.Tensor, stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device)
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _gated(entry: str, q, k, v, h, group, out, stream):
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    lh = _check_filter("h", h, q, group)
+    y = torch.empty_like(q) if out is None else out
+    _check_act("out", y, q)
+    B, L, D = q.shape
+    with torch.cuda.device(q.device):
+        rc = getattr(lib(), entry)(q.data_ptr(), k.data_ptr(), v.data_ptr(), h.data_ptr(), y.data_ptr(),
+                                   B, L, D, lh, int(group), _dtype_code(q), _stream(q, stream))
+    if rc != HY_OK:
+        raise HyenaError(rc, entry)
+    return y
+
+
+def hyena_se_fwd(q, k, v, h, group: int = 1, out=None, stream=None) -> torch.Tensor:
+    """y = q * (h conv (k * v)), short filters; see ``hyena_se_fwd`` in hyena.h."""
+    return _gated("hyena_se_fwd", q, k, v, h, group, out, stream)
+
+
+def hyena_mr_fwd(q, k, v, h, group: int = 16, out=None, stream=None) -> torch.Tensor:
+    """y = q * (h conv (k * v)), medium grouped filters; see ``hyena_mr_fwd`` in hyena.h."""
+    return _gated("hyena_mr_fwd", q, k, v, h, group, out, stream)
+
+
+def hyena_featurize_fwd(x, h, group: int = 1, out=None, stream=None) -> torch.Tensor:
+    """y = h conv x, no gating; see ``hyena_featurize_fwd`` in hyena.h."""
+    _check_act("x", x)
+    lh = _check_filter("h", h, x, group)
+    y = torch.empty_like(x) if out is None else out
+    _check_act("out", y, x)
+    B, L, D = x.shape
+    with torch.cuda.device(x.device):
+        rc = lib().hyena_featurize_fwd(x.data_ptr(), h.data_ptr(), y.data_ptr(), B, L, D, lh, int(group),
+                                       _dtype_code(x), _stream(x, stream))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_featurize_fwd")
+    return y
+
+
+def hyena_featurize3_fwd(q, k, v, hq, hk, hv, group: int = 1, out=None, stream=None):
+    """(hq conv q, hk conv k, hv conv v) in one launch; see ``hyena_featurize3_fwd`` in hyena.h."""
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    lh = _check_filter("hq", hq, q, group)
+    if _check_filter("hk", hk, q, group) != lh or _check_filter("hv", hv, q, group) != lh:
+        raise ValueError("the three featurizer filters must share one length")
+    outs = tuple(torch.empty_like(q) for _ in range(3)) if out is None else tuple(out)
+    for name, o in zip(("qo", "ko", "vo"), outs):
+        _check_act(name, o, q)
+    B, L, D = q.shape
+    with torch.cuda.device(q.device):
+        rc = lib().hyena_featurize3_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), hq.data_ptr(), hk.data_ptr(),
+                                        hv.data_ptr(), outs[0].data_ptr(), outs[1].data_ptr(), outs[2].data_ptr(),
+                                        B, L, D, lh, int(group), _dtype_code(q), _stream(q, stream))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_featurize3_fwd")
+    return outs
+
+
+def hyena_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.Tensor:
+    """Plain streaming copy (bandwidth yardstick); see ``hyena_stream_copy`` in hyena.h."""
+    if src.device.type != "cuda" or not src.is_contiguous() or not dst.is_contiguous():
+        raise ValueError("src and dst must be contiguous GPU tensors")
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or dst.device != src.device:
+        raise ValueError("src and dst must have the same size and device")
+    with torch.cuda.device(src.device):
+        rc = lib().hyena_stream_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream(src, stream))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_stream_copy")
+    return dst

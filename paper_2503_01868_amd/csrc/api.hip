@@ -1,0 +1,197 @@
+// C ABI of the library: argument validation (before any HIP call), kernel selection, tuning options.
+#include <string.h>
+
+#include "hy_common.hpp"
+#include "hy_launch.hpp"
+
+namespace hy {
+
+Tuning& tuning() {
+    static Tuning t;
+    return t;
+}
+
+namespace {
+
+constexpr int kCopyBlock = 256;
+constexpr int kCopyPerLane = 4;  // 16-byte words per lane
+
+__global__ __launch_bounds__(kCopyBlock) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                          int64_t n16, uint32_t nblocks) {
+    const uint32_t lb = xcd_contiguous(blockIdx.x, nblocks);
+    const int64_t base = (int64_t)lb * (kCopyBlock * kCopyPerLane) + threadIdx.x;
+    uint4 r[kCopyPerLane];
+#pragma unroll
+    for (int i = 0; i < kCopyPerLane; ++i) {
+        const int64_t idx = base + (int64_t)i * kCopyBlock;
+        if (idx < n16) r[i] = src[idx];
+    }
+#pragma unroll
+    for (int i = 0; i < kCopyPerLane; ++i) {
+        const int64_t idx = base + (int64_t)i * kCopyBlock;
+        if (idx < n16) dst[idx] = r[i];
+    }
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlaps(const void* a, const void* b, int64_t bytes) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + (uintptr_t)bytes && y < x + (uintptr_t)bytes;
+}
+
+// Checks shared by every convolution entry point.  `ins`/`outs` hold activation pointers.
+hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_out, const float* const* hs,
+                   int n_h, int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype) {
+    for (int i = 0; i < n_in; ++i)
+        if (!ins[i]) return HY_ERR_NULL;
+    for (int i = 0; i < n_out; ++i)
+        if (!outs[i]) return HY_ERR_NULL;
+    for (int i = 0; i < n_h; ++i)
+        if (!hs[i]) return HY_ERR_NULL;
+    if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1) return HY_ERR_SHAPE;
+    if (D % group != 0) return HY_ERR_SHAPE;
+    if (dtype != HY_F32 && dtype != HY_BF16) return HY_ERR_DTYPE;
+    for (int i = 0; i < n_in; ++i)
+        if (!aligned16(ins[i])) return HY_ERR_ALIGN;
+    for (int i = 0; i < n_out; ++i)
+        if (!aligned16(outs[i])) return HY_ERR_ALIGN;
+    for (int i = 0; i < n_h; ++i)
+        if (!aligned16(hs[i])) return HY_ERR_ALIGN;
+    // sizes must stay addressable with signed 64-bit byte offsets
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    if (B > 0 && L > 0 && D > 0) {
+        if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > INT64_MAX / esz) return HY_ERR_SHAPE;
+        const int64_t bytes = B * L * D * esz;
+        for (int o = 0; o < n_out; ++o) {
+            for (int i = 0; i < n_in; ++i)
+                if (overlaps(outs[o], ins[i], bytes)) return HY_ERR_ALIGN;
+            for (int o2 = o + 1; o2 < n_out; ++o2)
+                if (overlaps(outs[o], outs[o2], bytes)) return HY_ERR_ALIGN;
+        }
+    }
+    return HY_OK;
+}
+
+bool empty(int64_t B, int64_t L, int64_t D) { return B == 0 || L == 0 || D == 0; }
+
+}  // namespace
+}  // namespace hy
+
+using namespace hy;
+
+extern "C" {
+
+hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
+                       int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+    const void* ins[3] = {q, k, v};
+    void* outs[1] = {y};
+    const float* hs[1] = {h};
+    hy_status rc = validate(ins, 3, outs, 1, hs, 1, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (empty(B, L, D)) return HY_OK;
+    ConvPtrs p{q, k, v, h, y};
+    ConvShape s{B, L, D, lh, group, dtype, true};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    rc = launch_stencil(&p, 1, s, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
+    return rc;
+}
+
+hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
+                       int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+    const void* ins[3] = {q, k, v};
+    void* outs[1] = {y};
+    const float* hs[1] = {h};
+    hy_status rc = validate(ins, 3, outs, 1, hs, 1, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (empty(B, L, D)) return HY_OK;
+    ConvPtrs p{q, k, v, h, y};
+    ConvShape s{B, L, D, lh, group, dtype, true};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    rc = launch_mr_mfma(p, s, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
+    return rc;
+}
+
+hy_status hyena_featurize_fwd(const void* x, const float* h, void* y, int64_t B, int64_t L, int64_t D, int32_t lh,
+                              int32_t group, hy_dtype dtype, void* hip_stream) {
+    const void* ins[1] = {x};
+    void* outs[1] = {y};
+    const float* hs[1] = {h};
+    hy_status rc = validate(ins, 1, outs, 1, hs, 1, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (empty(B, L, D)) return HY_OK;
+    ConvPtrs p{nullptr, x, nullptr, h, y};
+    ConvShape s{B, L, D, lh, group, dtype, false};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    rc = launch_stencil(&p, 1, s, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
+    return rc;
+}
+
+hy_status hyena_featurize3_fwd(const void* q, const void* k, const void* v, const float* hq, const float* hk,
+                               const float* hv, void* qo, void* ko, void* vo, int64_t B, int64_t L, int64_t D,
+                               int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+    const void* ins[3] = {q, k, v};
+    void* outs[3] = {qo, ko, vo};
+    const float* hs[3] = {hq, hk, hv};
+    hy_status rc = validate(ins, 3, outs, 3, hs, 3, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (empty(B, L, D)) return HY_OK;
+    ConvPtrs p[3] = {{nullptr, q, nullptr, hq, qo}, {nullptr, k, nullptr, hk, ko}, {nullptr, v, nullptr, hv, vo}};
+    ConvShape s{B, L, D, lh, group, dtype, false};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    rc = launch_stencil(p, 3, s, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(p, 3, s, st);
+    return rc;
+}
+
+hy_status hyena_stream_copy(const void* src, void* dst, int64_t bytes, void* hip_stream) {
+    if (!src || !dst) return HY_ERR_NULL;
+    if (bytes < 0 || bytes % 16 != 0) return HY_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst) || (bytes > 0 && overlaps(src, dst, bytes))) return HY_ERR_ALIGN;
+    if (bytes == 0) return HY_OK;
+    const int64_t n16 = bytes / 16;
+    const int64_t per_block = kCopyBlock * kCopyPerLane;
+    const int64_t nb = (n16 + per_block - 1) / per_block;
+    if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)nb), dim3(kCopyBlock), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16, (uint32_t)nb);
+    return launch_status();
+}
+
+hy_status hyena_set_option(const char* name, int32_t value) {
+    if (!name) return HY_ERR_NULL;
+    if (value < 0) return HY_ERR_SHAPE;
+    Tuning& t = tuning();
+    if (strcmp(name, "se_vec") == 0) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return HY_ERR_SHAPE;
+        t.se_vec = value;
+    } else if (strcmp(name, "se_rows") == 0) {
+        t.se_rows = value;
+    } else if (strcmp(name, "mr_rows") == 0) {
+        if (value % 32 != 0) return HY_ERR_SHAPE;
+        t.mr_rows = value;
+    } else {
+        return HY_ERR_UNSUPPORTED;
+    }
+    return HY_OK;
+}
+
+const char* hyena_status_string(hy_status s) {
+    switch (s) {
+        case HY_OK: return "ok";
+        case HY_ERR_NULL: return "null pointer argument";
+        case HY_ERR_SHAPE: return "invalid shape or size argument";
+        case HY_ERR_DTYPE: return "unknown dtype";
+        case HY_ERR_ALIGN: return "pointer not 16-byte aligned, or output aliases an input";
+        case HY_ERR_UNSUPPORTED: return "no kernel for this problem";
+        case HY_ERR_LAUNCH: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+int32_t hyena_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,43 @@
+// Host-side launch interface between the C ABI (api.hip) and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hyena.h"
+
+namespace hy {
+
+// One convolution problem; up to three are batched into a launch (blockIdx.y selects).
+struct ConvPtrs {
+    const void* q;   // post-gate, unused when not gated
+    const void* k;   // pre-gate operand, or the plain input x when not gated
+    const void* v;   // pre-gate operand, unused when not gated
+    const float* h;  // [D/group, lh] fp32
+    void* y;
+};
+
+struct ConvShape {
+    int64_t B, L, D;
+    int32_t lh, group;
+    hy_dtype dtype;
+    bool gated;
+};
+
+struct Tuning {
+    int se_vec = 0;
+    int se_rows = 0;
+    int mr_rows = 0;
+};
+Tuning& tuning();
+
+// Short-filter streaming stencil on the vector ALUs.  HY_ERR_UNSUPPORTED when lh is above its limit.
+hy_status launch_stencil(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
+// General fp32 direct convolution: any lh, any group, both dtypes.
+hy_status launch_direct(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
+// Block-Toeplitz contraction on bf16 MFMA.  HY_ERR_UNSUPPORTED outside its domain.
+hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
+hy_status launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
+
+inline hy_status launch_status() { return hipGetLastError() == hipSuccess ? HY_OK : HY_ERR_LAUNCH; }
+
+}  // namespace hy

@@ -1,0 +1,247 @@
+// Hyena-MR forward on the gfx950 matrix cores: block-Toeplitz contraction (Sec. 3.1, hat y_n = sum_k H_k
+// hat x_{n-k}) with bf16 operands and fp32 accumulation, both gates fused (Algorithm 1).
+//
+// Mapping.  v_mfma_f32_16x16x32_bf16 computes a 16 x 16 tile from a 16 x 32 and a 32 x 16 operand.  Here
+//   M = the 16 channels of one filter group slice,  N = 16 output time steps,  K = 32 source time steps:
+//   Z^T[c, t] = sum_s U^T[c, s] * Tz^T[s, t],   Tz[t, s] = h[t - s]   (Eq. 3).
+// Because Tz is Toeplitz, the operand for output tile t0 and source block s0 depends only on d = t0 - s0,
+// so the 2*NKB operands d = 0, 16, 32, ... are built once per wave from h and stay in registers for the
+// whole sequence: the filter is never re-read and no Toeplitz factor is ever materialised in memory.
+// With channels on M the accumulator of a lane holds 4 adjacent channels of one time step, which is
+// also how q is loaded and y is stored (8 bytes per lane, no transposition of the output).
+// The source operand needs 8 consecutive time steps of one channel per lane while memory has channels
+// contiguous, so u = k*v goes through LDS: written row-wise (16 B per lane), read column-wise.
+//
+// A workgroup of NW waves owns 16*NW adjacent channels (wave w: channels 16w..16w+15, one filter) and
+// `rows` time steps, and walks them in chunks of 32 steps.  Per chunk: the workgroup loads 32 x 16NW
+// elements of k and v with full-line coalesced 16-byte loads (prefetched kPrefetch chunks ahead in
+// registers), multiplies, rounds u to bf16 and stores it to a double-buffered LDS stage; after one
+// barrier each wave reads its group's 32 x 16 block transposed, pushes it into a register window of the
+// last NKB blocks, and issues 2*NKB MFMAs for the two 16-step output tiles of the chunk.  A tile that
+// does not start the sequence first runs NKB-1 warm-up chunks that only fill the window (the halo).
+#include "hy_common.hpp"
+#include "hy_launch.hpp"
+
+namespace hy {
+namespace {
+
+struct MrArgs {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    const float* h;
+    uint16_t* y;
+    int64_t L, D;
+    int32_t lh, group;
+    int32_t rows;           // time steps per workgroup, multiple of 32
+    int32_t tiles_per_seq;  // ceil(L / rows)
+    int32_t ncb;            // channel blocks = D / (16 NW)
+    uint32_t nblocks;
+};
+
+constexpr int kChunk = 32;
+constexpr int kPrefetch = 3;
+
+template <int NKB, int NW>
+__global__ __launch_bounds__(NW * 64) void mr_mfma_kernel(MrArgs a) {
+    constexpr int PPR = 2 * NW;  // 16-byte pieces per staged row
+    static_assert(NW % 4 == 0, "the LDS swizzle needs 8 pieces per row");
+    __shared__ uint4 stage[2][kChunk * PPR];
+
+    const int tid = threadIdx.x;
+    const int w = tid / 64, lane = tid % 64;
+    const int li = lane % 16, lq = lane / 16;
+
+    const uint32_t lb = xcd_contiguous(blockIdx.x, a.nblocks);
+    const int cb = lb % a.ncb;
+    const int64_t tile = lb / a.ncb;
+    const int64_t b = tile / a.tiles_per_seq;
+    const int64_t t_start = (tile % a.tiles_per_seq) * (int64_t)a.rows;
+    const int64_t t_end = (t_start + a.rows < a.L) ? t_start + a.rows : a.L;
+    int64_t t_begin = t_start - (int64_t)kChunk * (NKB - 1);
+    if (t_begin < 0) t_begin = 0;
+    const int nchunks = (int)((t_end - t_begin + kChunk - 1) / kChunk);
+
+    const int64_t D = a.D;
+    const int64_t cblock0 = (int64_t)cb * 16 * NW;  // first channel of the workgroup
+    const int64_t c0 = cblock0 + 16 * w;            // first channel of this wave
+    const int64_t seq0 = b * a.L * D;
+
+    // ---- Toeplitz operands: frag i is for d = 16 i; lane (li = output step, lq = source octet), element e
+    // holds h[d + li - 8 lq - e] (zero outside [0, lh)), rounded to bf16.
+    bf16x8_t tz[2 * NKB];
+    {
+        const float* hp = a.h + (c0 / a.group) * (int64_t)a.lh;
+#pragma unroll
+        for (int i = 0; i < 2 * NKB; ++i) {
+            Words<4> wds;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const int i0 = 16 * i + li - 8 * lq - 2 * e2;
+                const int i1 = i0 - 1;
+                const float f0 = (i0 >= 0 && i0 < a.lh) ? hp[i0] : 0.0f;
+                const float f1 = (i1 >= 0 && i1 < a.lh) ? hp[i1] : 0.0f;
+                wds.w[e2] = pack_bf16x2(f0, f1);
+            }
+            tz[i] = __builtin_bit_cast(bf16x8_t, wds);
+        }
+    }
+
+    // ---- register window of the last NKB source blocks (block m starts 32 m steps before the chunk)
+    bf16x8_t uw[NKB];
+    {
+        Words<4> z = zero_words<4>();
+#pragma unroll
+        for (int m = 0; m < NKB; ++m) uw[m] = __builtin_bit_cast(bf16x8_t, z);
+    }
+
+    // cooperative load coordinates of this lane
+    const int lr = tid / PPR, lp = tid % PPR;
+    const int64_t ld_off = cblock0 + 8 * lp;
+    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
+        const int64_t t = t_begin + (int64_t)ci * kChunk + lr;
+        if (ci < nchunks && t < t_end) {
+            const int64_t off = seq0 + t * D + ld_off;
+            kk = load_words<4>(a.k + off);
+            vv = load_words<4>(a.v + off);
+        } else {
+            kk = zero_words<4>();
+            vv = zero_words<4>();
+        }
+    };
+    // q / y coordinates: lane holds channels c0 + 4 lq .. +3 at step (tile base) + li
+    auto load_q = [&](int ci, Words<2> (&qq)[2]) {
+        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int64_t t = t0 + 16 * p + li;
+            if (ci < nchunks && t0 >= t_start && t < t_end)
+                qq[p] = load_words<2>(a.q + seq0 + t * D + c0 + 4 * lq);
+            else
+                qq[p] = zero_words<2>();
+        }
+    };
+
+    Words<4> kpre[kPrefetch], vpre[kPrefetch];
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) load_kv(i, kpre[i], vpre[i]);
+    Words<2> qnext[2];
+    load_q(0, qnext);
+
+    for (int ci = 0; ci < nchunks; ++ci) {
+        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
+        const bool main_chunk = t0 >= t_start;
+
+        // u = k * v for this lane's 8 channels of one row -> bf16 -> LDS
+        {
+            float kf[8], vf[8];
+            Pack<BF16, 8>::unpack(kpre[0], kf);
+            Pack<BF16, 8>::unpack(vpre[0], vf);
+            Words<4> uu;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) uu.w[e2] = pack_bf16x2(kf[2 * e2] * vf[2 * e2], kf[2 * e2 + 1] * vf[2 * e2 + 1]);
+            const int swz = ((lr >> 3) & 3) << 1;
+            stage[ci & 1][lr * PPR + (lp ^ swz)] = make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]);
+        }
+#pragma unroll
+        for (int i = 0; i + 1 < kPrefetch; ++i) {
+            kpre[i] = kpre[i + 1];
+            vpre[i] = vpre[i + 1];
+        }
+        load_kv(ci + kPrefetch, kpre[kPrefetch - 1], vpre[kPrefetch - 1]);
+        Words<2> qcur[2] = {qnext[0], qnext[1]};
+        load_q(ci + 1, qnext);
+
+        __syncthreads();
+
+        // transposed read: element e of this lane = u[row 8 lq + e][channel 16 w + li]
+#pragma unroll
+        for (int m = NKB - 1; m > 0; --m) uw[m] = uw[m - 1];
+        {
+            const uint16_t* s16 = reinterpret_cast<const uint16_t*>(stage[ci & 1]);
+            const int piece = (2 * w + (li >> 3)) ^ (lq << 1);
+            Words<4> wds;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const int r0 = 8 * lq + 2 * e2;
+                const uint32_t lo = s16[((r0 * PPR + piece) << 3) + (li & 7)];
+                const uint32_t hi = s16[(((r0 + 1) * PPR + piece) << 3) + (li & 7)];
+                wds.w[e2] = lo | (hi << 16);
+            }
+            uw[0] = __builtin_bit_cast(bf16x8_t, wds);
+        }
+
+        if (main_chunk) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int m = 0; m < NKB; ++m)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw[m], tz[p + 2 * m], acc, 0, 0, 0);
+                const int64_t t = t0 + 16 * p + li;
+                if (t < t_end) {
+                    float qf[4];
+                    Pack<BF16, 4>::unpack(qcur[p], qf);
+                    float z[4] = {acc[0] * qf[0], acc[1] * qf[1], acc[2] * qf[2], acc[3] * qf[3]};
+                    store_words<2>(a.y + seq0 + t * D + c0 + 4 * lq, Pack<BF16, 4>::pack(z));
+                }
+            }
+        }
+    }
+}
+
+template <int NKB>
+hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
+    constexpr int NW = 4;
+    MrArgs a;
+    a.q = static_cast<const uint16_t*>(p.q);
+    a.k = static_cast<const uint16_t*>(p.k);
+    a.v = static_cast<const uint16_t*>(p.v);
+    a.h = p.h;
+    a.y = static_cast<uint16_t*>(p.y);
+    a.L = s.L;
+    a.D = s.D;
+    a.lh = s.lh;
+    a.group = s.group;
+    a.ncb = (int32_t)(s.D / (16 * NW));
+    int64_t rows = tuning().mr_rows;
+    if (rows <= 0) {
+        // aim for ~4 workgroups per CU, but never tiles so short that the (NKB-1)*32-step halo dominates
+        const int64_t want = 256 * 4;
+        int64_t tiles = (want + s.B * a.ncb - 1) / (s.B * a.ncb);
+        rows = (s.L + tiles - 1) / tiles;
+        const int64_t min_rows = 8LL * kChunk * (NKB > 1 ? NKB - 1 : 1);
+        if (rows < min_rows) rows = min_rows;
+    }
+    rows = (rows + kChunk - 1) / kChunk * kChunk;
+    if (rows > (s.L + kChunk - 1) / kChunk * kChunk) rows = (s.L + kChunk - 1) / kChunk * kChunk;
+    a.rows = (int32_t)rows;
+    a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
+    const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
+    if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
+    a.nblocks = (uint32_t)nb;
+    hipLaunchKernelGGL((mr_mfma_kernel<NKB, NW>), dim3(a.nblocks), dim3(NW * 64), 0, st, a);
+    return launch_status();
+}
+
+}  // namespace
+
+hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
+    if (s.dtype != HY_BF16 || !s.gated || s.group % 16 != 0 || s.D % 64 != 0 || s.lh > 257)
+        return HY_ERR_UNSUPPORTED;
+    const int nkb = (s.lh - 1 + 31) / 32 + 1;  // 32-step source blocks that can meet a 16-step output tile
+    switch (nkb) {
+        case 1: return launch_nkb<1>(p, s, st);
+        case 2: return launch_nkb<2>(p, s, st);
+        case 3: return launch_nkb<3>(p, s, st);
+        case 4: return launch_nkb<4>(p, s, st);
+        case 5: return launch_nkb<5>(p, s, st);
+        case 6: return launch_nkb<6>(p, s, st);
+        case 7: return launch_nkb<7>(p, s, st);
+        case 8: return launch_nkb<8>(p, s, st);
+        case 9: return launch_nkb<9>(p, s, st);
+        default: return HY_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace hy

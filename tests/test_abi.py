@@ -1,0 +1,121 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments before touching the GPU.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_01868_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not fn.endswith(".h"):
+            continue
+        src = open(os.path.join(ROOT, "include", fn)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names += re.findall(r"\b(hyena_\w+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_header_declares_the_three_required_entry_points():
+    names = declared_functions()
+    for need in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd"):
+        assert need in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.lib()
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_binding_exposes_the_same_names():
+    import paper_2503_01868_amd as pkg
+
+    for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd", "hyena_stream_copy"):
+        assert callable(getattr(pkg, name))
+
+
+def test_version_and_status_strings():
+    assert binding.version() >= 100
+    seen = {binding.status_string(c) for c in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+# fake but well-formed device addresses: validation must finish before any of them is dereferenced
+P = [0x10000 * (i + 1) for i in range(9)]
+
+
+def conv(entry, q=P[0], k=P[1], v=P[2], h=P[3], y=P[4], B=1, L=8, D=16, lh=3, group=1, dtype=0):
+    return getattr(binding.lib(), entry)(q, k, v, h, y, B, L, D, lh, group, dtype, None)
+
+
+@pytest.mark.parametrize("entry", ["hyena_se_fwd", "hyena_mr_fwd"])
+def test_gated_entry_points_reject_bad_arguments(entry):
+    assert conv(entry, q=None) == 1
+    assert conv(entry, k=None) == 1
+    assert conv(entry, v=None) == 1
+    assert conv(entry, h=None) == 1
+    assert conv(entry, y=None) == 1
+    assert conv(entry, B=-1) == 2
+    assert conv(entry, L=-5) == 2
+    assert conv(entry, lh=0) == 2
+    assert conv(entry, group=0) == 2
+    assert conv(entry, D=16, group=3) == 2
+    assert conv(entry, dtype=7) == 3
+    assert conv(entry, q=P[0] + 4) == 4
+    assert conv(entry, y=P[4] + 2) == 4
+    assert conv(entry, h=P[3] + 8) == 4
+    assert conv(entry, y=P[1]) == 4  # output aliases k
+    assert conv(entry, y=P[1] + 16) == 4  # partial overlap
+    assert conv(entry, B=1 << 40, L=1 << 40, D=16) == 2  # size overflows 64-bit offsets
+    # empty problems are valid and launch nothing
+    assert conv(entry, B=0) == 0
+    assert conv(entry, L=0) == 0
+    assert conv(entry, D=0, group=1) == 0
+
+
+def test_featurizer_entry_points_reject_bad_arguments():
+    lib = binding.lib()
+    f = lambda x=P[0], h=P[1], y=P[2], B=1, L=8, D=16, lh=3, group=1, dtype=1: lib.hyena_featurize_fwd(
+        x, h, y, B, L, D, lh, group, dtype, None)
+    assert f(x=None) == 1 and f(h=None) == 1 and f(y=None) == 1
+    assert f(lh=-1) == 2 and f(D=10, group=4) == 2 and f(dtype=2) == 3
+    assert f(x=P[0] + 1) == 4 and f(y=P[0]) == 4 and f(L=0) == 0
+
+    def f3(**kw):
+        a = dict(q=P[0], k=P[1], v=P[2], hq=P[3], hk=P[4], hv=P[5], qo=P[6], ko=P[7], vo=P[8],
+                 B=1, L=8, D=16, lh=3, group=1, dtype=1)
+        a.update(kw)
+        return lib.hyena_featurize3_fwd(*[a[n] for n in ("q", "k", "v", "hq", "hk", "hv", "qo", "ko", "vo", "B",
+                                                            "L", "D", "lh", "group", "dtype")], None)
+
+    assert f3(hv=None) == 1 and f3(vo=None) == 1 and f3(group=5) == 2 and f3(dtype=-1) == 3
+    assert f3(ko=P[6]) == 4  # two outputs alias
+    assert f3(qo=P[2]) == 4 and f3(B=0) == 0
+
+
+def test_stream_copy_and_options_reject_bad_arguments():
+    lib = binding.lib()
+    assert lib.hyena_stream_copy(None, P[1], 16, None) == 1
+    assert lib.hyena_stream_copy(P[0], P[1], 24, None) == 2
+    assert lib.hyena_stream_copy(P[0], P[0] + 16, 64, None) == 4
+    assert lib.hyena_stream_copy(P[0], P[1], 0, None) == 0
+    assert lib.hyena_set_option(b"no_such_knob", 1) == 5
+    assert lib.hyena_set_option(None, 1) == 1
+    assert lib.hyena_set_option(b"se_vec", 3) == 2
+    assert lib.hyena_set_option(b"mr_rows", 48) == 2
+    assert lib.hyena_set_option(b"se_vec", 0) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    x = torch.zeros(1, 4, 8)
+    with pytest.raises(ValueError):
+        binding.hyena_se_fwd(x, x, x, torch.zeros(8, 3))

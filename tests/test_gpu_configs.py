@@ -1,0 +1,82 @@
+"""GPU parity at the five benchmark configurations, in the launch configuration bench.py times.
+c0-c2 are compared in full; c3 and c4 (half a billion outputs each) on sampled outputs the oracle
+evaluates one by one plus whole filter groups over all (b, t)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_01868_amd import binding, synth
+
+from gpu_util import TOL, dev, host, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_inner(w):
+    entry = binding.hyena_se_fwd if w["kind"] == "se" else binding.hyena_mr_fwd
+    return entry(dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["h"]), w["group"])
+
+
+@pytest.mark.parametrize("name", ["c0", "c1", "c2"])
+def test_full_tensor_parity(name):
+    say("config %s full" % name)
+    w = synth.make(name)
+    y = host(run_inner(w))
+    ref = oracle.gated_conv(w["q"], w["k"], w["v"], w["h"], group=w["group"])
+    err = oracle.rel_err(y, ref)
+    say("config %s rel_err=%.3e" % (name, err))
+    assert err <= TOL[w["dtype"]]
+
+
+def subset_channels(w, groups):
+    """Slices of q, k, v and h that hold whole filter groups (channels are independent given their group)."""
+    dg = w["group"]
+    chans = np.concatenate([np.arange(g * dg, (g + 1) * dg) for g in groups])
+    idx = torch.from_numpy(chans)
+    sub = {key: w[key].index_select(2, idx).contiguous() for key in ("q", "k", "v")}
+    return chans, sub, w["h"][groups]
+
+
+def test_c3_long_context_sampled_and_group_subset():
+    say("config c3")
+    w = synth.make("c3")
+    y_dev = run_inner(w)
+    torch.cuda.synchronize()
+    pts = synth.sample_points(7, w["B"], w["L"], w["D"], 20000, w["lh"])
+    ref = oracle.gated_conv_points(w["q"], w["k"], w["v"], w["h"], pts, group=w["group"])
+    got = y_dev[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() / scale <= TOL["bf16"]
+    groups = [0, 100, 255]
+    chans, sub, hsub = subset_channels(w, groups)
+    ref_sub = oracle.gated_conv(sub["q"], sub["k"], sub["v"], hsub, group=w["group"])
+    got_sub = y_dev.index_select(2, torch.from_numpy(chans).to(y_dev.device)).float().cpu().numpy().astype(np.float64)
+    err = oracle.rel_err(got_sub, ref_sub)
+    say("config c3 subset rel_err=%.3e" % err)
+    assert err <= TOL["bf16"]
+
+
+def test_c4_operator_chain_sampled_and_group_subset():
+    say("config c4")
+    w = synth.make("c4")
+    dq, dk, dv = dev(w["q"]), dev(w["k"]), dev(w["v"])
+    qf, kf, vf = binding.hyena_featurize3_fwd(dq, dk, dv, dev(w["hq"]), dev(w["hk"]), dev(w["hv"]), w["feat_group"])
+    del dq, dk, dv
+    y_dev = binding.hyena_mr_fwd(qf, kf, vf, dev(w["h"]), w["group"])
+    torch.cuda.synchronize()
+    del qf, kf, vf
+    pts = synth.sample_points(8, w["B"], w["L"], w["D"], 5000, w["lh"])
+    ref = oracle.chain_points(w["q"], w["k"], w["v"], w["hq"], w["hk"], w["hv"], w["h"], pts,
+                              group=w["group"], feat_group=w["feat_group"])
+    got = y_dev[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() / np.abs(ref).max() <= TOL["bf16"]
+    groups = [0, 255]
+    chans, sub, hsub = subset_channels(w, groups)
+    idx = torch.from_numpy(chans)
+    ref_sub = oracle.chain(sub["q"], sub["k"], sub["v"], w["hq"][chans], w["hk"][chans], w["hv"][chans], hsub,
+                           group=w["group"], feat_group=1)
+    got_sub = y_dev.index_select(2, idx.to(y_dev.device)).float().cpu().numpy().astype(np.float64)
+    err = oracle.rel_err(got_sub, ref_sub)
+    say("config c4 subset rel_err=%.3e" % err)
+    assert err <= TOL["bf16"]

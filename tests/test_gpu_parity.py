@@ -1,0 +1,235 @@
+"""GPU parity: every entry point of the C ABI against the fp64 CPU oracle on identical seeded inputs,
+element by element.  Sizes span several tiles and ragged tails; edge cases cover the left boundary,
+batch boundaries, short sequences, odd widths and every kernel family behind the entry points."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_01868_amd import binding, synth
+
+from gpu_util import TOL, check_gated, dev, draw, gated, host, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    yield
+    for name in ("se_vec", "se_rows", "mr_rows"):
+        binding.set_option(name, 0)
+
+
+# ------------------------------------------------------------------------------------------ Hyena-SE
+SE_CASES = [
+    # B, L, D, lh, group
+    (1, 1024, 256, 7, 1),    # the tiny fp32 configuration
+    (2, 777, 512, 7, 1),     # ragged L, two batch items
+    (3, 100, 264, 4, 1),     # D not a multiple of the block's channel span
+    (1, 5, 64, 7, 1),        # L < lh
+    (1, 1, 8, 3, 1),         # single time step
+    (2, 333, 96, 1, 1),      # lh = 1: elementwise
+    (2, 400, 128, 8, 4),     # grouped short filter
+    (1, 300, 100, 5, 2),     # D = 100: vector width falls back
+    (1, 260, 33, 6, 1),      # odd D: scalar lanes
+    (2, 129, 64, 2, 64),     # one filter for all channels
+    (1, 513, 256, 3, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", SE_CASES)
+def test_se_matches_oracle(case, dtype):
+    B, L, D, lh, group = case
+    check_gated("hyena_se_fwd", 11, B, L, D, lh, group, dtype)
+
+
+@pytest.mark.parametrize("vec", [1, 2, 4, 8])
+@pytest.mark.parametrize("rows", [1, 5, 32, 1000])
+def test_se_every_lane_width_and_tile_length(vec, rows):
+    binding.set_option("se_vec", vec)
+    binding.set_option("se_rows", rows)
+    for dtype in ("f32", "bf16"):
+        check_gated("hyena_se_fwd", 12, 2, 203, 192, 7, 1, dtype)
+
+
+def test_se_long_filter_falls_back_to_general_kernel():
+    for dtype in ("f32", "bf16"):
+        check_gated("hyena_se_fwd", 13, 2, 150, 72, 13, 1, dtype)
+        check_gated("hyena_se_fwd", 13, 1, 90, 40, 40, 2, dtype)
+
+
+# --------------------------------------------------------------------------------------- featurizer
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [(2, 300, 256, 7, 1), (1, 4, 32, 7, 1), (3, 65, 48, 3, 2), (1, 128, 40, 20, 1)])
+def test_featurize_matches_oracle(case, dtype):
+    B, L, D, lh, group = case
+    say("featurize B=%d L=%d D=%d lh=%d group=%d %s" % (B, L, D, lh, group, dtype))
+    rng = np.random.Generator(np.random.PCG64(21))
+    x = synth.normal_tensor(rng, (B, L, D), dtype)
+    h = synth.short_filter(rng, D // group, lh)
+    y = host(binding.hyena_featurize_fwd(dev(x), dev(h), group))
+    assert oracle.rel_err(y, oracle.causal_conv(x, h, group)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_featurize3_matches_three_single_calls_and_oracle(dtype):
+    B, L, D, lh = 2, 211, 320, 7
+    say("featurize3 %s" % dtype)
+    rng = np.random.Generator(np.random.PCG64(22))
+    xs = [synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(3)]
+    hs = [synth.short_filter(rng, D, lh) for _ in range(3)]
+    outs = binding.hyena_featurize3_fwd(*[dev(x) for x in xs], *[dev(h) for h in hs], 1)
+    for x, h, o in zip(xs, hs, outs):
+        single = binding.hyena_featurize_fwd(dev(x), dev(h), 1)
+        assert torch.equal(single, o)
+        assert oracle.rel_err(host(o), oracle.causal_conv(x, h, 1)) <= TOL[dtype]
+
+
+# ------------------------------------------------------------------------------------------ Hyena-MR
+MR_MFMA_CASES = [
+    # B, L, D, lh, group, mr_rows (0 = library's choice)
+    (1, 512, 64, 128, 16, 0),
+    (2, 1000, 128, 128, 16, 256),   # several time tiles with halo warm-up, ragged tail, two batch items
+    (1, 333, 64, 128, 16, 32),      # tile length = one chunk: every tile is mostly halo
+    (2, 97, 64, 128, 16, 64),       # L < lh
+    (1, 1, 64, 128, 16, 0),
+    (1, 31, 64, 7, 16, 0),
+    (1, 640, 192, 33, 16, 128),     # lh = 32 + 1: exactly two source blocks
+    (1, 640, 64, 34, 16, 128),      # one tap past that boundary
+    (1, 500, 64, 64, 32, 96),       # group of 32 channels = two matrix tiles per filter
+    (1, 500, 128, 65, 64, 160),
+    (1, 300, 64, 1, 16, 64),        # lh = 1
+    (1, 700, 64, 129, 16, 128),     # one tap past 128
+    (1, 900, 64, 200, 16, 224),
+    (1, 1100, 64, 257, 64, 288),    # longest filter of the matrix-core path
+    (3, 256, 256, 128, 16, 128),
+]
+
+
+@pytest.mark.parametrize("case", MR_MFMA_CASES)
+def test_mr_matrix_core_path_matches_oracle(case):
+    B, L, D, lh, group, rows = case
+    binding.set_option("mr_rows", rows)
+    check_gated("hyena_mr_fwd", 31, B, L, D, lh, group, "bf16", kind="mr")
+
+
+@pytest.mark.parametrize("case", [
+    (1, 300, 64, 128, 16, "f32"),   # fp32: exact-to-1e-5 check of the Toeplitz indexing on the general kernel
+    (2, 257, 48, 128, 8, "bf16"),   # group smaller than a matrix tile
+    (1, 200, 40, 50, 1, "bf16"),    # ungrouped medium filter
+    (1, 400, 64, 300, 16, "bf16"),  # filter longer than the matrix-core path takes
+    (2, 130, 64, 128, 16, "f32"),
+    (1, 64, 16, 128, 16, "bf16"),   # D below the 64-channel block
+])
+def test_mr_general_path_matches_oracle(case):
+    B, L, D, lh, group, dtype = case
+    check_gated("hyena_mr_fwd", 32, B, L, D, lh, group, dtype, kind="mr")
+
+
+def test_mr_and_se_entry_points_agree_on_a_short_grouped_filter():
+    q, k, v, h = draw(33, 2, 300, 128, 7, 16, "bf16", kind="mr")
+    y_mr = host(gated("hyena_mr_fwd", q, k, v, h, 16))
+    y_se = host(gated("hyena_se_fwd", q, k, v, h, 16))
+    ref = oracle.gated_conv(q, k, v, h, group=16)
+    assert oracle.rel_err(y_mr, ref) <= TOL["bf16"] and oracle.rel_err(y_se, ref) <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------------- exact-arithmetic cases
+def dyadic_filter(n, lh, seed):
+    """Taps that are small multiples of 1/8: exact in bf16, and sums of a few of them exact in fp32."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return (rng.integers(-8, 9, size=(n, lh)) / 8.0).astype(np.float32)
+
+
+@pytest.mark.parametrize("entry,lh,group,dtype", [
+    ("hyena_se_fwd", 7, 1, "bf16"), ("hyena_se_fwd", 7, 1, "f32"),
+    ("hyena_mr_fwd", 128, 16, "bf16"), ("hyena_mr_fwd", 128, 16, "f32"),
+])
+def test_impulse_response_is_bit_exact(entry, lh, group, dtype):
+    """q = k = 1, v = unit impulses: y must reproduce the filter taps exactly (every product and sum
+    is exactly representable), at the first row, mid-sequence and across a tile boundary."""
+    B, L, D = 2, 600, 64
+    say("impulse %s %s" % (entry, dtype))
+    binding.set_option("mr_rows", 256)
+    binding.set_option("se_rows", 50)
+    h = dyadic_filter(D // group, lh, 41)
+    td = synth.torch_dtype(dtype)
+    one = torch.ones(B, L, D, dtype=td)
+    v = torch.zeros(B, L, D, dtype=td)
+    hits = [(0, 0, 0), (0, 250, 17), (1, 301, 63), (1, 0, 5), (0, 599, 1)]
+    expect = np.zeros((B, L, D))
+    for b, t0, c in hits:
+        v[b, t0, c] = 1.0
+        n = min(lh, L - t0)
+        expect[b, t0:t0 + n, c] += h[c // group, :n]
+    y = host(gated(entry, one, one, v, h, group))
+    assert np.array_equal(y, expect)
+
+
+@pytest.mark.parametrize("entry,lh,group", [("hyena_se_fwd", 7, 1), ("hyena_mr_fwd", 128, 16)])
+def test_sparse_signed_inputs_are_bit_exact_in_bf16(entry, lh, group):
+    """k, v in {-1, 0, 1} (sparse), q in {-2, ..., 2}, dyadic taps: every partial sum is a multiple of
+    1/8 below 2^8, so fp32 accumulation is exact in any order and the bf16 result is exact."""
+    B, L, D = 2, 700, 128
+    say("sparse exact %s" % entry)
+    binding.set_option("mr_rows", 192)
+    rng = np.random.Generator(np.random.PCG64(42))
+    h = dyadic_filter(D // group, lh, 43) * (rng.random((D // group, lh)) < 0.25)
+    h = h.astype(np.float32)
+    k = torch.from_numpy(rng.integers(-1, 2, (B, L, D)).astype(np.float32)).bfloat16()
+    v = torch.from_numpy((rng.integers(-1, 2, (B, L, D)) * (rng.random((B, L, D)) < 0.3)).astype(np.float32)).bfloat16()
+    q = torch.from_numpy(rng.integers(-2, 3, (B, L, D)).astype(np.float32)).bfloat16()
+    ref = oracle.gated_conv(q, k, v, h, group=group)
+    assert np.array_equal(ref, torch.from_numpy(ref).bfloat16().double().numpy())  # the case really is exact
+    y = host(gated(entry, q, k, v, h, group))
+    assert np.array_equal(y, ref)
+
+
+# --------------------------------------------------------------- memory safety and determinism
+@pytest.mark.parametrize("entry,lh,group,kind", [("hyena_se_fwd", 7, 1, "se"), ("hyena_mr_fwd", 128, 16, "mr")])
+def test_writes_stay_inside_the_output_and_cover_all_of_it(entry, lh, group, kind):
+    B, L, D = 2, 301, 128
+    say("guard bands %s" % entry)
+    q, k, v, h = draw(51, B, L, D, lh, group, "bf16", kind)
+    n = B * L * D
+    guard = 4096
+    buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    out = buf[guard:guard + n].view(B, L, D)
+    getattr(binding, entry)(dev(q), dev(k), dev(v), dev(h), group, out=out)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all()
+    assert not torch.isnan(out).any()
+    assert oracle.rel_err(host(out), oracle.gated_conv(q, k, v, h, group=group)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("entry,lh,group,kind", [("hyena_se_fwd", 7, 1, "se"), ("hyena_mr_fwd", 128, 16, "mr")])
+def test_repeat_runs_are_bit_identical_and_batch_items_do_not_leak(entry, lh, group, kind):
+    B, L, D = 2, 500, 128
+    say("determinism %s" % entry)
+    q, k, v, h = draw(52, 1, L, D, lh, group, "bf16", kind)
+    q2, k2, v2 = (torch.cat([x, x], dim=0) for x in (q, k, v))  # two identical batch items
+    y_a = gated(entry, q2, k2, v2, h, group)
+    y_b = gated(entry, q2, k2, v2, h, group)
+    torch.cuda.synchronize()
+    assert torch.equal(y_a, y_b)
+    assert torch.equal(y_a[0], y_a[1])  # item 1 must not see the tail of item 0 as its past
+
+
+def test_runs_on_a_side_stream():
+    q, k, v, h = draw(53, 1, 256, 128, 7, 1, "bf16")
+    s = torch.cuda.Stream()
+    dq, dk, dv, dh = dev(q), dev(k), dev(v), dev(h)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        y = binding.hyena_se_fwd(dq, dk, dv, dh, 1)
+    s.synchronize()
+    assert oracle.rel_err(host(y), oracle.gated_conv(q, k, v, h)) <= TOL["bf16"]
+
+
+def test_stream_copy_copies():
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    binding.hyena_stream_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
