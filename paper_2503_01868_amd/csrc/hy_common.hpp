@@ -58,6 +58,42 @@ __device__ __forceinline__ void store_words(void* p, const Words<N>& r) {
     }
 }
 
+// Streaming variants: the non-temporal hint keeps once-touched activations from displacing other
+// lines in L2 and the memory-side cache.  Measured on MI355X: a 3-read/1-write stream of 64 MiB arrays
+// runs ~10% faster with the hint on both loads and stores.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+template <int N>
+__device__ __forceinline__ Words<N> load_words_nt(const void* p) {
+    Words<N> r;
+    if constexpr (N == 4) {
+        u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+        r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
+    } else if constexpr (N == 2) {
+        u32x2_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+        r.w[0] = t.x; r.w[1] = t.y;
+    } else {
+        static_assert(N == 1, "1, 2 or 4 words");
+        r.w[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+    }
+    return r;
+}
+
+template <int N>
+__device__ __forceinline__ void store_words_nt(void* p, const Words<N>& r) {
+    if constexpr (N == 4) {
+        u32x4_t t = {r.w[0], r.w[1], r.w[2], r.w[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
+    } else if constexpr (N == 2) {
+        u32x2_t t = {r.w[0], r.w[1]};
+        __builtin_nontemporal_store(t, reinterpret_cast<u32x2_t*>(p));
+    } else {
+        static_assert(N == 1, "1, 2 or 4 words");
+        __builtin_nontemporal_store(r.w[0], reinterpret_cast<uint32_t*>(p));
+    }
+}
+
 template <int N>
 __device__ __forceinline__ Words<N> zero_words() {
     Words<N> r;
@@ -98,6 +134,23 @@ struct Pack {
             store_words<kWords>(p, r);
         }
     }
+    // streaming (non-temporal) forms for data touched once
+    static __device__ __forceinline__ Raw load_nt(const void* p) {
+        if constexpr (kBytes == 2) {
+            Raw r;
+            r.w[0] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(p));
+            return r;
+        } else {
+            return load_words_nt<kWords>(p);
+        }
+    }
+    static __device__ __forceinline__ void store_nt(void* p, const Raw& r) {
+        if constexpr (kBytes == 2) {
+            __builtin_nontemporal_store(static_cast<uint16_t>(r.w[0]), reinterpret_cast<uint16_t*>(p));
+        } else {
+            store_words_nt<kWords>(p, r);
+        }
+    }
     static __device__ __forceinline__ void unpack(const Raw& r, float (&f)[VEC]) {
         if constexpr (T::kBytes == 4) {
 #pragma unroll
@@ -129,8 +182,9 @@ struct Pack {
 
 // Workgroups are handed to the 8 XCDs round-robin by launch index, and each XCD has its own L2.
 // This maps launch index -> logical index so that every XCD owns one contiguous range of logical
-// indices and walks it in launch order: logically adjacent tiles (which share halo rows) then meet in
-// the same L2 close in time.  Bijective for any n.
+// indices and walks it in launch order.  Bijective for any n.  (Measured on MI355X: for pure streaming
+// the plain launch order, where all XCDs sweep one compact address window together, is faster; this
+// mapping is for kernels whose neighbouring workgroups re-use each other's lines through L2.)
 __device__ __forceinline__ uint32_t xcd_contiguous(uint32_t launch_idx, uint32_t n) {
     uint32_t x = launch_idx % kXcds, i = launch_idx / kXcds;
     uint32_t q = n / kXcds, r = n % kXcds;

@@ -7,18 +7,20 @@
 // Because Tz is Toeplitz, the operand for output tile t0 and source block s0 depends only on d = t0 - s0,
 // so the 2*NKB operands d = 0, 16, 32, ... are built once per wave from h and stay in registers for the
 // whole sequence: the filter is never re-read and no Toeplitz factor is ever materialised in memory.
-// With channels on M the accumulator of a lane holds 4 adjacent channels of one time step, which is
-// also how q is loaded and y is stored (8 bytes per lane, no transposition of the output).
 // The source operand needs 8 consecutive time steps of one channel per lane while memory has channels
-// contiguous, so u = k*v goes through LDS: written row-wise (16 B per lane), read column-wise.
+// contiguous, so u = k*v goes through LDS: written row-wise (16 B per lane), read column-wise.  With
+// channels on M the accumulator of a lane holds 4 adjacent channels of one time step; z goes back through
+// LDS as fp32 rows so that q is loaded and y is stored as whole row pieces, 16 bytes per lane, like k and v.
 //
 // A workgroup of NW waves owns 16*NW adjacent channels (wave w: channels 16w..16w+15, one filter) and
 // `rows` time steps, and walks them in chunks of 32 steps.  Per chunk: the workgroup loads 32 x 16NW
-// elements of k and v with full-line coalesced 16-byte loads (prefetched kPrefetch chunks ahead in
-// registers), multiplies, rounds u to bf16 and stores it to a double-buffered LDS stage; after one
+// elements of k and v with full-line coalesced 16-byte loads (k, v and q are prefetched several chunks
+// ahead in registers, so a chunk iteration never waits a full memory latency), multiplies, rounds u to bf16 and stores it to a double-buffered LDS stage; after one
 // barrier each wave reads its group's 32 x 16 block transposed, pushes it into a register window of the
-// last NKB blocks, and issues 2*NKB MFMAs for the two 16-step output tiles of the chunk.  A tile that
-// does not start the sequence first runs NKB-1 warm-up chunks that only fill the window (the halo).
+// last NKB blocks, issues 2*NKB MFMAs for the two 16-step output tiles of the chunk and parks z in LDS;
+// the post-gate and store of a chunk run one iteration late, after the next barrier, so there is a
+// single barrier per chunk.  A tile that does not start the sequence first runs NKB-1 warm-up chunks that
+// only fill the window (the halo).
 #include "hy_common.hpp"
 #include "hy_launch.hpp"
 
@@ -40,19 +42,25 @@ struct MrArgs {
 };
 
 constexpr int kChunk = 32;
-constexpr int kPrefetch = 3;
 
-template <int NKB, int NW>
-__global__ __launch_bounds__(NW * 64) void mr_mfma_kernel(MrArgs a) {
-    constexpr int PPR = 2 * NW;  // 16-byte pieces per staged row
+// kPrefetch = chunks of k, v and q in flight per lane (registers).  Two waves per SIMD must fit.
+template <int NKB, int NW, int kPrefetch>
+__global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
+    constexpr int PPR = 2 * NW;              // 16-byte pieces per staged row of u (bf16)
+    constexpr int kTaps = 32 * NKB;          // >= lh
+    constexpr int ZROW = 16 * NW * 4 + 16;   // bytes per staged row of z (fp32), padded against bank conflicts
     static_assert(NW % 4 == 0, "the LDS swizzle needs 8 pieces per row");
     __shared__ uint4 stage[2][kChunk * PPR];
+    __shared__ __attribute__((aligned(16))) char zst[2][kChunk * ZROW];
+    __shared__ float hs[NW][kTaps];
 
     const int tid = threadIdx.x;
     const int w = tid / 64, lane = tid % 64;
     const int li = lane % 16, lq = lane / 16;
 
-    const uint32_t lb = xcd_contiguous(blockIdx.x, a.nblocks);
+    // launch order: channel block fastest, so neighbouring workgroups read neighbouring 32*NW-byte
+    // pieces of the same rows and the chip sweeps whole rows
+    const uint32_t lb = blockIdx.x;
     const int cb = lb % a.ncb;
     const int64_t tile = lb / a.ncb;
     const int64_t b = tile / a.tiles_per_seq;
@@ -67,11 +75,37 @@ __global__ __launch_bounds__(NW * 64) void mr_mfma_kernel(MrArgs a) {
     const int64_t c0 = cblock0 + 16 * w;            // first channel of this wave
     const int64_t seq0 = b * a.L * D;
 
-    // ---- Toeplitz operands: frag i is for d = 16 i; lane (li = output step, lq = source octet), element e
-    // holds h[d + li - 8 lq - e] (zero outside [0, lh)), rounded to bf16.
+    // cooperative coordinates of this lane: row lr of the chunk, 16-byte piece lp (8 channels) of the row;
+    // used for the k, v, q loads and the y store, all of them whole 32*NW-byte row pieces
+    const int lr = tid / PPR, lp = tid % PPR;
+    const int64_t ld_off = cblock0 + 8 * lp;
+    auto load_kvq = [&](int ci, Words<4>& kk, Words<4>& vv, Words<4>& qq) {
+        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
+        const int64_t t = t0 + lr;
+        kk = zero_words<4>();
+        vv = zero_words<4>();
+        qq = zero_words<4>();
+        if (ci < nchunks && t < t_end) {
+            const int64_t off = seq0 + t * D + ld_off;
+            kk = load_words_nt<4>(a.k + off);
+            vv = load_words_nt<4>(a.v + off);
+            if (t0 >= t_start) qq = load_words_nt<4>(a.q + off);
+        }
+    };
+
+    // start the first loads before anything else so their latency overlaps the filter set-up
+    Words<4> kpre[kPrefetch], vpre[kPrefetch], qpre[kPrefetch];
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) load_kvq(i, kpre[i], vpre[i], qpre[i]);
+
+    // ---- Toeplitz operands: operand i serves d = (output tile start) - (source block start) = 16 i; in it
+    // lane (li = output step, lq = source octet), element e holds h[d + li - 8 lq - e] (zero outside
+    // [0, lh)), rounded to bf16.  The wave's filter goes through LDS once so the gather is not 80 global loads.
     bf16x8_t tz[2 * NKB];
     {
         const float* hp = a.h + (c0 / a.group) * (int64_t)a.lh;
+        for (int j = lane; j < kTaps; j += 64) hs[w][j] = (j < a.lh) ? hp[j] : 0.0f;
+        __syncthreads();
 #pragma unroll
         for (int i = 0; i < 2 * NKB; ++i) {
             Words<4> wds;
@@ -79,8 +113,8 @@ __global__ __launch_bounds__(NW * 64) void mr_mfma_kernel(MrArgs a) {
             for (int e2 = 0; e2 < 4; ++e2) {
                 const int i0 = 16 * i + li - 8 * lq - 2 * e2;
                 const int i1 = i0 - 1;
-                const float f0 = (i0 >= 0 && i0 < a.lh) ? hp[i0] : 0.0f;
-                const float f1 = (i1 >= 0 && i1 < a.lh) ? hp[i1] : 0.0f;
+                const float f0 = (i0 >= 0 && i0 < kTaps) ? hs[w][i0] : 0.0f;
+                const float f1 = (i1 >= 0 && i1 < kTaps) ? hs[w][i1] : 0.0f;
                 wds.w[e2] = pack_bf16x2(f0, f1);
             }
             tz[i] = __builtin_bit_cast(bf16x8_t, wds);
@@ -95,104 +129,95 @@ __global__ __launch_bounds__(NW * 64) void mr_mfma_kernel(MrArgs a) {
         for (int m = 0; m < NKB; ++m) uw[m] = __builtin_bit_cast(bf16x8_t, z);
     }
 
-    // cooperative load coordinates of this lane
-    const int lr = tid / PPR, lp = tid % PPR;
-    const int64_t ld_off = cblock0 + 8 * lp;
-    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
-        const int64_t t = t_begin + (int64_t)ci * kChunk + lr;
-        if (ci < nchunks && t < t_end) {
-            const int64_t off = seq0 + t * D + ld_off;
-            kk = load_words<4>(a.k + off);
-            vv = load_words<4>(a.v + off);
-        } else {
-            kk = zero_words<4>();
-            vv = zero_words<4>();
-        }
-    };
-    // q / y coordinates: lane holds channels c0 + 4 lq .. +3 at step (tile base) + li
-    auto load_q = [&](int ci, Words<2> (&qq)[2]) {
+    const int swz = ((lr >> 3) & 3) << 1;
+    const int st_idx = lr * PPR + (lp ^ swz);
+    const int rd_piece = (2 * w + (li >> 3)) ^ (lq << 1);
+    const int zwr_off = li * ZROW + (16 * w + 4 * lq) * 4;  // + 16 * ZROW for the second 16-step tile
+    const int zrd_off = lr * ZROW + 8 * lp * 4;
+
+    // Post-gate and store of a finished chunk: z comes back from LDS in row layout, so the lane multiplies
+    // 8 adjacent channels of one row by q and writes 16 contiguous bytes.
+    auto gate_store = [&](int ci, const Words<4>& qq) {
         const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int64_t t = t0 + 16 * p + li;
-            if (ci < nchunks && t0 >= t_start && t < t_end)
-                qq[p] = load_words<2>(a.q + seq0 + t * D + c0 + 4 * lq);
-            else
-                qq[p] = zero_words<2>();
+        const int64_t t = t0 + lr;
+        if (t0 >= t_start && t < t_end) {
+            const char* zp = zst[ci & 1] + zrd_off;
+            const float4 za = *reinterpret_cast<const float4*>(zp);
+            const float4 zb = *reinterpret_cast<const float4*>(zp + 16);
+            float qf[8];
+            Pack<BF16, 8>::unpack(qq, qf);
+            float y8[8] = {za.x * qf[0], za.y * qf[1], za.z * qf[2], za.w * qf[3],
+                           zb.x * qf[4], zb.y * qf[5], zb.z * qf[6], zb.w * qf[7]};
+            store_words_nt<4>(a.y + seq0 + t * D + ld_off, Pack<BF16, 8>::pack(y8));
         }
     };
 
-    Words<4> kpre[kPrefetch], vpre[kPrefetch];
+    Words<4> qhold = zero_words<4>();  // q of the previous chunk, whose z is gated one iteration late
+    for (int base = 0; base < nchunks; base += kPrefetch) {
 #pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) load_kv(i, kpre[i], vpre[i]);
-    Words<2> qnext[2];
-    load_q(0, qnext);
+        for (int sgi = 0; sgi < kPrefetch; ++sgi) {
+            const int ci = base + sgi;
+            if (ci >= nchunks) break;
+            const int64_t t0 = t_begin + (int64_t)ci * kChunk;
+            const bool main_chunk = t0 >= t_start;
 
-    for (int ci = 0; ci < nchunks; ++ci) {
-        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-        const bool main_chunk = t0 >= t_start;
-
-        // u = k * v for this lane's 8 channels of one row -> bf16 -> LDS
-        {
-            float kf[8], vf[8];
-            Pack<BF16, 8>::unpack(kpre[0], kf);
-            Pack<BF16, 8>::unpack(vpre[0], vf);
-            Words<4> uu;
+            // u = k * v for this lane's 8 channels of one row -> bf16 -> LDS
+            {
+                float kf[8], vf[8];
+                Pack<BF16, 8>::unpack(kpre[sgi], kf);
+                Pack<BF16, 8>::unpack(vpre[sgi], vf);
+                Words<4> uu;
 #pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) uu.w[e2] = pack_bf16x2(kf[2 * e2] * vf[2 * e2], kf[2 * e2 + 1] * vf[2 * e2 + 1]);
-            const int swz = ((lr >> 3) & 3) << 1;
-            stage[ci & 1][lr * PPR + (lp ^ swz)] = make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]);
-        }
-#pragma unroll
-        for (int i = 0; i + 1 < kPrefetch; ++i) {
-            kpre[i] = kpre[i + 1];
-            vpre[i] = vpre[i + 1];
-        }
-        load_kv(ci + kPrefetch, kpre[kPrefetch - 1], vpre[kPrefetch - 1]);
-        Words<2> qcur[2] = {qnext[0], qnext[1]};
-        load_q(ci + 1, qnext);
-
-        __syncthreads();
-
-        // transposed read: element e of this lane = u[row 8 lq + e][channel 16 w + li]
-#pragma unroll
-        for (int m = NKB - 1; m > 0; --m) uw[m] = uw[m - 1];
-        {
-            const uint16_t* s16 = reinterpret_cast<const uint16_t*>(stage[ci & 1]);
-            const int piece = (2 * w + (li >> 3)) ^ (lq << 1);
-            Words<4> wds;
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const int r0 = 8 * lq + 2 * e2;
-                const uint32_t lo = s16[((r0 * PPR + piece) << 3) + (li & 7)];
-                const uint32_t hi = s16[(((r0 + 1) * PPR + piece) << 3) + (li & 7)];
-                wds.w[e2] = lo | (hi << 16);
+                for (int e2 = 0; e2 < 4; ++e2)
+                    uu.w[e2] = pack_bf16x2(kf[2 * e2] * vf[2 * e2], kf[2 * e2 + 1] * vf[2 * e2 + 1]);
+                stage[ci & 1][st_idx] = make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]);
             }
-            uw[0] = __builtin_bit_cast(bf16x8_t, wds);
-        }
+            const Words<4> qcur = qpre[sgi];
+            // refill this register stage with the chunk kPrefetch ahead
+            load_kvq(ci + kPrefetch, kpre[sgi], vpre[sgi], qpre[sgi]);
 
-        if (main_chunk) {
+            __syncthreads();  // u of this chunk and z of the previous chunk are now visible
+
+            // transposed read: element e of this lane = u[row 8 lq + e][channel 16 w + li]
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int m = NKB - 1; m > 0; --m) uw[m] = uw[m - 1];
+            {
+                const uint16_t* s16 = reinterpret_cast<const uint16_t*>(stage[ci & 1]);
+                Words<4> wds;
 #pragma unroll
-                for (int m = 0; m < NKB; ++m)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw[m], tz[p + 2 * m], acc, 0, 0, 0);
-                const int64_t t = t0 + 16 * p + li;
-                if (t < t_end) {
-                    float qf[4];
-                    Pack<BF16, 4>::unpack(qcur[p], qf);
-                    float z[4] = {acc[0] * qf[0], acc[1] * qf[1], acc[2] * qf[2], acc[3] * qf[3]};
-                    store_words<2>(a.y + seq0 + t * D + c0 + 4 * lq, Pack<BF16, 4>::pack(z));
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const int r0 = 8 * lq + 2 * e2;
+                    const uint32_t lo = s16[((r0 * PPR + rd_piece) << 3) + (li & 7)];
+                    const uint32_t hi = s16[(((r0 + 1) * PPR + rd_piece) << 3) + (li & 7)];
+                    wds.w[e2] = lo | (hi << 16);
                 }
+                uw[0] = __builtin_bit_cast(bf16x8_t, wds);
             }
+
+            if (main_chunk) {
+                f32x4_t acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int m = 0; m < NKB; ++m) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw[m], tz[2 * m], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw[m], tz[2 * m + 1], acc1, 0, 0, 0);
+                }
+                // the lane holds z for channels 16 w + 4 lq .. +3 at steps li and 16 + li of the chunk
+                char* zp = zst[ci & 1] + zwr_off;
+                *reinterpret_cast<float4*>(zp) = make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
+                *reinterpret_cast<float4*>(zp + 16 * ZROW) = make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
+            }
+            if (ci > 0) gate_store(ci - 1, qhold);
+            qhold = qcur;
         }
     }
+    __syncthreads();
+    gate_store(nchunks - 1, qhold);
 }
 
 template <int NKB>
 hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     constexpr int NW = 4;
+    constexpr int PF = NKB <= 5 ? 6 : (NKB <= 7 ? 4 : 3);
     MrArgs a;
     a.q = static_cast<const uint16_t*>(p.q);
     a.k = static_cast<const uint16_t*>(p.k);
@@ -220,7 +245,7 @@ hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
     a.nblocks = (uint32_t)nb;
-    hipLaunchKernelGGL((mr_mfma_kernel<NKB, NW>), dim3(a.nblocks), dim3(NW * 64), 0, st, a);
+    hipLaunchKernelGGL((mr_mfma_kernel<NKB, NW, PF>), dim3(a.nblocks), dim3(NW * 64), 0, st, a);
     return launch_status();
 }
 

@@ -3,9 +3,9 @@
 // Each lane owns VEC adjacent channels and walks down `rows` time steps of one batch item.  The taps of
 // its channels and the last LH-1 values of u = k*v sit in registers, so every input element is loaded
 // exactly once per tile plus LH-1 halo rows of k and v at the tile start.  A wave covers 64*VEC
-// adjacent channels of a row: every load and store is one contiguous, fully used segment.  Tiles are
-// ordered time-major inside each XCD's share so that the halo rows of a tile are the rows its
-// neighbour in launch order has just fetched into the same L2.
+// adjacent channels of a row: every load and store is one contiguous, fully used segment.  Workgroups
+// take tiles in launch order with the channel strip fastest, so the chip sweeps each tile row of the
+// tensor left to right; loads and stores of the bulk rows carry the non-temporal hint.
 // Arithmetic: fp32 multiply for the pre-gate, fp32 FMA chain over taps in ascending tap order, fp32
 // multiply for the post-gate, one rounding to the storage type at the store.
 #include "hy_common.hpp"
@@ -32,8 +32,7 @@ __global__ __launch_bounds__(kStencilBlock) void stencil_kernel(StencilArgs a) {
     using P = Pack<T, VEC>;
     using Raw = typename P::Raw;
     const ConvPtrs pr = a.p[blockIdx.y];
-    const uint32_t lb = xcd_contiguous(blockIdx.x, a.nblocks);
-    const int64_t item = (int64_t)lb * kStencilBlock + threadIdx.x;
+    const int64_t item = (int64_t)blockIdx.x * kStencilBlock + threadIdx.x;
     if (item >= a.nitems) return;
     const int64_t cv = item % a.nvec;
     const int64_t tile = item / a.nvec;
@@ -82,10 +81,10 @@ __global__ __launch_bounds__(kStencilBlock) void stencil_kernel(StencilArgs a) {
         for (int r = 0; r < R; ++r) {
             if (t + r < t1) {
                 const int64_t off = (seq0 + (t + r) * D) * T::kBytes;
-                kr[r] = P::load(kp + off);
+                kr[r] = P::load_nt(kp + off);
                 if constexpr (GATED) {
-                    vr[r] = P::load(vp + off);
-                    qr[r] = P::load(qp + off);
+                    vr[r] = P::load_nt(vp + off);
+                    qr[r] = P::load_nt(qp + off);
                 }
             } else {
                 kr[r] = zero_words<P::kWords>();
@@ -135,7 +134,7 @@ __global__ __launch_bounds__(kStencilBlock) void stencil_kernel(StencilArgs a) {
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) z[e] *= qf[e];
                 }
-                P::store(yp + (seq0 + (t + r) * D) * T::kBytes, P::pack(z));
+                P::store_nt(yp + (seq0 + (t + r) * D) * T::kBytes, P::pack(z));
             }
         }
 #pragma unroll
@@ -148,8 +147,7 @@ __global__ __launch_bounds__(kStencilBlock) void stencil_kernel(StencilArgs a) {
 
 template <typename T, int VEC, int LH, bool GATED>
 hy_status launch_one(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st) {
-    // rows in flight per lane: keep about 16 B * 3 * R bytes outstanding
-    constexpr int R = (VEC * T::kBytes >= 16) ? 4 : 8;
+    constexpr int R = 8;  // rows in flight per lane while the previous batch is computed
     StencilArgs a;
     for (int i = 0; i < 3; ++i) a.p[i] = p[i < nprob ? i : 0];
     a.L = s.L;
@@ -158,15 +156,12 @@ hy_status launch_one(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream
     a.nvec = s.D / VEC;
     int rows = tuning().se_rows;
     if (rows <= 0) {
-        // enough lanes to fill the chip several times over, but tiles long enough that the halo is small
-        const int64_t lanes_per_row = a.nvec * s.B;
-        const int64_t want_lanes = 256LL * 2048;  // 256 CUs x 2048 lanes
-        int64_t tiles = (want_lanes * 2 + lanes_per_row - 1) / lanes_per_row;
-        if (tiles < 1) tiles = 1;
-        int64_t r = (s.L + tiles - 1) / tiles;
-        if (r < 32) r = 32;
-        if (r > 256) r = 256;
-        rows = (int)r;
+        // Tile length in t: 128 steps (halo re-reads 2.3% at lh = 7) when that still leaves about 8 waves
+        // per CU, shorter powers of two for small problems.  Powers of two keep the spacing of the
+        // concurrently walked tiles a power of two in memory, which measured best on MI355X.
+        const int64_t waves_per_row = (a.nvec * nprob + kWave - 1) / kWave;
+        rows = 128;
+        while (rows > 32 && s.B * ((s.L + rows - 1) / rows) * waves_per_row < 2048) rows >>= 1;
     }
     if (rows > s.L) rows = (int)s.L;
     if (rows < 1) rows = 1;
@@ -198,7 +193,8 @@ hy_status by_lh(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st
 template <typename T, bool GATED>
 hy_status by_vec(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st) {
     constexpr int kMaxVec = 16 / T::kBytes;
-    int vec = tuning().se_vec > 0 ? tuning().se_vec : (T::kBytes == 2 ? 4 : 4);
+    // 4 bytes per lane: narrow strips give the most waves per tile row; measured fastest for bf16 at D = 4096
+    int vec = tuning().se_vec > 0 ? tuning().se_vec : (T::kBytes == 2 ? 2 : 1);
     if (vec > kMaxVec) vec = kMaxVec;
     while (vec > 1 && s.D % vec != 0) vec >>= 1;
     if constexpr (T::kBytes == 2) {
