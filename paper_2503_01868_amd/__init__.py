@@ -5,6 +5,9 @@ benchmark inputs; ``build`` compiles the library.
 """
 from .binding import (  # noqa: F401
     HyenaError,
+    Plan,
+    plan_featurize3,
+    plan_gated,
     hyena_featurize3_fwd,
     hyena_featurize_fwd,
     hyena_mr_fwd,

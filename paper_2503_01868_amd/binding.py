@@ -112,6 +112,62 @@ def _gated(entry: str, q, k, v, h, group, out, stream):
     return y
 
 
+class Plan:
+    """A fully marshalled call: ``plan()`` re-issues the same C-ABI call on the same buffers and stream.
+
+    Nothing is computed or cached here; it only keeps the ctypes arguments (and references to the
+    tensors, so they stay alive) to take Python's per-call checks out of a launch loop."""
+
+    __slots__ = ("_fn", "_args", "_what", "_keep", "out")
+
+    def __init__(self, fn, args, what, keep, out):
+        self._fn, self._args, self._what, self._keep, self.out = fn, args, what, keep, out
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != HY_OK:
+            raise HyenaError(rc, self._what)
+        return self.out
+
+
+def plan_gated(entry: str, q, k, v, h, group: int, out=None, stream=None) -> Plan:
+    """Marshal one ``hyena_se_fwd`` / ``hyena_mr_fwd`` call (``entry`` names which) for repeated issue."""
+    if entry not in ("hyena_se_fwd", "hyena_mr_fwd"):
+        raise ValueError("entry must be hyena_se_fwd or hyena_mr_fwd")
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    lh = _check_filter("h", h, q, group)
+    y = torch.empty_like(q) if out is None else out
+    _check_act("out", y, q)
+    B, L, D = q.shape
+    c = ctypes
+    args = (c.c_void_p(q.data_ptr()), c.c_void_p(k.data_ptr()), c.c_void_p(v.data_ptr()), c.c_void_p(h.data_ptr()),
+            c.c_void_p(y.data_ptr()), c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lh), c.c_int32(int(group)),
+            c.c_int(_dtype_code(q)), c.c_void_p(_stream(q, stream)))
+    return Plan(getattr(lib(), entry), args, entry, (q, k, v, h, y), y)
+
+
+def plan_featurize3(q, k, v, hq, hk, hv, group: int = 1, out=None, stream=None) -> Plan:
+    """Marshal one ``hyena_featurize3_fwd`` call for repeated issue."""
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    lh = _check_filter("hq", hq, q, group)
+    if _check_filter("hk", hk, q, group) != lh or _check_filter("hv", hv, q, group) != lh:
+        raise ValueError("the three featurizer filters must share one length")
+    outs = tuple(torch.empty_like(q) for _ in range(3)) if out is None else tuple(out)
+    for name, o in zip(("qo", "ko", "vo"), outs):
+        _check_act(name, o, q)
+    B, L, D = q.shape
+    c = ctypes
+    ptrs = [t.data_ptr() for t in (q, k, v, hq, hk, hv) + outs]
+    args = tuple(c.c_void_p(p) for p in ptrs) + (c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lh),
+                                                  c.c_int32(int(group)), c.c_int(_dtype_code(q)),
+                                                  c.c_void_p(_stream(q, stream)))
+    return Plan(lib().hyena_featurize3_fwd, args, "hyena_featurize3_fwd", (q, k, v, hq, hk, hv) + outs, outs)
+
+
 def hyena_se_fwd(q, k, v, h, group: int = 1, out=None, stream=None) -> torch.Tensor:
     """y = q * (h conv (k * v)), short filters; see ``hyena_se_fwd`` in hyena.h."""
     return _gated("hyena_se_fwd", q, k, v, h, group, out, stream)

@@ -173,6 +173,11 @@ hy_status hyena_set_option(const char* name, int32_t value) {
     } else if (strcmp(name, "mr_rows") == 0) {
         if (value % 32 != 0) return HY_ERR_SHAPE;
         t.mr_rows = value;
+    } else if (strcmp(name, "mr_order") == 0) {
+        t.mr_order = value;
+    } else if (strcmp(name, "mr_waves") == 0) {
+        if (value != 0 && value != 4 && value != 8) return HY_ERR_SHAPE;
+        t.mr_waves = value;
     } else {
         return HY_ERR_UNSUPPORTED;
     }

@@ -39,6 +39,7 @@ struct MrArgs {
     int32_t tiles_per_seq;  // ceil(L / rows)
     int32_t ncb;            // channel blocks = D / (16 NW)
     uint32_t nblocks;
+    int32_t order;  // 0: launch order, 1: contiguous range of tiles per XCD
 };
 
 constexpr int kChunk = 32;
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
 
     // launch order: channel block fastest, so neighbouring workgroups read neighbouring 32*NW-byte
     // pieces of the same rows and the chip sweeps whole rows
-    const uint32_t lb = blockIdx.x;
+    const uint32_t lb = a.order ? xcd_contiguous(blockIdx.x, a.nblocks) : blockIdx.x;
     const int cb = lb % a.ncb;
     const int64_t tile = lb / a.ncb;
     const int64_t b = tile / a.tiles_per_seq;
@@ -79,24 +80,34 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
     // used for the k, v, q loads and the y store, all of them whole 32*NW-byte row pieces
     const int lr = tid / PPR, lp = tid % PPR;
     const int64_t ld_off = cblock0 + 8 * lp;
-    auto load_kvq = [&](int ci, Words<4>& kk, Words<4>& vv, Words<4>& qq) {
-        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-        const int64_t t = t0 + lr;
-        kk = zero_words<4>();
-        vv = zero_words<4>();
-        qq = zero_words<4>();
-        if (ci < nchunks && t < t_end) {
-            const int64_t off = seq0 + t * D + ld_off;
-            kk = load_words_nt<4>(a.k + off);
-            vv = load_words_nt<4>(a.v + off);
-            if (t0 >= t_start) qq = load_words_nt<4>(a.q + off);
-        }
+    // Every lane issues exactly three loads per chunk, with no control flow around them, so the loop keeps
+    // kPrefetch chunks in flight without ever draining the queue.  Addresses are clamped instead:
+    //  - rows past the end of the tile read the tile's last row (a source step >= t_end only reaches
+    //    outputs >= t_end, which are never stored);
+    //  - chunk indices past the last chunk re-read the last chunk (result unused);
+    //  - warm-up chunks, which need no q, read the q rows of the first real chunk (cache hits, unused).
+    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
+        const int cic = ci < nchunks ? ci : nchunks - 1;
+        int64_t t = t_begin + (int64_t)cic * kChunk + lr;
+        t = t < t_end ? t : t_end - 1;
+        kk = load_words_nt<4>(a.k + seq0 + t * D + ld_off);
+        vv = load_words_nt<4>(a.v + seq0 + t * D + ld_off);
+    };
+    auto load_q = [&](int ci, Words<4>& qq) {
+        const int cic = ci < nchunks ? ci : nchunks - 1;
+        const int64_t t0 = t_begin + (int64_t)cic * kChunk;
+        int64_t tq = (t0 >= t_start ? t0 : t_start) + lr;
+        tq = tq < t_end ? tq : t_end - 1;
+        qq = load_words_nt<4>(a.q + seq0 + tq * D + ld_off);
     };
 
     // start the first loads before anything else so their latency overlaps the filter set-up
     Words<4> kpre[kPrefetch], vpre[kPrefetch], qpre[kPrefetch];
 #pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) load_kvq(i, kpre[i], vpre[i], qpre[i]);
+    for (int i = 0; i < kPrefetch; ++i) {
+        load_kv(i, kpre[i], vpre[i]);
+        if (i + 1 < kPrefetch) load_q(i, qpre[i]);  // the last q stage is filled by the first iteration
+    }
 
     // ---- Toeplitz operands: operand i serves d = (output tile start) - (source block start) = 16 i; in it
     // lane (li = output step, lq = source octet), element e holds h[d + li - 8 lq - e] (zero outside
@@ -152,14 +163,16 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
         }
     };
 
-    Words<4> qhold = zero_words<4>();  // q of the previous chunk, whose z is gated one iteration late
+    // q of chunk c lives in register stage c % kPrefetch until chunk c is gated (one iteration after its
+    // MFMAs); only then is that stage refilled, so no loaded value is ever copied between registers.
+    // The chunk loop is unrolled by the prefetch depth so that register stages are addressed statically;
+    // iterations past the last chunk (at most kPrefetch-1) run empty but keep the barriers aligned.
     for (int base = 0; base < nchunks; base += kPrefetch) {
 #pragma unroll
         for (int sgi = 0; sgi < kPrefetch; ++sgi) {
             const int ci = base + sgi;
-            if (ci >= nchunks) break;
             const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-            const bool main_chunk = t0 >= t_start;
+            const bool main_chunk = t0 >= t_start && ci < nchunks;
 
             // u = k * v for this lane's 8 channels of one row -> bf16 -> LDS
             {
@@ -172,9 +185,8 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
                     uu.w[e2] = pack_bf16x2(kf[2 * e2] * vf[2 * e2], kf[2 * e2 + 1] * vf[2 * e2 + 1]);
                 stage[ci & 1][st_idx] = make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]);
             }
-            const Words<4> qcur = qpre[sgi];
             // refill this register stage with the chunk kPrefetch ahead
-            load_kvq(ci + kPrefetch, kpre[sgi], vpre[sgi], qpre[sgi]);
+            load_kv(ci + kPrefetch, kpre[sgi], vpre[sgi]);
 
             __syncthreads();  // u of this chunk and z of the previous chunk are now visible
 
@@ -206,17 +218,19 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
                 *reinterpret_cast<float4*>(zp) = make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
                 *reinterpret_cast<float4*>(zp + 16 * ZROW) = make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
             }
-            if (ci > 0) gate_store(ci - 1, qhold);
-            qhold = qcur;
+            const int prev = (sgi + kPrefetch - 1) % kPrefetch;  // static after unrolling
+            if (ci > 0 && ci <= nchunks) gate_store(ci - 1, qpre[prev]);
+            load_q(ci - 1 + kPrefetch, qpre[prev]);
         }
     }
-    __syncthreads();
-    gate_store(nchunks - 1, qhold);
+    if (nchunks % kPrefetch == 0) {  // the last chunk's z has not been gated inside the loop
+        __syncthreads();
+        gate_store(nchunks - 1, qpre[kPrefetch - 1]);
+    }
 }
 
-template <int NKB>
-hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
-    constexpr int NW = 4;
+template <int NKB, int NW>
+hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     constexpr int PF = NKB <= 5 ? 6 : (NKB <= 7 ? 4 : 3);
     MrArgs a;
     a.q = static_cast<const uint16_t*>(p.q);
@@ -231,9 +245,11 @@ hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.ncb = (int32_t)(s.D / (16 * NW));
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
-        // aim for ~4 workgroups per CU, but never tiles so short that the (NKB-1)*32-step halo dominates
-        const int64_t want = 256 * 4;
-        int64_t tiles = (want + s.B * a.ncb - 1) / (s.B * a.ncb);
+        // One workgroup per CU: measured on MI355X, few large workgroups that each stream a wide piece of
+        // every row beat many small ones, and each extra tile costs (NKB-1)*32 halo steps of k and v.
+        const int64_t want = 256;
+        int64_t tiles = want / (s.B * a.ncb);
+        if (tiles < 1) tiles = 1;
         rows = (s.L + tiles - 1) / tiles;
         const int64_t min_rows = 8LL * kChunk * (NKB > 1 ? NKB - 1 : 1);
         if (rows < min_rows) rows = min_rows;
@@ -245,8 +261,17 @@ hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
     a.nblocks = (uint32_t)nb;
+    a.order = tuning().mr_order;
     hipLaunchKernelGGL((mr_mfma_kernel<NKB, NW, PF>), dim3(a.nblocks), dim3(NW * 64), 0, st, a);
     return launch_status();
+}
+
+template <int NKB>
+hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
+    // 8 waves = 128 channels = 256-byte row pieces per workgroup when the width allows it
+    const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 8;
+    if (nw == 8 && s.D % 128 == 0) return launch_nkb_nw<NKB, 8>(p, s, st);
+    return launch_nkb_nw<NKB, 4>(p, s, st);
 }
 
 }  // namespace
