@@ -7,7 +7,7 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c1  Hyena-SE  bf16 B1 L8192   D4096 lh7            hyena_se_fwd            (default; the headline case)
   c2  Hyena-MR  bf16 B1 L8192   D4096 lh128 group16  hyena_mr_fwd
   c3  Hyena-MR  bf16 B1 L131072 D4096 lh128 group16  hyena_mr_fwd
-  c4  chain     bf16 B4 L32768  D4096                hyena_featurize3_fwd + hyena_mr_fwd
+  c4  chain     bf16 B4 L32768  D4096                hyena_chain_fwd (featurizers + MR in one kernel)
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
 Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded slice of the same workload.
@@ -60,7 +60,7 @@ class Workload:
         c = self.cfg
         self.n_out = c["B"] * c["L"] * c["D"]
         self.tokens = c["B"] * c["L"]
-        bytes_set = self.n_out * 2 * (4 if c["kind"] != "chain" else 7)
+        bytes_set = self.n_out * 2 * 4
         if nsets <= 0:
             nsets = max(1, min(6, int((1.5 * 2 ** 30) // bytes_set) + 1))
         self.host0 = None
@@ -72,11 +72,8 @@ class Workload:
             d = upload(w, torch)
             d["y"] = torch.empty_like(d["q"])
             if c["kind"] == "chain":
-                d["f"] = tuple(torch.empty_like(d["q"]) for _ in range(3))
-                self.pre.append(pkg.plan_featurize3(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"],
-                                                    c["feat_group"], out=d["f"]))
-                self.main.append(pkg.plan_gated("hyena_mr_fwd", d["f"][0], d["f"][1], d["f"][2], d["h"],
-                                                c["group"], out=d["y"]))
+                self.main.append(pkg.plan_chain(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"], d["h"],
+                                                c["group"], c["feat_group"], out=d["y"]))
             else:
                 entry = "hyena_se_fwd" if c["kind"] == "se" else "hyena_mr_fwd"
                 self.main.append(pkg.plan_gated(entry, d["q"], d["k"], d["v"], d["h"], c["group"], out=d["y"]))
@@ -128,7 +125,10 @@ class Workload:
         return 8.0 * self.n_out  # bf16: q, k, v read once, y written once
 
     def algo_flops(self):
-        return (2.0 * self.cfg["lh"] + 2.0) * self.n_out
+        f = 2.0 * self.cfg["lh"] + 2.0
+        if self.cfg["kind"] == "chain":
+            f += 3 * 2.0 * self.cfg["lf"]
+        return f * self.n_out
 
 
 def cpu_baseline(wl, target_s, np, oracle):
@@ -209,7 +209,7 @@ def main():
 
     wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup)
     cfg = wl.cfg
-    kernel = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_mr_fwd"}[cfg["kind"]]
+    kernel = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd"}[cfg["kind"]]
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -222,7 +222,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %s bf16 B=%d L=%d D=%d lh=%d group=%d" % (
-            args.workload, {"se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurize x3 + Hyena-MR"}[cfg["kind"]],
+            args.workload, {"se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,"}[cfg["kind"]],
             cfg["B"], cfg["L"], cfg["D"], cfg["lh"], cfg["group"]), "buffer_sets": res["sets"]},
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": res["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": res["hbm_gbs"] / HBM_PEAK_GBS, "traffic": traffic,

@@ -84,6 +84,30 @@ hy_status hyena_featurize3_fwd(const void *q, const void *k, const void *v, cons
                                hy_dtype dtype, void *hip_stream);
 
 /*
+ * The Hyena-MR operator chain of Sec. 2.1 Eq. 1 without its dense projections, forward:
+ *     q' = hq * q,  k' = hk * k,  v' = hv * v      (featurizers: lf taps, filters [D/feat_group, lf])
+ *     y[b,t,c] = q'[b,t,c] * sum_{j=0}^{min(lh-1,t)} h[c/group, j] * k'[b,t-j,c] * v'[b,t-j,c]
+ * For HY_BF16 with group a multiple of 16, D a multiple of 128, lh <= 129 and lf <= 8 this is ONE kernel:
+ * q, k, v are read once, y is written once, q', k', v' stay on chip in fp32 (u = k'v' is rounded once to
+ * bf16 for the matrix cores, y once at the store); `workspace` is not touched and may be NULL.
+ * Every other valid problem is run as hyena_featurize3_fwd into `workspace` followed by hyena_mr_fwd;
+ * `workspace` must then hold 3*B*L*D elements of `dtype` (16-byte aligned, disjoint from all other
+ * arguments), the featurized tensors are rounded to `dtype` there.  hyena_chain_workspace_bytes tells
+ * which case applies.  q,k,v,y: [B,L,D] of `dtype`; hq,hk,hv: fp32 [D/feat_group, lf]; h: fp32 [D/group, lh].
+ */
+hy_status hyena_chain_fwd(const void *q, const void *k, const void *v, const float *hq, const float *hk,
+                          const float *hv, const float *h, void *y, void *workspace, int64_t B, int64_t L,
+                          int64_t D, int32_t lf, int32_t feat_group, int32_t lh, int32_t group,
+                          hy_dtype dtype, void *hip_stream);
+
+/*
+ * Bytes of workspace hyena_chain_fwd needs for this problem: 0 when the single-kernel path applies,
+ * 3*B*L*D*sizeof(dtype) otherwise, -1 if the arguments are not a valid problem.  Host-only, no HIP call.
+ */
+int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group,
+                                    int32_t lh, int32_t group, hy_dtype dtype);
+
+/*
  * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16) with the same launch
  * shape as the streaming kernels.  Used to measure the practical HBM ceiling and to calibrate
  * hardware byte counters; not part of the operator.

@@ -6,8 +6,10 @@ benchmark inputs; ``build`` compiles the library.
 from .binding import (  # noqa: F401
     HyenaError,
     Plan,
+    plan_chain,
     plan_featurize3,
     plan_gated,
+    hyena_chain_fwd,
     hyena_featurize3_fwd,
     hyena_featurize_fwd,
     hyena_mr_fwd,

@@ -38,10 +38,13 @@ def lib() -> ctypes.CDLL:
         L.hyena_mr_fwd.argtypes = conv_args
         L.hyena_featurize_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_featurize3_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_chain_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, i32, i32, ci, vp]
+        L.hyena_chain_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, i32, i32, ci]
+        L.hyena_chain_workspace_bytes.restype = i64
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd",
-                     "hyena_stream_copy", "hyena_set_option"):
+                     "hyena_chain_fwd", "hyena_stream_copy", "hyena_set_option"):
             getattr(L, name).restype = ci
         L.hyena_status_string.argtypes = [ci]
         L.hyena_status_string.restype = ctypes.c_char_p
@@ -212,6 +215,51 @@ def hyena_featurize3_fwd(q, k, v, hq, hk, hv, group: int = 1, out=None, stream=N
     if rc != HY_OK:
         raise HyenaError(rc, "hyena_featurize3_fwd")
     return outs
+
+
+def _chain_args(q, k, v, hq, hk, hv, h, group, feat_group, out, workspace, stream):
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    lf = _check_filter("hq", hq, q, feat_group)
+    if _check_filter("hk", hk, q, feat_group) != lf or _check_filter("hv", hv, q, feat_group) != lf:
+        raise ValueError("the three featurizer filters must share one length")
+    lh = _check_filter("h", h, q, group)
+    y = torch.empty_like(q) if out is None else out
+    _check_act("out", y, q)
+    B, L, D = q.shape
+    need = int(lib().hyena_chain_workspace_bytes(B, L, D, lf, int(feat_group), lh, int(group), _dtype_code(q)))
+    if need < 0:
+        raise ValueError("not a valid chain problem")
+    if need > 0 and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)  # device memory from PyTorch
+    if need > 0 and (workspace.device != q.device or not workspace.is_contiguous()
+                     or workspace.numel() * workspace.element_size() < need):
+        raise ValueError("workspace must be a contiguous tensor of at least %d bytes on the same GPU" % need)
+    c = ctypes
+    ptrs = [t.data_ptr() for t in (q, k, v, hq, hk, hv, h, y)] + [workspace.data_ptr() if need > 0 else None]
+    args = tuple(c.c_void_p(p) for p in ptrs) + (c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lf),
+                                                  c.c_int32(int(feat_group)), c.c_int32(lh), c.c_int32(int(group)),
+                                                  c.c_int(_dtype_code(q)), c.c_void_p(_stream(q, stream)))
+    return args, (q, k, v, hq, hk, hv, h, y, workspace), y
+
+
+def hyena_chain_fwd(q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, out=None, workspace=None,
+                    stream=None) -> torch.Tensor:
+    """Featurize q, k, v and apply the gated medium convolution; see ``hyena_chain_fwd`` in hyena.h."""
+    args, _, y = _chain_args(q, k, v, hq, hk, hv, h, group, feat_group, out, workspace, stream)
+    with torch.cuda.device(q.device):
+        rc = lib().hyena_chain_fwd(*args)
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_chain_fwd")
+    return y
+
+
+def plan_chain(q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, out=None, workspace=None,
+               stream=None) -> Plan:
+    """Marshal one ``hyena_chain_fwd`` call for repeated issue."""
+    args, keep, y = _chain_args(q, k, v, hq, hk, hv, h, group, feat_group, out, workspace, stream)
+    return Plan(lib().hyena_chain_fwd, args, "hyena_chain_fwd", keep, y)
 
 
 def hyena_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.Tensor:

@@ -35,10 +35,12 @@ __global__ __launch_bounds__(kCopyBlock) void copy_kernel(const uint4* __restric
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-bool overlaps(const void* a, const void* b, int64_t bytes) {
+bool overlaps2(const void* a, int64_t abytes, const void* b, int64_t bbytes) {
     const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-    return x < y + (uintptr_t)bytes && y < x + (uintptr_t)bytes;
+    return x < y + (uintptr_t)bbytes && y < x + (uintptr_t)abytes;
 }
+
+bool overlaps(const void* a, const void* b, int64_t bytes) { return overlaps2(a, bytes, b, bytes); }
 
 // Checks shared by every convolution entry point.  `ins`/`outs` hold activation pointers.
 hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_out, const float* const* hs,
@@ -144,6 +146,57 @@ hy_status hyena_featurize3_fwd(const void* q, const void* k, const void* v, cons
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_stencil(p, 3, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(p, 3, s, st);
+    return rc;
+}
+
+int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh,
+                                    int32_t group, hy_dtype dtype) {
+    if (B < 0 || L < 0 || D < 0 || lf < 1 || lh < 1 || feat_group < 1 || group < 1) return -1;
+    if (D % group != 0 || D % feat_group != 0) return -1;
+    if (dtype != HY_F32 && dtype != HY_BF16) return -1;
+    ChainShape s{B, L, D, lf, feat_group, lh, group, dtype};
+    if (empty(B, L, D) || chain_fused_supported(s)) return 0;
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > INT64_MAX / (3 * esz)) return -1;
+    return 3 * B * L * D * esz;
+}
+
+hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const float* hq, const float* hk,
+                          const float* hv, const float* h, void* y, void* workspace, int64_t B, int64_t L, int64_t D,
+                          int32_t lf, int32_t feat_group, int32_t lh, int32_t group, hy_dtype dtype,
+                          void* hip_stream) {
+    const void* ins[3] = {q, k, v};
+    void* outs[1] = {y};
+    const float* hs[4] = {hq, hk, hv, h};
+    hy_status rc = validate(ins, 3, outs, 1, hs, 4, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (lf < 1 || feat_group < 1 || D % feat_group != 0) return HY_ERR_SHAPE;
+    if (empty(B, L, D)) return HY_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    ChainShape cs{B, L, D, lf, feat_group, lh, group, dtype};
+    if (chain_fused_supported(cs)) {
+        ChainPtrs cp{q, k, v, hq, hk, hv, h, y};
+        return launch_chain_fused(cp, cs, st);
+    }
+    // two-kernel path through the caller's workspace
+    if (!workspace) return HY_ERR_NULL;
+    if (!aligned16(workspace)) return HY_ERR_ALIGN;
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    const int64_t bytes = B * L * D * esz;
+    if (B * L * D > INT64_MAX / (3 * esz)) return HY_ERR_SHAPE;
+    const void* all[4] = {q, k, v, y};
+    for (int i = 0; i < 4; ++i)
+        if (overlaps2(all[i], bytes, workspace, 3 * bytes)) return HY_ERR_ALIGN;
+    char* ws = static_cast<char*>(workspace);
+    ConvPtrs f[3] = {{nullptr, q, nullptr, hq, ws}, {nullptr, k, nullptr, hk, ws + bytes}, {nullptr, v, nullptr, hv, ws + 2 * bytes}};
+    ConvShape fs{B, L, D, lf, feat_group, dtype, false};
+    rc = launch_stencil(f, 3, fs, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(f, 3, fs, st);
+    if (rc != HY_OK) return rc;
+    ConvPtrs m{ws, ws + bytes, ws + 2 * bytes, h, y};
+    ConvShape ms{B, L, D, lh, group, dtype, true};
+    rc = launch_mr_mfma(m, ms, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&m, 1, ms, st);
     return rc;
 }
 

@@ -23,6 +23,24 @@ struct ConvShape {
     bool gated;
 };
 
+// The operator chain: featurize q, k, v (filters hq, hk, hv), then the gated medium convolution with h.
+struct ChainPtrs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const float* hq;
+    const float* hk;
+    const float* hv;
+    const float* h;
+    void* y;
+};
+
+struct ChainShape {
+    int64_t B, L, D;
+    int32_t lf, feat_group, lh, group;
+    hy_dtype dtype;
+};
+
 struct Tuning {
     int se_vec = 0;
     int se_rows = 0;
@@ -38,6 +56,9 @@ hy_status launch_stencil(const ConvPtrs* p, int nprob, const ConvShape& s, hipSt
 hy_status launch_direct(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
 // Block-Toeplitz contraction on bf16 MFMA.  HY_ERR_UNSUPPORTED outside its domain.
 hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
+// Whole chain in one pass over q, k, v.  HY_ERR_UNSUPPORTED outside chain_fused_supported().
+bool chain_fused_supported(const ChainShape& s);
+hy_status launch_chain_fused(const ChainPtrs& p, const ChainShape& s, hipStream_t st);
 hy_status launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
 
 inline hy_status launch_status() { return hipGetLastError() == hipSuccess ? HY_OK : HY_ERR_LAUNCH; }

@@ -37,7 +37,8 @@ def test_library_exports_every_declared_symbol():
 def test_binding_exposes_the_same_names():
     import paper_2503_01868_amd as pkg
 
-    for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd", "hyena_stream_copy"):
+    for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd", "hyena_chain_fwd",
+                 "hyena_stream_copy"):
         assert callable(getattr(pkg, name))
 
 
@@ -119,3 +120,30 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 4, 8)
     with pytest.raises(ValueError):
         binding.hyena_se_fwd(x, x, x, torch.zeros(8, 3))
+
+
+def test_chain_entry_point_rejects_bad_arguments_and_sizes_its_workspace():
+    lib = binding.lib()
+
+    def ch(**kw):
+        a = dict(q=P[0], k=P[1], v=P[2], hq=P[3], hk=P[4], hv=P[5], h=P[6], y=P[7], ws=P[8],
+                 B=1, L=8, D=128, lf=7, fg=1, lh=128, group=16, dtype=1)
+        a.update(kw)
+        return lib.hyena_chain_fwd(*[a[n] for n in ("q", "k", "v", "hq", "hk", "hv", "h", "y", "ws", "B", "L", "D",
+                                                    "lf", "fg", "lh", "group", "dtype")], None)
+
+    assert ch(q=None) == 1 and ch(hv=None) == 1 and ch(h=None) == 1 and ch(y=None) == 1
+    assert ch(lf=0) == 2 and ch(fg=3) == 2 and ch(group=24) == 2 and ch(lh=0) == 2 and ch(dtype=9) == 3
+    assert ch(y=P[2]) == 4 and ch(hq=P[3] + 4) == 4
+    assert ch(B=0) == 0 and ch(L=0, ws=None) == 0
+    # problems outside the single-kernel domain need a workspace
+    assert ch(dtype=0, ws=None) == 1 and ch(D=64, group=16, ws=None) == 1 and ch(dtype=0, ws=P[8] + 2) == 4
+    assert ch(dtype=0, ws=P[0]) == 4  # workspace overlaps an input
+    wb = lib.hyena_chain_workspace_bytes
+    assert wb(4, 32768, 4096, 7, 1, 128, 16, 1) == 0
+    assert wb(1, 100, 64, 7, 1, 128, 16, 1) == 3 * 100 * 64 * 2
+    assert wb(1, 100, 128, 7, 1, 128, 16, 0) == 3 * 100 * 128 * 4
+    assert wb(1, 100, 128, 7, 1, 130, 16, 1) == 3 * 100 * 128 * 2
+    assert wb(1, 100, 128, 9, 1, 128, 16, 1) == 3 * 100 * 128 * 2
+    assert wb(1, 100, 128, 7, 1, 128, 24, 1) == -1 and wb(1, 100, 128, 0, 1, 128, 16, 1) == -1
+    assert wb(0, 100, 128, 7, 1, 128, 16, 0) == 0

@@ -233,3 +233,99 @@ def test_stream_copy_copies():
     binding.hyena_stream_copy(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+# ------------------------------------------------------------------------------- operator chain
+def draw_chain(seed, B, L, D, lf, feat_group, lh, group, dtype):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(3))
+    hq, hk, hv = (synth.short_filter(rng, D // feat_group, lf) for _ in range(3))
+    h = synth.decay_filter(rng, D // group, lh)
+    return q, k, v, hq, hk, hv, h
+
+
+def check_chain(seed, B, L, D, lf, feat_group, lh, group, dtype, expect_fused):
+    say("chain seed=%d B=%d L=%d D=%d lf=%d fg=%d lh=%d group=%d %s" % (seed, B, L, D, lf, feat_group, lh, group, dtype))
+    code = binding.HY_BF16 if dtype == "bf16" else binding.HY_F32
+    need = binding.lib().hyena_chain_workspace_bytes(B, L, D, lf, feat_group, lh, group, code)
+    assert (need == 0) == expect_fused
+    q, k, v, hq, hk, hv, h = draw_chain(seed, B, L, D, lf, feat_group, lh, group, dtype)
+    y = host(binding.hyena_chain_fwd(dev(q), dev(k), dev(v), dev(hq), dev(hk), dev(hv), dev(h), group, feat_group))
+    ref = oracle.chain(q, k, v, hq, hk, hv, h, group=group, feat_group=feat_group)
+    err = oracle.rel_err(y, ref)
+    assert np.isfinite(y).all() and err <= TOL[dtype], err
+    return err
+
+
+CHAIN_FUSED_CASES = [
+    # B, L, D, lf, feat_group, lh, group, mr_rows
+    (1, 512, 128, 7, 1, 128, 16, 0),
+    (2, 1000, 256, 7, 1, 128, 16, 256),   # several tiles: look-back chunk + warm-up chunks, ragged tail
+    (1, 333, 128, 7, 1, 128, 16, 32),     # one-chunk tiles
+    (2, 97, 128, 7, 1, 128, 16, 64),      # L < lh
+    (1, 1, 128, 7, 1, 128, 16, 0),
+    (1, 300, 128, 1, 1, 33, 16, 64),      # lf = 1: featurizer is a per-channel scale
+    (1, 450, 128, 8, 1, 65, 32, 96),      # longest fused featurizer
+    (1, 200, 128, 3, 1, 1, 128, 64),      # lh = 1, one inner filter for all channels
+    (3, 256, 384, 4, 1, 129, 16, 128),    # longest fused inner filter
+    (1, 700, 128, 7, 1, 7, 16, 128),
+    (1, 260, 256, 7, 2, 128, 16, 96),     # featurizer filters shared by channel pairs
+    (1, 2100, 128, 7, 1, 128, 16, 1024),
+]
+
+
+@pytest.mark.parametrize("case", CHAIN_FUSED_CASES)
+def test_chain_single_kernel_path_matches_oracle(case):
+    B, L, D, lf, fg, lh, group, rows = case
+    binding.set_option("mr_rows", rows)
+    check_chain(61, B, L, D, lf, fg, lh, group, "bf16", expect_fused=True)
+
+
+@pytest.mark.parametrize("case", [
+    (2, 200, 64, 7, 1, 128, 16, "bf16"),    # D below the 128-channel block
+    (1, 150, 128, 7, 1, 128, 16, "f32"),    # fp32
+    (1, 300, 128, 7, 1, 200, 16, "bf16"),   # inner filter longer than the fused kernel takes
+    (1, 120, 128, 12, 1, 64, 16, "bf16"),   # featurizer longer than the fused kernel takes
+    (1, 90, 96, 5, 3, 40, 8, "bf16"),       # small odd groups
+])
+def test_chain_two_kernel_path_matches_oracle(case):
+    B, L, D, lf, fg, lh, group, dtype = case
+    check_chain(62, B, L, D, lf, fg, lh, group, dtype, expect_fused=False)
+
+
+def test_chain_impulse_is_bit_exact():
+    """q = 1 through a delta featurizer, k = 1 through a delta featurizer, v = impulse through a dyadic
+    featurizer, dyadic inner filter: y is the convolution of the two filters, exactly representable."""
+    B, L, D, lf, lh, group = 1, 400, 128, 7, 128, 16
+    say("chain impulse")
+    binding.set_option("mr_rows", 128)
+    rng = np.random.Generator(np.random.PCG64(63))
+    delta = np.zeros((D, lf), dtype=np.float32)
+    delta[:, 0] = 1.0
+    hv = (rng.integers(-4, 5, size=(D, lf)) / 4.0).astype(np.float32)
+    h = ((rng.integers(-4, 5, size=(D // group, lh)) / 4.0) * (rng.random((D // group, lh)) < 0.2)).astype(np.float32)
+    one = torch.ones(B, L, D, dtype=torch.bfloat16)
+    v = torch.zeros(B, L, D, dtype=torch.bfloat16)
+    hits = [(0, 3, 0), (0, 130, 77), (0, 255, 127)]
+    for b, t0, c in hits:
+        v[b, t0, c] = 1.0
+    ref = oracle.chain(one, one, v, delta, delta, hv, h, group=group)
+    assert np.array_equal(ref, torch.from_numpy(ref).bfloat16().double().numpy())
+    y = host(binding.hyena_chain_fwd(dev(one), dev(one), dev(v), dev(delta), dev(delta), dev(hv), dev(h), group, 1))
+    assert np.array_equal(y, ref)
+
+
+def test_chain_guard_bands_and_determinism():
+    B, L, D = 2, 301, 128
+    say("chain guard bands")
+    q, k, v, hq, hk, hv, h = draw_chain(64, B, L, D, 7, 1, 128, 16, "bf16")
+    n = B * L * D
+    guard = 4096
+    buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    out = buf[guard:guard + n].view(B, L, D)
+    args = [dev(x) for x in (q, k, v, hq, hk, hv, h)]
+    binding.hyena_chain_fwd(*args, 16, 1, out=out)
+    again = binding.hyena_chain_fwd(*args, 16, 1)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all() and not torch.isnan(out).any()
+    assert torch.equal(out, again)
