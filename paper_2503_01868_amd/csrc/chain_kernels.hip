@@ -41,17 +41,20 @@ struct ChainArgs {
 };
 
 constexpr int kChunk = 32;
-constexpr int kNW = 8;            // waves per workgroup
-constexpr int kPPR = 2 * kNW;     // 16-byte pieces per 256-byte row piece
-constexpr int kRing = 3;          // chunks of raw q, k, v kept in LDS
-constexpr int kZRow = 16 * kNW * 4 + 16;
-constexpr int kSeg = kChunk / kNW;  // steps per column-layout lane
+constexpr int kRing = 3;   // chunk slots of raw q, k, v kept in LDS
+constexpr int kLook = 8;   // look-back rows stored in front of every slot (>= lf - 1)
+constexpr int kSlotRows = kLook + kChunk;
+constexpr int kSeg = 4;   // steps per column-layout lane: 8 segments per chunk
 
-template <int NKB, int LF, int PF>
+// kNW = waves per workgroup = 16-channel groups per workgroup (4 or 8)
+template <int NKB, int LF, int PF, int kNW>
 __global__ __launch_bounds__(kNW * 64, 2) void chain_mfma_kernel(ChainArgs a) {
+    constexpr int kPPR = 2 * kNW;              // 16-byte pieces per row piece
+    constexpr int kZRow = 16 * kNW * 4 + 16;   // bytes per staged row of z, padded
+    constexpr int kPairs = 8 * kNW;            // channel pairs per workgroup
     constexpr int kTaps = 32 * NKB;
-    static_assert(kSeg == 4 && LF >= 1 && LF <= 8, "column lanes own 4 steps and look back at most 7");
-    __shared__ uint4 raw[3][kRing * kChunk * kPPR];  // [tensor k,v,q][ring row][piece]
+    static_assert(kSeg == 4 && LF >= 1 && LF - 1 <= kLook, "column lanes own 4 steps and look back at most 7");
+    __shared__ uint4 raw[3][kRing * kSlotRows * kPPR];  // [tensor k,v,q][slot][look-back rows, chunk rows][piece]
     __shared__ uint4 ust[kChunk * kPPR];
     __shared__ __attribute__((aligned(16))) char zst[kChunk * kZRow];
     __shared__ float hs[kNW][kTaps];
@@ -81,24 +84,47 @@ __global__ __launch_bounds__(kNW * 64, 2) void chain_mfma_kernel(ChainArgs a) {
     const int64_t ld_off = cblock0 + 8 * lp;
     const int64_t lo_kv = (t_begin - 8 > 0) ? t_begin - 8 : 0;  // oldest k, v step ever read
     const int64_t lo_q = (t_start - 8 > 0) ? t_start - 8 : 0;   // oldest q step ever read
+    const uint32_t lane_off = (uint32_t)lr * (uint32_t)D + (uint32_t)(8 * lp);  // within a chunk, in elements
     auto load_raw = [&](int j, Words<4>& kk, Words<4>& vv, Words<4>& qq) {
         const int jc = j <= nch ? j : nch;
-        int64_t t = t_begin + (int64_t)(jc - 1) * kChunk + lr;
-        t = t < t_end ? t : t_end - 1;
-        const int64_t tk = t > lo_kv ? t : lo_kv;
-        const int64_t tq = t > lo_q ? t : lo_q;
-        kk = load_words_nt<4>(a.k + seq0 + tk * D + ld_off);
-        vv = load_words_nt<4>(a.v + seq0 + tk * D + ld_off);
-        qq = load_words_nt<4>(a.q + seq0 + tq * D + ld_off);
+        const int64_t tb = t_begin + (int64_t)(jc - 1) * kChunk;
+        // Only the addresses depend on the (uniform) case; the three loads themselves are unconditional.
+        int64_t ok_, oq_;
+        if (tb >= lo_kv && tb >= lo_q && tb + kChunk <= t_end) {
+            // interior chunk: one scalar base plus a fixed per-lane offset
+            ok_ = oq_ = seq0 + tb * D + cblock0 + lane_off;
+        } else {
+            int64_t t = tb + lr;
+            t = t < t_end ? t : t_end - 1;
+            ok_ = seq0 + (t > lo_kv ? t : lo_kv) * D + ld_off;
+            oq_ = seq0 + (t > lo_q ? t : lo_q) * D + ld_off;
+        }
+        kk = load_words_nt<4>(a.k + ok_);
+        vv = load_words_nt<4>(a.v + ok_);
+        qq = load_words_nt<4>(a.q + oq_);
     };
-    // steps before the start of the sequence are zeros (zero left padding of every batch item)
+    // Ring slot j % 3 holds chunk j behind kLook look-back rows (the last rows of chunk j - 1), so a featurizer
+    // window never straddles slots.  The writer of a chunk therefore also drops its last kLook rows into the
+    // look-back area of the next slot.  Steps before the start of the sequence are zeros (zero left padding
+    // of every batch item).
     auto ring_write = [&](int j, const Words<4>& kk, const Words<4>& vv, const Words<4>& qq) {
         const int64_t t = t_begin + (int64_t)(j - 1) * kChunk + lr;
-        const bool pad = t < 0;
-        const int idx = ((j % kRing) * kChunk + lr) * kPPR + lp;
-        raw[0][idx] = pad ? make_uint4(0, 0, 0, 0) : make_uint4(kk.w[0], kk.w[1], kk.w[2], kk.w[3]);
-        raw[1][idx] = pad ? make_uint4(0, 0, 0, 0) : make_uint4(vv.w[0], vv.w[1], vv.w[2], vv.w[3]);
-        raw[2][idx] = pad ? make_uint4(0, 0, 0, 0) : make_uint4(qq.w[0], qq.w[1], qq.w[2], qq.w[3]);
+        const bool pad = t < 0;  // only ever true in chunk 0 of a tile that starts the sequence
+        const uint4 k4 = pad ? make_uint4(0, 0, 0, 0) : make_uint4(kk.w[0], kk.w[1], kk.w[2], kk.w[3]);
+        const uint4 v4 = pad ? make_uint4(0, 0, 0, 0) : make_uint4(vv.w[0], vv.w[1], vv.w[2], vv.w[3]);
+        const uint4 q4 = pad ? make_uint4(0, 0, 0, 0) : make_uint4(qq.w[0], qq.w[1], qq.w[2], qq.w[3]);
+        const int slot = __builtin_amdgcn_readfirstlane(j % kRing);
+        const int idx = (slot * kSlotRows + kLook + lr) * kPPR + lp;
+        raw[0][idx] = k4;
+        raw[1][idx] = v4;
+        raw[2][idx] = q4;
+        if (lr >= kChunk - kLook) {  // whole waves
+            const int nslot = slot == kRing - 1 ? 0 : slot + 1;
+            const int nidx = (nslot * kSlotRows + lr - (kChunk - kLook)) * kPPR + lp;
+            raw[0][nidx] = k4;
+            raw[1][nidx] = v4;
+            raw[2][nidx] = q4;
+        }
     };
 
     Words<4> kpre[PF], vpre[PF], qpre[PF];
@@ -106,7 +132,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void chain_mfma_kernel(ChainArgs a) {
     for (int i = 0; i < PF; ++i) load_raw(i, kpre[i], vpre[i], qpre[i]);
 
     // ---- column layout: channels cblock0 + 2 cp, +1; steps 4 seg .. 4 seg + 3 of a chunk
-    const int cp = lane, seg = w;
+    const int cp = tid % kPairs, seg = tid / kPairs;
     float tk_[2][LF], tv_[2][LF], tq_[2][LF];
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
@@ -152,13 +178,12 @@ __global__ __launch_bounds__(kNW * 64, 2) void chain_mfma_kernel(ChainArgs a) {
     // One featurizer output set: x'[e][r] for channels e = 0, 1 and steps r = 0..3 of this lane, from the ring.
     auto featurize = [&](int tensor, int j, const float (&taps)[2][LF], float (&out)[2][4]) {
         const uint32_t* r32 = reinterpret_cast<const uint32_t*>(raw[tensor]);
+        const int slot = __builtin_amdgcn_readfirstlane(j % kRing);
+        const uint32_t* rp = r32 + (slot * kSlotRows + kLook + kSeg * seg - (LF - 1)) * (kPPR * 4) + cp;
         float win[2][LF - 1 + kSeg];
 #pragma unroll
         for (int i = 0; i < LF - 1 + kSeg; ++i) {
-            const int ro = kSeg * seg - (LF - 1) + i;  // row relative to the chunk, negative = previous chunk
-            const int jj = ro < 0 ? j - 1 : j;
-            const int row = (jj % kRing) * kChunk + (ro & (kChunk - 1));
-            const uint32_t pr = r32[row * (kPPR * 4) + cp];
+            const uint32_t pr = rp[i * (kPPR * 4)];
             win[0][i] = bf16_lo(pr);
             win[1][i] = bf16_hi(pr);
         }
@@ -263,8 +288,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void chain_mfma_kernel(ChainArgs a) {
     if (nch % PF == 0) gate_store(nch);  // otherwise an idle iteration of the unrolled loop already did it
 }
 
-template <int NKB, int LF>
-hy_status launch_chain(const ChainPtrs& p, const ChainShape& s, hipStream_t st) {
+template <int NKB, int LF, int kNW>
+hy_status launch_chain_nw(const ChainPtrs& p, const ChainShape& s, hipStream_t st) {
     constexpr int PF = 4;  // chunks of raw q, k, v in flight per lane; two waves per SIMD must fit
     ChainArgs a;
     a.q = static_cast<const uint16_t*>(p.q);
@@ -283,7 +308,7 @@ hy_status launch_chain(const ChainPtrs& p, const ChainShape& s, hipStream_t st) 
     a.ncb = (int32_t)(s.D / (16 * kNW));
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
-        const int64_t want = 256;  // one workgroup per CU
+        const int64_t want = 256 * (8 / kNW);  // 8 waves per CU
         int64_t tiles = want / (s.B * a.ncb);
         if (tiles < 1) tiles = 1;
         rows = (s.L + tiles - 1) / tiles;
@@ -296,8 +321,14 @@ hy_status launch_chain(const ChainPtrs& p, const ChainShape& s, hipStream_t st) 
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((chain_mfma_kernel<NKB, LF, PF>), dim3((uint32_t)nb), dim3(kNW * 64), 0, st, a);
+    hipLaunchKernelGGL((chain_mfma_kernel<NKB, LF, PF, kNW>), dim3((uint32_t)nb), dim3(kNW * 64), 0, st, a);
     return launch_status();
+}
+
+template <int NKB, int LF>
+hy_status launch_chain(const ChainPtrs& p, const ChainShape& s, hipStream_t st) {
+    if (tuning().mr_waves == 4) return launch_chain_nw<NKB, LF, 4>(p, s, st);
+    return launch_chain_nw<NKB, LF, 8>(p, s, st);
 }
 
 template <int NKB>
