@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle slice")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
+                    help="library tuning knob (hyena_set_option), may repeat; results never depend on these")
     ap.add_argument("--also", default="c2", help="comma list of further workloads to time briefly (c1 only)")
     return ap.parse_args()
 
@@ -203,6 +205,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    for item in args.opt:
+        name, value = item.split("=")
+        pkg.set_option(name, int(value))
     if args.workload == "copy":
         calibrate_copy(args, torch, pkg)
         return

@@ -118,7 +118,8 @@ hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip
  * Tuning knobs (process-wide, not thread-safe; 0 restores the built-in choice).  Names:
  *   "se_vec"   channels per lane in the SE / featurizer stencil (1, 2, 4 or 8)
  *   "se_rows"  time steps each lane walks (tile length in t)
- *   "mr_rows"  time steps per workgroup in the MR kernel (multiple of 32)
+ *   "mr_rows"  time steps per workgroup in the MR and chain kernels (multiple of 32)
+ *   "mr_waves" waves (= 16-channel groups) per workgroup in the MR and chain kernels (4, 8 or 16)
  * Unknown names return HY_ERR_UNSUPPORTED.  Results never depend on these, only speed.
  */
 hy_status hyena_set_option(const char *name, int32_t value);

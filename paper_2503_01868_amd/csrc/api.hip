@@ -17,9 +17,8 @@ constexpr int kCopyBlock = 256;
 constexpr int kCopyPerLane = 4;  // 16-byte words per lane
 
 __global__ __launch_bounds__(kCopyBlock) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                          int64_t n16, uint32_t nblocks) {
-    const uint32_t lb = xcd_contiguous(blockIdx.x, nblocks);
-    const int64_t base = (int64_t)lb * (kCopyBlock * kCopyPerLane) + threadIdx.x;
+                                                          int64_t n16) {
+    const int64_t base = (int64_t)blockIdx.x * (kCopyBlock * kCopyPerLane) + threadIdx.x;
     uint4 r[kCopyPerLane];
 #pragma unroll
     for (int i = 0; i < kCopyPerLane; ++i) {
@@ -210,7 +209,7 @@ hy_status hyena_stream_copy(const void* src, void* dst, int64_t bytes, void* hip
     const int64_t nb = (n16 + per_block - 1) / per_block;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)nb), dim3(kCopyBlock), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16, (uint32_t)nb);
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
     return launch_status();
 }
 
@@ -226,10 +225,8 @@ hy_status hyena_set_option(const char* name, int32_t value) {
     } else if (strcmp(name, "mr_rows") == 0) {
         if (value % 32 != 0) return HY_ERR_SHAPE;
         t.mr_rows = value;
-    } else if (strcmp(name, "mr_order") == 0) {
-        t.mr_order = value;
     } else if (strcmp(name, "mr_waves") == 0) {
-        if (value != 0 && value != 4 && value != 8) return HY_ERR_SHAPE;
+        if (value != 0 && value != 4 && value != 8 && value != 16) return HY_ERR_SHAPE;
         t.mr_waves = value;
     } else {
         return HY_ERR_UNSUPPORTED;

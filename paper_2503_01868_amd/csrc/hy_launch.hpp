@@ -45,7 +45,6 @@ struct Tuning {
     int se_vec = 0;
     int se_rows = 0;
     int mr_rows = 0;
-    int mr_order = 0;
     int mr_waves = 0;
 };
 Tuning& tuning();

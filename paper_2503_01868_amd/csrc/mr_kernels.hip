@@ -38,15 +38,13 @@ struct MrArgs {
     int32_t rows;           // time steps per workgroup, multiple of 32
     int32_t tiles_per_seq;  // ceil(L / rows)
     int32_t ncb;            // channel blocks = D / (16 NW)
-    uint32_t nblocks;
-    int32_t order;  // 0: launch order, 1: contiguous range of tiles per XCD
 };
 
 constexpr int kChunk = 32;
 
 // kPrefetch = chunks of k, v and q in flight per lane (registers).  Two waves per SIMD must fit.
 template <int NKB, int NW, int kPrefetch>
-__global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
+__global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void mr_mfma_kernel(MrArgs a) {
     constexpr int PPR = 2 * NW;              // 16-byte pieces per staged row of u (bf16)
     constexpr int kTaps = 32 * NKB;          // >= lh
     constexpr int ZROW = 16 * NW * 4 + 16;   // bytes per staged row of z (fp32), padded against bank conflicts
@@ -61,7 +59,7 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
 
     // launch order: channel block fastest, so neighbouring workgroups read neighbouring 32*NW-byte
     // pieces of the same rows and the chip sweeps whole rows
-    const uint32_t lb = a.order ? xcd_contiguous(blockIdx.x, a.nblocks) : blockIdx.x;
+    const uint32_t lb = blockIdx.x;
     const int cb = lb % a.ncb;
     const int64_t tile = lb / a.ncb;
     const int64_t b = tile / a.tiles_per_seq;
@@ -231,7 +229,7 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_mfma_kernel(MrArgs a) {
 
 template <int NKB, int NW>
 hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
-    constexpr int PF = NKB <= 5 ? 6 : (NKB <= 7 ? 4 : 3);
+    constexpr int PF = 2;  // chunks of k, v, q in flight per lane: measured best on MI355X (deeper queues ran slower)
     MrArgs a;
     a.q = static_cast<const uint16_t*>(p.q);
     a.k = static_cast<const uint16_t*>(p.k);
@@ -251,7 +249,7 @@ hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
         int64_t tiles = want / (s.B * a.ncb);
         if (tiles < 1) tiles = 1;
         rows = (s.L + tiles - 1) / tiles;
-        const int64_t min_rows = 8LL * kChunk * (NKB > 1 ? NKB - 1 : 1);
+        const int64_t min_rows = 4LL * kChunk * (NKB > 1 ? NKB - 1 : 1);
         if (rows < min_rows) rows = min_rows;
     }
     rows = (rows + kChunk - 1) / kChunk * kChunk;
@@ -260,17 +258,19 @@ hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    a.nblocks = (uint32_t)nb;
-    a.order = tuning().mr_order;
-    hipLaunchKernelGGL((mr_mfma_kernel<NKB, NW, PF>), dim3(a.nblocks), dim3(NW * 64), 0, st, a);
+    hipLaunchKernelGGL((mr_mfma_kernel<NKB, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), 0, st, a);
     return launch_status();
 }
 
 template <int NKB>
 hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
-    // 8 waves = 128 channels = 256-byte row pieces per workgroup when the width allows it
-    const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 8;
-    if (nw == 8 && s.D % 128 == 0) return launch_nkb_nw<NKB, 8>(p, s, st);
+    // Widest row piece per workgroup the width allows: 16 waves = 256 channels = 512 bytes of every row,
+    // then 8, then 4.  Measured on MI355X (L = 131072): 694 us with 16 waves against 787 us with 8.
+    const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 16;
+    if constexpr (NKB <= 5) {  // 16 waves only where the kernel fits 128 registers without spilling
+        if (nw == 16 && s.D % 256 == 0) return launch_nkb_nw<NKB, 16>(p, s, st);
+    }
+    if (nw >= 8 && s.D % 128 == 0) return launch_nkb_nw<NKB, 8>(p, s, st);
     return launch_nkb_nw<NKB, 4>(p, s, st);
 }
 

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("se_vec", "se_rows", "mr_rows"):
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves"):
         binding.set_option(name, 0)
 
 
@@ -112,6 +112,15 @@ def test_mr_matrix_core_path_matches_oracle(case):
     B, L, D, lh, group, rows = case
     binding.set_option("mr_rows", rows)
     check_gated("hyena_mr_fwd", 31, B, L, D, lh, group, "bf16", kind="mr")
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("case", [(2, 700, 512, 128, 16, 256), (1, 333, 256, 65, 32, 96), (1, 1500, 256, 128, 16, 0)])
+def test_mr_every_workgroup_width(case, waves):
+    B, L, D, lh, group, rows = case
+    binding.set_option("mr_waves", waves)
+    binding.set_option("mr_rows", rows)
+    check_gated("hyena_mr_fwd", 34, B, L, D, lh, group, "bf16", kind="mr")
 
 
 @pytest.mark.parametrize("case", [
