@@ -47,6 +47,7 @@ def _load():
         lib.oracle_gated_conv.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci]
         lib.oracle_gated_conv_points.argtypes = [vp, vp, vp, vp, vp, i64, vp] + [i64] * 5 + [ci, ci]
         lib.oracle_chain_points.argtypes = [vp] * 8 + [i64, vp] + [i64] * 7 + [ci, ci]
+        lib.oracle_gated_conv_bwd.argtypes = [vp] * 9 + [i64] * 5 + [ci, ci]
         _lib = lib
     return _lib
 
@@ -187,6 +188,25 @@ def chain_points(q, k, v, hq, hk, hv, h, pts, group: int = 1, feat_group: int = 
                                     _ptr(ha), _ptr(p), p.shape[0], _ptr(out), B, L, D, hqa.shape[1],
                                     feat_group, ha.shape[1], group, xd, hd), "oracle_chain_points")
     return out
+
+
+def gated_conv_bwd(dy, q, k, v, h, group: int = 1):
+    """Gradients of ``gated_conv`` w.r.t. q, k, v (each [B, L, D]) and h ([D // group, l_h]) given dy: the
+    chain rule of Eq. 1 / Eq. 2 written out in fp64.  Returns (dq, dk, dv, dh)."""
+    ga, gd = _arr(dy)
+    qa, qd = _arr(q)
+    ka, kd = _arr(k)
+    va, vd = _arr(v)
+    xd = _same(gd, qd, kd, vd)
+    if not (ga.shape == qa.shape == ka.shape == va.shape) or qa.ndim != 3:
+        raise ValueError("dy, q, k, v must share one [B, L, D] shape")
+    B, L, D = qa.shape
+    ha, hd = _filt(h, D // group if group > 0 and D % group == 0 else -1)
+    dq, dk, dv = (np.empty((B, L, D), dtype=np.float64) for _ in range(3))
+    dh = np.empty(ha.shape, dtype=np.float64)
+    _ok(_load().oracle_gated_conv_bwd(_ptr(ga), _ptr(qa), _ptr(ka), _ptr(va), _ptr(ha), _ptr(dq), _ptr(dk), _ptr(dv),
+                                      _ptr(dh), B, L, D, ha.shape[1], group, xd, hd), "oracle_gated_conv_bwd")
+    return dq, dk, dv, dh
 
 
 def rel_err(y, y_ref) -> float:

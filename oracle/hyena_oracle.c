@@ -201,3 +201,70 @@ int oracle_chain_points(const void *q, const void *k, const void *v, const void 
     }
     return 0;
 }
+
+/*
+ * Backward of oracle_gated_conv: gradients of  y = q (.) (h * (k (.) v))  (Eq. 1 last line, Eq. 2) with respect
+ * to q, k, v and h, given dy = dLoss/dy.  The paper describes its backward kernel only by structure (App. A.4:
+ * a first pass with the forward's blocking that also accumulates partial filter gradients, a second pass that
+ * reduces them); what it must compute is the chain rule of the forward definition, written out here term by
+ * term in fp64:
+ *     u = k*v,  z[t] = sum_j h[j] u[t-j]
+ *     dq[t] = dy[t] * z[t]
+ *     g[t]  = dy[t] * q[t]                               (= dLoss/dz)
+ *     du[s] = sum_{j<lh, s+j<L} h[j] * g[s+j]            (the transposed, anti-causal convolution)
+ *     dk[s] = du[s] * v[s],   dv[s] = du[s] * k[s]
+ *     dh[g', j] = sum_b sum_{c in group g'} sum_{t>=j} g[b,t,c] * u[b,t-j,c]
+ * dq, dk, dv: [B,L,D] fp64; dh: [D/dg, lh] fp64 (summed over batch, time and the channels of the group).
+ */
+int oracle_gated_conv_bwd(const void *dy, const void *q, const void *k, const void *v, const void *h,
+                          double *dq, double *dk, double *dv, double *dh, int64_t B, int64_t L, int64_t D,
+                          int64_t lh, int64_t dg, int x_dtype, int h_dtype)
+{
+    int rc = orc_check(q, k, v, B, L, D, lh, dg, x_dtype, h_dtype);
+    if (rc)
+        return rc;
+    if (!dy || !h || !dq || !dk || !dv || !dh)
+        return 1;
+    int64_t rows = B * L;
+    int64_t G = D / dg;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        int64_t b = r / L, t = r % L;
+        for (int64_t c = 0; c < D; ++c) {
+            int64_t g = c / dg;
+            size_t at = (size_t)(r * D + c);
+            /* dq: forward convolution value z[t] */
+            double z = 0.0;
+            for (int64_t j = 0; j < lh && j <= t; ++j) {
+                size_t src = (size_t)((b * L + (t - j)) * D + c);
+                z += orc_load(h, h_dtype, (size_t)(g * lh + j)) * (orc_load(k, x_dtype, src) * orc_load(v, x_dtype, src));
+            }
+            dq[at] = orc_load(dy, x_dtype, at) * z;
+            /* du at this position: taps reach forward in time */
+            double du = 0.0;
+            for (int64_t j = 0; j < lh && t + j < L; ++j) {
+                size_t fut = (size_t)((b * L + (t + j)) * D + c);
+                du += orc_load(h, h_dtype, (size_t)(g * lh + j)) * (orc_load(dy, x_dtype, fut) * orc_load(q, x_dtype, fut));
+            }
+            dk[at] = du * orc_load(v, x_dtype, at);
+            dv[at] = du * orc_load(k, x_dtype, at);
+        }
+    }
+    /* filter gradient: one (group, tap) at a time, plain triple sum */
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t g = 0; g < G; ++g) {
+        for (int64_t j = 0; j < lh; ++j) {
+            double s = 0.0;
+            for (int64_t b = 0; b < B; ++b)
+                for (int64_t c = g * dg; c < (g + 1) * dg; ++c)
+                    for (int64_t t = j; t < L; ++t) {
+                        size_t at = (size_t)((b * L + t) * D + c);
+                        size_t src = (size_t)((b * L + (t - j)) * D + c);
+                        s += (orc_load(dy, x_dtype, at) * orc_load(q, x_dtype, at)) *
+                             (orc_load(k, x_dtype, src) * orc_load(v, x_dtype, src));
+                    }
+            dh[(size_t)(g * lh + j)] = s;
+        }
+    }
+    return 0;
+}

@@ -1,0 +1,127 @@
+"""Pins for the backward oracle: it must be the gradient of the (already pinned) forward oracle.
+Checked by central finite differences, by the adjoint identity, by closed forms and against numpy
+correlations; none of these re-uses the backward formulas."""
+import numpy as np
+import pytest
+
+import oracle
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def loss(q, k, v, h, w, group):
+    return float(np.sum(w * oracle.gated_conv(q, k, v, h, group=group)))
+
+
+@pytest.mark.parametrize("B,L,D,lh,group", [(1, 9, 2, 3, 1), (2, 12, 4, 5, 2), (1, 7, 4, 9, 4), (1, 10, 2, 1, 1)])
+def test_matches_central_finite_differences(B, L, D, lh, group):
+    """The forward is multilinear in (q), (k), (v), (h) separately, so a central difference in one argument
+    is exact up to rounding."""
+    r = rng(B * 100 + L * 10 + lh)
+    q, k, v, w = (r.standard_normal((B, L, D)) for _ in range(4))
+    h = r.standard_normal((D // group, lh))
+    dq, dk, dv, dh = oracle.gated_conv_bwd(w, q, k, v, h, group=group)
+    eps = 1e-3
+    for name, arr, grad in (("q", q, dq), ("k", k, dk), ("v", v, dv), ("h", h, dh)):
+        num = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = arr[idx]
+            arr[idx] = old + eps
+            lp = loss(q, k, v, h, w, group)
+            arr[idx] = old - eps
+            lm = loss(q, k, v, h, w, group)
+            arr[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        np.testing.assert_allclose(grad, num, rtol=0, atol=1e-8, err_msg=name)
+
+
+def test_adjoint_identity():
+    """<dy, J_v . delta> = <J_v^T dy, delta> for the linear map v -> y, and likewise for k, q and h."""
+    r = rng(3)
+    B, L, D, lh, group = 2, 40, 6, 11, 3
+    q, k, v, dy = (r.standard_normal((B, L, D)) for _ in range(4))
+    h = r.standard_normal((D // group, lh))
+    dq, dk, dv, dh = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    zero = np.zeros((B, L, D))
+    for arr, grad, which in ((q, dq, "q"), (k, dk, "k"), (v, dv, "v")):
+        delta = r.standard_normal((B, L, D))
+        args = dict(q=q, k=k, v=v)
+        args[which] = delta
+        jd = oracle.gated_conv(args["q"], args["k"], args["v"], h, group=group)
+        assert abs(np.sum(dy * jd) - np.sum(grad * delta)) < 1e-9
+    dlt = r.standard_normal(h.shape)
+    assert abs(np.sum(dy * oracle.gated_conv(q, k, v, dlt, group=group)) - np.sum(dh * dlt)) < 1e-9
+    assert zero.shape == dq.shape
+
+
+def test_filter_gradient_is_a_correlation():
+    """dh[j] = sum_t g[t] u[t-j] with g = dy*q, u = k*v: numpy.correlate per channel, summed over the group."""
+    r = rng(4)
+    B, L, D, lh, group = 2, 50, 4, 8, 2
+    q, k, v, dy = (r.standard_normal((B, L, D)) for _ in range(4))
+    h = r.standard_normal((D // group, lh))
+    _, _, _, dh = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    g, u = dy * q, k * v
+    ref = np.zeros_like(dh)
+    for b in range(B):
+        for c in range(D):
+            full = np.correlate(g[b, :, c], u[b, :, c], mode="full")  # lag j at index L-1+j
+            ref[c // group] += full[L - 1:L - 1 + lh]
+    np.testing.assert_allclose(dh, ref, rtol=0, atol=1e-10)
+
+
+def test_input_gradients_against_numpy_convolutions():
+    r = rng(5)
+    L, D, lh = 33, 3, 6
+    q, k, v, dy = (r.standard_normal((1, L, D)) for _ in range(4))
+    h = r.standard_normal((D, lh))
+    dq, dk, dv, _ = oracle.gated_conv_bwd(dy, q, k, v, h)
+    for c in range(D):
+        z = np.convolve(k[0, :, c] * v[0, :, c], h[c])[:L]
+        np.testing.assert_allclose(dq[0, :, c], dy[0, :, c] * z, rtol=0, atol=1e-12)
+        g = dy[0, :, c] * q[0, :, c]
+        du = np.convolve(g[::-1], h[c])[:L][::-1]  # anti-causal = causal on the reversed signal
+        np.testing.assert_allclose(dk[0, :, c], du * v[0, :, c], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(dv[0, :, c], du * k[0, :, c], rtol=0, atol=1e-12)
+
+
+def test_closed_form_length_one_filter():
+    r = rng(6)
+    q, k, v, dy = (r.standard_normal((2, 8, 3)) for _ in range(4))
+    h = r.standard_normal((3, 1))
+    dq, dk, dv, dh = oracle.gated_conv_bwd(dy, q, k, v, h)
+    np.testing.assert_allclose(dq, dy * h[:, 0] * k * v, rtol=1e-14)
+    np.testing.assert_allclose(dk, dy * q * h[:, 0] * v, rtol=1e-14)
+    np.testing.assert_allclose(dv, dy * q * h[:, 0] * k, rtol=1e-14)
+    np.testing.assert_allclose(dh[:, 0], np.sum(dy * q * k * v, axis=(0, 1)), rtol=1e-13)
+
+
+def test_anti_causality_of_input_gradients():
+    """dk[s], dv[s] depend on dy and q only at times >= s, and on nothing before s."""
+    r = rng(7)
+    B, L, D, lh, s = 1, 40, 2, 7, 20
+    q, k, v, dy = (r.standard_normal((B, L, D)) for _ in range(4))
+    h = r.standard_normal((D, lh))
+    _, dk0, dv0, _ = oracle.gated_conv_bwd(dy, q, k, v, h)
+    dy2, q2 = dy.copy(), q.copy()
+    dy2[:, :s] = r.standard_normal((B, s, D))
+    q2[:, :s] = r.standard_normal((B, s, D))
+    _, dk1, dv1, _ = oracle.gated_conv_bwd(dy2, q2, k, v, h)
+    assert np.array_equal(dk0[:, s:], dk1[:, s:]) and np.array_equal(dv0[:, s:], dv1[:, s:])
+    assert not np.array_equal(dk0[:, :s], dk1[:, :s])
+
+
+def test_batch_and_group_sums_in_filter_gradient():
+    r = rng(8)
+    L, D, lh, group = 20, 4, 5, 2
+    q, k, v, dy = (r.standard_normal((3, L, D)) for _ in range(4))
+    h = r.standard_normal((D // group, lh))
+    _, _, _, dh = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    per_item = sum(oracle.gated_conv_bwd(dy[b:b + 1], q[b:b + 1], k[b:b + 1], v[b:b + 1], h, group=group)[3] for b in range(3))
+    np.testing.assert_allclose(dh, per_item, rtol=0, atol=1e-12)
+    per_chan = oracle.gated_conv_bwd(dy, q, k, v, np.repeat(h, group, axis=0), group=1)[3]
+    np.testing.assert_allclose(dh, per_chan.reshape(D // group, group, lh).sum(axis=1), rtol=0, atol=1e-12)
