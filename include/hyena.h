@@ -108,6 +108,36 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
                                     int32_t lh, int32_t group, hy_dtype dtype);
 
 /*
+ * Backward of hyena_se_fwd / hyena_mr_fwd: gradients of y = q (.) (h * (k (.) v)) given dy = dLoss/dy.
+ * With u = k*v, z = h * u (the forward sum of Sec. 3.1 Eq. 2) and g = dy*q:
+ *     dq[b,t,c] = dy[b,t,c] * z[b,t,c]
+ *     du[b,s,c] = sum_{j<lh, s+j<L} h[c/group, j] * g[b,s+j,c]
+ *     dk = du * v,   dv = du * k
+ *     dh[G,j]   = sum_b sum_{c in group G} sum_{t>=j} g[b,t,c] * u[b,t-j,c]
+ * Structure as in the paper's backward (App. A.4, two passes): the main kernel produces dq, dk, dv and one
+ * partial filter gradient per tile, written contiguously into `workspace`; a second kernel reduces them into dh.
+ * dy,q,k,v,dq,dk,dv: [B,L,D] of `dtype`; h: fp32 [D/group, lh]; dh: fp32 [D/group, lh], overwritten.
+ * `workspace` must hold hyena_bwd_workspace_bytes(...) bytes (16-byte aligned, disjoint from every other
+ * argument; may be NULL when that is 0); it is scratch, its contents after the call are unspecified.
+ * Arithmetic is fp32 throughout with one rounding per stored element; dh is summed in fp32, first within a
+ * tile in time order, then over tiles and channels in index order (deterministic, no atomics).
+ * Short filters (lh <= 8) run a fused streaming stencil; everything else runs a general kernel.
+ * hyena_se_bwd and hyena_mr_bwd are the same operation and differ only in which shapes they are tuned for.
+ */
+hy_status hyena_se_bwd(const void *dy, const void *q, const void *k, const void *v, const float *h, void *dq,
+                       void *dk, void *dv, float *dh, void *workspace, int64_t workspace_bytes, int64_t B,
+                       int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void *hip_stream);
+hy_status hyena_mr_bwd(const void *dy, const void *q, const void *k, const void *v, const float *h, void *dq,
+                       void *dk, void *dv, float *dh, void *workspace, int64_t workspace_bytes, int64_t B,
+                       int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void *hip_stream);
+
+/*
+ * Bytes of workspace the backward entry points need for this problem under the current tuning options
+ * (0 for shapes served by the general kernel), -1 if the arguments are not a valid problem.  Host-only.
+ */
+int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype);
+
+/*
  * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16) with the same launch
  * shape as the streaming kernels.  Used to measure the practical HBM ceiling and to calibrate
  * hardware byte counters; not part of the operator.

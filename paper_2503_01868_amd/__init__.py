@@ -12,7 +12,9 @@ from .binding import (  # noqa: F401
     hyena_chain_fwd,
     hyena_featurize3_fwd,
     hyena_featurize_fwd,
+    hyena_mr_bwd,
     hyena_mr_fwd,
+    hyena_se_bwd,
     hyena_se_fwd,
     hyena_stream_copy,
     set_option,

@@ -41,10 +41,15 @@ def lib() -> ctypes.CDLL:
         L.hyena_chain_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, i32, i32, ci, vp]
         L.hyena_chain_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, i32, i32, ci]
         L.hyena_chain_workspace_bytes.restype = i64
+        bwd_args = [vp] * 10 + [i64, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_se_bwd.argtypes = bwd_args
+        L.hyena_mr_bwd.argtypes = bwd_args
+        L.hyena_bwd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
+        L.hyena_bwd_workspace_bytes.restype = i64
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd",
-                     "hyena_chain_fwd", "hyena_stream_copy", "hyena_set_option"):
+                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_stream_copy", "hyena_set_option"):
             getattr(L, name).restype = ci
         L.hyena_status_string.argtypes = [ci]
         L.hyena_status_string.restype = ctypes.c_char_p
@@ -260,6 +265,42 @@ def plan_chain(q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, out
     """Marshal one ``hyena_chain_fwd`` call for repeated issue."""
     args, keep, y = _chain_args(q, k, v, hq, hk, hv, h, group, feat_group, out, workspace, stream)
     return Plan(lib().hyena_chain_fwd, args, "hyena_chain_fwd", keep, y)
+
+
+def _bwd(entry: str, dy, q, k, v, h, group, workspace, stream):
+    _check_act("dy", dy)
+    _check_act("q", q, dy)
+    _check_act("k", k, dy)
+    _check_act("v", v, dy)
+    lh = _check_filter("h", h, dy, group)
+    B, L, D = dy.shape
+    code = _dtype_code(dy)
+    need = int(lib().hyena_bwd_workspace_bytes(B, L, D, lh, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid backward problem")
+    if need > 0 and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dy.device)  # device memory from PyTorch
+    ws_ptr = workspace.data_ptr() if workspace is not None and workspace.numel() > 0 else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    dq, dk, dv = (torch.empty_like(dy) for _ in range(3))
+    dh = torch.empty_like(h)
+    with torch.cuda.device(dy.device):
+        rc = getattr(lib(), entry)(dy.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), h.data_ptr(), dq.data_ptr(),
+                                   dk.data_ptr(), dv.data_ptr(), dh.data_ptr(), ws_ptr, ws_bytes, B, L, D, lh,
+                                   int(group), code, _stream(dy, stream))
+    if rc != HY_OK:
+        raise HyenaError(rc, entry)
+    return dq, dk, dv, dh
+
+
+def hyena_se_bwd(dy, q, k, v, h, group: int = 1, workspace=None, stream=None):
+    """(dq, dk, dv, dh) of ``hyena_se_fwd``; see ``hyena_se_bwd`` in hyena.h."""
+    return _bwd("hyena_se_bwd", dy, q, k, v, h, group, workspace, stream)
+
+
+def hyena_mr_bwd(dy, q, k, v, h, group: int = 16, workspace=None, stream=None):
+    """(dq, dk, dv, dh) of ``hyena_mr_fwd``; see ``hyena_mr_bwd`` in hyena.h."""
+    return _bwd("hyena_mr_bwd", dy, q, k, v, h, group, workspace, stream)
 
 
 def hyena_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.Tensor:

@@ -199,6 +199,59 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
     return rc;
 }
 
+int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype) {
+    if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1 || D % group != 0) return -1;
+    if (dtype != HY_F32 && dtype != HY_BF16) return -1;
+    if (empty(B, L, D)) return 0;
+    BwdShape s{B, L, D, lh, group, dtype};
+    return bwd_stencil_supported(s) ? bwd_stencil_workspace_bytes(s) : 0;
+}
+
+static hy_status gated_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,
+                           void* dk, void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B,
+                           int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+    const void* ins[4] = {dy, q, k, v};
+    void* outs[3] = {dq, dk, dv};
+    const float* hs[2] = {h, dh};
+    hy_status rc = validate(ins, 4, outs, 3, hs, 2, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (workspace_bytes < 0) return HY_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t nh = (D / group) * (int64_t)lh * (int64_t)sizeof(float);
+    if (overlaps2(h, nh, dh, nh)) return HY_ERR_ALIGN;
+    if (empty(B, L, D)) {
+        // an empty batch has a zero filter gradient
+        return launch_bwd_zero_dh(dh, D, lh, group, st);
+    }
+    BwdPtrs p{dy, q, k, v, h, dq, dk, dv, dh};
+    BwdShape s{B, L, D, lh, group, dtype};
+    if (bwd_stencil_supported(s)) {
+        const int64_t need = bwd_stencil_workspace_bytes(s);
+        if (!workspace) return HY_ERR_NULL;
+        if (!aligned16(workspace)) return HY_ERR_ALIGN;
+        if (workspace_bytes < need) return HY_ERR_SHAPE;
+        const int64_t bytes = B * L * D * (dtype == HY_F32 ? 4 : 2);
+        const void* all[7] = {dy, q, k, v, dq, dk, dv};
+        for (int i = 0; i < 7; ++i)
+            if (overlaps2(all[i], bytes, workspace, need)) return HY_ERR_ALIGN;
+        if (overlaps2(h, nh, workspace, need) || overlaps2(dh, nh, workspace, need)) return HY_ERR_ALIGN;
+        return launch_bwd_stencil(p, s, workspace, st);
+    }
+    return launch_bwd_direct(p, s, st);
+}
+
+hy_status hyena_se_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq, void* dk,
+                       void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D,
+                       int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+    return gated_bwd(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype, hip_stream);
+}
+
+hy_status hyena_mr_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq, void* dk,
+                       void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D,
+                       int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+    return gated_bwd(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype, hip_stream);
+}
+
 hy_status hyena_stream_copy(const void* src, void* dst, int64_t bytes, void* hip_stream) {
     if (!src || !dst) return HY_ERR_NULL;
     if (bytes < 0 || bytes % 16 != 0) return HY_ERR_SHAPE;

@@ -41,6 +41,25 @@ struct ChainShape {
     hy_dtype dtype;
 };
 
+// Backward of the gated convolution.
+struct BwdPtrs {
+    const void* dy;
+    const void* q;
+    const void* k;
+    const void* v;
+    const float* h;
+    void* dq;
+    void* dk;
+    void* dv;
+    float* dh;  // [D/group, lh] fp32, overwritten
+};
+
+struct BwdShape {
+    int64_t B, L, D;
+    int32_t lh, group;
+    hy_dtype dtype;
+};
+
 struct Tuning {
     int se_vec = 0;
     int se_rows = 0;
@@ -58,6 +77,14 @@ hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // Whole chain in one pass over q, k, v.  HY_ERR_UNSUPPORTED outside chain_fused_supported().
 bool chain_fused_supported(const ChainShape& s);
 hy_status launch_chain_fused(const ChainPtrs& p, const ChainShape& s, hipStream_t st);
+// Backward, short filters: fused streaming pass + reduction of partial filter gradients held in `ws`.
+bool bwd_stencil_supported(const BwdShape& s);
+int64_t bwd_stencil_workspace_bytes(const BwdShape& s);
+hy_status launch_bwd_stencil(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
+// Backward, any shape (no workspace).
+hy_status launch_bwd_direct(const BwdPtrs& p, const BwdShape& s, hipStream_t st);
+// dh := 0 (the filter gradient of an empty batch).
+hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st);
 hy_status launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
 
 inline hy_status launch_status() { return hipGetLastError() == hipSuccess ? HY_OK : HY_ERR_LAUNCH; }

@@ -38,7 +38,7 @@ def test_binding_exposes_the_same_names():
     import paper_2503_01868_amd as pkg
 
     for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd", "hyena_chain_fwd",
-                 "hyena_stream_copy"):
+                 "hyena_se_bwd", "hyena_mr_bwd", "hyena_stream_copy"):
         assert callable(getattr(pkg, name))
 
 
@@ -147,3 +147,27 @@ def test_chain_entry_point_rejects_bad_arguments_and_sizes_its_workspace():
     assert wb(1, 100, 128, 9, 1, 128, 16, 1) == 3 * 100 * 128 * 2
     assert wb(1, 100, 128, 7, 1, 128, 24, 1) == -1 and wb(1, 100, 128, 0, 1, 128, 16, 1) == -1
     assert wb(0, 100, 128, 7, 1, 128, 16, 0) == 0
+
+
+def test_backward_entry_points_reject_bad_arguments_and_size_their_workspace():
+    lib = binding.lib()
+    Q = [0x100000 * (i + 1) for i in range(11)]
+
+    def bw(entry="hyena_se_bwd", **kw):
+        a = dict(dy=Q[0], q=Q[1], k=Q[2], v=Q[3], h=Q[4], dq=Q[5], dk=Q[6], dv=Q[7], dh=Q[8], ws=Q[9], wsb=1 << 19,
+                 B=1, L=8, D=16, lh=3, group=1, dtype=1)
+        a.update(kw)
+        return getattr(lib, entry)(*[a[n] for n in ("dy", "q", "k", "v", "h", "dq", "dk", "dv", "dh", "ws", "wsb",
+                                                    "B", "L", "D", "lh", "group", "dtype")], None)
+
+    for entry in ("hyena_se_bwd", "hyena_mr_bwd"):
+        for name in ("dy", "q", "k", "v", "h", "dq", "dk", "dv", "dh"):
+            assert bw(entry, **{name: None}) == 1
+        assert bw(entry, lh=0) == 2 and bw(entry, group=3) == 2 and bw(entry, dtype=4) == 3 and bw(entry, wsb=-1) == 2
+        assert bw(entry, dq=Q[1]) == 4 and bw(entry, dk=Q[5]) == 4 and bw(entry, dh=Q[4]) == 4 and bw(entry, dv=Q[7] + 2) == 4
+        assert bw(entry, ws=None) == 1 and bw(entry, wsb=16) == 2 and bw(entry, ws=Q[9] + 4) == 4 and bw(entry, ws=Q[0]) == 4
+    wb = lib.hyena_bwd_workspace_bytes
+    assert wb(1, 8, 16, 3, 1, 1) == 1 * 1 * 16 * 3 * 4        # one tile
+    assert wb(2, 1000, 256, 7, 1, 1) % (256 * 7 * 4) == 0 and wb(2, 1000, 256, 7, 1, 1) > 0
+    assert wb(1, 100, 64, 128, 16, 1) == 0                      # general kernel: no workspace
+    assert wb(0, 100, 64, 7, 1, 1) == 0 and wb(1, 100, 64, 0, 1, 1) == -1 and wb(1, 100, 64, 7, 5, 1) == -1

@@ -1,0 +1,108 @@
+"""GPU parity of the backward entry points against the fp64 backward oracle (itself pinned by finite
+differences of the forward oracle), element by element on identical seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_01868_amd import binding, synth
+
+from gpu_util import TOL, dev, host, say
+
+pytestmark = pytest.mark.gpu
+
+# dh is an fp32 sum over B*L*group products and is returned in fp32 for both storage types: its error is
+# accumulation rounding only (~sqrt(n) * 2^-24 relative to the sum's scale)
+DH_TOL = 2e-5
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    yield
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves"):
+        binding.set_option(name, 0)
+
+
+def draw(seed, B, L, D, lh, group, dtype, kind):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    dy, q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(4))
+    n = D // group
+    h = synth.short_filter(rng, n, lh) if kind == "se" else synth.decay_filter(rng, n, lh)
+    return dy, q, k, v, h
+
+
+def check(entry, seed, B, L, D, lh, group, dtype, kind="se", expect_ws=None):
+    say("%s seed=%d B=%d L=%d D=%d lh=%d group=%d %s" % (entry, seed, B, L, D, lh, group, dtype))
+    dy, q, k, v, h = draw(seed, B, L, D, lh, group, dtype, kind)
+    code = binding.HY_BF16 if dtype == "bf16" else binding.HY_F32
+    need = binding.lib().hyena_bwd_workspace_bytes(B, L, D, lh, group, code)
+    if expect_ws is not None:
+        assert (need > 0) == expect_ws
+    outs = getattr(binding, entry)(dev(dy), dev(q), dev(k), dev(v), dev(h), group)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for name, got, want, tol in zip(("dq", "dk", "dv", "dh"), outs, ref, (TOL[dtype],) * 3 + (DH_TOL,)):
+        g = host(got)
+        assert np.isfinite(g).all(), name
+        err = oracle.rel_err(g, want)
+        assert err <= tol, (name, err)
+
+
+STENCIL_CASES = [
+    (1, 1024, 256, 7, 1), (2, 777, 512, 7, 1), (3, 100, 264, 4, 1), (1, 5, 64, 7, 1), (1, 1, 8, 3, 1),
+    (2, 333, 96, 1, 1), (2, 400, 128, 8, 4), (1, 300, 100, 5, 2), (2, 129, 64, 2, 64), (1, 513, 256, 3, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", STENCIL_CASES)
+def test_short_filter_backward_matches_oracle(case, dtype):
+    B, L, D, lh, group = case
+    check("hyena_se_bwd", 71, B, L, D, lh, group, dtype, expect_ws=True)
+
+
+@pytest.mark.parametrize("rows", [1, 5, 32, 1000])
+def test_short_filter_backward_every_tile_length(rows):
+    binding.set_option("se_rows", rows)
+    for dtype in ("f32", "bf16"):
+        check("hyena_se_bwd", 72, 2, 203, 192, 7, 1, dtype)
+
+
+@pytest.mark.parametrize("case", [
+    (1, 300, 64, 128, 16, "bf16"), (2, 130, 64, 128, 16, "f32"), (1, 200, 40, 50, 1, "bf16"),
+    (2, 150, 72, 13, 1, "f32"), (1, 90, 48, 40, 8, "bf16"), (1, 64, 33, 3, 1, "bf16"),  # odd D: general kernel
+])
+def test_general_backward_matches_oracle(case):
+    B, L, D, lh, group, dtype = case
+    check("hyena_mr_bwd", 73, B, L, D, lh, group, dtype, kind="mr")
+
+
+def test_backward_of_a_linear_loss_equals_forward_value():
+    """sum(dy * y) = sum(dq * q) = sum(dk * k) = sum(dv * v) = sum(dh * h): y is linear in each of q, k, v, h."""
+    B, L, D, lh = 2, 300, 128, 7
+    say("euler identity")
+    dy, q, k, v, h = draw(74, B, L, D, lh, 1, "f32", "se")
+    y = host(binding.hyena_se_fwd(dev(q), dev(k), dev(v), dev(h), 1))
+    dq, dk, dv, dh = (host(t) for t in binding.hyena_se_bwd(dev(dy), dev(q), dev(k), dev(v), dev(h), 1))
+    total = float(np.sum(dy.double().numpy() * y))
+    scale = float(np.sum(np.abs(dy.double().numpy() * y)))
+    for grad, arg in ((dq, q), (dk, k), (dv, v)):
+        assert abs(float(np.sum(grad * arg.double().numpy())) - total) <= 1e-5 * scale
+    assert abs(float(np.sum(dh * h.astype(np.float64))) - total) <= 1e-5 * scale
+
+
+def test_backward_guard_bands_determinism_and_empty_batch():
+    B, L, D, lh = 2, 301, 128, 7
+    say("bwd guard bands")
+    dy, q, k, v, h = draw(75, B, L, D, lh, 1, "bf16", "se")
+    args = [dev(x) for x in (dy, q, k, v, h)]
+    a = binding.hyena_se_bwd(*args, 1)
+    b = binding.hyena_se_bwd(*args, 1)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    # L = 0: nothing to do, dh must come back as zeros
+    dh = torch.full_like(args[4], 7.0)
+    ptr = [t.data_ptr() for t in args[:4]] + [args[4].data_ptr()] + [t.data_ptr() for t in a[:3]] + [dh.data_ptr()]
+    rc = binding.lib().hyena_se_bwd(*ptr, None, 0, B, 0, D, lh, 1, binding.HY_BF16, None)
+    torch.cuda.synchronize()
+    assert rc == 0 and torch.count_nonzero(dh) == 0
