@@ -204,7 +204,9 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
     if (empty(B, L, D)) return 0;
     BwdShape s{B, L, D, lh, group, dtype};
-    return bwd_stencil_supported(s) ? bwd_stencil_workspace_bytes(s) : 0;
+    if (bwd_stencil_supported(s)) return bwd_stencil_workspace_bytes(s);
+    if (mr_bwd_supported(s)) return mr_bwd_workspace_bytes(s);
+    return 0;
 }
 
 static hy_status gated_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,
@@ -225,8 +227,10 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
     }
     BwdPtrs p{dy, q, k, v, h, dq, dk, dv, dh};
     BwdShape s{B, L, D, lh, group, dtype};
-    if (bwd_stencil_supported(s)) {
-        const int64_t need = bwd_stencil_workspace_bytes(s);
+    const bool stencil = bwd_stencil_supported(s);
+    const bool mfma = !stencil && mr_bwd_supported(s);
+    if (stencil || mfma) {
+        const int64_t need = stencil ? bwd_stencil_workspace_bytes(s) : mr_bwd_workspace_bytes(s);
         if (!workspace) return HY_ERR_NULL;
         if (!aligned16(workspace)) return HY_ERR_ALIGN;
         if (workspace_bytes < need) return HY_ERR_SHAPE;
@@ -235,7 +239,13 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
         for (int i = 0; i < 7; ++i)
             if (overlaps2(all[i], bytes, workspace, need)) return HY_ERR_ALIGN;
         if (overlaps2(h, nh, workspace, need) || overlaps2(dh, nh, workspace, need)) return HY_ERR_ALIGN;
-        return launch_bwd_stencil(p, s, workspace, st);
+        if (stencil) return launch_bwd_stencil(p, s, workspace, st);
+        // medium grouped filters: dq is the forward operator applied to (dy, k, v); then dk, dv, dh
+        ConvPtrs f{dy, k, v, h, dq};
+        ConvShape fs{B, L, D, lh, group, dtype, true};
+        rc = launch_mr_mfma(f, fs, st);
+        if (rc != HY_OK) return rc;
+        return launch_mr_bwd(p, s, workspace, st);
     }
     return launch_bwd_direct(p, s, st);
 }

@@ -420,6 +420,15 @@ hy_status launch_bwd_stencil(const BwdPtrs& p, const BwdShape& s, void* ws, hipS
     return s.dtype == HY_BF16 ? launch_stencil_t<BF16>(p, s, ws, st) : launch_stencil_t<F32>(p, s, ws, st);
 }
 
+hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64_t n_rows, int32_t lh, int32_t group,
+                           hipStream_t st) {
+    const int64_t nout = (n_rows / group) * lh;
+    if (nout == 0) return HY_OK;
+    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, partial, dh,
+                       nsets, n_rows, lh, group);
+    return launch_status();
+}
+
 hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st) {
     const int64_t nout = (D / group) * lh;
     if (nout == 0) return HY_OK;

@@ -83,6 +83,14 @@ int64_t bwd_stencil_workspace_bytes(const BwdShape& s);
 hy_status launch_bwd_stencil(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
 // Backward, any shape (no workspace).
 hy_status launch_bwd_direct(const BwdPtrs& p, const BwdShape& s, hipStream_t st);
+// Backward on the matrix cores for medium grouped bf16 filters: dk, dv, dh (dq is the forward kernel with q := dy).
+bool mr_bwd_supported(const BwdShape& s);
+int64_t mr_bwd_rows(const BwdShape& s);
+int64_t mr_bwd_workspace_bytes(const BwdShape& s);
+hy_status launch_mr_bwd(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
+// dh[g][j] = sum over nsets partial sets and over `group` adjacent rows of a set; a set is [n_rows][lh].
+hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64_t n_rows, int32_t lh, int32_t group,
+                           hipStream_t st);
 // dh := 0 (the filter gradient of an empty batch).
 hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st);
 hy_status launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);

@@ -68,12 +68,75 @@ def test_short_filter_backward_every_tile_length(rows):
 
 
 @pytest.mark.parametrize("case", [
-    (1, 300, 64, 128, 16, "bf16"), (2, 130, 64, 128, 16, "f32"), (1, 200, 40, 50, 1, "bf16"),
+    (1, 300, 48, 128, 16, "bf16"), (2, 130, 64, 128, 16, "f32"), (1, 200, 40, 50, 1, "bf16"),
     (2, 150, 72, 13, 1, "f32"), (1, 90, 48, 40, 8, "bf16"), (1, 64, 33, 3, 1, "bf16"),  # odd D: general kernel
 ])
 def test_general_backward_matches_oracle(case):
     B, L, D, lh, group, dtype = case
     check("hyena_mr_bwd", 73, B, L, D, lh, group, dtype, kind="mr")
+
+
+# The matrix-core backward rounds u = k*v and g = dy*q to bf16 before the filter-gradient contraction: each
+# product g*u carries two independent roundings of up to 2^-9 (rms ~1.6e-3 relative).  dh[j] sums n random-sign
+# products, so its error and its own size both grow like sqrt(n): the error of an entry stays ~1.6e-3 of the
+# typical |dh|; the largest of G*lh errors over the largest |dh| comes to ~2e-3..3e-3.  Bound with margin:
+DH_TOL_MFMA = 1e-2
+
+MR_BWD_CASES = [
+    # B, L, D, lh, group, mr_rows
+    (1, 512, 64, 128, 16, 0),
+    (2, 1000, 128, 128, 16, 256),   # several tiles, halo warm-up in reversed time, ragged sequence end
+    (1, 333, 64, 128, 16, 32),      # one-chunk tiles
+    (2, 97, 64, 128, 16, 64),       # L < lh
+    (1, 1, 64, 128, 16, 0),
+    (1, 640, 192, 33, 16, 128),
+    (1, 640, 64, 34, 16, 128),
+    (1, 500, 64, 64, 32, 96),       # group of 32 channels: two 16-channel slices per filter
+    (1, 500, 128, 65, 64, 160),
+    (1, 700, 64, 129, 16, 128),
+    (1, 300, 64, 9, 16, 64),        # shortest filter of this path
+    (3, 256, 256, 128, 16, 128),
+    (1, 2100, 128, 128, 16, 1024),
+]
+
+
+@pytest.mark.parametrize("case", MR_BWD_CASES)
+def test_matrix_core_backward_matches_oracle(case):
+    B, L, D, lh, group, rows = case
+    binding.set_option("mr_rows", rows)
+    say("mr bwd B=%d L=%d D=%d lh=%d group=%d rows=%d" % case)
+    dy, q, k, v, h = draw(76, B, L, D, lh, group, "bf16", "mr")
+    assert binding.lib().hyena_bwd_workspace_bytes(B, L, D, lh, group, binding.HY_BF16) > 0
+    outs = binding.hyena_mr_bwd(dev(dy), dev(q), dev(k), dev(v), dev(h), group)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for name, got, want, tol in zip(("dq", "dk", "dv", "dh"), outs, ref, (TOL["bf16"],) * 3 + (DH_TOL_MFMA,)):
+        g = host(got)
+        assert np.isfinite(g).all(), name
+        err = oracle.rel_err(g, want)
+        assert err <= tol, (name, err)
+
+
+def test_matrix_core_backward_exact_case():
+    """Sparse signed inputs and dyadic taps: every product and partial sum is exactly representable, so
+    dq, dk, dv and dh must match the oracle bit for bit."""
+    B, L, D, lh, group = 2, 700, 128, 128, 16
+    say("mr bwd exact")
+    binding.set_option("mr_rows", 192)
+    rng = np.random.Generator(np.random.PCG64(77))
+    h = ((rng.integers(-8, 9, size=(D // group, lh)) / 8.0) * (rng.random((D // group, lh)) < 0.25)).astype(np.float32)
+
+    def sparse(p, lo, hi):
+        x = rng.integers(lo, hi + 1, (B, L, D)) * (rng.random((B, L, D)) < p)
+        return torch.from_numpy(x.astype(np.float32)).bfloat16()
+
+    dy, q, k, v = sparse(0.3, -2, 2), sparse(0.5, -1, 1), sparse(0.5, -1, 1), sparse(0.3, -1, 1)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for r in ref[:3]:
+        assert np.array_equal(r, torch.from_numpy(r).bfloat16().double().numpy())
+    assert np.abs(ref[3]).max() < 2 ** 20 and np.array_equal(ref[3], np.round(ref[3]))
+    outs = binding.hyena_mr_bwd(dev(dy), dev(q), dev(k), dev(v), dev(h), group)
+    for got, want in zip(outs, ref):
+        assert np.array_equal(host(got), want)
 
 
 def test_backward_of_a_linear_loss_equals_forward_value():
