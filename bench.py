@@ -8,6 +8,7 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c2  Hyena-MR  bf16 B1 L8192   D4096 lh128 group16  hyena_mr_fwd
   c3  Hyena-MR  bf16 B1 L131072 D4096 lh128 group16  hyena_mr_fwd
   c4  chain     bf16 B4 L32768  D4096                hyena_chain_fwd (featurizers + MR in one kernel)
+  c1_bwd / c2_bwd / c3_bwd: the backward entry points (hyena_se_bwd / hyena_mr_bwd) on the shapes of c1 / c2 / c3
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
 Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded slice of the same workload.
@@ -17,6 +18,8 @@ import json
 import os
 import sys
 import time
+
+import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -32,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "copy"],
+    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c1_bwd", "c2_bwd", "c3_bwd", "copy"],
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -67,11 +70,13 @@ class Workload:
 
     def __init__(self, name, nsets, torch, pkg, synth):
         self.name, self.torch, self.pkg = name, torch, pkg
+        self.bwd = name.endswith("_bwd")
+        name = name[:-4] if self.bwd else name
         self.cfg = synth.config(name)
         c = self.cfg
         self.n_out = c["B"] * c["L"] * c["D"]
         self.tokens = c["B"] * c["L"]
-        bytes_set = self.n_out * 2 * 4
+        bytes_set = self.n_out * 2 * (8 if self.bwd else 4)
         if nsets <= 0:
             nsets = max(1, min(6, int((1.5 * 2 ** 30) // bytes_set) + 1))
         self.host0 = None
@@ -81,7 +86,20 @@ class Workload:
             if i == 0:
                 self.host0 = w
             d = upload(w, torch)
-            if c["kind"] == "chain":
+            if self.bwd:
+                # dy is drawn like the activations; dq, dk, dv share one more allocation
+                rng = np.random.Generator(np.random.PCG64(synth.seed_for(name, i) + 500000))
+                dy_host = synth.normal_tensor(rng, tuple(d["q"].shape), c["dtype"])
+                if i == 0:
+                    self.host0["dy"] = dy_host
+                d["dy"] = dy_host.cuda()
+                grads = torch.empty((3,) + tuple(d["q"].shape), dtype=d["q"].dtype, device="cuda")
+                d["dq"], d["dk"], d["dv"] = grads[0], grads[1], grads[2]
+                d["dh"] = torch.empty_like(d["h"])
+                self.main.append(pkg.plan_bwd("hyena_se_bwd" if c["kind"] == "se" else "hyena_mr_bwd", d["dy"], d["q"],
+                                              d["k"], d["v"], d["h"], c["group"],
+                                              out=(d["dq"], d["dk"], d["dv"], d["dh"])))
+            elif c["kind"] == "chain":
                 self.main.append(pkg.plan_chain(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"], d["h"],
                                                 c["group"], c["feat_group"], out=d["y"]))
             else:
@@ -132,10 +150,14 @@ class Workload:
 
     # algorithmic work of the dominant kernel per launch
     def algo_bytes(self):
+        if self.bwd:
+            return 14.0 * self.n_out  # bf16: dy, q, k, v read once, dq, dk, dv written once
         return 8.0 * self.n_out  # bf16: q, k, v read once, y written once
 
     def algo_flops(self):
         f = 2.0 * self.cfg["lh"] + 2.0
+        if self.bwd:
+            return (3 * 2.0 * self.cfg["lh"] + 5.0) * self.n_out  # z, du, dh contractions + five gates
         if self.cfg["kind"] == "chain":
             f += 3 * 2.0 * self.cfg["lf"]
         return f * self.n_out
@@ -150,7 +172,11 @@ def cpu_baseline(wl, target_s, np, oracle):
     def run(rows):
         q, k, v = (w[key][:1, :rows].contiguous() for key in ("q", "k", "v"))
         t0 = time.perf_counter()
-        if c["kind"] == "chain":
+        if wl.bwd:
+            # dq[t] only looks at the past, so the first rows of the slice's dq equal those of the full problem
+            dy = w["dy"][:1, :rows].contiguous()
+            y = oracle.gated_conv_bwd(dy, q, k, v, w["h"], group=c["group"])[0]
+        elif c["kind"] == "chain":
             y = oracle.chain(q, k, v, w["hq"], w["hk"], w["hv"], w["h"], group=c["group"], feat_group=c["feat_group"])
         else:
             y = oracle.gated_conv(q, k, v, w["h"], group=c["group"])
@@ -223,6 +249,8 @@ def main():
     wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup)
     cfg = wl.cfg
     kernel = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd"}[cfg["kind"]]
+    if wl.bwd:
+        kernel = kernel.replace("_fwd", "_bwd")
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -234,8 +262,9 @@ def main():
         "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: %s bf16 B=%d L=%d D=%d lh=%d group=%d" % (
+        "config": {"workload": "%s: %s%s bf16 B=%d L=%d D=%d lh=%d group=%d" % (
             args.workload, {"se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,"}[cfg["kind"]],
+            " backward (all launches of the entry point)" if wl.bwd else "",
             cfg["B"], cfg["L"], cfg["D"], cfg["lh"], cfg["group"]), "buffer_sets": res["sets"]},
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": res["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": res["hbm_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
@@ -255,7 +284,7 @@ def main():
         wl.i = 0
         wl.step()
         torch.cuda.synchronize()
-        got = d["y"][:1, :rows].float().cpu().numpy().astype(np.float64)
+        got = (d["dq"] if wl.bwd else d["y"])[:1, :rows].float().cpu().numpy().astype(np.float64)
         out["parity_rel_err"] = oracle.rel_err(got, y_ref)
 
     if args.workload == "c1" and args.also:

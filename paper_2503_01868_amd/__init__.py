@@ -6,6 +6,7 @@ benchmark inputs; ``build`` compiles the library.
 from .binding import (  # noqa: F401
     HyenaError,
     Plan,
+    plan_bwd,
     plan_chain,
     plan_featurize3,
     plan_gated,

@@ -267,6 +267,37 @@ def plan_chain(q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, out
     return Plan(lib().hyena_chain_fwd, args, "hyena_chain_fwd", keep, y)
 
 
+def plan_bwd(entry: str, dy, q, k, v, h, group: int, out=None, workspace=None, stream=None) -> Plan:
+    """Marshal one ``hyena_se_bwd`` / ``hyena_mr_bwd`` call for repeated issue; ``out`` = (dq, dk, dv, dh)."""
+    if entry not in ("hyena_se_bwd", "hyena_mr_bwd"):
+        raise ValueError("entry must be hyena_se_bwd or hyena_mr_bwd")
+    _check_act("dy", dy)
+    _check_act("q", q, dy)
+    _check_act("k", k, dy)
+    _check_act("v", v, dy)
+    lh = _check_filter("h", h, dy, group)
+    B, L, D = dy.shape
+    code = _dtype_code(dy)
+    need = int(lib().hyena_bwd_workspace_bytes(B, L, D, lh, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid backward problem")
+    if need > 0 and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dy.device)
+    if out is None:
+        out = tuple(torch.empty_like(dy) for _ in range(3)) + (torch.empty_like(h),)
+    for name, o in zip(("dq", "dk", "dv"), out[:3]):
+        _check_act(name, o, dy)
+    _check_filter("dh", out[3], dy, group)
+    c = ctypes
+    ptrs = [t.data_ptr() for t in (dy, q, k, v, h) + tuple(out)]
+    ws_ptr = workspace.data_ptr() if need > 0 else None
+    ws_bytes = workspace.numel() * workspace.element_size() if need > 0 else 0
+    args = tuple(c.c_void_p(p) for p in ptrs) + (c.c_void_p(ws_ptr), c.c_int64(ws_bytes), c.c_int64(B), c.c_int64(L),
+                                                  c.c_int64(D), c.c_int32(lh), c.c_int32(int(group)), c.c_int(code),
+                                                  c.c_void_p(_stream(dy, stream)))
+    return Plan(getattr(lib(), entry), args, entry, (dy, q, k, v, h, workspace) + tuple(out), tuple(out))
+
+
 def _bwd(entry: str, dy, q, k, v, h, group, workspace, stream):
     _check_act("dy", dy)
     _check_act("q", q, dy)
