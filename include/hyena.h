@@ -36,6 +36,8 @@ typedef enum hy_status {
     HY_ERR_LAUNCH = 6       /* the HIP runtime reported an error at launch */
 } hy_status;
 
+/* Storage types.  Entry points take the value as a plain int32_t so that any integer a caller passes is
+ * well defined and can be rejected with HY_ERR_DTYPE. */
 typedef enum hy_dtype { HY_F32 = 0, HY_BF16 = 1 } hy_dtype;
 
 /*
@@ -47,7 +49,7 @@ typedef enum hy_dtype { HY_F32 = 0, HY_BF16 = 1 } hy_dtype;
  * filters fall to a slower general kernel.  q,k,v,y: [B,L,D] of `dtype`; h: fp32 [D/group, lh].
  */
 hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
-                       int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype,
+                       int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
                        void *hip_stream);
 
 /*
@@ -60,7 +62,7 @@ hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float 
  * filters) runs a general fp32 vector-ALU kernel.
  */
 hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
-                       int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype,
+                       int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
                        void *hip_stream);
 
 /*
@@ -70,7 +72,7 @@ hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float 
  * x,y: [B,L,D] of `dtype`; h: fp32 [D/group, lh].
  */
 hy_status hyena_featurize_fwd(const void *x, const float *h, void *y, int64_t B, int64_t L,
-                              int64_t D, int32_t lh, int32_t group, hy_dtype dtype,
+                              int64_t D, int32_t lh, int32_t group, int32_t dtype,
                               void *hip_stream);
 
 /*
@@ -81,7 +83,7 @@ hy_status hyena_featurize_fwd(const void *x, const float *h, void *y, int64_t B,
 hy_status hyena_featurize3_fwd(const void *q, const void *k, const void *v, const float *hq,
                                const float *hk, const float *hv, void *qo, void *ko, void *vo,
                                int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group,
-                               hy_dtype dtype, void *hip_stream);
+                               int32_t dtype, void *hip_stream);
 
 /*
  * The Hyena-MR operator chain of Sec. 2.1 Eq. 1 without its dense projections, forward:
@@ -98,14 +100,14 @@ hy_status hyena_featurize3_fwd(const void *q, const void *k, const void *v, cons
 hy_status hyena_chain_fwd(const void *q, const void *k, const void *v, const float *hq, const float *hk,
                           const float *hv, const float *h, void *y, void *workspace, int64_t B, int64_t L,
                           int64_t D, int32_t lf, int32_t feat_group, int32_t lh, int32_t group,
-                          hy_dtype dtype, void *hip_stream);
+                          int32_t dtype, void *hip_stream);
 
 /*
  * Bytes of workspace hyena_chain_fwd needs for this problem: 0 when the single-kernel path applies,
  * 3*B*L*D*sizeof(dtype) otherwise, -1 if the arguments are not a valid problem.  Host-only, no HIP call.
  */
 int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group,
-                                    int32_t lh, int32_t group, hy_dtype dtype);
+                                    int32_t lh, int32_t group, int32_t dtype);
 
 /*
  * Backward of hyena_se_fwd / hyena_mr_fwd: gradients of y = q (.) (h * (k (.) v)) given dy = dLoss/dy.
@@ -130,16 +132,16 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
  */
 hy_status hyena_se_bwd(const void *dy, const void *q, const void *k, const void *v, const float *h, void *dq,
                        void *dk, void *dv, float *dh, void *workspace, int64_t workspace_bytes, int64_t B,
-                       int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void *hip_stream);
+                       int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void *hip_stream);
 hy_status hyena_mr_bwd(const void *dy, const void *q, const void *k, const void *v, const float *h, void *dq,
                        void *dk, void *dv, float *dh, void *workspace, int64_t workspace_bytes, int64_t B,
-                       int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void *hip_stream);
+                       int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void *hip_stream);
 
 /*
  * Bytes of workspace the backward entry points need for this problem under the current tuning options
  * (0 for shapes served by the general kernel), -1 if the arguments are not a valid problem.  Host-only.
  */
-int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype);
+int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype);
 
 /*
  * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16) with the same launch
@@ -159,7 +161,7 @@ hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip
 hy_status hyena_set_option(const char *name, int32_t value);
 
 /* Static, NUL-terminated description of a status code. */
-const char *hyena_status_string(hy_status s);
+const char *hyena_status_string(int32_t status);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int32_t hyena_version(void);

@@ -43,7 +43,7 @@ bool overlaps(const void* a, const void* b, int64_t bytes) { return overlaps2(a,
 
 // Checks shared by every convolution entry point.  `ins`/`outs` hold activation pointers.
 hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_out, const float* const* hs,
-                   int n_h, int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype) {
+                   int n_h, int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
     for (int i = 0; i < n_in; ++i)
         if (!ins[i]) return HY_ERR_NULL;
     for (int i = 0; i < n_out; ++i)
@@ -84,7 +84,7 @@ using namespace hy;
 extern "C" {
 
 hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
-                       int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+                       int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     const void* ins[3] = {q, k, v};
     void* outs[1] = {y};
     const float* hs[1] = {h};
@@ -92,7 +92,7 @@ hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float*
     if (rc != HY_OK) return rc;
     if (empty(B, L, D)) return HY_OK;
     ConvPtrs p{q, k, v, h, y};
-    ConvShape s{B, L, D, lh, group, dtype, true};
+    ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_stencil(&p, 1, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
@@ -100,7 +100,7 @@ hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float*
 }
 
 hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
-                       int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+                       int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     const void* ins[3] = {q, k, v};
     void* outs[1] = {y};
     const float* hs[1] = {h};
@@ -108,7 +108,7 @@ hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float*
     if (rc != HY_OK) return rc;
     if (empty(B, L, D)) return HY_OK;
     ConvPtrs p{q, k, v, h, y};
-    ConvShape s{B, L, D, lh, group, dtype, true};
+    ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_mr_mfma(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
@@ -116,7 +116,7 @@ hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float*
 }
 
 hy_status hyena_featurize_fwd(const void* x, const float* h, void* y, int64_t B, int64_t L, int64_t D, int32_t lh,
-                              int32_t group, hy_dtype dtype, void* hip_stream) {
+                              int32_t group, int32_t dtype, void* hip_stream) {
     const void* ins[1] = {x};
     void* outs[1] = {y};
     const float* hs[1] = {h};
@@ -124,7 +124,7 @@ hy_status hyena_featurize_fwd(const void* x, const float* h, void* y, int64_t B,
     if (rc != HY_OK) return rc;
     if (empty(B, L, D)) return HY_OK;
     ConvPtrs p{nullptr, x, nullptr, h, y};
-    ConvShape s{B, L, D, lh, group, dtype, false};
+    ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), false};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_stencil(&p, 1, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
@@ -133,7 +133,7 @@ hy_status hyena_featurize_fwd(const void* x, const float* h, void* y, int64_t B,
 
 hy_status hyena_featurize3_fwd(const void* q, const void* k, const void* v, const float* hq, const float* hk,
                                const float* hv, void* qo, void* ko, void* vo, int64_t B, int64_t L, int64_t D,
-                               int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+                               int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     const void* ins[3] = {q, k, v};
     void* outs[3] = {qo, ko, vo};
     const float* hs[3] = {hq, hk, hv};
@@ -141,7 +141,7 @@ hy_status hyena_featurize3_fwd(const void* q, const void* k, const void* v, cons
     if (rc != HY_OK) return rc;
     if (empty(B, L, D)) return HY_OK;
     ConvPtrs p[3] = {{nullptr, q, nullptr, hq, qo}, {nullptr, k, nullptr, hk, ko}, {nullptr, v, nullptr, hv, vo}};
-    ConvShape s{B, L, D, lh, group, dtype, false};
+    ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), false};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_stencil(p, 3, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(p, 3, s, st);
@@ -149,11 +149,11 @@ hy_status hyena_featurize3_fwd(const void* q, const void* k, const void* v, cons
 }
 
 int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh,
-                                    int32_t group, hy_dtype dtype) {
+                                    int32_t group, int32_t dtype) {
     if (B < 0 || L < 0 || D < 0 || lf < 1 || lh < 1 || feat_group < 1 || group < 1) return -1;
     if (D % group != 0 || D % feat_group != 0) return -1;
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
-    ChainShape s{B, L, D, lf, feat_group, lh, group, dtype};
+    ChainShape s{B, L, D, lf, feat_group, lh, group, static_cast<hy_dtype>(dtype)};
     if (empty(B, L, D) || chain_fused_supported(s)) return 0;
     const int64_t esz = dtype == HY_F32 ? 4 : 2;
     if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > INT64_MAX / (3 * esz)) return -1;
@@ -162,7 +162,7 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
 
 hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const float* hq, const float* hk,
                           const float* hv, const float* h, void* y, void* workspace, int64_t B, int64_t L, int64_t D,
-                          int32_t lf, int32_t feat_group, int32_t lh, int32_t group, hy_dtype dtype,
+                          int32_t lf, int32_t feat_group, int32_t lh, int32_t group, int32_t dtype,
                           void* hip_stream) {
     const void* ins[3] = {q, k, v};
     void* outs[1] = {y};
@@ -172,7 +172,7 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
     if (lf < 1 || feat_group < 1 || D % feat_group != 0) return HY_ERR_SHAPE;
     if (empty(B, L, D)) return HY_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    ChainShape cs{B, L, D, lf, feat_group, lh, group, dtype};
+    ChainShape cs{B, L, D, lf, feat_group, lh, group, static_cast<hy_dtype>(dtype)};
     if (chain_fused_supported(cs)) {
         ChainPtrs cp{q, k, v, hq, hk, hv, h, y};
         return launch_chain_fused(cp, cs, st);
@@ -188,22 +188,22 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
         if (overlaps2(all[i], bytes, workspace, 3 * bytes)) return HY_ERR_ALIGN;
     char* ws = static_cast<char*>(workspace);
     ConvPtrs f[3] = {{nullptr, q, nullptr, hq, ws}, {nullptr, k, nullptr, hk, ws + bytes}, {nullptr, v, nullptr, hv, ws + 2 * bytes}};
-    ConvShape fs{B, L, D, lf, feat_group, dtype, false};
+    ConvShape fs{B, L, D, lf, feat_group, static_cast<hy_dtype>(dtype), false};
     rc = launch_stencil(f, 3, fs, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(f, 3, fs, st);
     if (rc != HY_OK) return rc;
     ConvPtrs m{ws, ws + bytes, ws + 2 * bytes, h, y};
-    ConvShape ms{B, L, D, lh, group, dtype, true};
+    ConvShape ms{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     rc = launch_mr_mfma(m, ms, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&m, 1, ms, st);
     return rc;
 }
 
-int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype) {
+int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
     if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1 || D % group != 0) return -1;
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
     if (empty(B, L, D)) return 0;
-    BwdShape s{B, L, D, lh, group, dtype};
+    BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
     if (bwd_stencil_supported(s)) return bwd_stencil_workspace_bytes(s);
     if (mr_bwd_supported(s)) return mr_bwd_workspace_bytes(s);
     return 0;
@@ -211,7 +211,7 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
 
 static hy_status gated_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,
                            void* dk, void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B,
-                           int64_t L, int64_t D, int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+                           int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     const void* ins[4] = {dy, q, k, v};
     void* outs[3] = {dq, dk, dv};
     const float* hs[2] = {h, dh};
@@ -226,7 +226,7 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
         return launch_bwd_zero_dh(dh, D, lh, group, st);
     }
     BwdPtrs p{dy, q, k, v, h, dq, dk, dv, dh};
-    BwdShape s{B, L, D, lh, group, dtype};
+    BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
     const bool stencil = bwd_stencil_supported(s);
     const bool mfma = !stencil && mr_bwd_supported(s);
     if (stencil || mfma) {
@@ -242,7 +242,7 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
         if (stencil) return launch_bwd_stencil(p, s, workspace, st);
         // medium grouped filters: dq is the forward operator applied to (dy, k, v); then dk, dv, dh
         ConvPtrs f{dy, k, v, h, dq};
-        ConvShape fs{B, L, D, lh, group, dtype, true};
+        ConvShape fs{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
         rc = launch_mr_mfma(f, fs, st);
         if (rc != HY_OK) return rc;
         return launch_mr_bwd(p, s, workspace, st);
@@ -252,13 +252,13 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
 
 hy_status hyena_se_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq, void* dk,
                        void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D,
-                       int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+                       int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     return gated_bwd(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype, hip_stream);
 }
 
 hy_status hyena_mr_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq, void* dk,
                        void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D,
-                       int32_t lh, int32_t group, hy_dtype dtype, void* hip_stream) {
+                       int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     return gated_bwd(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype, hip_stream);
 }
 
@@ -297,8 +297,8 @@ hy_status hyena_set_option(const char* name, int32_t value) {
     return HY_OK;
 }
 
-const char* hyena_status_string(hy_status s) {
-    switch (s) {
+const char* hyena_status_string(int32_t status) {
+    switch (status) {
         case HY_OK: return "ok";
         case HY_ERR_NULL: return "null pointer argument";
         case HY_ERR_SHAPE: return "invalid shape or size argument";

@@ -1,0 +1,24 @@
+// Stand-ins for the kernel launchers so that the C ABI's host logic can be linked and run without device code.
+#include "hy_launch.hpp"
+
+namespace hy {
+hy_status launch_stencil(const ConvPtrs*, int, const ConvShape& s, hipStream_t) { return s.lh > 8 ? HY_ERR_UNSUPPORTED : HY_OK; }
+hy_status launch_direct(const ConvPtrs*, int, const ConvShape&, hipStream_t) { return HY_OK; }
+hy_status launch_mr_mfma(const ConvPtrs&, const ConvShape& s, hipStream_t) {
+    return (s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.lh <= 257) ? HY_OK : HY_ERR_UNSUPPORTED;
+}
+bool chain_fused_supported(const ChainShape& s) {
+    return s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 128 == 0 && s.lh <= 129 && s.lf >= 1 && s.lf <= 8;
+}
+hy_status launch_chain_fused(const ChainPtrs&, const ChainShape&, hipStream_t) { return HY_OK; }
+bool bwd_stencil_supported(const BwdShape& s) { return s.lh <= 8 && s.D % (s.dtype == HY_BF16 ? 2 : 1) == 0; }
+int64_t bwd_stencil_workspace_bytes(const BwdShape& s) { return s.B * ((s.L + 127) / 128) * s.D * s.lh * 4; }
+hy_status launch_bwd_stencil(const BwdPtrs&, const BwdShape&, void*, hipStream_t) { return HY_OK; }
+hy_status launch_bwd_direct(const BwdPtrs&, const BwdShape&, hipStream_t) { return HY_OK; }
+bool mr_bwd_supported(const BwdShape& s) { return s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.lh > 8 && s.lh <= 129; }
+int64_t mr_bwd_rows(const BwdShape& s) { return (s.L + 31) / 32 * 32; }
+int64_t mr_bwd_workspace_bytes(const BwdShape& s) { return s.B * (s.D / 16) * s.lh * 4; }
+hy_status launch_mr_bwd(const BwdPtrs&, const BwdShape&, void*, hipStream_t) { return HY_OK; }
+hy_status launch_dh_reduce(const float*, float*, int64_t, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
+hy_status launch_bwd_zero_dh(float*, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
+}  // namespace hy
