@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libhyena.so")
 
-SOURCES = ["api.hip", "se_kernels.hip", "direct_kernels.hip", "mr_kernels.hip", "chain_kernels.hip", "bwd_kernels.hip", "mr_bwd_kernels.hip"]
+SOURCES = ["api.hip", "se_kernels.hip", "direct_kernels.hip", "mr_kernels.hip", "cp_kernels.hip", "chain_kernels.hip", "bwd_kernels.hip", "mr_bwd_kernels.hip"]
 
 # Packed-fp32 instruction selection is switched off for all device code in this library.
 HIPCC_FLAGS = [
@@ -38,7 +38,7 @@ def _compile(src: str) -> str:
 def build_library(verbose: bool = False) -> str:
     """Compile every kernel translation unit for gfx950 and link the shared library."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         objs = list(pool.map(_compile, SOURCES))
     tmp = LIB + ".%d.tmp" % os.getpid()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs

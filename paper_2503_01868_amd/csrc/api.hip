@@ -95,6 +95,7 @@ hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float*
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_stencil(&p, 1, s, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp_mfma(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
     return rc;
 }
@@ -111,6 +112,7 @@ hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float*
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_mr_mfma(p, s, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp_mfma(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
     return rc;
 }

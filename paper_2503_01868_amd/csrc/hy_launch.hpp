@@ -74,6 +74,10 @@ hy_status launch_stencil(const ConvPtrs* p, int nprob, const ConvShape& s, hipSt
 hy_status launch_direct(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
 // Block-Toeplitz contraction on bf16 MFMA.  HY_ERR_UNSUPPORTED outside its domain.
 hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
+// Chunk-parallel block-Toeplitz contraction on bf16 MFMA for filters not shared by 16 channels (any group).
+// HY_ERR_UNSUPPORTED outside cp_mfma_supported().
+bool cp_mfma_supported(const ConvShape& s);
+hy_status launch_cp_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // Whole chain in one pass over q, k, v.  HY_ERR_UNSUPPORTED outside chain_fused_supported().
 bool chain_fused_supported(const ChainShape& s);
 hy_status launch_chain_fused(const ChainPtrs& p, const ChainShape& s, hipStream_t st);

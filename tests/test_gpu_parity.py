@@ -136,6 +136,73 @@ def test_mr_general_path_matches_oracle(case):
     check_gated("hyena_mr_fwd", 32, B, L, D, lh, group, dtype, kind="mr")
 
 
+# Chunk-parallel matrix-core path (App. A.1): bf16, filters not shared by 16 channels, 9 <= lh <= 145, D % 64 == 0.
+# (B, L, D, lh, group, rows): rows = 0 keeps the default tile length, 256 forces a tile boundary every iteration.
+CP_CASES = [
+    (1, 700, 64, 128, 1, 0),        # ungrouped medium filter, ragged last iteration
+    (2, 1000, 128, 128, 1, 256),    # tiles of one iteration: every history path
+    (1, 2300, 64, 145, 1, 512),     # longest filter of this path, ring wraps several times
+    (1, 515, 64, 17, 1, 256),       # K = 32 exactly filled (lh + 15 = 32)
+    (1, 515, 64, 18, 1, 256),       # first length that needs K = 64
+    (1, 300, 64, 49, 2, 0),
+    (1, 300, 64, 50, 4, 0),
+    (1, 777, 128, 81, 8, 256),
+    (2, 513, 64, 113, 1, 256),
+    (1, 259, 64, 9, 1, 0),          # shortest filter routed here
+    (1, 3, 64, 128, 1, 0),          # sequence shorter than one row group
+    (1, 1, 64, 20, 1, 0),
+    (1, 256, 192, 64, 3, 0),        # group that does not divide the 64-channel block evenly
+    (3, 256, 64, 128, 32, 0),       # hyena_se_fwd entry with a shared filter also lands here (see test below)
+]
+
+
+@pytest.mark.parametrize("case", CP_CASES)
+def test_chunk_parallel_path_matches_oracle(case):
+    B, L, D, lh, group, rows = case
+    binding.set_option("mr_rows", rows)
+    entry = "hyena_se_fwd" if group == 32 else "hyena_mr_fwd"
+    check_gated(entry, 35, B, L, D, lh, group, "bf16", kind="mr")
+
+
+def test_chunk_parallel_impulse_and_tile_boundaries_are_bit_exact():
+    """Ungrouped dyadic taps, q = k = 1, v = unit impulses placed so that responses cross iteration and tile
+    boundaries and the ring's wrap-around: y must reproduce each channel's own taps exactly."""
+    B, L, D, lh = 2, 1500, 128, 100
+    say("impulse chunk-parallel")
+    binding.set_option("mr_rows", 512)
+    h = dyadic_filter(D, lh, 44)
+    one = torch.ones(B, L, D, dtype=torch.bfloat16)
+    v = torch.zeros(B, L, D, dtype=torch.bfloat16)
+    hits = [(0, 0, 0), (0, 200, 17), (0, 500, 63), (1, 511, 64), (1, 1023, 127), (1, 1450, 5), (0, 1499, 9), (0, 255, 70)]
+    expect = np.zeros((B, L, D))
+    for b, t0, c in hits:
+        v[b, t0, c] = 1.0
+        n = min(lh, L - t0)
+        expect[b, t0:t0 + n, c] += h[c, :n]
+    y = host(gated("hyena_mr_fwd", one, one, v, h, 1))
+    assert np.array_equal(y, expect)
+
+
+def test_chunk_parallel_guard_bands_determinism_and_no_leak_between_batch_items():
+    B, L, D, lh = 2, 301, 128, 77
+    say("guard bands chunk-parallel")
+    q, k, v, h = draw(54, 1, L, D, lh, 1, "bf16", "mr")
+    q2, k2, v2 = (torch.cat([x, x], dim=0) for x in (q, k, v))
+    n = B * L * D
+    guard = 4096
+    buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    out = buf[guard:guard + n].view(B, L, D)
+    binding.hyena_mr_fwd(dev(q2), dev(k2), dev(v2), dev(h), 1, out=out)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all()
+    assert not torch.isnan(out).any()
+    assert torch.equal(out[0], out[1])
+    again = binding.hyena_mr_fwd(dev(q2), dev(k2), dev(v2), dev(h), 1)
+    torch.cuda.synchronize()
+    assert torch.equal(again, out)
+    assert oracle.rel_err(host(out[:1]), oracle.gated_conv(q, k, v, h, group=1)) <= TOL["bf16"]
+
+
 def test_mr_and_se_entry_points_agree_on_a_short_grouped_filter():
     q, k, v, h = draw(33, 2, 300, 128, 7, 16, "bf16", kind="mr")
     y_mr = host(gated("hyena_mr_fwd", q, k, v, h, 16))
