@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c1_bwd", "c2_bwd", "c3_bwd", "copy"],
+    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c2u", "c1_bwd", "c2_bwd", "c3_bwd", "copy"],
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -54,11 +54,15 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
     constexpr int kUS = kR * 2;        // bytes per channel line of u
     constexpr int kQS = kT * 2;        // bytes per channel line of q / y
     constexpr int kGW = 16 * NKB + 8;  // dwords per copy of the reversed filter
-    // each block of 8 channels starts 64 bytes further than the line stride alone would put it, so that
-    // the 8 row pieces of a wave's transposing writes alternate between the two halves of the banks
-    __shared__ __attribute__((aligned(16))) char us[kC * kUS + (kC / 8) * 64];
-    __shared__ __attribute__((aligned(16))) char qs[kC * kQS + (kC / 8) * 64];
-    __shared__ uint32_t gt[kC][2][kGW];
+    // each block of 8 channels starts 16 bytes further than the line stride alone would put it: measured on
+    // MI355X, the transposing 8-byte writes of a wave (8 row groups x 8 channel blocks) then run at the full
+    // write rate of the LDS, against a quarter of it with blocks a multiple of 128 bytes apart
+    __shared__ __attribute__((aligned(16))) char us[kC * kUS + (kC / 8) * 16];
+    __shared__ __attribute__((aligned(16))) char qs[kC * kQS + (kC / 8) * 16];
+    // reversed-filter tables, copy-major; the second copy starts 16 banks off the first, so that the even and
+    // the odd lanes of a matrix-operand read (12 adjacent dwords of either copy) never meet in a bank
+    constexpr int kGC = kC * kGW + (16 - (kC * kGW) % 32 + 32) % 32;
+    __shared__ uint32_t gt[2 * kGC];
 
     const int tid = threadIdx.x;
     const int w = tid / 64, lane = tid % 64;
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
     // ---- row layout: rows 4 rg .. 4 rg + 3 of an iteration, channels 8 lp .. 8 lp + 7 of the block
     const int lp = tid % 8, rg = tid / 8;
     const int64_t col = seq0 + cblock0 + 8 * lp;
-    auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 64; };
+    auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 16; };
     char* const u_lines = us + line_off(8 * lp, kUS);  // this lane's 8 channel lines are kUS apart
     char* const q_lines = qs + line_off(8 * lp, kQS) + 8 * rg;
 
@@ -125,7 +129,7 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
         const int j0 = kK - 1 - (2 * x + par);
         const float g0 = (j0 >= 0 && j0 < a.lh) ? hp[j0] : 0.0f;
         const float g1 = (j0 - 1 >= 0 && j0 - 1 < a.lh) ? hp[j0 - 1] : 0.0f;
-        gt[c][par][x] = pack_bf16x2(g0, g1);
+        gt[par * kGC + c * kGW + x] = pack_bf16x2(g0, g1);
     }
 
     // ---- history: the K steps before the tile go to ring positions 256 - K .. 255 (whole waves take part)
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
     }
 
     // matrix-phase constants of this lane
-    const uint32_t* const g_lane = &gt[8 * w][(li & 1) ^ 1][((15 - li) >> 1) + 4 * lq];
+    const uint32_t* const g_lane = gt + ((li & 1) ^ 1) * kGC + 8 * w * kGW + ((15 - li) >> 1) + 4 * lq;
     const int x_lane = 16 * li + 16 - kK + 8 * lq;  // ring position of the lane's first source octet, relative to wb
     const int qy_lane = (16 * li + 4 * lq) * 2;
 
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
             for (int cc = 0; cc < 8; ++cc) {
                 const int c = 8 * w + cc;
                 const char* ul = us + line_off(c, kUS);
-                const uint32_t* gl = g_lane + cc * (2 * kGW);
+                const uint32_t* gl = g_lane + cc * kGW;
                 f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
                 int x = x0;
 #pragma unroll

@@ -24,6 +24,8 @@ CONFIGS = {
     "c2": dict(kind="mr", B=1, L=8192, D=4096, lh=128, group=16, dtype="bf16"),
     "c3": dict(kind="mr", B=1, L=131072, D=4096, lh=128, group=16, dtype="bf16"),
     "c4": dict(kind="chain", B=4, L=32768, D=4096, lh=128, group=16, lf=7, feat_group=1, dtype="bf16"),
+    # not one of the five: c2 with a filter per channel (no grouping), the shape of the chunk-parallel path (App. A.1)
+    "c2u": dict(kind="mr", B=1, L=8192, D=4096, lh=128, group=1, dtype="bf16"),
 }
 
 _BASE_SEED = 186800

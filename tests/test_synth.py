@@ -7,7 +7,9 @@ from paper_2503_01868_amd import synth
 
 def test_five_configs_as_named():
     c = synth.CONFIGS
-    assert list(c) == ["c0", "c1", "c2", "c3", "c4"]
+    assert list(c)[:5] == ["c0", "c1", "c2", "c3", "c4"]  # the five named configurations keep their seeds
+    assert {k: v for k, v in c["c2u"].items() if k != "group"} == {k: v for k, v in c["c2"].items() if k != "group"}
+    assert c["c2u"]["group"] == 1
     assert (c["c0"]["B"], c["c0"]["L"], c["c0"]["D"], c["c0"]["lh"], c["c0"]["dtype"]) == (1, 1024, 256, 7, "f32")
     assert (c["c1"]["L"], c["c1"]["D"], c["c1"]["lh"], c["c1"]["group"], c["c1"]["dtype"]) == (8192, 4096, 7, 1, "bf16")
     assert (c["c2"]["L"], c["c2"]["D"], c["c2"]["lh"], c["c2"]["group"]) == (8192, 4096, 128, 16)
