@@ -152,6 +152,23 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
     const int x_lane = 16 * li + 16 - kK + 8 * lq;  // ring position of the lane's first source octet, relative to wb
     const int qy_lane = (16 * li + 4 * lq) * 2;
 
+    // The Toeplitz operands of the wave's 8 channels never change: the first kAR source blocks of each stay in
+    // registers for the whole tile (the register file has room for 4 x 8 of them beside the row phase), the
+    // rest is re-read from the tables every iteration.  Reading them all from LDS made the matrix phase
+    // LDS-bound (8 of the 12 LDS cycles per product were operand A).
+    constexpr int kAR = NKB < 4 ? NKB : 4;
+    bf16x8_t ares[8][kAR];
+    __syncthreads();  // tables complete
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc)
+#pragma unroll
+        for (int m = 0; m < kAR; ++m) {
+            Words<4> aw;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) aw.w[d] = g_lane[cc * kGW + 16 * m + d];
+            ares[cc][m] = __builtin_bit_cast(bf16x8_t, aw);
+        }
+
     int wb = 0;
     for (int it = 1; it <= nit; ++it) {
         wb += kT;
@@ -182,7 +199,7 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
         {
             int x0 = wb + x_lane;
             if (x0 < 0) x0 += kR;
-#pragma unroll 2
+#pragma unroll
             for (int cc = 0; cc < 8; ++cc) {
                 const int c = 8 * w + cc;
                 const char* ul = us + line_off(c, kUS);
@@ -192,14 +209,21 @@ __global__ __launch_bounds__(kThreads, 2) void cp_mfma_kernel(CpArgs a) {
 #pragma unroll
                 for (int m = 0; m < NKB; ++m) {
                     if (x >= kR) x -= kR;
-                    Words<4> aw;
+                    bf16x8_t av;
+                    {
+                        if (m < kAR) {
+                            av = ares[cc][m < kAR ? m : 0];
+                        } else {
+                            Words<4> aw;
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) aw.w[d] = gl[16 * m + d];
+                            for (int d = 0; d < 4; ++d) aw.w[d] = gl[16 * m + d];
+                            av = __builtin_bit_cast(bf16x8_t, aw);
+                        }
+                    }
                     const uint4 bw = *reinterpret_cast<const uint4*>(ul + x * 2);
                     Words<4> bww;
                     bww.w[0] = bw.x; bww.w[1] = bw.y; bww.w[2] = bw.z; bww.w[3] = bw.w;
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aw),
-                                                                  __builtin_bit_cast(bf16x8_t, bww), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8_t, bww), acc, 0, 0, 0);
                     x += 32;
                 }
                 char* ql = qs + line_off(c, kQS) + qy_lane;
