@@ -45,8 +45,9 @@ typedef enum hy_dtype { HY_F32 = 0, HY_BF16 = 1 } hy_dtype;
  * both optional gates on; FIR sum of Sec. 3.1 Eq. 2):
  *     y[b,t,c] = q[b,t,c] * sum_{j=0}^{min(lh-1,t)} h[c/group, j] * k[b,t-j,c] * v[b,t-j,c]
  * Meant for short filters (the paper runs lh = 4..7, always below 14): a fused streaming stencil on
- * the vector ALUs, fp32 arithmetic, one rounding at the store.  Any lh >= 1 is accepted; long
- * filters fall to a slower general kernel.  q,k,v,y: [B,L,D] of `dtype`; h: fp32 [D/group, lh].
+ * the vector ALUs, fp32 arithmetic, one rounding at the store.  Any lh >= 1 is accepted; filters
+ * longer than 8 taps take the chunk-parallel matrix-core path described under hyena_mr_fwd when it
+ * applies, else a slower general kernel.  q,k,v,y: [B,L,D] of `dtype`; h: fp32 [D/group, lh].
  */
 hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
                        int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
@@ -58,8 +59,11 @@ hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float 
  * group a multiple of 16, D a multiple of 64 and lh <= 257 the convolution is evaluated as the
  * block-Toeplitz contraction of Sec. 3.1 (hat y_n = sum_k H_k hat x_{n-k}) on bf16 matrix cores with
  * fp32 accumulation: u = k*v is rounded once to bf16, h is rounded once to bf16, the output is
- * rounded once at the store.  Every other valid combination (HY_F32, other group sizes, longer
- * filters) runs a general fp32 vector-ALU kernel.
+ * rounded once at the store.  For HY_BF16 with any other group size (down to one filter per
+ * channel), D a multiple of 64 and lh <= 145, the same contraction runs chunk-parallel (App. A.1):
+ * 16 consecutive 16-step chunks of one channel are the columns of the product and the Toeplitz
+ * operand is per channel; same roundings.  Every other valid combination (HY_F32, other widths,
+ * longer filters) runs a general fp32 vector-ALU kernel.
  */
 hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
                        int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
