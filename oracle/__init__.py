@@ -5,7 +5,9 @@ this package.  It imports nothing from the HIP package and shares no code with i
 
 What it computes (paper Sec. 2.1 Eq. 1, Sec. 2.2 filter grouping, Sec. 3.1 Eq. 2):
 ``y[b,t,c] = q[b,t,c] * sum_{j<l_h, j<=t} h[c // d_g, j] * k[b,t-j,c] * v[b,t-j,c]`` in fp64, inputs
-widened exactly from the bits handed over (fp64, fp32 or bf16).
+widened exactly from the bits handed over (fp64, fp32 or bf16).  For Hyena-LI (Sec. 2.1) the filter is the sum
+of real exponentials ``h[g, j] = sum_n R[g, n] lam[g, n]^j``, materialised over the whole sequence and fed to the
+same direct convolution (``li_filter``, ``li_conv``): the definition, not the recurrence and not an FFT.
 """
 from __future__ import annotations
 
@@ -207,6 +209,31 @@ def gated_conv_bwd(dy, q, k, v, h, group: int = 1):
     _ok(_load().oracle_gated_conv_bwd(_ptr(ga), _ptr(qa), _ptr(ka), _ptr(va), _ptr(ha), _ptr(dq), _ptr(dk), _ptr(dv),
                                       _ptr(dh), B, L, D, ha.shape[1], group, xd, hd), "oracle_gated_conv_bwd")
     return dq, dk, dv, dh
+
+
+def li_filter(R, lam, L: int) -> np.ndarray:
+    """Hyena-LI inner filter (Sec. 2.1, "long implicit"): a sum of real exponentials per filter group,
+    ``h[g, j] = sum_n R[g, n] * lam[g, n] ** j`` for j = 0 .. L-1, i.e. the paper's ``h_t = sum_n R_n lambda_n^(t-1)``
+    with t counted from 1, so tap 0 is ``sum_n R_n`` (0 ** 0 = 1).  R, lam: [G, d]; returns fp64 [G, L]."""
+    R = np.asarray(R, dtype=np.float64)
+    lam = np.asarray(lam, dtype=np.float64)
+    if R.ndim != 2 or R.shape != lam.shape:
+        raise ValueError("R and lam must share one [G, d] shape")
+    j = np.arange(int(L), dtype=np.int64)
+    h = np.zeros((R.shape[0], int(L)), dtype=np.float64)
+    for n in range(R.shape[1]):  # one exponential at a time: [G, L] temporaries only
+        h += R[:, n, None] * np.power(lam[:, n, None], j[None, :])
+    return h
+
+
+def li_conv(q, k, v, R, lam, group: int = 1) -> np.ndarray:
+    """Hyena-LI inner operator: ``gated_conv`` with the filter of ``li_filter`` as long as the sequence."""
+    return gated_conv(q, k, v, li_filter(R, lam, int(q.shape[1])), group=group)
+
+
+def li_conv_points(q, k, v, R, lam, pts, group: int = 1) -> np.ndarray:
+    """``li_conv`` evaluated only at the listed (b, t, c) outputs."""
+    return gated_conv_points(q, k, v, li_filter(R, lam, int(q.shape[1])), pts, group=group)
 
 
 def rel_err(y, y_ref) -> float:
