@@ -70,6 +70,31 @@ hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float 
                        void *hip_stream);
 
 /*
+ * Hyena-LI inner operator, forward (Sec. 2.1, the "long implicit" filter; gates as in Eq. 1 / Algorithm 1):
+ *     y[b,t,c] = q[b,t,c] * sum_{j=0}^{t} h[c/group, j] * k[b,t-j,c] * v[b,t-j,c],
+ *     h[g, j]  = sum_{n=0}^{order-1} R[g,n] * lambda[g,n]^j         (the paper's h_t with t = j + 1)
+ * The filter is as long as the sequence and is never materialised: the sum of exponentials is evaluated
+ * in its recurrent form, as a chunked scan whose per-chunk products run on the bf16 matrix cores with
+ * fp32 accumulation (HY_BF16, group a multiple of 16, D a multiple of 64); u = k*v and the filter
+ * coefficients are rounded once to bf16, the running sums stay in fp32.  Other valid combinations run the
+ * plain fp32 recurrence, one lane per channel.  1 <= order <= 16, else HY_ERR_UNSUPPORTED.
+ * q,k,v,y: [B,L,D] of `dtype` (device); R, lambda: fp32 [D/group, order] (device).  |lambda| <= 1 is the
+ * caller's business: larger poles overflow like the definition does.
+ * workspace: device memory of at least hyena_li_workspace_bytes(...) bytes, 16-byte aligned, disjoint
+ * from every argument, owned by the caller, contents undefined afterwards; may be NULL when that size
+ * is 0.  workspace_bytes is its size: HY_ERR_SHAPE if too small or negative.
+ */
+hy_status hyena_li_fwd(const void *q, const void *k, const void *v, const float *R, const float *lambda,
+                       void *y, void *workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D,
+                       int32_t order, int32_t group, int32_t dtype, void *hip_stream);
+
+/* Bytes of workspace hyena_li_fwd needs for this problem under the current tuning options (0 when the
+ * sequence is scanned in one piece or by the general kernel), -1 if the arguments are not a valid
+ * problem.  Host-only. */
+int64_t hyena_li_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order, int32_t group,
+                                 int32_t dtype);
+
+/*
  * Featurizer convolution, forward (Sec. 2.1 Eq. 1, first three lines: the short explicit filters
  * h_T, h_H, h_K applied to the projected q, k, v; no gating):
  *     y[b,t,c] = sum_{j=0}^{min(lh-1,t)} h[c/group, j] * x[b,t-j,c]

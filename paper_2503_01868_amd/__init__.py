@@ -10,9 +10,11 @@ from .binding import (  # noqa: F401
     plan_chain,
     plan_featurize3,
     plan_gated,
+    plan_li,
     hyena_chain_fwd,
     hyena_featurize3_fwd,
     hyena_featurize_fwd,
+    hyena_li_fwd,
     hyena_mr_bwd,
     hyena_mr_fwd,
     hyena_se_bwd,

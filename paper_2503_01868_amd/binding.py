@@ -46,10 +46,14 @@ def lib() -> ctypes.CDLL:
         L.hyena_mr_bwd.argtypes = bwd_args
         L.hyena_bwd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_bwd_workspace_bytes.restype = i64
+        L.hyena_li_fwd.argtypes = [vp] * 7 + [i64, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_li_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
+        L.hyena_li_workspace_bytes.restype = i64
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd",
-                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_stream_copy", "hyena_set_option"):
+                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_stream_copy",
+                     "hyena_set_option"):
             getattr(L, name).restype = ci
         L.hyena_status_string.argtypes = [ci]
         L.hyena_status_string.restype = ctypes.c_char_p
@@ -332,6 +336,38 @@ def hyena_se_bwd(dy, q, k, v, h, group: int = 1, workspace=None, stream=None):
 def hyena_mr_bwd(dy, q, k, v, h, group: int = 16, workspace=None, stream=None):
     """(dq, dk, dv, dh) of ``hyena_mr_fwd``; see ``hyena_mr_bwd`` in hyena.h."""
     return _bwd("hyena_mr_bwd", dy, q, k, v, h, group, workspace, stream)
+
+
+def plan_li(q, k, v, R, lam, group: int = 16, out=None, workspace=None, stream=None) -> Plan:
+    """Marshal one ``hyena_li_fwd`` call for repeated issue (workspace sized under the current options)."""
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    order = _check_filter("R", R, q, group)
+    if _check_filter("lam", lam, q, group) != order:
+        raise ValueError("R and lam must share one [D // group, order] shape")
+    y = torch.empty_like(q) if out is None else out
+    _check_act("out", y, q)
+    B, L, D = q.shape
+    code = _dtype_code(q)
+    need = int(lib().hyena_li_workspace_bytes(B, L, D, order, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid Hyena-LI problem")
+    if need > 0 and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    c = ctypes
+    ws_ptr = workspace.data_ptr() if need > 0 else None
+    ws_bytes = workspace.numel() * workspace.element_size() if need > 0 else 0
+    args = tuple(c.c_void_p(t.data_ptr()) for t in (q, k, v, R, lam, y)) + (
+        c.c_void_p(ws_ptr), c.c_int64(ws_bytes), c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(order),
+        c.c_int32(int(group)), c.c_int(code), c.c_void_p(_stream(q, stream)))
+    return Plan(lib().hyena_li_fwd, args, "hyena_li_fwd", (q, k, v, R, lam, y, workspace), y)
+
+
+def hyena_li_fwd(q, k, v, R, lam, group: int = 16, out=None, workspace=None, stream=None) -> torch.Tensor:
+    """y = q * (h conv (k * v)) with h[g, j] = sum_n R[g, n] lam[g, n]^j; see ``hyena_li_fwd`` in hyena.h."""
+    with torch.cuda.device(q.device):
+        return plan_li(q, k, v, R, lam, group, out, workspace, stream)()
 
 
 def hyena_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.Tensor:

@@ -201,6 +201,46 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
     return rc;
 }
 
+int64_t hyena_li_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype) {
+    if (B < 0 || L < 0 || D < 0 || order < 1 || group < 1 || D % group != 0) return -1;
+    if (dtype != HY_F32 && dtype != HY_BF16) return -1;
+    if (empty(B, L, D)) return 0;
+    LiShape s{B, L, D, order, group, static_cast<hy_dtype>(dtype)};
+    return li_workspace_bytes(s);
+}
+
+hy_status hyena_li_fwd(const void* q, const void* k, const void* v, const float* R, const float* lambda, void* y,
+                       void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D, int32_t order,
+                       int32_t group, int32_t dtype, void* hip_stream) {
+    const void* ins[3] = {q, k, v};
+    void* outs[1] = {y};
+    const float* hs[2] = {R, lambda};
+    hy_status rc = validate(ins, 3, outs, 1, hs, 2, B, L, D, order, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (workspace_bytes < 0) return HY_ERR_SHAPE;
+    if (order > 16) return HY_ERR_UNSUPPORTED;
+    if (empty(B, L, D)) return HY_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    LiPtrs p{q, k, v, R, lambda, y};
+    LiShape s{B, L, D, order, group, static_cast<hy_dtype>(dtype)};
+    if (li_mfma_supported(s)) {
+        const int64_t need = li_workspace_bytes(s);
+        if (need > 0) {
+            if (!workspace) return HY_ERR_NULL;
+            if (!aligned16(workspace)) return HY_ERR_ALIGN;
+            if (workspace_bytes < need) return HY_ERR_SHAPE;
+            const int64_t bytes = B * L * D * 2;
+            const void* all[4] = {q, k, v, y};
+            for (int i = 0; i < 4; ++i)
+                if (overlaps2(all[i], bytes, workspace, need)) return HY_ERR_ALIGN;
+            const int64_t nf = (D / group) * (int64_t)order * (int64_t)sizeof(float);
+            if (overlaps2(R, nf, workspace, need) || overlaps2(lambda, nf, workspace, need)) return HY_ERR_ALIGN;
+        }
+        return launch_li_mfma(p, s, workspace, st);
+    }
+    return launch_li_direct(p, s, st);
+}
+
 int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
     if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1 || D % group != 0) return -1;
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;

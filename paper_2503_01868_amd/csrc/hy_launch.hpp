@@ -60,6 +60,22 @@ struct BwdShape {
     hy_dtype dtype;
 };
 
+// Hyena-LI forward: filter given by residues R and poles lam, fp32 [D/group, order] each.
+struct LiPtrs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const float* R;
+    const float* lam;
+    void* y;
+};
+
+struct LiShape {
+    int64_t B, L, D;
+    int32_t order, group;
+    hy_dtype dtype;
+};
+
 struct Tuning {
     int se_vec = 0;
     int se_rows = 0;
@@ -81,6 +97,11 @@ hy_status launch_cp_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // Whole chain in one pass over q, k, v.  HY_ERR_UNSUPPORTED outside chain_fused_supported().
 bool chain_fused_supported(const ChainShape& s);
 hy_status launch_chain_fused(const ChainPtrs& p, const ChainShape& s, hipStream_t st);
+// Hyena-LI as a two-pass chunked scan on bf16 MFMA (end-of-tile states in `ws`), and the plain recurrence.
+bool li_mfma_supported(const LiShape& s);
+int64_t li_workspace_bytes(const LiShape& s);
+hy_status launch_li_mfma(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st);
+hy_status launch_li_direct(const LiPtrs& p, const LiShape& s, hipStream_t st);
 // Backward, short filters: fused streaming pass + reduction of partial filter gradients held in `ws`.
 bool bwd_stencil_supported(const BwdShape& s);
 int64_t bwd_stencil_workspace_bytes(const BwdShape& s);

@@ -1,0 +1,427 @@
+// Hyena-LI forward on gfx950: gated causal convolution with the long implicit filter of Sec. 2.1,
+//   h[g, j] = sum_{n < order} R[g, n] * lambda[g, n]^j,   j = 0 .. L-1  (as long as the sequence).
+// The filter is never materialised.  Because it is a sum of real exponentials, everything older than the
+// current 32-step chunk acts through `order` running sums per channel (the recurrent form the paper
+// mentions for this operator), and the whole operator becomes three small dense products per chunk:
+//   z_chunk = T u_chunk + Q s,        T[t, i] = h[t - i] (lower triangular, 32 x 32: the H_0 of Sec. 3.1),
+//                                      Q[t, n] = R_n lambda_n^(t+1),
+//   s'      = Lambda^32 s + P u_chunk, P[n, i] = lambda_n^(31-i),   s[n, c] = sum_{i<=end} lambda_n^(end-i) u[i, c].
+// With 16 channels of one filter group on a matrix tile (as in mr_kernels.hip) these are two
+// v_mfma_f32_16x16x32_bf16 for T, one for P and two pairs of v_mfma_f32_16x16x16_bf16 for Q; s stays in fp32
+// accumulators and enters the Q product split into a bf16 head and a bf16 remainder, so carrying the state
+// over 10^5 steps costs no precision beyond the bf16 rounding of the coefficients.  The state product comes
+// out with 4 consecutive n of one channel per lane, which is exactly the operand layout of the Q product:
+// the state never leaves its registers.
+//
+// The recurrence runs along time, and one GPU needs more than B * D / 256 workgroups, so the sequence is cut
+// into tiles and scanned in two passes (the classic chunked scan): pass 1 walks every tile but the last of
+// each sequence with a zero start and leaves the tile's final state in a workspace (reads k and v only);
+// pass 2 rebuilds its start state from the tiles before it, s_in = sum_tau Lambda^(rows * (tile-1-tau)) s_tau
+// (a short Horner loop over 1 KiB records), and computes y.  With a single tile per sequence pass 1 is skipped.
+// Data movement per chunk is that of mr_kernels.hip: whole row pieces, u and z through LDS, one barrier.
+#include "hy_common.hpp"
+#include "hy_launch.hpp"
+
+namespace hy {
+namespace {
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+struct LiArgs {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    const float* R;
+    const float* lam;
+    uint16_t* y;
+    float* ws;              // [B][tiles_per_seq - 1][D / 16][64 lanes][4] end-of-tile states
+    int64_t L, D;
+    int32_t order, group;
+    int32_t rows;           // time steps per workgroup, multiple of 32
+    int32_t tiles_per_seq;  // ceil(L / rows)
+    int32_t ncb;            // channel blocks = D / (16 NW)
+};
+
+constexpr int kChunk = 32;
+constexpr int kMaxOrder = 16;
+
+__device__ __forceinline__ float powi(float x, int e) {  // x^e, e >= 0, by squaring
+    float r = 1.0f;
+    while (e > 0) {
+        if (e & 1) r *= x;
+        x *= x;
+        e >>= 1;
+    }
+    return r;
+}
+
+// kStateOnly: pass 1 (no q, no output, the tile's final state goes to the workspace).
+template <int NW, int kPrefetch, bool kStateOnly>
+__global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiArgs a) {
+    constexpr int PPR = 2 * NW;             // 16-byte pieces per staged row of u (bf16)
+    constexpr int ZROW = 16 * NW * 4 + 16;  // bytes per staged row of z (fp32), padded against bank conflicts
+    static_assert(NW % 4 == 0, "the LDS swizzle needs 8 pieces per row");
+    __shared__ uint4 stage[2][kChunk * PPR];
+    __shared__ __attribute__((aligned(16))) char zst[kStateOnly ? 1 : 2][kStateOnly ? 16 : kChunk * ZROW];
+    __shared__ float rs[NW][kMaxOrder], ls[NW][kMaxOrder], hs[NW][kChunk];
+
+    const int tid = threadIdx.x;
+    const int w = tid / 64, lane = tid % 64;
+    const int li = lane % 16, lq = lane / 16;
+
+    const uint32_t lb = blockIdx.x;
+    const int cb = lb % a.ncb;
+    const int64_t tl = lb / a.ncb;
+    const int tiles_run = kStateOnly ? a.tiles_per_seq - 1 : a.tiles_per_seq;  // pass 1 skips the last tile
+    const int64_t b = tl / tiles_run;
+    const int tile = (int)(tl % tiles_run);
+    const int64_t t_start = (int64_t)tile * a.rows;
+    const int64_t t_end = (t_start + a.rows < a.L) ? t_start + a.rows : a.L;
+    const int nchunks = (int)((t_end - t_start + kChunk - 1) / kChunk);
+
+    const int64_t D = a.D;
+    const int64_t cblock0 = (int64_t)cb * 16 * NW;
+    const int64_t c0 = cblock0 + 16 * w;
+    const int64_t seq0 = b * a.L * D;
+
+    const int lr = tid / PPR, lp = tid % PPR;
+    const int64_t ld_off = cblock0 + 8 * lp;
+    // unconditional, clamped loads (see mr_kernels.hip): rows past the end of the tile re-read its last row
+    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
+        const int cic = ci < nchunks ? ci : nchunks - 1;
+        int64_t t = t_start + (int64_t)cic * kChunk + lr;
+        t = t < t_end ? t : t_end - 1;
+        kk = load_words_nt<4>(a.k + seq0 + t * D + ld_off);
+        vv = load_words_nt<4>(a.v + seq0 + t * D + ld_off);
+    };
+    auto load_q = [&](int ci, Words<4>& qq) {
+        const int cic = ci < nchunks ? ci : nchunks - 1;
+        int64_t t = t_start + (int64_t)cic * kChunk + lr;
+        t = t < t_end ? t : t_end - 1;
+        qq = load_words_nt<4>(a.q + seq0 + t * D + ld_off);
+    };
+
+    Words<4> kpre[kPrefetch], vpre[kPrefetch], qpre[kPrefetch];
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) {
+        load_kv(i, kpre[i], vpre[i]);
+        if constexpr (!kStateOnly)
+            if (i + 1 < kPrefetch) load_q(i, qpre[i]);
+    }
+
+    // ---- per-wave filter set-up: residues and poles of the wave's group, taps 0..31 of the implicit filter
+    {
+        const int64_t g = c0 / a.group;
+        if (lane < kMaxOrder) {
+            rs[w][lane] = lane < a.order ? a.R[g * a.order + lane] : 0.0f;
+            ls[w][lane] = lane < a.order ? a.lam[g * a.order + lane] : 0.0f;
+        }
+    }
+    __syncthreads();
+    if (lane < kChunk) {
+        float hj = 0.0f;
+        for (int n = 0; n < kMaxOrder; ++n) hj += rs[w][n] * powi(ls[w][n], lane);
+        hs[w][lane] = hj;
+    }
+    __syncthreads();
+
+    // T operands: tile x (steps 16x..16x+15 of the chunk) against the chunk's 32 source steps; lane (li = step,
+    // lq = source octet), element e = h[16x + li - 8lq - e]
+    bf16x8_t tz[2];
+    if constexpr (!kStateOnly) {
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            Words<4> wds;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const int i0 = 16 * x + li - 8 * lq - 2 * e2;
+                const int i1 = i0 - 1;
+                const float f0 = (i0 >= 0 && i0 < kChunk) ? hs[w][i0] : 0.0f;
+                const float f1 = (i1 >= 0 && i1 < kChunk) ? hs[w][i1] : 0.0f;
+                wds.w[e2] = pack_bf16x2(f0, f1);
+            }
+            tz[x] = __builtin_bit_cast(bf16x8_t, wds);
+        }
+    }
+    // P operand: lane (li = n, lq = source octet), element e = lambda_n^(31 - 8lq - e)
+    bf16x8_t pop;
+    {
+        const float ln = ls[w][li];
+        Words<4> wds;
+        float pw = powi(ln, 31 - 8 * lq - 7);  // smallest exponent of the lane (element 7), then multiply up
+        float pe[8];
+#pragma unroll
+        for (int e = 7; e >= 0; --e) {
+            pe[e] = pw;
+            pw *= ln;
+        }
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) wds.w[e2] = pack_bf16x2(pe[2 * e2], pe[2 * e2 + 1]);
+        pop = __builtin_bit_cast(bf16x8_t, wds);
+    }
+    // state layout: lane (li = channel, lq) holds s[n = 4lq + r][channel], r = 0..3
+    float lam32[4], lam_rows[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        lam32[r] = powi(ls[w][4 * lq + r], kChunk);
+        lam_rows[r] = powi(ls[w][4 * lq + r], a.rows);
+    }
+    // Q operands: lane (li = step of tile x, lq), element e = R_n lambda_n^(16x + li + 1), n = 4lq + e
+    s16x4_t qop[2];
+    if constexpr (!kStateOnly) {
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            float qe[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) qe[e] = rs[w][4 * lq + e] * powi(ls[w][4 * lq + e], 16 * x + li + 1);
+            Words<2> wds;
+            wds.w[0] = pack_bf16x2(qe[0], qe[1]);
+            wds.w[1] = pack_bf16x2(qe[2], qe[3]);
+            qop[x] = __builtin_bit_cast(s16x4_t, wds);
+        }
+    }
+
+    // ---- start state: zero at the start of a sequence, else the Horner sum over the earlier tiles' end states
+    f32x4_t s = {0.0f, 0.0f, 0.0f, 0.0f};
+    const int64_t ws_wave = ((c0 / 16) * 64 + lane) * 4;  // this lane's 4 floats inside one (b, tile) record set
+    const int64_t ws_tile = (D / 16) * 256;               // floats per (b, tile)
+    if constexpr (!kStateOnly) {
+        const float* wp = a.ws + b * (a.tiles_per_seq - 1) * ws_tile + ws_wave;
+        for (int tau = 0; tau < tile; ++tau) {
+            const float4 st = *reinterpret_cast<const float4*>(wp + tau * ws_tile);
+            s[0] = lam_rows[0] * s[0] + st.x;
+            s[1] = lam_rows[1] * s[1] + st.y;
+            s[2] = lam_rows[2] * s[2] + st.z;
+            s[3] = lam_rows[3] * s[3] + st.w;
+        }
+    }
+
+    const int swz = ((lr >> 3) & 3) << 1;
+    const int st_idx = lr * PPR + (lp ^ swz);
+    const int rd_piece = (2 * w + (li >> 3)) ^ (lq << 1);
+    const int zwr_off = li * ZROW + (16 * w + 4 * lq) * 4;
+    const int zrd_off = lr * ZROW + 8 * lp * 4;
+
+    auto gate_store = [&](int ci, const Words<4>& qq) {
+        const int64_t t = t_start + (int64_t)ci * kChunk + lr;
+        if (t < t_end) {
+            const char* zp = zst[ci & 1] + zrd_off;
+            const float4 za = *reinterpret_cast<const float4*>(zp);
+            const float4 zb = *reinterpret_cast<const float4*>(zp + 16);
+            float qf[8];
+            Pack<BF16, 8>::unpack(qq, qf);
+            float y8[8] = {za.x * qf[0], za.y * qf[1], za.z * qf[2], za.w * qf[3],
+                           zb.x * qf[4], zb.y * qf[5], zb.z * qf[6], zb.w * qf[7]};
+            store_words_nt<4>(a.y + seq0 + t * D + ld_off, Pack<BF16, 8>::pack(y8));
+        }
+    };
+
+    for (int base = 0; base < nchunks; base += kPrefetch) {
+#pragma unroll
+        for (int sgi = 0; sgi < kPrefetch; ++sgi) {
+            const int ci = base + sgi;
+            const bool live = ci < nchunks;
+            {
+                float kf[8], vf[8];
+                Pack<BF16, 8>::unpack(kpre[sgi], kf);
+                Pack<BF16, 8>::unpack(vpre[sgi], vf);
+                Words<4> uu;
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2)
+                    uu.w[e2] = pack_bf16x2(kf[2 * e2] * vf[2 * e2], kf[2 * e2 + 1] * vf[2 * e2 + 1]);
+                stage[ci & 1][st_idx] = make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]);
+            }
+            load_kv(ci + kPrefetch, kpre[sgi], vpre[sgi]);
+
+            __syncthreads();
+
+            // transposed read: element e of this lane = u[row 8 lq + e][channel 16 w + li]
+            bf16x8_t uw;
+            {
+                const uint16_t* s16 = reinterpret_cast<const uint16_t*>(stage[ci & 1]);
+                Words<4> wds;
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const int r0 = 8 * lq + 2 * e2;
+                    const uint32_t lo = s16[((r0 * PPR + rd_piece) << 3) + (li & 7)];
+                    const uint32_t hi = s16[(((r0 + 1) * PPR + rd_piece) << 3) + (li & 7)];
+                    wds.w[e2] = lo | (hi << 16);
+                }
+                uw = __builtin_bit_cast(bf16x8_t, wds);
+            }
+
+            if (live) {
+                if constexpr (!kStateOnly) {
+                    // carry-in: the state in two bf16 parts, head and remainder
+                    const uint32_t h01 = pack_bf16x2(s[0], s[1]), h23 = pack_bf16x2(s[2], s[3]);
+                    const uint32_t l01 = pack_bf16x2(s[0] - bf16_lo(h01), s[1] - bf16_hi(h01));
+                    const uint32_t l23 = pack_bf16x2(s[2] - bf16_lo(h23), s[3] - bf16_hi(h23));
+                    Words<2> hw, lw;
+                    hw.w[0] = h01; hw.w[1] = h23;
+                    lw.w[0] = l01; lw.w[1] = l23;
+                    const s16x4_t shi = __builtin_bit_cast(s16x4_t, hw), slo = __builtin_bit_cast(s16x4_t, lw);
+                    f32x4_t acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw, tz[0], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw, tz[1], acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop[0], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop[1], acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(slo, qop[0], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(slo, qop[1], acc1, 0, 0, 0);
+                    char* zp = zst[ci & 1] + zwr_off;
+                    *reinterpret_cast<float4*>(zp) = make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
+                    *reinterpret_cast<float4*>(zp + 16 * ZROW) = make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
+                }
+                // state update: s' = Lambda^32 s + P u
+                s[0] *= lam32[0];
+                s[1] *= lam32[1];
+                s[2] *= lam32[2];
+                s[3] *= lam32[3];
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pop, uw, s, 0, 0, 0);
+            }
+            if constexpr (!kStateOnly) {
+                const int prev = (sgi + kPrefetch - 1) % kPrefetch;
+                if (ci > 0 && ci <= nchunks) gate_store(ci - 1, qpre[prev]);
+                load_q(ci - 1 + kPrefetch, qpre[prev]);
+            }
+        }
+    }
+    if constexpr (!kStateOnly) {
+        if (nchunks % kPrefetch == 0) {
+            __syncthreads();
+            gate_store(nchunks - 1, qpre[kPrefetch - 1]);
+        }
+    } else {
+        float* wp = a.ws + (b * (a.tiles_per_seq - 1) + tile) * ws_tile + ws_wave;
+        *reinterpret_cast<float4*>(wp) = make_float4(s[0], s[1], s[2], s[3]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// General kernel: the recurrence itself, one lane per (batch item, channel), fp32 states.  Any dtype, any
+// group; slow (B * D lanes in all), the correctness path for what the matrix-core kernel does not take.
+template <typename T>
+__global__ __launch_bounds__(64) void li_direct_kernel(const void* qv, const void* kv, const void* vv, const float* R,
+                                                       const float* lam, void* yv, int64_t B, int64_t L, int64_t D,
+                                                       int32_t order, int32_t group) {
+    const int64_t idx = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (idx >= B * D) return;
+    const int64_t b = idx / D, c = idx % D;
+    const int64_t g = c / group;
+    float rn[kMaxOrder], ln[kMaxOrder], sn[kMaxOrder];
+#pragma unroll
+    for (int n = 0; n < kMaxOrder; ++n) {
+        rn[n] = n < order ? R[g * order + n] : 0.0f;
+        ln[n] = n < order ? lam[g * order + n] : 0.0f;
+        sn[n] = 0.0f;
+    }
+    const char* qp = static_cast<const char*>(qv);
+    const char* kp = static_cast<const char*>(kv);
+    const char* vp = static_cast<const char*>(vv);
+    char* yp = static_cast<char*>(yv);
+    for (int64_t t = 0; t < L; ++t) {
+        const int64_t off = ((b * L + t) * D + c) * T::kBytes;
+        float qf[1], kf[1], vf[1];
+        Pack<T, 1>::unpack(Pack<T, 1>::load(qp + off), qf);
+        Pack<T, 1>::unpack(Pack<T, 1>::load(kp + off), kf);
+        Pack<T, 1>::unpack(Pack<T, 1>::load(vp + off), vf);
+        const float u = kf[0] * vf[0];
+        float z = 0.0f;
+#pragma unroll
+        for (int n = 0; n < kMaxOrder; ++n) {
+            sn[n] = __builtin_fmaf(ln[n], sn[n], u);
+            z = __builtin_fmaf(rn[n], sn[n], z);
+        }
+        float y1[1] = {qf[0] * z};
+        Pack<T, 1>::store(yp + off, Pack<T, 1>::pack(y1));
+    }
+}
+
+int64_t li_rows(const LiShape& s, int nw) {
+    int64_t rows = tuning().mr_rows;
+    const int64_t ncb = s.D / (16 * nw);
+    if (rows <= 0) {
+        int64_t tiles = 256 / (s.B * ncb);
+        if (tiles < 1) tiles = 1;
+        rows = (s.L + tiles - 1) / tiles;
+        if (rows < 4 * kChunk) rows = 4 * kChunk;
+    }
+    rows = (rows + kChunk - 1) / kChunk * kChunk;
+    const int64_t cap = (s.L + kChunk - 1) / kChunk * kChunk;
+    return rows > cap ? cap : rows;
+}
+
+int li_waves(const LiShape& s) {
+    const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 16;
+    if (nw == 16 && s.D % 256 == 0) return 16;
+    if (nw >= 8 && s.D % 128 == 0) return 8;
+    return 4;
+}
+
+template <int NW>
+hy_status launch_li_nw(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st) {
+    constexpr int PF = 2;
+    LiArgs a;
+    a.q = static_cast<const uint16_t*>(p.q);
+    a.k = static_cast<const uint16_t*>(p.k);
+    a.v = static_cast<const uint16_t*>(p.v);
+    a.R = p.R;
+    a.lam = p.lam;
+    a.y = static_cast<uint16_t*>(p.y);
+    a.ws = static_cast<float*>(ws);
+    a.L = s.L;
+    a.D = s.D;
+    a.order = s.order;
+    a.group = s.group;
+    a.ncb = (int32_t)(s.D / (16 * NW));
+    const int64_t rows = li_rows(s, NW);
+    a.rows = (int32_t)rows;
+    a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
+    const int64_t nb2 = s.B * a.tiles_per_seq * a.ncb;
+    const int64_t nb1 = s.B * (a.tiles_per_seq - 1) * a.ncb;
+    if (nb2 > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
+    if (nb1 > 0) {
+        hipLaunchKernelGGL((li_mfma_kernel<NW, PF, true>), dim3((uint32_t)nb1), dim3(NW * 64), 0, st, a);
+        if (launch_status() != HY_OK) return HY_ERR_LAUNCH;
+    }
+    hipLaunchKernelGGL((li_mfma_kernel<NW, PF, false>), dim3((uint32_t)nb2), dim3(NW * 64), 0, st, a);
+    return launch_status();
+}
+
+}  // namespace
+
+bool li_mfma_supported(const LiShape& s) {
+    return s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.order >= 1 && s.order <= kMaxOrder &&
+           s.L <= 0x7fffffffLL - 64;
+}
+
+int64_t li_workspace_bytes(const LiShape& s) {
+    if (!li_mfma_supported(s) || s.B == 0 || s.L == 0 || s.D == 0) return 0;
+    const int64_t rows = li_rows(s, li_waves(s));
+    const int64_t tiles = (s.L + rows - 1) / rows;
+    return s.B * (tiles - 1) * (s.D / 16) * 256 * (int64_t)sizeof(float);
+}
+
+hy_status launch_li_mfma(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st) {
+    if (!li_mfma_supported(s)) return HY_ERR_UNSUPPORTED;
+    switch (li_waves(s)) {
+        case 16: return launch_li_nw<16>(p, s, ws, st);
+        case 8: return launch_li_nw<8>(p, s, ws, st);
+        default: return launch_li_nw<4>(p, s, ws, st);
+    }
+}
+
+hy_status launch_li_direct(const LiPtrs& p, const LiShape& s, hipStream_t st) {
+    if (s.order < 1 || s.order > kMaxOrder) return HY_ERR_UNSUPPORTED;
+    const int64_t n = s.B * s.D;
+    const int64_t nb = (n + 63) / 64;
+    if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
+    if (s.dtype == HY_F32)
+        hipLaunchKernelGGL((li_direct_kernel<F32>), dim3((uint32_t)nb), dim3(64), 0, st, p.q, p.k, p.v, p.R, p.lam, p.y,
+                           s.B, s.L, s.D, s.order, s.group);
+    else
+        hipLaunchKernelGGL((li_direct_kernel<BF16>), dim3((uint32_t)nb), dim3(64), 0, st, p.q, p.k, p.v, p.R, p.lam, p.y,
+                           s.B, s.L, s.D, s.order, s.group);
+    return launch_status();
+}
+
+}  // namespace hy

@@ -26,6 +26,9 @@ CONFIGS = {
     "c4": dict(kind="chain", B=4, L=32768, D=4096, lh=128, group=16, lf=7, feat_group=1, dtype="bf16"),
     # not one of the five: c2 with a filter per channel (no grouping), the shape of the chunk-parallel path (App. A.1)
     "c2u": dict(kind="mr", B=1, L=8192, D=4096, lh=128, group=1, dtype="bf16"),
+    # not of the five either: Hyena-LI (long implicit filter, Sec. 2.1) at the shapes of c2 and c3
+    "li2": dict(kind="li", B=1, L=8192, D=4096, order=16, group=16, dtype="bf16"),
+    "li3": dict(kind="li", B=1, L=131072, D=4096, order=16, group=16, dtype="bf16"),
 }
 
 _BASE_SEED = 186800
@@ -66,6 +69,15 @@ def decay_filter(rng: np.random.Generator, n_filters: int, lh: int) -> np.ndarra
     return (w * np.exp(-alpha * j)).astype(np.float32)
 
 
+def li_params(rng: np.random.Generator, n_filters: int, order: int):
+    """Residues and poles of the long implicit filter h[g, j] = sum_n R[g, n] lam[g, n]^j (Sec. 2.1):
+    R ~ N(0, 1/order); lam = exp(-a) with a log-uniform in [1e-3, 1], i.e. time constants from one step to a
+    thousand steps, every pole real and inside the unit circle.  fp32 [n_filters, order] each."""
+    R = rng.standard_normal(size=(n_filters, order)) * order ** -0.5
+    a = np.exp(rng.uniform(np.log(1e-3), np.log(1.0), size=(n_filters, order)))
+    return R.astype(np.float32), np.exp(-a).astype(np.float32)
+
+
 def make(name: str, variant: int = 0, **overrides) -> dict:
     """Build one workload on the host.
 
@@ -80,6 +92,9 @@ def make(name: str, variant: int = 0, **overrides) -> dict:
     for key in ("q", "k", "v"):
         out[key] = normal_tensor(rng, shape, cfg["dtype"])
     n_filters = cfg["D"] // cfg["group"]
+    if cfg["kind"] == "li":
+        out["R"], out["lam"] = li_params(rng, n_filters, cfg["order"])
+        return out
     if cfg["kind"] == "se":
         out["h"] = short_filter(rng, n_filters, cfg["lh"])
     else:

@@ -38,7 +38,7 @@ def test_binding_exposes_the_same_names():
     import paper_2503_01868_amd as pkg
 
     for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd", "hyena_chain_fwd",
-                 "hyena_se_bwd", "hyena_mr_bwd", "hyena_stream_copy"):
+                 "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_stream_copy"):
         assert callable(getattr(pkg, name))
 
 
@@ -172,3 +172,33 @@ def test_backward_entry_points_reject_bad_arguments_and_size_their_workspace():
     assert wb(1, 100, 64, 128, 16, 1) == 1 * 1 * (64 // 16) * 128 * 4   # matrix-core path: one row per tile and slice
     assert wb(1, 100, 64, 128, 16, 0) == 0 and wb(1, 100, 40, 50, 1, 1) == 0  # general kernel: no workspace
     assert wb(0, 100, 64, 7, 1, 1) == 0 and wb(1, 100, 64, 0, 1, 1) == -1 and wb(1, 100, 64, 7, 5, 1) == -1
+
+
+def li(q=P[0], k=P[1], v=P[2], R=P[3], lam=P[5], y=P[4], ws=P[6], ws_bytes=1 << 30, B=1, L=8, D=16, order=4, group=1,
+       dtype=0):
+    return binding.lib().hyena_li_fwd(q, k, v, R, lam, y, ws, ws_bytes, B, L, D, order, group, dtype, None)
+
+
+def test_long_implicit_entry_point_rejects_bad_arguments():
+    lib = binding.lib()
+    assert li(q=None) == 1 and li(R=None) == 1 and li(lam=None) == 1 and li(y=None) == 1
+    assert li(B=-1) == 2 and li(order=0) == 2 and li(group=0) == 2 and li(D=16, group=3) == 2
+    assert li(dtype=9) == 3
+    assert li(lam=P[5] + 4) == 4 and li(y=P[2]) == 4
+    assert li(order=17) == 5                      # more exponentials than the kernels hold
+    assert li(ws_bytes=-1) == 2
+    assert li(B=0) == 0 and li(L=0) == 0          # empty problems launch nothing
+    # matrix-core shapes that span several tiles need the workspace: present, aligned, large enough, disjoint
+    big = dict(B=1, L=1 << 16, D=256, order=16, group=16, dtype=1)
+    need = lib.hyena_li_workspace_bytes(big["B"], big["L"], big["D"], big["order"], big["group"], big["dtype"])
+    assert need > 0 and need % 1024 == 0
+    far = 1 << 40
+    ptrs = dict(q=far, k=2 * far, v=3 * far, y=4 * far, R=P[3], lam=P[5])
+    assert li(ws=None, **ptrs, **big) == 1
+    assert li(ws=5 * far + 8, **ptrs, **big) == 4
+    assert li(ws=5 * far, ws_bytes=need - 1, **ptrs, **big) == 2
+    assert li(ws=far + 64, **ptrs, **big) == 4    # inside q
+    assert lib.hyena_li_workspace_bytes(1, 1 << 16, 256, 16, 16, 0) == 0   # fp32: general kernel, no workspace
+    assert lib.hyena_li_workspace_bytes(1, 64, 256, 16, 16, 1) == 0        # one tile
+    assert lib.hyena_li_workspace_bytes(1, 64, 256, 0, 16, 1) == -1
+    assert lib.hyena_li_workspace_bytes(1, 64, 250, 16, 16, 1) == -1

@@ -1,0 +1,155 @@
+"""GPU parity of hyena_li_fwd (Hyena-LI, Sec. 2.1: filter = sum of real exponentials, as long as the sequence)
+against the oracle's definition: filter materialised in fp64 over the whole sequence, direct convolution."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_01868_amd import binding, synth
+
+from gpu_util import TOL, dev, host, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    yield
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves"):
+        binding.set_option(name, 0)
+
+
+def draw_li(seed, B, L, D, order, group, dtype):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(3))
+    R, lam = synth.li_params(rng, D // group, order)
+    return q, k, v, R, lam
+
+
+def check_li(seed, B, L, D, order, group, dtype, tol=None, params=None):
+    say("hyena_li_fwd seed=%d B=%d L=%d D=%d order=%d group=%d dtype=%s" % (seed, B, L, D, order, group, dtype))
+    q, k, v, R, lam = draw_li(seed, B, L, D, order, group, dtype)
+    if params is not None:
+        R, lam = params
+    y = host(binding.hyena_li_fwd(dev(q), dev(k), dev(v), dev(R), dev(lam), group))
+    ref = oracle.li_conv(q, k, v, R, lam, group=group)
+    err = oracle.rel_err(y, ref)
+    assert np.isfinite(y).all()
+    assert err <= (TOL[dtype] if tol is None else tol), err
+    return err
+
+
+# (B, L, D, order, group, rows): rows = 0 keeps the default tile length; small values force many tiles, i.e. the
+# two-pass scan with its workspace
+LI_MFMA_CASES = [
+    (1, 700, 64, 16, 16, 0),        # one tile, ragged last chunk
+    (2, 1000, 128, 16, 16, 128),    # 8 tiles per sequence: pass 1 + Horner over up to 7 states
+    (1, 2300, 256, 8, 32, 256),     # two matrix tiles per filter group, order below 16
+    (1, 515, 64, 1, 16, 32),        # a single exponential, one chunk per tile
+    (3, 96, 64, 16, 64, 32),
+    (1, 1, 64, 16, 16, 0),          # one step
+    (1, 33, 64, 5, 16, 32),         # second tile holds a single step
+    (2, 4096, 64, 16, 16, 1024),
+]
+
+
+@pytest.mark.parametrize("case", LI_MFMA_CASES)
+def test_scan_on_matrix_cores_matches_the_definition(case):
+    B, L, D, order, group, rows = case
+    binding.set_option("mr_rows", rows)
+    check_li(61, B, L, D, order, group, "bf16")
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_every_workgroup_width(waves):
+    binding.set_option("mr_waves", waves)
+    binding.set_option("mr_rows", 160)
+    check_li(62, 2, 900, 512, 16, 16, "bf16")
+
+
+def test_slow_poles_negative_poles_and_a_pole_at_one():
+    """Poles next to the unit circle keep the whole past alive: the state must survive thousands of steps in
+    fp32 and enter the products without losing its low bits.  Negative poles alternate in sign."""
+    B, L, D, order, group = 1, 6000, 64, 4, 16
+    G = D // group
+    lam = np.tile(np.array([0.9999, 1.0, -0.97, 0.5], dtype=np.float32), (G, 1))
+    R = np.tile(np.array([0.5, 0.05, 1.0, -2.0], dtype=np.float32), (G, 1))
+    binding.set_option("mr_rows", 512)
+    check_li(63, B, L, D, order, group, "bf16", params=(R, lam))
+
+
+@pytest.mark.parametrize("case", [
+    (1, 300, 64, 16, 16, "f32"),    # fp32 storage: the plain recurrence
+    (2, 257, 48, 7, 8, "bf16"),     # group smaller than a matrix tile
+    (1, 200, 40, 3, 1, "bf16"),     # one filter per channel
+    (1, 129, 16, 16, 16, "bf16"),   # width below the 64-channel block
+    (2, 500, 32, 2, 4, "f32"),
+])
+def test_general_recurrence_matches_the_definition(case):
+    B, L, D, order, group, dtype = case
+    check_li(64, B, L, D, order, group, dtype)
+
+
+def test_impulse_response_is_bit_exact_across_chunks_and_tiles():
+    """Dyadic residues and poles +-1/2: every coefficient, state and product is a power of two times a small
+    integer, so the response to unit impulses must equal sum_n R_n lambda_n^j bit for bit, through chunk
+    boundaries, tile boundaries (workspace states) and the two-part split of the state.  Compared exactly over
+    the first 100 lags (2^-100 is still a normal number), loosely where the response sinks below that."""
+    B, L, D, group = 2, 700, 64, 16
+    say("impulse hyena_li_fwd")
+    binding.set_option("mr_rows", 128)
+    G = D // group
+    R = np.tile(np.array([1.0, -0.5], dtype=np.float32), (G, 1)) * np.arange(1, G + 1, dtype=np.float32)[:, None]
+    lam = np.tile(np.array([0.5, -0.5], dtype=np.float32), (G, 1))
+    one = torch.ones(B, L, D, dtype=torch.bfloat16)
+    v = torch.zeros(B, L, D, dtype=torch.bfloat16)
+    hits = [(0, 0, 0), (0, 250, 17), (1, 127, 63), (1, 640, 33)]
+    h = oracle.li_filter(R, lam, L)
+    for b, t0, c in hits:
+        v[b, t0, c] = 1.0
+    y = host(binding.hyena_li_fwd(dev(one), dev(one), dev(v), dev(R), dev(lam), group))
+    mask = np.ones((B, L, D), dtype=bool)
+    for b, t0, c in hits:
+        n = min(100, L - t0)
+        want = h[c // group, :n]
+        assert np.array_equal(want, torch.from_numpy(want).bfloat16().double().numpy())  # the case really is exact
+        assert np.array_equal(y[b, t0:t0 + n, c], want)
+        assert np.all(np.abs(y[b, t0 + n:, c]) <= 2.0 ** -98)
+        mask[b, t0:, c] = False
+    assert np.all(y[mask] == 0.0)
+
+
+def test_guard_bands_determinism_and_no_leak_between_batch_items():
+    B, L, D, order, group = 2, 301, 128, 16, 16
+    say("guard bands hyena_li_fwd")
+    binding.set_option("mr_rows", 96)
+    q, k, v, R, lam = draw_li(65, 1, L, D, order, group, "bf16")
+    q2, k2, v2 = (torch.cat([x, x], dim=0) for x in (q, k, v))
+    n = B * L * D
+    guard = 4096
+    buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    out = buf[guard:guard + n].view(B, L, D)
+    binding.hyena_li_fwd(dev(q2), dev(k2), dev(v2), dev(R), dev(lam), group, out=out)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all()
+    assert not torch.isnan(out).any()
+    assert torch.equal(out[0], out[1])  # item 1 must start from a zero state
+    again = binding.hyena_li_fwd(dev(q2), dev(k2), dev(v2), dev(R), dev(lam), group)
+    torch.cuda.synchronize()
+    assert torch.equal(again, out)
+    assert oracle.rel_err(host(out[:1]), oracle.li_conv(q, k, v, R, lam, group=group)) <= TOL["bf16"]
+
+
+def test_full_size_config_on_sampled_outputs():
+    """li2 (B=1, L=8192, D=4096, 16 exponentials per group of 16) in the launch configuration bench.py times,
+    checked at sampled outputs the oracle computes one by one with the filter materialised over all 8192 steps."""
+    w = synth.make("li2")
+    say("li2 full size")
+    y = binding.hyena_li_fwd(dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["R"]), dev(w["lam"]), w["group"])
+    torch.cuda.synchronize()
+    pts = synth.sample_points(777, w["B"], w["L"], w["D"], 3000, 128)
+    ref = oracle.li_conv_points(w["q"], w["k"], w["v"], w["R"], w["lam"], pts, group=w["group"])
+    got = y[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= TOL["bf16"] * scale
+    assert torch.isfinite(y).all()
