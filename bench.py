@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c2u", "c1_bwd", "c2_bwd", "c3_bwd", "copy"],
+    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "copy"],
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -59,7 +59,7 @@ def upload(w, torch):
         if key != "y":
             t.copy_(w[key])
         d[key] = t
-    for key in ("h", "hq", "hk", "hv"):
+    for key in ("h", "hq", "hk", "hv", "R", "lam"):
         if key in w:
             d[key] = torch.from_numpy(w[key]).cuda()
     return d
@@ -99,6 +99,8 @@ class Workload:
                 self.main.append(pkg.plan_bwd("hyena_se_bwd" if c["kind"] == "se" else "hyena_mr_bwd", d["dy"], d["q"],
                                               d["k"], d["v"], d["h"], c["group"],
                                               out=(d["dq"], d["dk"], d["dv"], d["dh"])))
+            elif c["kind"] == "li":
+                self.main.append(pkg.plan_li(d["q"], d["k"], d["v"], d["R"], d["lam"], c["group"], out=d["y"]))
             elif c["kind"] == "chain":
                 self.main.append(pkg.plan_chain(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"], d["h"],
                                                 c["group"], c["feat_group"], out=d["y"]))
@@ -155,6 +157,9 @@ class Workload:
         return 8.0 * self.n_out  # bf16: q, k, v read once, y written once
 
     def algo_flops(self):
+        if self.cfg["kind"] == "li":
+            # recurrent form: per exponential one FMA for the running sum and one for the output, plus two gates
+            return (4.0 * self.cfg["order"] + 2.0) * self.n_out
         f = 2.0 * self.cfg["lh"] + 2.0
         if self.bwd:
             return (3 * 2.0 * self.cfg["lh"] + 5.0) * self.n_out  # z, du, dh contractions + five gates
@@ -176,6 +181,8 @@ def cpu_baseline(wl, target_s, np, oracle):
             # dq[t] only looks at the past, so the first rows of the slice's dq equal those of the full problem
             dy = w["dy"][:1, :rows].contiguous()
             y = oracle.gated_conv_bwd(dy, q, k, v, w["h"], group=c["group"])[0]
+        elif c["kind"] == "li":
+            y = oracle.li_conv(q, k, v, w["R"], w["lam"], group=c["group"])
         elif c["kind"] == "chain":
             y = oracle.chain(q, k, v, w["hq"], w["hk"], w["hv"], w["h"], group=c["group"], feat_group=c["feat_group"])
         else:
@@ -184,7 +191,10 @@ def cpu_baseline(wl, target_s, np, oracle):
 
     probe_rows = min(L, 128)
     t_probe, _ = run(probe_rows)
-    rows = int(min(L, max(probe_rows, probe_rows * target_s / max(t_probe, 1e-4))))
+    grow = target_s / max(t_probe, 1e-4)
+    if c["kind"] == "li":
+        grow = grow ** 0.5  # the filter is as long as the slice: the oracle's work grows with rows squared
+    rows = int(min(L, max(probe_rows, probe_rows * grow)))
     t, y = run(rows)
     times = [t]
     while sum(times) < 0.8 * target_s and len(times) < 200:
@@ -248,7 +258,8 @@ def main():
 
     wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup)
     cfg = wl.cfg
-    kernel = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd"}[cfg["kind"]]
+    kernel = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd",
+              "li": "hyena_li_fwd (both passes of the scan)"}[cfg["kind"]]
     if wl.bwd:
         kernel = kernel.replace("_fwd", "_bwd")
 
@@ -262,10 +273,12 @@ def main():
         "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: %s%s bf16 B=%d L=%d D=%d lh=%d group=%d" % (
-            args.workload, {"se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,"}[cfg["kind"]],
+        "config": {"workload": "%s: %s%s bf16 B=%d L=%d D=%d %s=%d group=%d" % (
+            args.workload, {"se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,",
+                            "li": "Hyena-LI"}[cfg["kind"]],
             " backward (all launches of the entry point)" if wl.bwd else "",
-            cfg["B"], cfg["L"], cfg["D"], cfg["lh"], cfg["group"]), "buffer_sets": res["sets"]},
+            cfg["B"], cfg["L"], cfg["D"], "order" if cfg["kind"] == "li" else "lh",
+            cfg["order"] if cfg["kind"] == "li" else cfg["lh"], cfg["group"]), "buffer_sets": res["sets"]},
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": res["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": res["hbm_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel_ms_avg": res["kernel_ms_avg"], "algorithmic_bytes_per_launch": wl.algo_bytes()},

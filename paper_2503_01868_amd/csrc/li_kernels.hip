@@ -186,13 +186,25 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
     const int64_t ws_wave = ((c0 / 16) * 64 + lane) * 4;  // this lane's 4 floats inside one (b, tile) record set
     const int64_t ws_tile = (D / 16) * 256;               // floats per (b, tile)
     if constexpr (!kStateOnly) {
+        // eight records in flight at a time (the loads do not depend on the running sum, only the FMAs do);
+        // indices past the last record are clamped so that the loads stay unconditional
         const float* wp = a.ws + b * (a.tiles_per_seq - 1) * ws_tile + ws_wave;
-        for (int tau = 0; tau < tile; ++tau) {
-            const float4 st = *reinterpret_cast<const float4*>(wp + tau * ws_tile);
-            s[0] = lam_rows[0] * s[0] + st.x;
-            s[1] = lam_rows[1] * s[1] + st.y;
-            s[2] = lam_rows[2] * s[2] + st.z;
-            s[3] = lam_rows[3] * s[3] + st.w;
+        for (int tau0 = 0; tau0 < tile; tau0 += 8) {
+            float4 st[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int tau = tau0 + i < tile ? tau0 + i : tile - 1;
+                st[i] = *reinterpret_cast<const float4*>(wp + tau * ws_tile);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (tau0 + i < tile) {
+                    s[0] = lam_rows[0] * s[0] + st[i].x;
+                    s[1] = lam_rows[1] * s[1] + st[i].y;
+                    s[2] = lam_rows[2] * s[2] + st[i].z;
+                    s[3] = lam_rows[3] * s[3] + st[i].w;
+                }
+            }
         }
     }
 
