@@ -1,6 +1,6 @@
 """GPU parity at the five benchmark configurations, in the launch configuration bench.py times.
-c0-c2 are compared in full; c3 and c4 (half a billion outputs each) on sampled outputs the oracle
-evaluates one by one plus whole filter groups over all (b, t)."""
+c0-c2 (and c2u, c2 with one filter per channel) are compared in full; c3 and c4 (half a billion outputs each)
+on sampled outputs the oracle evaluates one by one plus whole filter groups over all (b, t)."""
 import numpy as np
 import pytest
 import torch
@@ -18,7 +18,7 @@ def run_inner(w):
     return entry(dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["h"]), w["group"])
 
 
-@pytest.mark.parametrize("name", ["c0", "c1", "c2"])
+@pytest.mark.parametrize("name", ["c0", "c1", "c2", "c2u"])
 def test_full_tensor_parity(name):
     say("config %s full" % name)
     w = synth.make(name)

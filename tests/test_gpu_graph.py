@@ -1,0 +1,111 @@
+"""The entry points launch kernels on the caller's stream and nothing else (no allocation, no memset, no
+synchronisation), so a caller may record them into a HIP graph.  Each test captures a few calls, replays the
+graph several times with eager work and synchronisations in between, and checks every replay against the
+eager result bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_01868_amd as pkg
+from paper_2503_01868_amd import binding, synth
+
+from gpu_util import dev, say
+
+pytestmark = pytest.mark.gpu
+
+
+def capture(build_plans):
+    """build_plans(stream) -> list of Plan objects bound to `stream`; returns (graph, outputs)."""
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plans = build_plans(side)
+        for p in plans:  # warm-up outside the capture (loads the code objects)
+            p()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        for p in plans:
+            p()
+    return g, plans
+
+
+def replay_and_compare(g, plans, eager, refill):
+    for it in range(3):
+        refill(it)            # eager work between replays: new inputs written into the captured buffers
+        torch.cuda.synchronize()
+        want = eager()
+        torch.cuda.synchronize()
+        for p in plans:       # spoil the outputs so that a replay that does nothing is noticed
+            outs = p.out if isinstance(p.out, tuple) else (p.out,)
+            for o in outs:
+                o.fill_(float("nan")) if o.dtype != torch.float32 else o.fill_(7.0)
+        g.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for p in plans for o in (p.out if isinstance(p.out, tuple) else (p.out,))]
+        assert len(got) == len(want)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), "replay %d differs from the eager result" % it
+
+
+def test_forward_entry_points_replay_from_a_graph():
+    say("graph: se, mr, chunk-parallel, chain, li forward")
+    B, L, D = 2, 700, 256
+    rng = np.random.Generator(np.random.PCG64(91))
+    q, k, v = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(3))
+    h_se = dev(synth.short_filter(rng, D, 7))
+    h_mr = dev(synth.decay_filter(rng, D // 16, 128))
+    h_un = dev(synth.decay_filter(rng, D, 100))
+    hq, hk, hv = (dev(synth.short_filter(rng, D, 7)) for _ in range(3))
+    R, lam = (dev(x) for x in synth.li_params(rng, D // 16, 16))
+    binding.set_option("mr_rows", 256)  # several tiles: the li scan uses its workspace
+
+    def build(stream):
+        return [
+            pkg.plan_gated("hyena_se_fwd", q, k, v, h_se, 1, stream=stream),
+            pkg.plan_gated("hyena_mr_fwd", q, k, v, h_mr, 16, stream=stream),
+            pkg.plan_gated("hyena_mr_fwd", q, k, v, h_un, 1, stream=stream),
+            pkg.plan_chain(q, k, v, hq, hk, hv, h_mr, 16, 1, stream=stream),
+            pkg.plan_li(q, k, v, R, lam, 16, stream=stream),
+        ]
+
+    try:
+        g, plans = capture(build)
+
+        def eager():
+            return [binding.hyena_se_fwd(q, k, v, h_se, 1), binding.hyena_mr_fwd(q, k, v, h_mr, 16),
+                    binding.hyena_mr_fwd(q, k, v, h_un, 1), binding.hyena_chain_fwd(q, k, v, hq, hk, hv, h_mr, 16, 1),
+                    binding.hyena_li_fwd(q, k, v, R, lam, 16)]
+
+        def refill(it):
+            for t in (q, k, v):
+                t.copy_(dev(synth.normal_tensor(rng, (B, L, D), "bf16")))
+
+        replay_and_compare(g, plans, eager, refill)
+    finally:
+        binding.set_option("mr_rows", 0)
+
+
+def test_backward_entry_points_replay_from_a_graph():
+    say("graph: se, mr backward")
+    B, L, D = 2, 500, 128
+    rng = np.random.Generator(np.random.PCG64(92))
+    dy, q, k, v = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(4))
+    h_se = dev(synth.short_filter(rng, D, 7))
+    h_mr = dev(synth.decay_filter(rng, D // 16, 128))
+
+    def build(stream):
+        return [pkg.plan_bwd("hyena_se_bwd", dy, q, k, v, h_se, 1, stream=stream),
+                pkg.plan_bwd("hyena_mr_bwd", dy, q, k, v, h_mr, 16, stream=stream)]
+
+    g, plans = capture(build)
+
+    def eager():
+        return list(binding.hyena_se_bwd(dy, q, k, v, h_se, 1)) + list(binding.hyena_mr_bwd(dy, q, k, v, h_mr, 16))
+
+    def refill(it):
+        for t in (dy, q, k, v):
+            t.copy_(dev(synth.normal_tensor(rng, (B, L, D), "bf16")))
+
+    replay_and_compare(g, plans, eager, refill)
