@@ -186,19 +186,44 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
         for (int j = 0; j < LH; ++j) pp[e * LH + j] = dh[e][j];
 }
 
-// second pass: dh[g][j] = sum over partial sets and over the channels of group g
+// second pass: dh[g][j] = sum over partial sets and over the channels of group g.  A workgroup owns 64 outputs;
+// its four waves each sum a contiguous quarter of the terms (fixed order: set, then channel of the group), wave 0
+// adds the four quarters in order.  Deterministic, no atomics.
+constexpr int kRedOut = 64, kRedParts = kBlock / kRedOut;
 __global__ __launch_bounds__(kBlock) void dh_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dh,
                                                            int64_t nsets, int64_t D, int32_t lh, int32_t group) {
-    const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;  // (g, j)
+    __shared__ float red[kRedParts][kRedOut];
+    const int o = threadIdx.x % kRedOut, part = threadIdx.x / kRedOut;
+    const int64_t idx = (int64_t)blockIdx.x * kRedOut + o;  // (g, j)
     const int64_t n = (D / group) * lh;
-    if (idx >= n) return;
-    const int64_t g = idx / lh, j = idx % lh;
+    const int64_t idc = idx < n ? idx : n - 1;  // lanes past the end repeat the last output and do not store
+    const int64_t g = idc / lh, j = idc % lh;
+    const float* base = partial + (g * group) * lh + j;
+    const int64_t total = nsets * group;
+    const int64_t per = (total + kRedParts - 1) / kRedParts;
+    const int64_t lo = part * per, hi = lo + per < total ? lo + per : total;
     float s = 0.0f;
-    for (int64_t p = 0; p < nsets; ++p) {
-        const float* row = partial + p * (D * lh) + (g * group) * lh + j;
-        for (int cc = 0; cc < group; ++cc) s += row[(int64_t)cc * lh];
+    // eight loads in flight at a time (they do not depend on the running sum); indices past the end are clamped
+    // so that the loads stay unconditional
+    for (int64_t x0 = lo; x0 < hi; x0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int64_t x = x0 + i < hi ? x0 + i : hi - 1;
+            v[i] = base[(x / group) * (D * lh) + (x % group) * lh];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (x0 + i < hi) s += v[i];
     }
-    dh[idx] = s;
+    red[part][o] = s;
+    __syncthreads();
+    if (part == 0 && idx < n) {
+        float t = red[0][o];
+#pragma unroll
+        for (int r = 1; r < kRedParts; ++r) t += red[r][o];
+        dh[idx] = t;
+    }
 }
 
 // ------------------------------------------------------------------------------------- general
@@ -368,7 +393,7 @@ hy_status launch_stencil_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipSt
     hipLaunchKernelGGL((bwd_stencil_kernel<T, VEC, LH, R>), dim3((uint32_t)nb), dim3(kBlock), 0, st, a);
     const int64_t nsets = s.B * a.tiles_per_seq;
     const int64_t nout = (s.D / s.group) * s.lh;
-    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), 0, st,
                        a.partial, p.dh, nsets, s.D, s.lh, s.group);
     return launch_status();
 }
@@ -426,7 +451,7 @@ hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64
                            hipStream_t st) {
     const int64_t nout = (n_rows / group) * lh;
     if (nout == 0) return HY_OK;
-    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, partial, dh,
+    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), 0, st, partial, dh,
                        nsets, n_rows, lh, group);
     return launch_status();
 }
@@ -436,7 +461,7 @@ hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hi
     if (nout == 0) return HY_OK;
     // a reduction over zero partial sets writes zeros (a fill kernel, not a memset, so that callers may
     // capture the call in a HIP graph)
-    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), 0, st,
                        static_cast<const float*>(dh), dh, (int64_t)0, D, lh, group);
     return launch_status();
 }
