@@ -1,0 +1,116 @@
+"""Seeded random shapes through every entry point against the oracle: whichever kernel the dispatcher picks for a
+shape (stencil, grouped or chunk-parallel matrix-core path, scan, general kernels), the result has to meet the
+same tolerance.  Shapes are small enough for the fp64 oracle and ragged on purpose."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_01868_amd import binding, synth
+
+from gpu_util import TOL, check_gated, dev, host, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    yield
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves"):
+        binding.set_option(name, 0)
+
+
+def pick(rng, xs):
+    return xs[int(rng.integers(0, len(xs)))]
+
+
+def gated_cases(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        group = pick(rng, [1, 1, 2, 4, 8, 16, 16, 32, 64])
+        D = group * int(rng.integers(1, 5)) * pick(rng, [1, 2, 4, 8, 16])
+        D = min(D, 512)
+        D -= D % group
+        D = max(D, group)
+        lh = pick(rng, [1, 2, 3, 7, 8, 9, 13, 17, 18, 31, 33, 50, 64, 100, 128, 129, 145, 146, 200, 257, 258])
+        L = int(rng.integers(1, 1400))
+        B = int(rng.integers(1, 4))
+        dtype = pick(rng, ["bf16", "bf16", "bf16", "f32"])
+        entry = pick(rng, ["hyena_se_fwd", "hyena_mr_fwd"])
+        rows = pick(rng, [0, 0, 32, 96, 256, 512])
+        out.append((i, entry, B, L, D, lh, group, dtype, rows))
+    return out
+
+
+@pytest.mark.parametrize("case", gated_cases(48, 2024), ids=lambda c: "%d-%s-B%dL%dD%dlh%dg%d%s-r%d" % c)
+def test_gated_entry_points_on_random_shapes(case):
+    i, entry, B, L, D, lh, group, dtype, rows = case
+    binding.set_option("mr_rows", rows)
+    binding.set_option("se_rows", rows)
+    check_gated(entry, 3000 + i, B, L, D, lh, group, dtype, kind="mr" if lh > 8 else "se")
+
+
+def li_cases(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        group = pick(rng, [1, 4, 16, 16, 16, 32, 48])
+        D = group * int(rng.integers(1, 9))
+        if rng.random() < 0.5:
+            D = max(64, D - D % 64) if group in (16, 32) else D
+        D = max(group, D - D % group)
+        order = int(rng.integers(1, 17))
+        L = int(rng.integers(1, 1500))
+        B = int(rng.integers(1, 4))
+        dtype = pick(rng, ["bf16", "bf16", "f32"])
+        rows = pick(rng, [0, 32, 64, 160, 512])
+        out.append((i, B, L, D, order, group, dtype, rows))
+    return out
+
+
+@pytest.mark.parametrize("case", li_cases(20, 2025), ids=lambda c: "%d-B%dL%dD%do%dg%d%s-r%d" % c)
+def test_long_implicit_entry_point_on_random_shapes(case):
+    i, B, L, D, order, group, dtype, rows = case
+    binding.set_option("mr_rows", rows)
+    say("hyena_li_fwd random %s" % (case,))
+    rng = np.random.Generator(np.random.PCG64(4000 + i))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(3))
+    R, lam = synth.li_params(rng, D // group, order)
+    y = host(binding.hyena_li_fwd(dev(q), dev(k), dev(v), dev(R), dev(lam), group))
+    ref = oracle.li_conv(q, k, v, R, lam, group=group)
+    assert np.isfinite(y).all()
+    # fp32: the plain recurrence accumulates one rounding per step and exponential; slow poles let them add up
+    tol = TOL["bf16"] if dtype == "bf16" else 2e-5
+    assert oracle.rel_err(y, ref) <= tol
+
+
+def chain_cases(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        group = pick(rng, [16, 16, 32, 8, 1])
+        D = pick(rng, [64, 128, 256, 48, 40])
+        D = max(group, D - D % group)
+        feat_group = pick(rng, [1, 1, 2]) if D % 2 == 0 else 1
+        lf = int(rng.integers(1, 9))
+        lh = pick(rng, [8, 33, 64, 128, 129, 130])
+        L = int(rng.integers(1, 900))
+        B = int(rng.integers(1, 3))
+        dtype = pick(rng, ["bf16", "bf16", "f32"])
+        out.append((i, B, L, D, lf, feat_group, lh, group, dtype))
+    return out
+
+
+@pytest.mark.parametrize("case", chain_cases(12, 2026), ids=lambda c: "%d-B%dL%dD%dlf%dfg%dlh%dg%d%s" % c)
+def test_chain_entry_point_on_random_shapes(case):
+    i, B, L, D, lf, feat_group, lh, group, dtype = case
+    say("hyena_chain_fwd random %s" % (case,))
+    rng = np.random.Generator(np.random.PCG64(5000 + i))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(3))
+    hq, hk, hv = (synth.short_filter(rng, D // feat_group, lf) for _ in range(3))
+    h = synth.decay_filter(rng, D // group, lh)
+    y = host(binding.hyena_chain_fwd(dev(q), dev(k), dev(v), dev(hq), dev(hk), dev(hv), dev(h), group, feat_group))
+    ref = oracle.chain(q, k, v, hq, hk, hv, h, group=group, feat_group=feat_group)
+    assert np.isfinite(y).all()
+    assert oracle.rel_err(y, ref) <= (TOL["bf16"] if dtype == "bf16" else 2e-5)
