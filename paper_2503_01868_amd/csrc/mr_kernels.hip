@@ -77,7 +77,10 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void mr_mfma_kernel(MrAr
     // cooperative coordinates of this lane: row lr of the chunk, 16-byte piece lp (8 channels) of the row;
     // used for the k, v, q loads and the y store, all of them whole 32*NW-byte row pieces
     const int lr = tid / PPR, lp = tid % PPR;
-    const int64_t ld_off = cblock0 + 8 * lp;
+    // 32-bit lane arithmetic (the launcher admits L, D < 2^31): fewer live registers than 64-bit row offsets
+    const uint32_t ld_off = (uint32_t)(cblock0 + 8 * lp);
+    const uint32_t D32 = (uint32_t)D;
+    const int tb32 = (int)t_begin, ts32 = (int)t_start, te32 = (int)t_end;
     // Every lane issues exactly three loads per chunk, with no control flow around them, so the loop keeps
     // kPrefetch chunks in flight without ever draining the queue.  Addresses are clamped instead:
     //  - rows past the end of the tile read the tile's last row (a source step >= t_end only reaches
@@ -86,17 +89,18 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void mr_mfma_kernel(MrAr
     //  - warm-up chunks, which need no q, read the q rows of the first real chunk (cache hits, unused).
     auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
         const int cic = ci < nchunks ? ci : nchunks - 1;
-        int64_t t = t_begin + (int64_t)cic * kChunk + lr;
-        t = t < t_end ? t : t_end - 1;
-        kk = load_words_nt<4>(a.k + seq0 + t * D + ld_off);
-        vv = load_words_nt<4>(a.v + seq0 + t * D + ld_off);
+        int t = tb32 + cic * kChunk + lr;
+        t = t < te32 ? t : te32 - 1;
+        const uint64_t off = (uint64_t)(uint32_t)t * D32 + ld_off;
+        kk = load_words_nt<4>(a.k + seq0 + off);
+        vv = load_words_nt<4>(a.v + seq0 + off);
     };
     auto load_q = [&](int ci, Words<4>& qq) {
         const int cic = ci < nchunks ? ci : nchunks - 1;
-        const int64_t t0 = t_begin + (int64_t)cic * kChunk;
-        int64_t tq = (t0 >= t_start ? t0 : t_start) + lr;
-        tq = tq < t_end ? tq : t_end - 1;
-        qq = load_words_nt<4>(a.q + seq0 + tq * D + ld_off);
+        const int t0 = tb32 + cic * kChunk;
+        int tq = (t0 >= ts32 ? t0 : ts32) + lr;
+        tq = tq < te32 ? tq : te32 - 1;
+        qq = load_words_nt<4>(a.q + seq0 + ((uint64_t)(uint32_t)tq * D32 + ld_off));
     };
 
     // start the first loads before anything else so their latency overlaps the filter set-up
@@ -147,9 +151,9 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void mr_mfma_kernel(MrAr
     // Post-gate and store of a finished chunk: z comes back from LDS in row layout, so the lane multiplies
     // 8 adjacent channels of one row by q and writes 16 contiguous bytes.
     auto gate_store = [&](int ci, const Words<4>& qq) {
-        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-        const int64_t t = t0 + lr;
-        if (t0 >= t_start && t < t_end) {
+        const int t0 = tb32 + ci * kChunk;
+        const int t = t0 + lr;
+        if (t0 >= ts32 && t < te32) {
             const char* zp = zst[ci & 1] + zrd_off;
             const float4 za = *reinterpret_cast<const float4*>(zp);
             const float4 zb = *reinterpret_cast<const float4*>(zp + 16);
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void mr_mfma_kernel(MrAr
             Pack<BF16, 8>::unpack(qq, qf);
             float y8[8] = {za.x * qf[0], za.y * qf[1], za.z * qf[2], za.w * qf[3],
                            zb.x * qf[4], zb.y * qf[5], zb.z * qf[6], zb.w * qf[7]};
-            store_words_nt<4>(a.y + seq0 + t * D + ld_off, Pack<BF16, 8>::pack(y8));
+            store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), Pack<BF16, 8>::pack(y8));
         }
     };
 
@@ -277,7 +281,8 @@ hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
 }  // namespace
 
 hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
-    if (s.dtype != HY_BF16 || !s.gated || s.group % 16 != 0 || s.D % 64 != 0 || s.lh > 257)
+    if (s.dtype != HY_BF16 || !s.gated || s.group % 16 != 0 || s.D % 64 != 0 || s.lh > 257 || s.L > 0x7fff0000LL ||
+        s.D > 0x7fff0000LL)
         return HY_ERR_UNSUPPORTED;
     const int nkb = (s.lh - 1 + 31) / 32 + 1;  // 32-step source blocks that can meet a 16-step output tile
     switch (nkb) {
