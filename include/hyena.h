@@ -45,7 +45,8 @@ typedef enum hy_dtype { HY_F32 = 0, HY_BF16 = 1 } hy_dtype;
  * both optional gates on; FIR sum of Sec. 3.1 Eq. 2):
  *     y[b,t,c] = q[b,t,c] * sum_{j=0}^{min(lh-1,t)} h[c/group, j] * k[b,t-j,c] * v[b,t-j,c]
  * Meant for short filters (the paper runs lh = 4..7, always below 14): a fused streaming stencil on
- * the vector ALUs, fp32 arithmetic, one rounding at the store.  Any lh >= 1 is accepted; filters
+ * the vector ALUs, fp32 arithmetic, one rounding at the store (two kernels with identical results, one
+ * for short and one for long sequences, chosen by problem size).  Any lh >= 1 is accepted; filters
  * longer than 8 taps take the chunk-parallel matrix-core path described under hyena_mr_fwd when it
  * applies, else a slower general kernel.  q,k,v,y: [B,L,D] of `dtype`; h: fp32 [D/group, lh].
  */
@@ -185,6 +186,8 @@ hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip
  *   "se_rows"  time steps each lane walks (tile length in t)
  *   "mr_rows"  time steps per workgroup in the MR and chain kernels (multiple of 32)
  *   "mr_waves" waves (= 16-channel groups) per workgroup in the MR and chain kernels (4, 8 or 16)
+ *   "se_walk"  which kernel hyena_se_fwd takes for bf16 filters of up to 8 taps: 0 = by problem size,
+ *              1 = always the long-sequence kernel (where D is a multiple of 128), 2 = always the stencil
  * Unknown names return HY_ERR_UNSUPPORTED.  Results never depend on these, only speed.
  */
 hy_status hyena_set_option(const char *name, int32_t value);

@@ -94,6 +94,7 @@ hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float*
     ConvPtrs p{q, k, v, h, y};
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (se_walk_preferred(s)) return launch_se_walk(p, s, st);
     rc = launch_stencil(&p, 1, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp_mfma(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
@@ -333,6 +334,9 @@ hy_status hyena_set_option(const char* name, int32_t value) {
     } else if (strcmp(name, "mr_waves") == 0) {
         if (value != 0 && value != 4 && value != 8 && value != 16) return HY_ERR_SHAPE;
         t.mr_waves = value;
+    } else if (strcmp(name, "se_walk") == 0) {
+        if (value > 2) return HY_ERR_SHAPE;
+        t.se_walk = value;
     } else {
         return HY_ERR_UNSUPPORTED;
     }

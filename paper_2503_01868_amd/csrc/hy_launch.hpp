@@ -81,11 +81,16 @@ struct Tuning {
     int se_rows = 0;
     int mr_rows = 0;
     int mr_waves = 0;
+    int se_walk = 0;  // 0: by size, 1: always the walking SE kernel where it applies, 2: never
 };
 Tuning& tuning();
 
 // Short-filter streaming stencil on the vector ALUs.  HY_ERR_UNSUPPORTED when lh is above its limit.
 hy_status launch_stencil(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
+// Short-filter kernel for long sequences (bf16, gated, lh <= 8, D % 128 == 0) on the MR kernel's data-movement
+// skeleton; se_walk_preferred() says whether the dispatcher should take it for this shape.
+bool se_walk_preferred(const ConvShape& s);
+hy_status launch_se_walk(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // General fp32 direct convolution: any lh, any group, both dtypes.
 hy_status launch_direct(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
 // Block-Toeplitz contraction on bf16 MFMA.  HY_ERR_UNSUPPORTED outside its domain.

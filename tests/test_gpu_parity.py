@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves"):
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk"):
         binding.set_option(name, 0)
 
 
@@ -57,6 +57,68 @@ def test_se_long_filter_falls_back_to_general_kernel():
     for dtype in ("f32", "bf16"):
         check_gated("hyena_se_fwd", 13, 2, 150, 72, 13, 1, dtype)
         check_gated("hyena_se_fwd", 13, 1, 90, 40, 40, 2, dtype)
+
+
+# Long-sequence SE kernel (the MR kernel's data movement with the stencil's fp32 arithmetic), forced on small shapes.
+# Tiles are at least 256 steps, so L above 256 per workgroup column gives several tiles with their warm-up chunks.
+SE_WALK_CASES = [
+    (1, 1000, 128, 7, 1),    # 8 waves, four tiles, ragged last chunk
+    (2, 700, 256, 7, 1),     # 16 waves
+    (1, 300, 512, 3, 2),
+    (3, 257, 128, 8, 1),     # longest filter, one step into the second tile
+    (1, 33, 128, 1, 1),      # lh = 1
+    (1, 5, 256, 7, 16),      # sequence shorter than the filter
+    (1, 2049, 256, 5, 1),
+    (4, 64, 384, 2, 4),      # D = 3 * 128
+]
+
+
+@pytest.mark.parametrize("case", SE_WALK_CASES)
+def test_se_long_sequence_kernel_matches_oracle(case):
+    B, L, D, lh, group = case
+    binding.set_option("se_walk", 1)
+    check_gated("hyena_se_fwd", 14, B, L, D, lh, group, "bf16")
+
+
+def test_se_long_sequence_kernel_is_bit_exact_on_impulses_and_agrees_with_the_stencil():
+    """Dyadic taps, q = k = 1, unit impulses around tile and chunk boundaries: exact.  On random data both SE kernels
+    do the same fp32 FMA chain in the same tap order, so they must agree bit for bit."""
+    B, L, D, lh = 2, 1100, 128, 7
+    say("impulse se walk")
+    h = dyadic_filter(D, lh, 45)
+    one = torch.ones(B, L, D, dtype=torch.bfloat16)
+    v = torch.zeros(B, L, D, dtype=torch.bfloat16)
+    hits = [(0, 0, 0), (0, 250, 17), (0, 255, 127), (1, 256, 64), (1, 511, 3), (1, 1099, 5), (0, 31, 9), (0, 1023, 77)]
+    expect = np.zeros((B, L, D))
+    for b, t0, c in hits:
+        v[b, t0, c] = 1.0
+        n = min(lh, L - t0)
+        expect[b, t0:t0 + n, c] += h[c, :n]
+    binding.set_option("se_walk", 1)
+    y = host(gated("hyena_se_fwd", one, one, v, h, 1))
+    assert np.array_equal(y, expect)
+    q, k, vv, hr = draw(15, 2, 900, 256, 7, 1, "bf16")
+    y_walk = gated("hyena_se_fwd", q, k, vv, hr, 1)
+    binding.set_option("se_walk", 2)
+    y_sten = gated("hyena_se_fwd", q, k, vv, hr, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(y_walk, y_sten)
+
+
+def test_se_long_sequence_kernel_guard_bands():
+    B, L, D, lh = 2, 301, 256, 7
+    say("guard bands se walk")
+    binding.set_option("se_walk", 1)
+    q, k, v, h = draw(16, B, L, D, lh, 1, "bf16")
+    n = B * L * D
+    guard = 4096
+    buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    out = buf[guard:guard + n].view(B, L, D)
+    binding.hyena_se_fwd(dev(q), dev(k), dev(v), dev(h), 1, out=out)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all()
+    assert not torch.isnan(out).any()
+    assert oracle.rel_err(host(out), oracle.gated_conv(q, k, v, h, group=1)) <= TOL["bf16"]
 
 
 # --------------------------------------------------------------------------------------- featurizer
