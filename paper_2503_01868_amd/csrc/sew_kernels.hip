@@ -180,10 +180,13 @@ hy_status launch_sew_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * NW));
-    int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
-    if (tiles < 1) tiles = 1;
-    int64_t rows = (s.L + tiles - 1) / tiles;
-    if (rows < 8 * kChunk) rows = 8 * kChunk;
+    int64_t rows = tuning().se_rows;
+    if (rows <= 0) {
+        int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
+        if (tiles < 1) tiles = 1;
+        rows = (s.L + tiles - 1) / tiles;
+        if (rows < 8 * kChunk) rows = 8 * kChunk;
+    }
     rows = (rows + kChunk - 1) / kChunk * kChunk;
     a.rows = (int32_t)rows;
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
@@ -195,7 +198,7 @@ hy_status launch_sew_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
 
 template <int LH>
 hy_status launch_sew_lh(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
-    if (s.D % 256 == 0) return launch_sew_nw<LH, 16>(p, s, st);
+    if (s.D % 256 == 0 && tuning().mr_waves != 8) return launch_sew_nw<LH, 16>(p, s, st);
     return launch_sew_nw<LH, 8>(p, s, st);
 }
 
