@@ -211,7 +211,12 @@ bool se_walk_preferred(const ConvShape& s) {
     const int force = tuning().se_walk;
     if (force == 1) return true;
     if (force == 2) return false;
-    return s.B * s.L * (s.D / 128) >= (int64_t)16384 * 32;  // D = 4096: B * L >= 16384
+    // Measured at D = 4096, B = 1: the stencil wins at L = 8192 (512 steps per workgroup), the walker from
+    // L = 16384 on (1024 steps per workgroup); short batch items never give a workgroup a long walk.
+    const int nw = (s.D % 256 == 0 && tuning().mr_waves != 8) ? 16 : 8;
+    int64_t tiles = 256 / (s.B * (s.D / (16 * nw)));
+    if (tiles < 1) tiles = 1;
+    return (s.L + tiles - 1) / tiles >= 1024;
 }
 
 hy_status launch_se_walk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
