@@ -113,6 +113,11 @@ hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float*
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = launch_mr_mfma(p, s, st);
+    // short filters that the grouped matrix-core path does not take are the SE kernels' business
+    if (rc == HY_ERR_UNSUPPORTED && lh <= 8) {
+        if (se_walk_preferred(s)) return launch_se_walk(p, s, st);
+        rc = launch_stencil(&p, 1, s, st);
+    }
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp_mfma(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
     return rc;
