@@ -109,3 +109,39 @@ def test_backward_entry_points_replay_from_a_graph():
             t.copy_(dev(synth.normal_tensor(rng, (B, L, D), "bf16")))
 
     replay_and_compare(g, plans, eager, refill)
+
+
+def test_entry_points_run_concurrently_on_separate_streams():
+    """Two streams issue different entry points back to back (each call with its own outputs and workspace); the
+    results must equal those of the same calls issued one after the other on the default stream."""
+    say("two streams")
+    B, L, D = 2, 3000, 256
+    rng = np.random.Generator(np.random.PCG64(93))
+    q, k, v, dy = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(4))
+    h_se = dev(synth.short_filter(rng, D, 7))
+    h_mr = dev(synth.decay_filter(rng, D // 16, 128))
+    h_un = dev(synth.decay_filter(rng, D, 64))
+    R, lam = (dev(x) for x in synth.li_params(rng, D // 16, 16))
+    binding.set_option("mr_rows", 512)
+    try:
+        want = [binding.hyena_se_fwd(q, k, v, h_se, 1), binding.hyena_mr_fwd(q, k, v, h_mr, 16),
+                binding.hyena_li_fwd(q, k, v, R, lam, 16), binding.hyena_mr_fwd(q, k, v, h_un, 1)]
+        want += list(binding.hyena_mr_bwd(dy, q, k, v, h_mr, 16)) + list(binding.hyena_se_bwd(dy, q, k, v, h_se, 1))
+        torch.cuda.synchronize()
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        a = [pkg.plan_gated("hyena_se_fwd", q, k, v, h_se, 1, stream=s1), pkg.plan_li(q, k, v, R, lam, 16, stream=s1),
+             pkg.plan_bwd("hyena_mr_bwd", dy, q, k, v, h_mr, 16, stream=s1)]
+        b = [pkg.plan_gated("hyena_mr_fwd", q, k, v, h_mr, 16, stream=s2),
+             pkg.plan_gated("hyena_mr_fwd", q, k, v, h_un, 1, stream=s2),
+             pkg.plan_bwd("hyena_se_bwd", dy, q, k, v, h_se, 1, stream=s2)]
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for pa, pb in zip(a, b):
+                pa()
+                pb()
+        torch.cuda.synchronize()
+        got = [a[0].out, b[0].out, a[1].out, b[1].out] + list(a[2].out) + list(b[2].out)
+        for x, y in zip(got, want):
+            assert torch.equal(x, y)
+    finally:
+        binding.set_option("mr_rows", 0)
