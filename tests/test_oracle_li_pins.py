@@ -100,3 +100,50 @@ def test_points_agree_with_the_full_tensor_and_groups_share_parameters():
     assert np.array_equal(got, full[pts[:, 0], pts[:, 1], pts[:, 2]])
     same = oracle.li_conv(q, k, v, np.repeat(R, group, axis=0), np.repeat(lam, group, axis=0), group=1)
     assert np.array_equal(full, same)
+
+
+def _mutants():
+    def base(R, lam, L, shift=0, drop=0, absval=False, square=False):
+        R = np.asarray(R, dtype=np.float64)
+        lam = np.asarray(lam, dtype=np.float64)
+        if absval:
+            lam = np.abs(lam)
+        j = np.arange(int(L)) + shift
+        h = np.zeros((R.shape[0], int(L)))
+        for n in range(R.shape[1] - drop):
+            p = np.power(lam[:, n, None], j[None, :])
+            h += (R[:, n, None] ** 2 if square else R[:, n, None]) * p
+        return h
+
+    return {
+        "exponent counted from t instead of t-1": lambda R, lam, L: base(R, lam, L, shift=1),
+        "last exponential dropped": lambda R, lam, L: base(R, lam, L, drop=1),
+        "sign of the poles lost": lambda R, lam, L: base(R, lam, L, absval=True),
+        "residues squared": lambda R, lam, L: base(R, lam, L, square=True),
+        "filter one tap short": lambda R, lam, L: np.concatenate(
+            [base(R, lam, L)[:, :-1], np.zeros((np.asarray(R).shape[0], 1))], axis=1) if L > 1 else base(R, lam, L),
+    }
+
+
+def test_planted_mistakes_in_the_filter_are_caught(monkeypatch):
+    """Each plausible mistake, planted in a copy of li_filter, must fail at least one of the pins above."""
+    pins = [
+        test_taps_of_a_hand_computed_example_and_first_tap_is_the_sum_of_residues,
+        test_zero_pole_is_the_identity_and_unit_pole_a_running_sum,
+        lambda: test_matches_scipy_recursive_filters_in_parallel_form(2),
+        test_matches_one_rational_transfer_function,
+        test_step_response_is_the_geometric_sum,
+        test_filter_reaches_back_to_the_first_step_and_not_beyond_the_batch_item,
+    ]
+    for name, mutant in _mutants().items():
+        monkeypatch.setattr(oracle, "li_filter", mutant)
+        caught = 0
+        for pin in pins:
+            try:
+                pin()
+            except AssertionError:
+                caught += 1
+        assert caught > 0, "no pin notices: " + name
+    monkeypatch.undo()
+    for pin in pins:  # and the real filter passes them all
+        pin()
