@@ -153,3 +153,19 @@ def test_full_size_config_on_sampled_outputs():
     scale = np.abs(ref).max()
     assert np.abs(got - ref).max() <= TOL["bf16"] * scale
     assert torch.isfinite(y).all()
+
+
+def test_long_sequence_config_on_sampled_outputs():
+    """li3 (B=1, L=131072, D=4096): the running sums cross 15 tile boundaries and 4096 chunks; sampled outputs
+    against the filter materialised over all 131072 steps."""
+    w = synth.make("li3")
+    say("li3 full size")
+    y = binding.hyena_li_fwd(dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["R"]), dev(w["lam"]), w["group"])
+    torch.cuda.synchronize()
+    pts = synth.sample_points(778, w["B"], w["L"], w["D"], 2000, 128)
+    ref = oracle.li_conv_points(w["q"], w["k"], w["v"], w["R"], w["lam"], pts, group=w["group"])
+    got = y[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= TOL["bf16"] * scale
+    del y
+    torch.cuda.empty_cache()
