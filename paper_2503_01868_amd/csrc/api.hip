@@ -96,6 +96,7 @@ hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float*
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (se_walk_preferred(s)) return launch_se_walk(p, s, st);
     rc = launch_stencil(&p, 1, s, st);
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp4(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp_mfma(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
     return rc;
@@ -118,6 +119,7 @@ hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float*
         if (se_walk_preferred(s)) return launch_se_walk(p, s, st);
         rc = launch_stencil(&p, 1, s, st);
     }
+    if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp4(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp_mfma(p, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
     return rc;

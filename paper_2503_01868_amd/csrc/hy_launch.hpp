@@ -99,6 +99,9 @@ hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // HY_ERR_UNSUPPORTED outside cp_mfma_supported().
 bool cp_mfma_supported(const ConvShape& s);
 hy_status launch_cp_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
+// The same on the batched 4x4x4 MFMA: 256 channels per workgroup, lh <= 129.  HY_ERR_UNSUPPORTED outside cp4_supported().
+bool cp4_supported(const ConvShape& s);
+hy_status launch_cp4(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // Whole chain in one pass over q, k, v.  HY_ERR_UNSUPPORTED outside chain_fused_supported().
 bool chain_fused_supported(const ChainShape& s);
 hy_status launch_chain_fused(const ChainPtrs& p, const ChainShape& s, hipStream_t st);

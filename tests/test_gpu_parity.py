@@ -218,6 +218,34 @@ CP_CASES = [
 ]
 
 
+# The same shapes with D a multiple of 128 land on the batched 4x4x4 kernel (lh <= 129); tiles are at least 256 steps.
+CP4_CASES = [
+    (1, 700, 128, 128, 1, 0),       # 8 waves, ragged last iteration
+    (2, 1000, 256, 128, 1, 256),    # four tiles per sequence: history passes
+    (1, 2300, 128, 129, 1, 512),    # longest filter of this path, ring cycles many times
+    (1, 515, 256, 17, 1, 256),      # 16 waves, 5 products
+    (1, 515, 256, 18, 1, 256),      # 9 products
+    (1, 300, 128, 49, 2, 0),
+    (1, 300, 256, 65, 4, 0),        # 17 products, 16 waves
+    (1, 777, 128, 81, 8, 256),
+    (2, 513, 384, 113, 1, 256),     # D = 3 * 128
+    (1, 259, 128, 9, 1, 0),
+    (1, 3, 128, 128, 1, 0),
+    (1, 1, 256, 20, 1, 0),
+    (1, 256, 384, 64, 3, 0),
+    (3, 256, 128, 128, 32, 0),      # through hyena_se_fwd
+    (1, 1000, 256, 100, 1, 320),    # tile length that is not a multiple of the ring
+]
+
+
+@pytest.mark.parametrize("case", CP4_CASES)
+def test_batched_small_tile_path_matches_oracle(case):
+    B, L, D, lh, group, rows = case
+    binding.set_option("mr_rows", rows)
+    entry = "hyena_se_fwd" if group == 32 else "hyena_mr_fwd"
+    check_gated(entry, 36, B, L, D, lh, group, "bf16", kind="mr")
+
+
 @pytest.mark.parametrize("case", CP_CASES)
 def test_chunk_parallel_path_matches_oracle(case):
     B, L, D, lh, group, rows = case
