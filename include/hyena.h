@@ -61,10 +61,11 @@ hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float 
  * block-Toeplitz contraction of Sec. 3.1 (hat y_n = sum_k H_k hat x_{n-k}) on bf16 matrix cores with
  * fp32 accumulation: u = k*v is rounded once to bf16, h is rounded once to bf16, the output is
  * rounded once at the store.  For HY_BF16 with any other group size (down to one filter per
- * channel), D a multiple of 64 and lh <= 145, the same contraction runs chunk-parallel (App. A.1):
- * 16 consecutive 16-step chunks of one channel are the columns of the product and the Toeplitz
- * operand is per channel; same roundings.  Every other valid combination (HY_F32, other widths,
- * longer filters) runs a general fp32 vector-ALU kernel.
+ * channel) the same contraction runs chunk-parallel (App. A.1), with the Toeplitz operands per
+ * channel and consecutive chunks of a channel as the columns of the product: 4-step chunks on the
+ * batched 4x4 matrix instruction when D is a multiple of 128 and lh <= 129, else 16-step chunks on
+ * the 16x16 instruction when D is a multiple of 64 and lh <= 145; same roundings.  Every other valid
+ * combination (HY_F32, other widths, longer filters) runs a general fp32 vector-ALU kernel.
  */
 hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
                        int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
