@@ -266,6 +266,249 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
     }
 }
 
+// ---- Wave-specialised version for the long filters (NBK >= 25), where the products take long enough that running
+// them between the row and store phases of the same waves leaves the memory stream idle.  Twelve waves share 128
+// channels: waves 0..7 only multiply (16 channels each, as above), waves 8..11 only move data (loads, u = k*v and
+// q into LDS, y out of LDS).  While the multipliers work on iteration j, the movers store y of iteration j - 1 and
+// prepare iteration j + 1; one barrier per iteration separates the steps.  The ring therefore has four slots of
+// 64 steps (the products of iteration j read slots j-2, j-1, j while slot j+1 is written) and the q/y buffer two
+// (a mover lane reads the y of iteration j - 1 and then writes the q of iteration j + 1 to the same addresses).
+constexpr int kWM = 8;     // multiplier waves
+constexpr int kWV = 4;     // mover waves
+constexpr int kR4 = 256;   // ring length in steps, 4 kT
+constexpr int kLS4 = 544;  // bytes per ring line (2 kR4 + 32: 8 banks per channel)
+constexpr int kQS4 = 288;  // bytes per q/y line (2 slots x 2 kT + 32)
+
+template <int NBK, int PF>
+__global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
+    constexpr int kH = 4 * (NBK - 1);
+    static_assert(kH <= 2 * kT, "history must fit two ring slots");
+    static_assert(PF == 1 || PF == 2, "one or two stages");
+    constexpr int C = 16 * kWM;  // channels per workgroup
+    constexpr int PPR = C / 8;   // 16-byte pieces per row
+    __shared__ __attribute__((aligned(16))) char ring[C * kLS4 + (C / 8) * 8];
+    __shared__ __attribute__((aligned(16))) char qy[C * kQS4 + (C / 8) * 8];
+
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const uint32_t lb = blockIdx.x;
+    const int cb = lb % a.ncb;
+    const int64_t tile = lb / a.ncb;
+    const int64_t b = tile / a.tiles_per_seq;
+    const int ts32 = (int)((tile % a.tiles_per_seq) * (int64_t)a.rows);
+    const int te32 = (ts32 + a.rows < a.L) ? ts32 + a.rows : (int)a.L;
+    const int nit = (te32 - ts32 + kT - 1) / kT;  // iterations 1..nit; iteration j holds steps ts32 + 64 (j - 1) ...
+
+    const uint32_t D32 = (uint32_t)a.D;
+    const int64_t cblock0 = (int64_t)cb * C;
+    const int64_t seq0 = b * a.L * a.D;
+    auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
+    using std::integral_constant;
+
+    if (w < kWM) {
+        // ================= multiplier waves
+        const int blk = lane >> 2, l4 = lane & 3;
+        s16x4_t ares[NBK];
+        {
+            const float* hp = a.h + ((cblock0 + 16 * w + blk) / a.group) * (int64_t)a.lh;
+            auto tapv = [&](int idx) { return (idx >= 0 && idx < a.lh) ? hp[idx] : 0.0f; };
+#pragma unroll
+            for (int m = 0; m < NBK; ++m) {
+                float t4[4];  // t4[k] = h[4m + i - k]
+                if (m >= 1 && 4 * m + 3 < a.lh) {
+                    const float* p = hp + 4 * m + l4 - 3;
+                    t4[3] = p[0]; t4[2] = p[1]; t4[1] = p[2]; t4[0] = p[3];
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) t4[kk] = tapv(4 * m + l4 - kk);
+                }
+                Words<2> wd;
+                wd.w[0] = pack_bf16x2(t4[0], t4[1]);
+                wd.w[1] = pack_bf16x2(t4[2], t4[3]);
+                ares[m] = __builtin_bit_cast(s16x4_t, wd);
+            }
+        }
+        const int cw = 16 * w + blk;
+        const char* const rl = ring + line_off(cw, kLS4);
+        const char* const ring_lane = rl + 8 * l4;                    // position 4 j
+        const char* const mix1 = rl + 2 * ((4 * l4 - 4 + kR4) % kR4);  // position 4 j - 4, wrapped per lane
+        const char* const mix2 = rl + 2 * ((4 * l4 - 8 + kR4) % kR4);
+        const char* const mix3 = rl + 2 * ((4 * l4 - 12 + kR4) % kR4);
+        char* const qy_lane = qy + line_off(cw, kQS4) + 8 * l4;
+
+        auto mstep = [&](auto j4_c) {
+            constexpr int J4 = decltype(j4_c)::value;  // iteration mod 4 = ring slot
+            constexpr int WB = kT * J4;
+            constexpr int SL = (J4 & 1) * 2 * kT;      // byte offset of the q/y slot
+            f32x4_t acc[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) acc[g] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int m = 0; m < NBK; ++m) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int c0 = (WB + 16 * g - 4 * m + 4 * kR4) % kR4;  // position of column 0, constant
+                    const char* p;
+                    if (c0 <= kR4 - 16) p = ring_lane + 2 * c0;
+                    else if (c0 == kR4 - 4) p = mix1;
+                    else if (c0 == kR4 - 8) p = mix2;
+                    else p = mix3;
+                    const uint2 bw = *reinterpret_cast<const uint2*>(p);
+                    Words<2> bb;
+                    bb.w[0] = bw.x; bb.w[1] = bw.y;
+                    acc[g] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ares[m], __builtin_bit_cast(s16x4_t, bb), acc[g], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                char* ql = qy_lane + SL + 32 * g;
+                const uint2 q4 = *reinterpret_cast<const uint2*>(ql);
+                *reinterpret_cast<uint2*>(ql) =
+                    make_uint2(pack_bf16x2(bf16_lo(q4.x) * acc[g][0], bf16_hi(q4.x) * acc[g][1]),
+                               pack_bf16x2(bf16_lo(q4.y) * acc[g][2], bf16_hi(q4.y) * acc[g][3]));
+            }
+            __syncthreads();
+        };
+
+        __syncthreads();  // history and iteration 1 are in place
+        for (int j = 1; j <= nit; j += 4) {
+            mstep(integral_constant<int, 1>{});
+            if (j + 1 <= nit) mstep(integral_constant<int, 2>{});
+            if (j + 2 <= nit) mstep(integral_constant<int, 3>{});
+            if (j + 3 <= nit) mstep(integral_constant<int, 0>{});
+        }
+    } else {
+        // ================= mover waves: lane = piece lp of rows 2 rp, 2 rp + 1, 2 rp + 32, 2 rp + 33 of an iteration
+        const int mt = tid - kWM * 64;
+        const int lp = mt % PPR, rp = mt / PPR;
+        const uint32_t ld_off = (uint32_t)(cblock0 + 8 * lp);
+        char* const u_lines = ring + line_off(8 * lp, kLS4) + 4 * rp;
+        char* const q_lines = qy + line_off(8 * lp, kQS4) + 4 * rp;
+
+        auto row_addr = [&](int t) {  // clamped into the rows this tile may touch
+            t = t < te32 ? t : te32 - 1;
+            t = t > 0 ? t : 0;
+            return seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off);
+        };
+        // u of 2 rows x 8 channels, transposed: one dword (2 steps) per channel at ring position `pos` + 2 rp
+        auto write_u = [&](const Words<4> (&kk)[2], const Words<4> (&vv)[2], bool keep0, bool keep1, int pos) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float a0 = keep0 ? bf16_lo(kk[0].w[p]) * bf16_lo(vv[0].w[p]) : 0.0f;
+                const float b0 = keep0 ? bf16_hi(kk[0].w[p]) * bf16_hi(vv[0].w[p]) : 0.0f;
+                const float a1 = keep1 ? bf16_lo(kk[1].w[p]) * bf16_lo(vv[1].w[p]) : 0.0f;
+                const float b1 = keep1 ? bf16_hi(kk[1].w[p]) * bf16_hi(vv[1].w[p]) : 0.0f;
+                *reinterpret_cast<uint32_t*>(u_lines + (2 * p) * kLS4 + pos * 2) = pack_bf16x2(a0, a1);
+                *reinterpret_cast<uint32_t*>(u_lines + (2 * p + 1) * kLS4 + pos * 2) = pack_bf16x2(b0, b1);
+            }
+        };
+
+        Words<4> kw[PF][2][2], vw[PF][2][2], qw[PF][2][2];  // [stage][half of the iteration][row of the pair]
+        auto load_rows = [&](int it, Words<4> (&kk)[2][2], Words<4> (&vv)[2][2], Words<4> (&qq)[2][2]) {
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int t0 = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const int64_t off = row_addr(t0 + r);
+                    kk[hf][r] = load_words_nt<4>(a.k + off);
+                    vv[hf][r] = load_words_nt<4>(a.v + off);
+                    qq[hf][r] = load_words_nt<4>(a.q + off);
+                }
+            }
+        };
+        // iteration `it` out of its register stage into ring position wb and q/y slot offset sl
+        auto prepare = [&](int it, int wb, int sl, Words<4> (&kk)[2][2], Words<4> (&vv)[2][2], Words<4> (&qq)[2][2]) {
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int t = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
+                write_u(kk[hf], vv[hf], t < te32, t + 1 < te32, wb + 32 * hf);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const uint32_t q0 = qq[hf][0].w[p], q1 = qq[hf][1].w[p];
+                    char* ql = q_lines + sl + 64 * hf;
+                    *reinterpret_cast<uint32_t*>(ql + (2 * p) * kQS4) = (q0 & 0xffffu) | (q1 << 16);
+                    *reinterpret_cast<uint32_t*>(ql + (2 * p + 1) * kQS4) = (q0 >> 16) | (q1 & 0xffff0000u);
+                }
+            }
+        };
+        auto store_y = [&](int it, int sl) {
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                uint32_t yc[8];
+                const char* ql = q_lines + sl + 64 * hf;
+#pragma unroll
+                for (int c8 = 0; c8 < 8; ++c8) yc[c8] = *reinterpret_cast<const uint32_t*>(ql + c8 * kQS4);
+                Words<4> row0, row1;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    row0.w[p] = (yc[2 * p] & 0xffffu) | (yc[2 * p + 1] << 16);
+                    row1.w[p] = (yc[2 * p] >> 16) | (yc[2 * p + 1] & 0xffff0000u);
+                }
+                const int t = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
+                if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), row0);
+                if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)(t + 1) * D32 + ld_off), row1);
+            }
+        };
+
+        // history: steps ts32 - 128 .. ts32 - 65 into slot 3, ts32 - 64 .. ts32 - 1 into slot 0; its loads go out
+        // first, the first iteration's behind them
+        {
+            const int t_lo = ts32 - kH;  // oldest step needed: older rows re-read it (unused)
+            Words<4> kh[2][2][2], vh[2][2][2];
+#pragma unroll
+            for (int hb = (kH <= kT ? 1 : 0); hb < 2; ++hb) {
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    const int t0 = ts32 - 2 * kT + hb * kT + 32 * hf + 2 * rp;
+#pragma unroll
+                    for (int r = 0; r < 2; ++r) {
+                        int t = t0 + r;
+                        t = t > t_lo ? t : t_lo;
+                        const int64_t off = row_addr(t);
+                        kh[hb][hf][r] = load_words_nt<4>(a.k + off);
+                        vh[hb][hf][r] = load_words_nt<4>(a.v + off);
+                    }
+                }
+            }
+            load_rows(1, kw[0], vw[0], qw[0]);
+#pragma unroll
+            for (int hb = (kH <= kT ? 1 : 0); hb < 2; ++hb) {
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    const int t0 = ts32 - 2 * kT + hb * kT + 32 * hf + 2 * rp;
+                    write_u(kh[hb][hf], vh[hb][hf], t0 >= 0, t0 + 1 >= 0, (hb == 0 ? 3 * kT : 0) + 32 * hf);
+                }
+            }
+        }
+        if constexpr (PF == 2) {
+            if (2 <= nit) load_rows(2, kw[1], vw[1], qw[1]);
+        }
+        prepare(1, kT, 2 * kT, kw[0], vw[0], qw[0]);
+        if (1 + PF <= nit) load_rows(1 + PF, kw[0], vw[0], qw[0]);
+        __syncthreads();
+
+        auto vstep = [&](auto j4_c, int j) {
+            constexpr int J4 = decltype(j4_c)::value;  // j mod 4
+            constexpr int ST = J4 % PF;                // stage of iteration j + 1
+            if (j >= 2) store_y(j - 1, ((J4 + 3) & 1) * 2 * kT);
+            if (j + 1 <= nit) {
+                prepare(j + 1, kT * ((J4 + 1) & 3), ((J4 + 1) & 1) * 2 * kT, kw[ST], vw[ST], qw[ST]);
+                if (j + 1 + PF <= nit) load_rows(j + 1 + PF, kw[ST], vw[ST], qw[ST]);
+            }
+            __syncthreads();
+        };
+        for (int j = 1; j <= nit; j += 4) {
+            vstep(integral_constant<int, 1>{}, j);
+            if (j + 1 <= nit) vstep(integral_constant<int, 2>{}, j + 1);
+            if (j + 2 <= nit) vstep(integral_constant<int, 3>{}, j + 2);
+            if (j + 3 <= nit) vstep(integral_constant<int, 0>{}, j + 3);
+        }
+        store_y(nit, (nit & 1) * 2 * kT);
+    }
+}
+
 template <int NBK, int NW, int PF>
 hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     Cp4Args a;
@@ -296,6 +539,36 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     return launch_status();
 }
 
+template <int NBK, int PF>
+hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
+    Cp4Args a;
+    a.q = static_cast<const uint16_t*>(p.q);
+    a.k = static_cast<const uint16_t*>(p.k);
+    a.v = static_cast<const uint16_t*>(p.v);
+    a.h = p.h;
+    a.y = static_cast<uint16_t*>(p.y);
+    a.L = s.L;
+    a.D = s.D;
+    a.lh = s.lh;
+    a.group = s.group;
+    a.ncb = (int32_t)(s.D / (16 * kWM));
+    int64_t rows = tuning().mr_rows;
+    if (rows <= 0) {
+        int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
+        if (tiles < 1) tiles = 1;
+        rows = (s.L + tiles - 1) / tiles;
+        if (rows < 4 * kT) rows = 4 * kT;
+    }
+    rows = (rows + kT - 1) / kT * kT;
+    if (rows > (s.L + kT - 1) / kT * kT) rows = (s.L + kT - 1) / kT * kT;
+    a.rows = (int32_t)rows;
+    a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
+    const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
+    if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((cp4ws_kernel<NBK, PF>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), 0, st, a);
+    return launch_status();
+}
+
 template <int NBK>
 hy_status launch_cp4_nbk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     // 16 waves (128 registers per lane) only where the operands of all products fit beside the rest; longer filters
@@ -305,6 +578,9 @@ hy_status launch_cp4_nbk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) 
         if (s.D % 256 == 0 && tuning().mr_waves != 8) return launch_cp4_nw<NBK, 16, 1>(p, s, st);
     }
     // (a second register stage of loads in flight, PF = 2, measured no faster here)
+    if constexpr (NBK >= 25) {
+        if (tuning().mr_waves != 8) return launch_cp4_ws<NBK, 2>(p, s, st);
+    }
     return launch_cp4_nw<NBK, 8, 1>(p, s, st);
 }
 

@@ -246,6 +246,17 @@ def test_batched_small_tile_path_matches_oracle(case):
     check_gated(entry, 36, B, L, D, lh, group, "bf16", kind="mr")
 
 
+@pytest.mark.parametrize("case", [c for c in CP4_CASES if c[3] >= 66])
+def test_batched_small_tile_path_without_mover_waves_matches_oracle(case):
+    """Filters above 65 taps run with separate multiplier and mover waves by default; `mr_waves` = 8 selects the
+    kernel whose waves do both."""
+    B, L, D, lh, group, rows = case
+    binding.set_option("mr_rows", rows)
+    binding.set_option("mr_waves", 8)
+    entry = "hyena_se_fwd" if group == 32 else "hyena_mr_fwd"
+    check_gated(entry, 37, B, L, D, lh, group, "bf16", kind="mr")
+
+
 @pytest.mark.parametrize("case", CP_CASES)
 def test_chunk_parallel_path_matches_oracle(case):
     B, L, D, lh, group, rows = case
