@@ -154,6 +154,30 @@ class Workload:
         wall = time.perf_counter() - t0
         return wall, sum(a.elapsed_time(b) for a, b in pairs) / steps
 
+    def launch_stats(self, n=60):
+        """Outside the timed region: an event pair around every one of n launches rotating through the buffer
+        sets (median and minimum duration), then n launches on buffer set 0 alone, which is the cache-warm
+        figure where one set fits the 256 MB memory-side cache.  Microseconds."""
+        torch = self.torch
+        ev = torch.cuda.Event
+
+        def series(pick):
+            pairs = [(ev(enable_timing=True), ev(enable_timing=True)) for _ in range(n)]
+            for i, (a, b) in enumerate(pairs):
+                j = pick(i)
+                if self.pre:
+                    self.pre[j]()
+                a.record()
+                self.main[j]()
+                b.record()
+            torch.cuda.synchronize()
+            return sorted(1e3 * a.elapsed_time(b) for a, b in pairs)
+
+        rot = series(lambda i: i % len(self.sets))
+        same = series(lambda i: 0)
+        return {"unit": "us", "launches": n, "median": rot[n // 2], "min": rot[0],
+                "same_buffers_median": same[n // 2], "same_buffers_min": same[0]}
+
     # algorithmic work of the dominant kernel per launch
     def algo_bytes(self):
         if self.bwd:
@@ -209,6 +233,25 @@ def cpu_baseline(wl, target_s, np, oracle):
         "sample": "first %d of %d time steps of batch item 0, all %d channels, fp64, %d run(s) of %.2f s" % (
             rows, L, c["D"], len(times), t_avg),
     }, rows, y
+
+
+def gpu_clocks():
+    """Current shader and memory clock as the driver's sysfs tables mark them (None where unreadable)."""
+    import glob
+
+    out = {}
+    for key, pat in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk")):
+        out[key] = None
+        for path in sorted(glob.glob("/sys/class/drm/card*/device/" + pat)):
+            try:
+                with open(path) as f:
+                    marked = [ln.split(":", 1)[1].replace("*", "").strip() for ln in f if ln.rstrip().endswith("*")]
+            except OSError:
+                continue
+            if marked:
+                out[key] = marked[0]
+                break
+    return out
 
 
 def measure(name, args, torch, pkg, synth, steps, warmup):
@@ -287,6 +330,8 @@ def main():
                      "frac": res["hbm_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel_ms_avg": res["kernel_ms_avg"], "algorithmic_bytes_per_launch": wl.algo_bytes()},
     }
+    out["launch_stats"] = wl.launch_stats()
+    out["launch_stats"]["clocks_after_run"] = gpu_clocks()
     if cfg["kind"] != "se":
         out["mfma"] = {"tflops_algorithmic": res["tflops_algorithmic"], "peak": MFMA_BF16_PEAK_TFLOPS,
                        "frac": res["tflops_algorithmic"] / MFMA_BF16_PEAK_TFLOPS}
