@@ -120,9 +120,13 @@ hy_status hyena_featurize3_fwd(const void *q, const void *k, const void *v, cons
  * The Hyena-MR operator chain of Sec. 2.1 Eq. 1 without its dense projections, forward:
  *     q' = hq * q,  k' = hk * k,  v' = hv * v      (featurizers: lf taps, filters [D/feat_group, lf])
  *     y[b,t,c] = q'[b,t,c] * sum_{j=0}^{min(lh-1,t)} h[c/group, j] * k'[b,t-j,c] * v'[b,t-j,c]
- * For HY_BF16 with group a multiple of 16, D a multiple of 128, lh <= 129 and lf <= 8 this is ONE kernel:
+ * For HY_BF16 with group a multiple of 16, D a multiple of 128, lh <= 129 and lf <= 9 this is ONE kernel:
  * q, k, v are read once, y is written once, q', k', v' stay on chip in fp32 (u = k'v' is rounded once to
- * bf16 for the matrix cores, y once at the store); `workspace` is not touched and may be NULL.
+ * bf16 for the matrix cores, y once at the store); `workspace` is not touched and may be NULL.  The
+ * featurizers run on the matrix cores too (per-channel Toeplitz products, App. A.1; the bf16 inputs enter
+ * exactly, each fp32 tap as a bf16 head plus a bf16 remainder, i.e. to 16 mantissa bits, fp32 accumulation).
+ * With the option "chain_valu" = 1 and lf <= 8 an earlier kernel is used that evaluates them on the vector
+ * ALUs with the fp32 taps.
  * Every other valid problem is run as hyena_featurize3_fwd into `workspace` followed by hyena_mr_fwd;
  * `workspace` must then hold 3*B*L*D elements of `dtype` (16-byte aligned, disjoint from all other
  * arguments), the featurized tensors are rounded to `dtype` there.  hyena_chain_workspace_bytes tells
@@ -189,7 +193,10 @@ hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip
  *   "mr_waves" waves (= 16-channel groups) per workgroup in the MR and chain kernels (4, 8 or 16)
  *   "se_walk"  which kernel hyena_se_fwd takes for bf16 filters of up to 8 taps: 0 = by problem size,
  *              1 = always the long-sequence kernel (where D is a multiple of 128), 2 = always the stencil
- * Unknown names return HY_ERR_UNSUPPORTED.  Results never depend on these, only speed.
+ *   "chain_valu" 1 = hyena_chain_fwd evaluates the featurizers on the vector ALUs with fp32 taps (its first
+ *              kernel) even where the kernel with the featurizers on the matrix cores applies
+ * Unknown names return HY_ERR_UNSUPPORTED.  Results depend on these only through rounding, within the
+ * documented precision of each entry point.
  */
 hy_status hyena_set_option(const char *name, int32_t value);
 

@@ -164,7 +164,7 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
     if (D % group != 0 || D % feat_group != 0) return -1;
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
     ChainShape s{B, L, D, lf, feat_group, lh, group, static_cast<hy_dtype>(dtype)};
-    if (empty(B, L, D) || chain_fused_supported(s)) return 0;
+    if (empty(B, L, D) || chain_fused_supported(s) || (chain4_supported(s) && !tuning().chain_valu)) return 0;
     const int64_t esz = dtype == HY_F32 ? 4 : 2;
     if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > INT64_MAX / (3 * esz)) return -1;
     return 3 * B * L * D * esz;
@@ -183,6 +183,10 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
     if (empty(B, L, D)) return HY_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     ChainShape cs{B, L, D, lf, feat_group, lh, group, static_cast<hy_dtype>(dtype)};
+    if (chain4_supported(cs) && !tuning().chain_valu) {
+        ChainPtrs cp{q, k, v, hq, hk, hv, h, y};
+        return launch_chain4(cp, cs, st);
+    }
     if (chain_fused_supported(cs)) {
         ChainPtrs cp{q, k, v, hq, hk, hv, h, y};
         return launch_chain_fused(cp, cs, st);
@@ -344,6 +348,9 @@ hy_status hyena_set_option(const char* name, int32_t value) {
     } else if (strcmp(name, "se_walk") == 0) {
         if (value > 2) return HY_ERR_SHAPE;
         t.se_walk = value;
+    } else if (strcmp(name, "chain_valu") == 0) {
+        if (value > 1) return HY_ERR_SHAPE;
+        t.chain_valu = value;
     } else {
         return HY_ERR_UNSUPPORTED;
     }

@@ -82,6 +82,7 @@ struct Tuning {
     int mr_rows = 0;
     int mr_waves = 0;
     int se_walk = 0;  // 0: by size, 1: always the walking SE kernel where it applies, 2: never
+    int chain_valu = 0;  // 1: featurizers of the fused chain on the vector ALUs (the first design) even where the matrix-core kernel applies
 };
 Tuning& tuning();
 
@@ -105,6 +106,9 @@ hy_status launch_cp4(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // Whole chain in one pass over q, k, v.  HY_ERR_UNSUPPORTED outside chain_fused_supported().
 bool chain_fused_supported(const ChainShape& s);
 hy_status launch_chain_fused(const ChainPtrs& p, const ChainShape& s, hipStream_t st);
+// The same chain with the featurizers on the matrix cores too (batched 4x4x4 products, taps as bf16 head + remainder).
+bool chain4_supported(const ChainShape& s);
+hy_status launch_chain4(const ChainPtrs& p, const ChainShape& s, hipStream_t st);
 // Hyena-LI as a two-pass chunked scan on bf16 MFMA (end-of-tile states in `ws`), and the plain recurrence.
 bool li_mfma_supported(const LiShape& s);
 int64_t li_workspace_bytes(const LiShape& s);

@@ -21,6 +21,10 @@ bool chain_fused_supported(const ChainShape& s) {
     return s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 128 == 0 && s.lh <= 129 && s.lf >= 1 && s.lf <= 8;
 }
 hy_status launch_chain_fused(const ChainPtrs&, const ChainShape&, hipStream_t) { return HY_OK; }
+bool chain4_supported(const ChainShape& s) {
+    return s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 128 == 0 && s.lh <= 129 && s.lf >= 1 && s.lf <= 9;
+}
+hy_status launch_chain4(const ChainPtrs&, const ChainShape&, hipStream_t) { return HY_OK; }
 bool bwd_stencil_supported(const BwdShape& s) { return s.lh <= 8 && s.D % (s.dtype == HY_BF16 ? 2 : 1) == 0; }
 int64_t bwd_stencil_workspace_bytes(const BwdShape& s) { return s.B * ((s.L + 127) / 128) * s.D * s.lh * 4; }
 hy_status launch_bwd_stencil(const BwdPtrs&, const BwdShape&, void*, hipStream_t) { return HY_OK; }

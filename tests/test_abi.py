@@ -144,7 +144,8 @@ def test_chain_entry_point_rejects_bad_arguments_and_sizes_its_workspace():
     assert wb(1, 100, 64, 7, 1, 128, 16, 1) == 3 * 100 * 64 * 2
     assert wb(1, 100, 128, 7, 1, 128, 16, 0) == 3 * 100 * 128 * 4
     assert wb(1, 100, 128, 7, 1, 130, 16, 1) == 3 * 100 * 128 * 2
-    assert wb(1, 100, 128, 9, 1, 128, 16, 1) == 3 * 100 * 128 * 2
+    assert wb(1, 100, 128, 9, 1, 128, 16, 1) == 0   # nine taps: single kernel with matrix-core featurizers
+    assert wb(1, 100, 128, 10, 1, 128, 16, 1) == 3 * 100 * 128 * 2
     assert wb(1, 100, 128, 7, 1, 128, 24, 1) == -1 and wb(1, 100, 128, 0, 1, 128, 16, 1) == -1
     assert wb(0, 100, 128, 7, 1, 128, 16, 0) == 0
 

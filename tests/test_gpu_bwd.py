@@ -19,7 +19,7 @@ DH_TOL = 2e-5
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk"):
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk", "chain_valu"):
         binding.set_option(name, 0)
 
 

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk"):
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk", "chain_valu"):
         binding.set_option(name, 0)
 
 
