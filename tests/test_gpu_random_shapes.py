@@ -114,3 +114,39 @@ def test_chain_entry_point_on_random_shapes(case):
     ref = oracle.chain(q, k, v, hq, hk, hv, h, group=group, feat_group=feat_group)
     assert np.isfinite(y).all()
     assert oracle.rel_err(y, ref) <= (TOL["bf16"] if dtype == "bf16" else 2e-5)
+
+
+def fused_chain_cases(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        D = pick(rng, [128, 128, 256, 384])
+        group = pick(rng, [16, 16, 32, 64, 128])
+        feat_group = pick(rng, [1, 1, 2, 4, 128])
+        lf = int(rng.integers(1, 10))
+        lh = int(rng.integers(1, 130))
+        L = int(rng.integers(1, 2500))
+        B = int(rng.integers(1, 3))
+        rows = pick(rng, [0, 32, 64, 96, 160, 256, 1024])
+        out.append((i, B, L, D, lf, feat_group, lh, group, rows))
+    return out
+
+
+@pytest.mark.parametrize("case", fused_chain_cases(16, 2027), ids=lambda c: "%d-B%dL%dD%dlf%dfg%dlh%dg%drows%d" % c)
+def test_single_kernel_chain_on_random_shapes_and_tile_lengths(case):
+    """Shapes both single-kernel designs take (bf16, D a multiple of 128, groups of 16 channels or more), random
+    filter lengths, tile lengths and sequence ends; nine-tap featurizers exist only in the matrix-core design."""
+    i, B, L, D, lf, feat_group, lh, group, rows = case
+    say("hyena_chain_fwd fused random %s" % (case,))
+    rng = np.random.Generator(np.random.PCG64(6000 + i))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3))
+    hq, hk, hv = (synth.short_filter(rng, D // feat_group, lf) for _ in range(3))
+    h = synth.decay_filter(rng, D // group, lh)
+    ref = oracle.chain(q, k, v, hq, hk, hv, h, group=group, feat_group=feat_group)
+    binding.set_option("mr_rows", rows)
+    for valu in (0, 1) if lf <= 8 else (0,):
+        binding.set_option("chain_valu", valu)
+        assert binding.lib().hyena_chain_workspace_bytes(B, L, D, lf, feat_group, lh, group, binding.HY_BF16) == 0
+        y = host(binding.hyena_chain_fwd(dev(q), dev(k), dev(v), dev(hq), dev(hk), dev(hv), dev(h), group, feat_group))
+        assert np.isfinite(y).all()
+        assert oracle.rel_err(y, ref) <= TOL["bf16"], valu
