@@ -77,8 +77,10 @@ hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float 
  *     h[g, j]  = sum_{n=0}^{order-1} R[g,n] * lambda[g,n]^j         (the paper's h_t with t = j + 1)
  * The filter is as long as the sequence and is never materialised: the sum of exponentials is evaluated
  * in its recurrent form, as a chunked scan whose per-chunk products run on the bf16 matrix cores with
- * fp32 accumulation (HY_BF16, group a multiple of 16, D a multiple of 64); u = k*v and the filter
- * coefficients are rounded once to bf16, the running sums stay in fp32.  Other valid combinations run the
+ * fp32 accumulation (HY_BF16, group a multiple of 16, D a multiple of 64); u = k*v and the first 32
+ * filter values are rounded once to bf16; the running sums stay in fp32 and, like the powers of the
+ * poles that feed and read them, enter the products with 16 significant bits (two bf16 parts), so that
+ * filters whose exponentials nearly cancel keep their accuracy.  Other valid combinations run the
  * plain fp32 recurrence, one lane per channel.  1 <= order <= 16, else HY_ERR_UNSUPPORTED.
  * q,k,v,y: [B,L,D] of `dtype` (device); R, lambda: fp32 [D/group, order] (device).  |lambda| <= 1 is the
  * caller's business: larger poles overflow like the definition does.

@@ -143,11 +143,14 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
             tz[x] = __builtin_bit_cast(bf16x8_t, wds);
         }
     }
-    // P operand: lane (li = n, lq = source octet), element e = lambda_n^(31 - 8lq - e)
-    bf16x8_t pop;
+    // P operand: lane (li = n, lq = source octet), element e = lambda_n^(31 - 8lq - e), as a bf16 head and a bf16
+    // remainder.  The exponentials of a filter may nearly cancel (close poles, residues of opposite sign); each
+    // one's running sum therefore has to be accurate well beyond bf16, or the error of the individual terms shows
+    // at full size in their small difference.  The same holds for the Q operands below.
+    bf16x8_t pop, pop_lo;
     {
         const float ln = ls[w][li];
-        Words<4> wds;
+        Words<4> wds, wlo;
         float pw = powi(ln, 31 - 8 * lq - 7);  // smallest exponent of the lane (element 7), then multiply up
         float pe[8];
 #pragma unroll
@@ -156,8 +159,12 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
             pw *= ln;
         }
 #pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) wds.w[e2] = pack_bf16x2(pe[2 * e2], pe[2 * e2 + 1]);
+        for (int e2 = 0; e2 < 4; ++e2) {
+            wds.w[e2] = pack_bf16x2(pe[2 * e2], pe[2 * e2 + 1]);
+            wlo.w[e2] = pack_bf16x2(pe[2 * e2] - bf16_lo(wds.w[e2]), pe[2 * e2 + 1] - bf16_hi(wds.w[e2]));
+        }
         pop = __builtin_bit_cast(bf16x8_t, wds);
+        pop_lo = __builtin_bit_cast(bf16x8_t, wlo);
     }
     // state layout: lane (li = channel, lq) holds s[n = 4lq + r][channel], r = 0..3
     float lam32[4], lam_rows[4];
@@ -167,17 +174,20 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
         lam_rows[r] = powi(ls[w][4 * lq + r], a.rows);
     }
     // Q operands: lane (li = step of tile x, lq), element e = R_n lambda_n^(16x + li + 1), n = 4lq + e
-    s16x4_t qop[2];
+    s16x4_t qop[2], qop_lo[2];
     if constexpr (!kStateOnly) {
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
             float qe[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) qe[e] = rs[w][4 * lq + e] * powi(ls[w][4 * lq + e], 16 * x + li + 1);
-            Words<2> wds;
+            Words<2> wds, wlo;
             wds.w[0] = pack_bf16x2(qe[0], qe[1]);
             wds.w[1] = pack_bf16x2(qe[2], qe[3]);
+            wlo.w[0] = pack_bf16x2(qe[0] - bf16_lo(wds.w[0]), qe[1] - bf16_hi(wds.w[0]));
+            wlo.w[1] = pack_bf16x2(qe[2] - bf16_lo(wds.w[1]), qe[3] - bf16_hi(wds.w[1]));
             qop[x] = __builtin_bit_cast(s16x4_t, wds);
+            qop_lo[x] = __builtin_bit_cast(s16x4_t, wlo);
         }
     }
 
@@ -272,13 +282,17 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
                     hw.w[0] = h01; hw.w[1] = h23;
                     lw.w[0] = l01; lw.w[1] = l23;
                     const s16x4_t shi = __builtin_bit_cast(s16x4_t, hw), slo = __builtin_bit_cast(s16x4_t, lw);
+                    // smallest terms first: head of the state against the remainder of Q, remainder of the state
+                    // against the head of Q, then the heads, then the chunk's own Toeplitz block
                     f32x4_t acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
-                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw, tz[0], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw, tz[1], acc1, 0, 0, 0);
-                    acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop[0], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop[1], acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop_lo[0], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop_lo[1], acc1, 0, 0, 0);
                     acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(slo, qop[0], acc0, 0, 0, 0);
                     acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(slo, qop[1], acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop[0], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop[1], acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw, tz[0], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw, tz[1], acc1, 0, 0, 0);
                     char* zp = zst[ci & 1] + zwr_off;
                     *reinterpret_cast<float4*>(zp) = make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
                     *reinterpret_cast<float4*>(zp + 16 * ZROW) = make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
@@ -289,6 +303,7 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
                 s[2] *= lam32[2];
                 s[3] *= lam32[3];
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pop, uw, s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pop_lo, uw, s, 0, 0, 0);
             }
             if constexpr (!kStateOnly) {
                 const int prev = (sgi + kPrefetch - 1) % kPrefetch;

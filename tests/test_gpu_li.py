@@ -78,6 +78,22 @@ def test_slow_poles_negative_poles_and_a_pole_at_one():
     check_li(63, B, L, D, order, group, "bf16", params=(R, lam))
 
 
+def test_nearly_cancelling_exponentials_keep_their_difference():
+    """Two close poles with opposite residues: the filter, about t * 2e-4 * lambda^t, is some 50 times smaller than
+    either exponential.  Each exponential's running sum and output weights therefore have to be carried well
+    beyond bf16 precision, or their individual rounding errors (0.4% of an exponential = 20% of the filter) show
+    at full size."""
+    B, L, D, group = 1, 1800, 128, 16
+    n = D // group
+    l1 = np.linspace(0.9900, 0.9960, n)
+    lam = np.stack([l1, l1 - 2e-4, np.full(n, 0.9), np.full(n, 0.5)], axis=1).astype(np.float32)
+    R = np.stack([np.full(n, 1.0), np.full(n, -1.0), np.full(n, 1e-3), np.full(n, -1e-3)], axis=1).astype(np.float32)
+    for rows in (0, 256):
+        binding.set_option("mr_rows", rows)
+        err = check_li(26, B, L, D, 4, group, "bf16", params=(R, lam))
+        assert err <= 1e-2, err
+
+
 @pytest.mark.parametrize("case", [
     (1, 300, 64, 16, 16, "f32"),    # fp32 storage: the plain recurrence
     (2, 257, 48, 7, 8, "bf16"),     # group smaller than a matrix tile
