@@ -66,6 +66,9 @@ hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float 
  * batched 4x4 matrix instruction when D is a multiple of 128 and lh <= 129, else 16-step chunks on
  * the 16x16 instruction when D is a multiple of 64 and lh <= 145; same roundings.  Every other valid
  * combination (HY_F32, other widths, longer filters) runs a general fp32 vector-ALU kernel.
+ * On the matrix-core paths a source sample shares a product with the structural zeros of the Toeplitz
+ * operand, so a non-finite k*v (Inf, NaN) makes outputs non-finite within the same 32-step block also
+ * BEFORE its own time step and in all channels of its group slice; finite inputs are never affected.
  */
 hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float *h, void *y,
                        int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
