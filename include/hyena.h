@@ -195,7 +195,9 @@ hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip
  *   "se_vec"   channels per lane in the SE / featurizer stencil (1, 2, 4 or 8)
  *   "se_rows"  time steps each lane walks (tile length in t)
  *   "mr_rows"  time steps per workgroup in the MR and chain kernels (multiple of 32)
- *   "mr_waves" waves (= 16-channel groups) per workgroup in the MR and chain kernels (4, 8 or 16)
+ *   "mr_waves" waves (= 16-channel groups) per workgroup in the MR, Hyena-LI and vector-ALU chain kernels (4, 8
+ *              or 16); for ungrouped filters above 65 taps, 8 also selects the chunk-parallel kernel whose waves
+ *              load, multiply and store in turn instead of the one with separate mover waves
  *   "se_walk"  which kernel hyena_se_fwd takes for bf16 filters of up to 8 taps: 0 = by problem size,
  *              1 = always the long-sequence kernel (where D is a multiple of 128), 2 = always the stencil
  *   "chain_valu" 1 = hyena_chain_fwd evaluates the featurizers on the vector ALUs with fp32 taps (its first
