@@ -188,11 +188,12 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
 
 // second pass: dh[g][j] = sum over partial sets and over the channels of group g.  A workgroup owns 64 outputs;
 // its four waves each sum a contiguous quarter of the terms (fixed order: set, then channel of the group), wave 0
-// adds the four quarters in order.  Deterministic, no atomics.
+// adds the four quarters in order.  Deterministic, no atomics.  The sums run in fp64 (the adds are a negligible
+// part of this kernel), so the reduction adds no rounding of its own to the fp32 partials.
 constexpr int kRedOut = 64, kRedParts = kBlock / kRedOut;
 __global__ __launch_bounds__(kBlock) void dh_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dh,
                                                            int64_t nsets, int64_t D, int32_t lh, int32_t group) {
-    __shared__ float red[kRedParts][kRedOut];
+    __shared__ double red[kRedParts][kRedOut];
     const int o = threadIdx.x % kRedOut, part = threadIdx.x / kRedOut;
     const int64_t idx = (int64_t)blockIdx.x * kRedOut + o;  // (g, j)
     const int64_t n = (D / group) * lh;
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(kBlock) void dh_reduce_kernel(const float* __restri
     const int64_t total = nsets * group;
     const int64_t per = (total + kRedParts - 1) / kRedParts;
     const int64_t lo = part * per, hi = lo + per < total ? lo + per : total;
-    float s = 0.0f;
+    double s = 0.0;
     // eight loads in flight at a time (they do not depend on the running sum); indices past the end are clamped
     // so that the loads stay unconditional
     for (int64_t x0 = lo; x0 < hi; x0 += 8) {
@@ -214,15 +215,15 @@ __global__ __launch_bounds__(kBlock) void dh_reduce_kernel(const float* __restri
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            if (x0 + i < hi) s += v[i];
+            if (x0 + i < hi) s += (double)v[i];
     }
     red[part][o] = s;
     __syncthreads();
     if (part == 0 && idx < n) {
-        float t = red[0][o];
+        double t = red[0][o];
 #pragma unroll
         for (int r = 1; r < kRedParts; ++r) t += red[r][o];
-        dh[idx] = t;
+        dh[idx] = (float)t;
     }
 }
 
