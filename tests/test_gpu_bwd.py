@@ -12,7 +12,8 @@ from gpu_util import TOL, dev, host, say
 pytestmark = pytest.mark.gpu
 
 # dh is an fp32 sum over B*L*group products and is returned in fp32 for both storage types: its error is
-# accumulation rounding only (~sqrt(n) * 2^-24 relative to the sum's scale)
+# accumulation rounding only (~sqrt(n) * 2^-24 relative to the sum's scale for the fp32 sums inside a tile; the
+# reduction over tiles and channels runs in fp64)
 DH_TOL = 2e-5
 
 
