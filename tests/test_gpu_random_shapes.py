@@ -150,3 +150,31 @@ def test_single_kernel_chain_on_random_shapes_and_tile_lengths(case):
         y = host(binding.hyena_chain_fwd(dev(q), dev(k), dev(v), dev(hq), dev(hk), dev(hv), dev(h), group, feat_group))
         assert np.isfinite(y).all()
         assert oracle.rel_err(y, ref) <= TOL["bf16"], valu
+
+
+def knob_cases(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        D = pick(rng, [128, 128, 256, 384])
+        group = pick(rng, [1, 2, 8, 16, 32, 64])
+        lh = pick(rng, [int(rng.integers(1, 9)), int(rng.integers(9, 130)), int(rng.integers(130, 258))])
+        L = int(rng.integers(1, 2600))
+        B = int(rng.integers(1, 3))
+        knobs = (pick(rng, [0, 32, 64, 96, 256, 1024]), pick(rng, [0, 4, 8, 16]), pick(rng, [0, 1, 2]),
+                 pick(rng, [0, 32, 100, 256, 1000]), pick(rng, [0, 2, 4, 8]))
+        out.append((i, pick(rng, ["hyena_se_fwd", "hyena_mr_fwd"]), B, L, D, lh, group) + knobs)
+    return out
+
+
+@pytest.mark.parametrize("case", knob_cases(48, 2028),
+                         ids=lambda c: "%d-%s-B%dL%dD%dlh%dg%d-mr%dw%dwalk%dse%dvec%d" % c)
+def test_every_tuning_knob_combination_leaves_the_result_within_tolerance(case):
+    """Widths where all bf16 kernels apply (stencil, tile walker, grouped, both chunk-parallel kernels with and
+    without mover waves), with the tuning options drawn at random: they may change which kernel runs and how it is
+    tiled, never the result beyond rounding."""
+    i, entry, B, L, D, lh, group, mr_rows, mr_waves, se_walk, se_rows, se_vec = case
+    for name, value in (("mr_rows", mr_rows), ("mr_waves", mr_waves), ("se_walk", se_walk), ("se_rows", se_rows),
+                        ("se_vec", se_vec)):
+        binding.set_option(name, value)
+    check_gated(entry, 7000 + i, B, L, D, lh, group, "bf16", kind="mr" if lh > 8 else "se")
