@@ -11,7 +11,9 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c1_bwd / c2_bwd / c3_bwd: the backward entry points (hyena_se_bwd / hyena_mr_bwd) on the shapes of c1 / c2 / c3
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
-Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded slice of the same workload.
+  c2u c2 with one filter per channel; li2 / li3: Hyena-LI at the shapes of c2 / c3
+Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded slice of the same workload.  With the default
+workload the line also carries, under "also", a short timing of c2, c3, c4, c2u and li2 (a quarter of the steps each).
 """
 import argparse
 import json
@@ -45,7 +47,7 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle slice")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
                     help="library tuning knob (hyena_set_option), may repeat; results never depend on these")
-    ap.add_argument("--also", default="c2", help="comma list of further workloads to time briefly (c1 only)")
+    ap.add_argument("--also", default="c2,c3,c4,c2u,li2", help="comma list of further workloads to time briefly (c1 only)")
     return ap.parse_args()
 
 
