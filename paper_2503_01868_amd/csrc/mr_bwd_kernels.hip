@@ -283,7 +283,7 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
 
 template <int NKB, int NW>
 hy_status launch_nw(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st, int64_t* nsets) {
-    constexpr int PF = 2;
+    constexpr int PF = 3;
     MrBwdArgs a;
     a.dy = static_cast<const uint16_t*>(p.dy);
     a.q = static_cast<const uint16_t*>(p.q);
