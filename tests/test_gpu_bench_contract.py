@@ -1,0 +1,46 @@
+"""bench.py prints one JSON line with the fields its callers rely on."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def run_bench(*args):
+    proc = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")] + list(args), capture_output=True, text=True,
+                          timeout=300, cwd=ROOT)
+    return proc
+
+
+def test_one_json_line_with_roofline_and_cpu_baseline():
+    proc = run_bench("--steps", "5", "--warmup", "2", "--cpu-seconds", "1", "--also", "c2")
+    assert proc.returncode == 0, proc.stderr[-2000:]
+    lines = [ln for ln in proc.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 5 and d["warmup"] == 2 and d["unit"] == "tokens/s"
+    assert d["higher_is_better"] is True and d["vs_baseline"] is None and d["data"] == "synthetic"
+    assert d["config"]["workload"].startswith("c1") and "model" not in d["config"]
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and 0.0 < r["frac"] < 1.0
+    assert abs(d["value"] - 8192 * 1e3 / d["ms_per_step"]) / d["value"] < 1e-6   # tokens per step over time per step
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["unit"] == "tokens/s" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
+    assert d["parity_rel_err"] <= 2e-2
+    assert set(d["also"]) == {"c2"} and d["also"]["c2"]["kernel_ms_avg"] > 0
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    proc = run_bench("--gpus", "2")
+    assert proc.returncode != 0
+    assert "one" in proc.stderr and "not supported" in proc.stderr
+    assert proc.stdout.strip() == ""
