@@ -8,6 +8,8 @@ What it computes (paper Sec. 2.1 Eq. 1, Sec. 2.2 filter grouping, Sec. 3.1 Eq. 2
 widened exactly from the bits handed over (fp64, fp32 or bf16).  For Hyena-LI (Sec. 2.1) the filter is the sum
 of real exponentials ``h[g, j] = sum_n R[g, n] lam[g, n]^j``, materialised over the whole sequence and fed to the
 same direct convolution (``li_filter``, ``li_conv``): the definition, not the recurrence and not an FFT.
+``li_recurrent`` is the same sum with its two summations exchanged (the recurrent form Sec. 2.1 mentions), linear
+in the sequence length, for sequences the quadratic definition cannot cover in full; it is pinned to ``li_conv``.
 """
 from __future__ import annotations
 
@@ -17,11 +19,35 @@ import subprocess
 
 import numpy as np
 
+import hashlib
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hyena_oracle.c")
-_SO = os.path.join(_HERE, "liboracle.so")
+
+# -O3 -march=native: the oracle doubles as the CPU baseline of bench.py and is built for the host it runs on.
+# -ffp-contract=off keeps every multiply and add of the C source a separately rounded fp64 operation (no fused
+# multiply-add is formed), so the arithmetic is the written sum on any host.
+CFLAGS = ["-O3", "-march=native", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 F64, F32, BF16 = 0, 1, 2
+
+
+def _host_tag() -> str:
+    """A short tag of this host's CPU feature flags: code built with -march=native must not be carried to a
+    host with another instruction set, so every distinct CPU gets a library of its own."""
+    flags = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("flags"):
+                    flags = " ".join(sorted(line.split(":", 1)[1].split()))
+                    break
+    except OSError:
+        pass
+    return hashlib.sha1(flags.encode()).hexdigest()[:10]
+
+
+_SO = os.path.join(_HERE, "liboracle_%s.so" % _host_tag())
 
 
 def build(force: bool = False) -> str:
@@ -29,9 +55,7 @@ def build(force: bool = False) -> str:
     stale = not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC)
     if force or stale:
         tmp = _SO + ".%d.tmp" % os.getpid()
-        subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", tmp, _SRC]
-        )
+        subprocess.check_call(["gcc"] + CFLAGS + ["-o", tmp, _SRC])
         os.replace(tmp, _SO)
     return _SO
 
@@ -50,6 +74,7 @@ def _load():
         lib.oracle_gated_conv_points.argtypes = [vp, vp, vp, vp, vp, i64, vp] + [i64] * 5 + [ci, ci]
         lib.oracle_chain_points.argtypes = [vp] * 8 + [i64, vp] + [i64] * 7 + [ci, ci]
         lib.oracle_gated_conv_bwd.argtypes = [vp] * 9 + [i64] * 5 + [ci, ci]
+        lib.oracle_li_recurrent.argtypes = [vp] * 7 + [i64] * 5 + [ci, ci]
         _lib = lib
     return _lib
 
@@ -234,6 +259,26 @@ def li_conv(q, k, v, R, lam, group: int = 1) -> np.ndarray:
 def li_conv_points(q, k, v, R, lam, pts, group: int = 1) -> np.ndarray:
     """``li_conv`` evaluated only at the listed (b, t, c) outputs."""
     return gated_conv_points(q, k, v, li_filter(R, lam, int(q.shape[1])), pts, group=group)
+
+
+def li_recurrent(q, k, v, R, lam, group: int = 1) -> np.ndarray:
+    """Hyena-LI inner operator through its recurrent form (``s_n[t] = lam_n s_n[t-1] + k[t] v[t]``,
+    ``y[t] = q[t] sum_n R_n s_n[t]``): the sum of ``li_conv`` with the order of summation exchanged."""
+    qa, qd = _arr(q)
+    ka, kd = _arr(k)
+    va, vd = _arr(v)
+    xd = _same(qd, kd, vd)
+    if not (qa.shape == ka.shape == va.shape) or qa.ndim != 3:
+        raise ValueError("q, k, v must share one [B, L, D] shape")
+    B, L, D = qa.shape
+    Ra, rd = _filt(R, D // group if group > 0 and D % group == 0 else -1)
+    la, ld = _filt(lam, Ra.shape[0], Ra.shape[1])
+    hd = _same(rd, ld)
+    y = np.empty((B, L, D), dtype=np.float64)
+    state = np.empty(B * D * Ra.shape[1], dtype=np.float64)
+    _ok(_load().oracle_li_recurrent(_ptr(qa), _ptr(ka), _ptr(va), _ptr(Ra), _ptr(la), _ptr(y), _ptr(state), B, L, D,
+                                    Ra.shape[1], group, xd, hd), "oracle_li_recurrent")
+    return y
 
 
 def rel_err(y, y_ref) -> float:

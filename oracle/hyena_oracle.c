@@ -268,3 +268,54 @@ int oracle_gated_conv_bwd(const void *dy, const void *q, const void *k, const vo
     }
     return 0;
 }
+
+/*
+ * Hyena-LI in its recurrent form (Sec. 2.1: the long implicit filter is a sum of real exponentials,
+ * h_t = sum_n R_n lambda_n^(t-1), t from 1, and the operator can be evaluated as a recurrence).  Per channel c with
+ * group g = c / dg and u = k (.) v:
+ *     s_n[t] = lambda[g,n] * s_n[t-1] + u[t],   s_n[-1] = 0            (so s_n[t] = sum_{i<=t} lambda_n^(t-i) u[i])
+ *     y[t]   = q[t] * sum_n R[g,n] * s_n[t]
+ * which is the sum of the definition (oracle_gated_conv with the filter sum_n R_n lambda_n^j as long as the
+ * sequence) with the order of its two sums exchanged: the same result up to fp64 rounding, at a cost linear in L.
+ * It exists so that sequences too long for the quadratic definition can be compared over every output; the
+ * tests pin it to the definition (small shapes in full, long sequences at sampled outputs).
+ * R, lam: [D/dg, order].  One time step at a time, channels in the inner loop (they are contiguous in memory).
+ */
+int oracle_li_recurrent(const void *q, const void *k, const void *v, const void *R, const void *lam, double *y,
+                        double *state, int64_t B, int64_t L, int64_t D, int64_t order, int64_t dg, int x_dtype,
+                        int h_dtype)
+{
+    int rc = orc_check(q, k, v, B, L, D, order, dg, x_dtype, h_dtype);
+    if (rc)
+        return rc;
+    if (!R || !lam || !y || !state)
+        return 1;
+    /* state: caller-provided scratch of B * D * order doubles, s_n of every (b, c) */
+    int64_t seqs = B * D;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < seqs * order; ++i)
+        state[i] = 0.0;
+    enum { BLOCK = 32 }; /* channels handled by one thread at a time */
+    int64_t nblk = (D + BLOCK - 1) / BLOCK;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t cb = 0; cb < nblk; ++cb) {
+            int64_t c_lo = cb * BLOCK, c_hi = c_lo + BLOCK < D ? c_lo + BLOCK : D;
+            for (int64_t t = 0; t < L; ++t) {
+                for (int64_t c = c_lo; c < c_hi; ++c) {
+                    int64_t g = c / dg;
+                    size_t at = (size_t)((b * L + t) * D + c);
+                    double u = orc_load(k, x_dtype, at) * orc_load(v, x_dtype, at);
+                    double *s = state + (size_t)((b * D + c) * order);
+                    double z = 0.0;
+                    for (int64_t n = 0; n < order; ++n) {
+                        s[n] = orc_load(lam, h_dtype, (size_t)(g * order + n)) * s[n] + u;
+                        z += orc_load(R, h_dtype, (size_t)(g * order + n)) * s[n];
+                    }
+                    y[at] = orc_load(q, x_dtype, at) * z;
+                }
+            }
+        }
+    }
+    return 0;
+}

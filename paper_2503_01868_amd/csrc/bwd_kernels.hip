@@ -322,10 +322,11 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
 }
 
 // dh[g][j]: one workgroup per (group, tap); lanes stride over (b, t, channel of the group), then a tree sum.
+// Products of fp32 factors and their sum are carried in fp64 (correctness path: the sum has B * L * group terms).
 template <typename T>
 __global__ __launch_bounds__(kBlock) void dh_direct_kernel(BwdDirectArgs a) {
     using P = Pack<T, 1>;
-    __shared__ float red[kBlock];
+    __shared__ double red[kBlock];
     const int64_t g = blockIdx.x;
     const int64_t j = blockIdx.y;
     const int64_t L = a.L, D = a.D;
@@ -340,13 +341,13 @@ __global__ __launch_bounds__(kBlock) void dh_direct_kernel(BwdDirectArgs a) {
         return f[0];
     };
     const int64_t span = (L - j) * group;  // (t, cc) pairs per batch item, channel fastest
-    float s = 0.0f;
+    double s = 0.0;
     for (int64_t b = 0; b < a.B; ++b) {
         for (int64_t i = threadIdx.x; i < span; i += kBlock) {
             const int64_t t = j + i / group;
             const int64_t c = g * group + i % group;
             const int64_t at = (b * L + t) * D + c, src = (b * L + (t - j)) * D + c;
-            s = __builtin_fmaf(ld(dyp, at) * ld(qp, at), ld(kp, src) * ld(vp, src), s);
+            s = __builtin_fma((double)ld(dyp, at) * (double)ld(qp, at), (double)ld(kp, src) * (double)ld(vp, src), s);
         }
     }
     red[threadIdx.x] = s;
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(kBlock) void dh_direct_kernel(BwdDirectArgs a) {
         if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) a.p.dh[g * a.lh + j] = red[0];
+    if (threadIdx.x == 0) a.p.dh[g * a.lh + j] = (float)red[0];
 }
 
 int stencil_rows(const BwdShape& s, int64_t nvec) {

@@ -328,8 +328,11 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// General kernel: the recurrence itself, one lane per (batch item, channel), fp32 states.  Any dtype, any
-// group; slow (B * D lanes in all), the correctness path for what the matrix-core kernel does not take.
+// General kernel: the recurrence itself, one lane per (batch item, channel).  Any dtype, any group; slow
+// (B * D lanes in all), the correctness path for what the matrix-core kernel does not take.  The running sums
+// and the output sum are kept in fp64: a slow pole (lambda close to 1) carries thousands of steps, and in fp32
+// one rounding per step and exponential would add up past the 1e-5 that fp32 storage is held to; in fp64 the
+// only roundings left are the final conversion of z and the gate.
 template <typename T>
 __global__ __launch_bounds__(64) void li_direct_kernel(const void* qv, const void* kv, const void* vv, const float* R,
                                                        const float* lam, void* yv, int64_t B, int64_t L, int64_t D,
@@ -338,12 +341,12 @@ __global__ __launch_bounds__(64) void li_direct_kernel(const void* qv, const voi
     if (idx >= B * D) return;
     const int64_t b = idx / D, c = idx % D;
     const int64_t g = c / group;
-    float rn[kMaxOrder], ln[kMaxOrder], sn[kMaxOrder];
+    double rn[kMaxOrder], ln[kMaxOrder], sn[kMaxOrder];
 #pragma unroll
     for (int n = 0; n < kMaxOrder; ++n) {
-        rn[n] = n < order ? R[g * order + n] : 0.0f;
-        ln[n] = n < order ? lam[g * order + n] : 0.0f;
-        sn[n] = 0.0f;
+        rn[n] = n < order ? (double)R[g * order + n] : 0.0;
+        ln[n] = n < order ? (double)lam[g * order + n] : 0.0;
+        sn[n] = 0.0;
     }
     const char* qp = static_cast<const char*>(qv);
     const char* kp = static_cast<const char*>(kv);
@@ -355,14 +358,14 @@ __global__ __launch_bounds__(64) void li_direct_kernel(const void* qv, const voi
         Pack<T, 1>::unpack(Pack<T, 1>::load(qp + off), qf);
         Pack<T, 1>::unpack(Pack<T, 1>::load(kp + off), kf);
         Pack<T, 1>::unpack(Pack<T, 1>::load(vp + off), vf);
-        const float u = kf[0] * vf[0];
-        float z = 0.0f;
+        const double u = (double)kf[0] * (double)vf[0];
+        double z = 0.0;
 #pragma unroll
         for (int n = 0; n < kMaxOrder; ++n) {
-            sn[n] = __builtin_fmaf(ln[n], sn[n], u);
-            z = __builtin_fmaf(rn[n], sn[n], z);
+            sn[n] = __builtin_fma(ln[n], sn[n], u);
+            z = __builtin_fma(rn[n], sn[n], z);
         }
-        float y1[1] = {qf[0] * z};
+        float y1[1] = {(float)((double)qf[0] * z)};
         Pack<T, 1>::store(yp + off, Pack<T, 1>::pack(y1));
     }
 }

@@ -147,3 +147,62 @@ def test_planted_mistakes_in_the_filter_are_caught(monkeypatch):
     monkeypatch.undo()
     for pin in pins:  # and the real filter passes them all
         pin()
+
+
+# ------------------------------------------------------------------ the recurrent form (oracle.li_recurrent)
+@pytest.mark.parametrize("case", [(1, 1, 1, 1, 1), (2, 257, 12, 5, 4), (3, 64, 33, 16, 1), (1, 500, 70, 3, 35)])
+def test_recurrent_form_equals_the_definition(case):
+    """Exchanging the two sums of the definition changes fp64 rounding only."""
+    B, L, D, d, group = case
+    rng = rng_for(40 + L)
+    q, k, v = (rng.standard_normal((B, L, D)) for _ in range(3))
+    R = rng.standard_normal((D // group, d))
+    lam = rng.uniform(-1.0, 1.0, (D // group, d))
+    want = oracle.li_conv(q, k, v, R, lam, group=group)
+    got = oracle.li_recurrent(q, k, v, R, lam, group=group)
+    assert np.allclose(got, want, rtol=0, atol=1e-12 * max(1.0, np.abs(want).max()))
+
+
+def test_recurrent_form_takes_the_stored_bits_of_bf16_and_fp32_inputs():
+    import torch
+
+    rng = rng_for(50)
+    B, L, D, d, group = 2, 90, 32, 4, 16
+    q, k, v = (torch.from_numpy(rng.standard_normal((B, L, D)).astype(np.float32)).bfloat16() for _ in range(3))
+    R = rng.standard_normal((D // group, d)).astype(np.float32)
+    lam = rng.uniform(0.0, 1.0, (D // group, d)).astype(np.float32)
+    want = oracle.li_conv(q, k, v, R, lam, group=group)
+    got = oracle.li_recurrent(q, k, v, R, lam, group=group)
+    assert np.allclose(got, want, rtol=0, atol=1e-12 * np.abs(want).max())
+
+
+def test_recurrent_form_against_scipy_and_closed_forms():
+    """The same outside pins as the definition: SciPy's first-order recursions, the geometric step response,
+    poles 0, 1 and -1, and batch items that do not see each other."""
+    rng = rng_for(60)
+    B, L, D, group, d = 2, 300, 6, 2, 3
+    q, k, v = (rng.standard_normal((B, L, D)) for _ in range(3))
+    R = rng.standard_normal((D // group, d))
+    lam = rng.uniform(-0.99, 0.99, (D // group, d))
+    u = k * v
+    want = np.zeros_like(u)
+    for c in range(D):
+        g = c // group
+        for n in range(d):
+            want[:, :, c] += R[g, n] * scipy.signal.lfilter([1.0], [1.0, -lam[g, n]], u[:, :, c], axis=1)
+    assert np.allclose(oracle.li_recurrent(q, k, v, R, lam, group=group), want * q, rtol=1e-10, atol=1e-10)
+    one = np.ones((1, 64, 1))
+    Rs, ls = np.array([[1.5, -0.5, 2.0]]), np.array([[0.5, 0.9, -0.8]])
+    t = np.arange(64)
+    step = sum(Rs[0, n] * (1 - ls[0, n] ** (t + 1)) / (1 - ls[0, n]) for n in range(3))
+    assert np.allclose(oracle.li_recurrent(one, one, one, Rs, ls)[0, :, 0], step, rtol=1e-12, atol=1e-12)
+    kk = rng.standard_normal((2, 50, 3))
+    o3 = np.ones_like(kk)
+    assert np.array_equal(oracle.li_recurrent(o3, kk, o3, np.full((3, 1), 2.5), np.zeros((3, 1))), 2.5 * kk)
+    assert np.allclose(oracle.li_recurrent(o3, kk, o3, np.ones((3, 1)), np.ones((3, 1))), np.cumsum(kk, axis=1),
+                       rtol=1e-13, atol=1e-13)
+    imp = np.zeros((2, 200, 1))
+    imp[0, 0, 0] = 1.0
+    y = oracle.li_recurrent(np.ones_like(imp), np.ones_like(imp), imp, np.array([[2.0]]), np.array([[0.97]]))
+    assert y[0, 199, 0] == pytest.approx(2.0 * 0.97 ** 199, rel=1e-12)
+    assert np.all(y[1] == 0.0)
