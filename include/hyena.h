@@ -8,14 +8,18 @@
  *   - Filters are fp32 for both dtypes, [D / group, lh] row-major, tap index contiguous; tap 0
  *     multiplies the current sample and tap j the sample j steps in the past (the FIR definition of
  *     Sec. 3.1, Eq. 2).  Channel c uses filter c / group (contiguous groups, Sec. 2.2).
- *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned; outputs must not alias
- *     inputs.  The library allocates nothing, keeps no state between calls besides the tuning
- *     options below, launches on `hip_stream` (a hipStream_t, NULL = default stream) and never
- *     synchronises.
+ *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned.  A buffer the call writes
+ *     (an output, the filter gradient, the workspace) must not overlap any other buffer of the call,
+ *     activations and filter tables alike: HY_ERR_ALIGN.  The library allocates nothing, keeps no
+ *     state between calls besides the tuning options below, launches on `hip_stream` (a hipStream_t,
+ *     NULL = default stream) and never synchronises.
  *   - Left boundary: zero padding, separately for each batch item (terms with t - j < 0 vanish).
  *   - Errors: a status code is returned, nothing is thrown and nothing aborts.  All argument checks
  *     run before the first HIP call, so they work on a machine without a GPU.  B, L or D equal to 0
- *     is a valid empty problem and returns HY_OK without launching.
+ *     is a valid empty problem and returns HY_OK without launching (the backward entry points still
+ *     issue one small launch that sets the filter gradient to zero).
+ *   - HY_ERR_LAUNCH reports the launch of this very call (the return value of hipLaunchKernel); the
+ *     thread's sticky HIP error state is neither read nor cleared.
  */
 #ifndef HYENA_H
 #define HYENA_H
@@ -31,7 +35,7 @@ typedef enum hy_status {
     HY_ERR_NULL = 1,        /* a required pointer is NULL */
     HY_ERR_SHAPE = 2,       /* negative size, lh < 1, group < 1, or D not a multiple of group */
     HY_ERR_DTYPE = 3,       /* dtype is not one of hy_dtype */
-    HY_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned, or an output aliases an input */
+    HY_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned, or a written buffer overlaps another buffer */
     HY_ERR_UNSUPPORTED = 5, /* valid problem, but no kernel in this build handles it */
     HY_ERR_LAUNCH = 6       /* the HIP runtime reported an error at launch */
 } hy_status;
@@ -130,17 +134,16 @@ hy_status hyena_featurize3_fwd(const void *q, const void *k, const void *v, cons
  * bf16 for the matrix cores, y once at the store); `workspace` is not touched and may be NULL.  The
  * featurizers run on the matrix cores too (per-channel Toeplitz products, App. A.1; the bf16 inputs enter
  * exactly, each fp32 tap as a bf16 head plus a bf16 remainder, i.e. to 16 mantissa bits, fp32 accumulation).
- * With the option "chain_valu" = 1 and lf <= 8 an earlier kernel is used that evaluates them on the vector
- * ALUs with the fp32 taps.
  * Every other valid problem is run as hyena_featurize3_fwd into `workspace` followed by hyena_mr_fwd;
  * `workspace` must then hold 3*B*L*D elements of `dtype` (16-byte aligned, disjoint from all other
  * arguments), the featurized tensors are rounded to `dtype` there.  hyena_chain_workspace_bytes tells
- * which case applies.  q,k,v,y: [B,L,D] of `dtype`; hq,hk,hv: fp32 [D/feat_group, lf]; h: fp32 [D/group, lh].
+ * which case applies; workspace_bytes is the size of `workspace` (HY_ERR_SHAPE if negative or too small).
+ * q,k,v,y: [B,L,D] of `dtype`; hq,hk,hv: fp32 [D/feat_group, lf]; h: fp32 [D/group, lh].
  */
 hy_status hyena_chain_fwd(const void *q, const void *k, const void *v, const float *hq, const float *hk,
-                          const float *hv, const float *h, void *y, void *workspace, int64_t B, int64_t L,
-                          int64_t D, int32_t lf, int32_t feat_group, int32_t lh, int32_t group,
-                          int32_t dtype, void *hip_stream);
+                          const float *hv, const float *h, void *y, void *workspace, int64_t workspace_bytes,
+                          int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh,
+                          int32_t group, int32_t dtype, void *hip_stream);
 
 /*
  * Bytes of workspace hyena_chain_fwd needs for this problem: 0 when the single-kernel path applies,
@@ -191,17 +194,16 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
 hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip_stream);
 
 /*
- * Tuning knobs (process-wide, not thread-safe; 0 restores the built-in choice).  Names:
+ * Tuning knobs (process-wide; 0 restores the built-in choice).  Thread-safe: every entry point takes one
+ * consistent snapshot of all options when it is entered, so an option set by another thread during a call
+ * affects later calls only; a *_workspace_bytes query and the call it sizes agree as long as no option that
+ * matters to them is set in between (if one is, the call notices the short workspace: HY_ERR_SHAPE).  Names:
  *   "se_vec"   channels per lane in the SE / featurizer stencil (1, 2, 4 or 8)
  *   "se_rows"  time steps each lane walks (tile length in t)
  *   "mr_rows"  time steps per workgroup in the MR and chain kernels (multiple of 32)
- *   "mr_waves" waves (= 16-channel groups) per workgroup in the MR, Hyena-LI and vector-ALU chain kernels (4, 8
- *              or 16); for ungrouped filters above 65 taps, 8 also selects the chunk-parallel kernel whose waves
- *              load, multiply and store in turn instead of the one with separate mover waves
+ *   "mr_waves" waves (= 16-channel groups) per workgroup in the MR and Hyena-LI kernels (4, 8 or 16)
  *   "se_walk"  which kernel hyena_se_fwd takes for bf16 filters of up to 8 taps: 0 = by problem size,
  *              1 = always the long-sequence kernel (where D is a multiple of 128), 2 = always the stencil
- *   "chain_valu" 1 = hyena_chain_fwd evaluates the featurizers on the vector ALUs with fp32 taps (its first
- *              kernel) even where the kernel with the featurizers on the matrix cores applies
  * Unknown names return HY_ERR_UNSUPPORTED.  Results depend on these only through rounding, within the
  * documented precision of each entry point.
  */

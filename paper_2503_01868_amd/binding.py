@@ -26,10 +26,11 @@ class HyenaError(RuntimeError):
 
 
 def lib() -> ctypes.CDLL:
-    """Load ``libhyena.so`` from the package directory (building it first only if it is absent)."""
+    """Load ``libhyena.so`` from the package directory, building it first if it is absent or older than any of
+    its sources (so that an edited kernel is never tested through a stale library)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        if _build.stale():
             _build.build_library()
         L = ctypes.CDLL(_build.LIB)
         vp, i64, i32, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int
@@ -38,7 +39,7 @@ def lib() -> ctypes.CDLL:
         L.hyena_mr_fwd.argtypes = conv_args
         L.hyena_featurize_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_featurize3_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, ci, vp]
-        L.hyena_chain_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, i32, i32, ci, vp]
+        L.hyena_chain_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i64, i32, i32, i32, i32, ci, vp]
         L.hyena_chain_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, i32, i32, ci]
         L.hyena_chain_workspace_bytes.restype = i64
         bwd_args = [vp] * 10 + [i64, i64, i64, i64, i32, i32, ci, vp]
@@ -247,7 +248,8 @@ def _chain_args(q, k, v, hq, hk, hv, h, group, feat_group, out, workspace, strea
         raise ValueError("workspace must be a contiguous tensor of at least %d bytes on the same GPU" % need)
     c = ctypes
     ptrs = [t.data_ptr() for t in (q, k, v, hq, hk, hv, h, y)] + [workspace.data_ptr() if need > 0 else None]
-    args = tuple(c.c_void_p(p) for p in ptrs) + (c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lf),
+    ws_bytes = workspace.numel() * workspace.element_size() if need > 0 else 0
+    args = tuple(c.c_void_p(p) for p in ptrs) + (c.c_int64(ws_bytes), c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lf),
                                                   c.c_int32(int(feat_group)), c.c_int32(lh), c.c_int32(int(group)),
                                                   c.c_int(_dtype_code(q)), c.c_void_p(_stream(q, stream)))
     return args, (q, k, v, hq, hk, hv, h, y, workspace), y

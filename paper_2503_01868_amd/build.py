@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libhyena.so")
 
-SOURCES = ["api.hip", "se_kernels.hip", "sew_kernels.hip", "direct_kernels.hip", "mr_kernels.hip", "cp_kernels.hip", "cp4_kernels.hip", "li_kernels.hip", "chain_kernels.hip", "chain4_kernels.hip", "bwd_kernels.hip", "mr_bwd_kernels.hip"]
+SOURCES = ["api.hip", "se_kernels.hip", "sew_kernels.hip", "direct_kernels.hip", "mr_kernels.hip", "cp_kernels.hip", "cp4_kernels.hip", "li_kernels.hip", "chain4_kernels.hip", "bwd_kernels.hip", "mr_bwd_kernels.hip"]
 
 # Packed-fp32 instruction selection is switched off for all device code in this library.
 HIPCC_FLAGS = [
@@ -33,6 +33,15 @@ def _compile(src: str) -> str:
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s" % (src, proc.stderr))
     return obj
+
+
+def stale() -> bool:
+    """True when the library is missing or older than any file it is built from."""
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "hyena.h")]
+    return any(os.path.getmtime(d) > built for d in deps)
 
 
 def build_library(verbose: bool = False) -> str:

@@ -1,14 +1,24 @@
 // C ABI of the library: argument validation (before any HIP call), kernel selection, tuning options.
 #include <string.h>
 
+#include <mutex>
+
 #include "hy_common.hpp"
 #include "hy_launch.hpp"
 
 namespace hy {
 
-Tuning& tuning() {
-    static Tuning t;
-    return t;
+namespace {
+std::mutex g_tuning_mu;
+Tuning g_tuning;                   // process-wide options, guarded by g_tuning_mu
+thread_local Tuning t_tuning;      // what the entry point running on this thread sees
+}  // namespace
+
+const Tuning& tuning() { return t_tuning; }
+
+TuningSnapshot::TuningSnapshot() {
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    t_tuning = g_tuning;
 }
 
 namespace {
@@ -41,15 +51,43 @@ bool overlaps2(const void* a, int64_t abytes, const void* b, int64_t bbytes) {
 
 bool overlaps(const void* a, const void* b, int64_t bytes) { return overlaps2(a, bytes, b, bytes); }
 
-// Checks shared by every convolution entry point.  `ins`/`outs` hold activation pointers.
-hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_out, const float* const* hs,
+// A device buffer an entry point reads or writes.
+struct Range {
+    const void* p;
+    int64_t bytes;
+};
+
+int64_t filter_bytes(int64_t D, int32_t group, int32_t lh) { return (D / group) * (int64_t)lh * (int64_t)sizeof(float); }
+
+// Every written buffer must be disjoint from every other buffer of the call (activations, filter tables, filter
+// gradient, workspace alike).  Empty ranges never overlap anything.
+hy_status check_disjoint(const Range* rd, int n_rd, const Range* wr, int n_wr) {
+    for (int o = 0; o < n_wr; ++o) {
+        if (wr[o].bytes <= 0) continue;
+        for (int i = 0; i < n_rd; ++i)
+            if (rd[i].bytes > 0 && overlaps2(wr[o].p, wr[o].bytes, rd[i].p, rd[i].bytes)) return HY_ERR_ALIGN;
+        for (int o2 = o + 1; o2 < n_wr; ++o2)
+            if (wr[o2].bytes > 0 && overlaps2(wr[o].p, wr[o].bytes, wr[o2].p, wr[o2].bytes)) return HY_ERR_ALIGN;
+    }
+    return HY_OK;
+}
+
+// A filter table the call reads: fp32 [D/group, lh].
+struct FilterArg {
+    const float* p;
+    int32_t group, lh;
+};
+
+// Checks shared by every convolution entry point.  `ins`/`outs` hold activation pointers, `hs` the fp32 filter
+// tables the call reads; lh and group are those of the inner filter.
+hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_out, const FilterArg* hs,
                    int n_h, int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
     for (int i = 0; i < n_in; ++i)
         if (!ins[i]) return HY_ERR_NULL;
     for (int i = 0; i < n_out; ++i)
         if (!outs[i]) return HY_ERR_NULL;
     for (int i = 0; i < n_h; ++i)
-        if (!hs[i]) return HY_ERR_NULL;
+        if (!hs[i].p) return HY_ERR_NULL;
     if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1) return HY_ERR_SHAPE;
     if (D % group != 0) return HY_ERR_SHAPE;
     if (dtype != HY_F32 && dtype != HY_BF16) return HY_ERR_DTYPE;
@@ -58,18 +96,20 @@ hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_ou
     for (int i = 0; i < n_out; ++i)
         if (!aligned16(outs[i])) return HY_ERR_ALIGN;
     for (int i = 0; i < n_h; ++i)
-        if (!aligned16(hs[i])) return HY_ERR_ALIGN;
+        if (!aligned16(hs[i].p)) return HY_ERR_ALIGN;
     // sizes must stay addressable with signed 64-bit byte offsets
     const int64_t esz = dtype == HY_F32 ? 4 : 2;
     if (B > 0 && L > 0 && D > 0) {
         if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > INT64_MAX / esz) return HY_ERR_SHAPE;
         const int64_t bytes = B * L * D * esz;
-        for (int o = 0; o < n_out; ++o) {
-            for (int i = 0; i < n_in; ++i)
-                if (overlaps(outs[o], ins[i], bytes)) return HY_ERR_ALIGN;
-            for (int o2 = o + 1; o2 < n_out; ++o2)
-                if (overlaps(outs[o], outs[o2], bytes)) return HY_ERR_ALIGN;
-        }
+        Range rd[8], wr[4];
+        int n_rd = 0;
+        for (int i = 0; i < n_in; ++i) rd[n_rd++] = Range{ins[i], bytes};
+        for (int i = 0; i < n_h; ++i)
+            if (hs[i].group >= 1 && hs[i].lh >= 1 && D % hs[i].group == 0)  // (else the caller reports the shape)
+                rd[n_rd++] = Range{hs[i].p, filter_bytes(D, hs[i].group, hs[i].lh)};
+        for (int o = 0; o < n_out; ++o) wr[o] = Range{outs[o], bytes};
+        return check_disjoint(rd, n_rd, wr, n_out);
     }
     return HY_OK;
 }
@@ -81,41 +121,23 @@ bool empty(int64_t B, int64_t L, int64_t D) { return B == 0 || L == 0 || D == 0;
 
 using namespace hy;
 
-extern "C" {
+namespace {
 
-hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
-                       int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+hy_status gated_fwd(bool mr_first, const void* q, const void* k, const void* v, const float* h, void* y, int64_t B,
+                    int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+    TuningSnapshot snap;
     const void* ins[3] = {q, k, v};
     void* outs[1] = {y};
-    const float* hs[1] = {h};
+    const FilterArg hs[1] = {{h, group, lh}};
     hy_status rc = validate(ins, 3, outs, 1, hs, 1, B, L, D, lh, group, dtype);
     if (rc != HY_OK) return rc;
     if (empty(B, L, D)) return HY_OK;
     ConvPtrs p{q, k, v, h, y};
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (se_walk_preferred(s)) return launch_se_walk(p, s, st);
-    rc = launch_stencil(&p, 1, s, st);
-    if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp4(p, s, st);
-    if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp_mfma(p, s, st);
-    if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
-    return rc;
-}
-
-hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
-                       int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
-    const void* ins[3] = {q, k, v};
-    void* outs[1] = {y};
-    const float* hs[1] = {h};
-    hy_status rc = validate(ins, 3, outs, 1, hs, 1, B, L, D, lh, group, dtype);
-    if (rc != HY_OK) return rc;
-    if (empty(B, L, D)) return HY_OK;
-    ConvPtrs p{q, k, v, h, y};
-    ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    rc = launch_mr_mfma(p, s, st);
-    // short filters that the grouped matrix-core path does not take are the SE kernels' business
-    if (rc == HY_ERR_UNSUPPORTED && lh <= 8) {
+    rc = mr_first ? launch_mr_mfma(p, s, st) : HY_ERR_UNSUPPORTED;
+    // short filters (that the grouped matrix-core path does not take) are the SE kernels' business
+    if (rc == HY_ERR_UNSUPPORTED && (lh <= 8 || !mr_first)) {
         if (se_walk_preferred(s)) return launch_se_walk(p, s, st);
         rc = launch_stencil(&p, 1, s, st);
     }
@@ -125,11 +147,45 @@ hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float*
     return rc;
 }
 
+// Argument checks shared by hyena_li_fwd and its static-scratch form.
+hy_status li_validate(const void* q, const void* k, const void* v, const float* R, const float* lambda, void* y,
+                      int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype) {
+    const void* ins[3] = {q, k, v};
+    void* outs[1] = {y};
+    const FilterArg hs[2] = {{R, group, order}, {lambda, group, order}};
+    return validate(ins, 3, outs, 1, hs, 2, B, L, D, order, group, dtype);
+}
+
+// The workspace of a call must be present, aligned, large enough and disjoint from every other buffer.
+hy_status check_workspace(const void* ws, int64_t ws_bytes, int64_t need, const Range* others, int n_others) {
+    if (need <= 0) return HY_OK;
+    if (!ws) return HY_ERR_NULL;
+    if (!aligned16(ws)) return HY_ERR_ALIGN;
+    if (ws_bytes < need) return HY_ERR_SHAPE;
+    const Range w{ws, need};
+    return check_disjoint(others, n_others, &w, 1);
+}
+
+}  // namespace
+
+extern "C" {
+
+hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
+                       int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+    return gated_fwd(false, q, k, v, h, y, B, L, D, lh, group, dtype, hip_stream);
+}
+
+hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
+                       int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+    return gated_fwd(true, q, k, v, h, y, B, L, D, lh, group, dtype, hip_stream);
+}
+
 hy_status hyena_featurize_fwd(const void* x, const float* h, void* y, int64_t B, int64_t L, int64_t D, int32_t lh,
                               int32_t group, int32_t dtype, void* hip_stream) {
+    TuningSnapshot snap;
     const void* ins[1] = {x};
     void* outs[1] = {y};
-    const float* hs[1] = {h};
+    const FilterArg hs[1] = {{h, group, lh}};
     hy_status rc = validate(ins, 1, outs, 1, hs, 1, B, L, D, lh, group, dtype);
     if (rc != HY_OK) return rc;
     if (empty(B, L, D)) return HY_OK;
@@ -144,9 +200,10 @@ hy_status hyena_featurize_fwd(const void* x, const float* h, void* y, int64_t B,
 hy_status hyena_featurize3_fwd(const void* q, const void* k, const void* v, const float* hq, const float* hk,
                                const float* hv, void* qo, void* ko, void* vo, int64_t B, int64_t L, int64_t D,
                                int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+    TuningSnapshot snap;
     const void* ins[3] = {q, k, v};
     void* outs[3] = {qo, ko, vo};
-    const float* hs[3] = {hq, hk, hv};
+    const FilterArg hs[3] = {{hq, group, lh}, {hk, group, lh}, {hv, group, lh}};
     hy_status rc = validate(ins, 3, outs, 3, hs, 3, B, L, D, lh, group, dtype);
     if (rc != HY_OK) return rc;
     if (empty(B, L, D)) return HY_OK;
@@ -164,42 +221,39 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
     if (D % group != 0 || D % feat_group != 0) return -1;
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
     ChainShape s{B, L, D, lf, feat_group, lh, group, static_cast<hy_dtype>(dtype)};
-    if (empty(B, L, D) || chain_fused_supported(s) || (chain4_supported(s) && !tuning().chain_valu)) return 0;
+    if (empty(B, L, D) || chain4_supported(s)) return 0;
     const int64_t esz = dtype == HY_F32 ? 4 : 2;
     if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > INT64_MAX / (3 * esz)) return -1;
     return 3 * B * L * D * esz;
 }
 
 hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const float* hq, const float* hk,
-                          const float* hv, const float* h, void* y, void* workspace, int64_t B, int64_t L, int64_t D,
-                          int32_t lf, int32_t feat_group, int32_t lh, int32_t group, int32_t dtype,
-                          void* hip_stream) {
+                          const float* hv, const float* h, void* y, void* workspace, int64_t workspace_bytes,
+                          int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh, int32_t group,
+                          int32_t dtype, void* hip_stream) {
+    TuningSnapshot snap;
     const void* ins[3] = {q, k, v};
     void* outs[1] = {y};
-    const float* hs[4] = {hq, hk, hv, h};
+    const FilterArg hs[4] = {{hq, feat_group, lf}, {hk, feat_group, lf}, {hv, feat_group, lf}, {h, group, lh}};
     hy_status rc = validate(ins, 3, outs, 1, hs, 4, B, L, D, lh, group, dtype);
     if (rc != HY_OK) return rc;
-    if (lf < 1 || feat_group < 1 || D % feat_group != 0) return HY_ERR_SHAPE;
+    if (lf < 1 || feat_group < 1 || D % feat_group != 0 || workspace_bytes < 0) return HY_ERR_SHAPE;
     if (empty(B, L, D)) return HY_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     ChainShape cs{B, L, D, lf, feat_group, lh, group, static_cast<hy_dtype>(dtype)};
-    if (chain4_supported(cs) && !tuning().chain_valu) {
+    if (chain4_supported(cs)) {
         ChainPtrs cp{q, k, v, hq, hk, hv, h, y};
         return launch_chain4(cp, cs, st);
     }
-    if (chain_fused_supported(cs)) {
-        ChainPtrs cp{q, k, v, hq, hk, hv, h, y};
-        return launch_chain_fused(cp, cs, st);
-    }
     // two-kernel path through the caller's workspace
-    if (!workspace) return HY_ERR_NULL;
-    if (!aligned16(workspace)) return HY_ERR_ALIGN;
     const int64_t esz = dtype == HY_F32 ? 4 : 2;
-    const int64_t bytes = B * L * D * esz;
     if (B * L * D > INT64_MAX / (3 * esz)) return HY_ERR_SHAPE;
-    const void* all[4] = {q, k, v, y};
-    for (int i = 0; i < 4; ++i)
-        if (overlaps2(all[i], bytes, workspace, 3 * bytes)) return HY_ERR_ALIGN;
+    const int64_t bytes = B * L * D * esz;
+    const Range others[8] = {{q, bytes}, {k, bytes}, {v, bytes}, {y, bytes},
+                             {hq, filter_bytes(D, feat_group, lf)}, {hk, filter_bytes(D, feat_group, lf)},
+                             {hv, filter_bytes(D, feat_group, lf)}, {h, filter_bytes(D, group, lh)}};
+    rc = check_workspace(workspace, workspace_bytes, 3 * bytes, others, 8);
+    if (rc != HY_OK) return rc;
     char* ws = static_cast<char*>(workspace);
     ConvPtrs f[3] = {{nullptr, q, nullptr, hq, ws}, {nullptr, k, nullptr, hk, ws + bytes}, {nullptr, v, nullptr, hv, ws + 2 * bytes}};
     ConvShape fs{B, L, D, lf, feat_group, static_cast<hy_dtype>(dtype), false};
@@ -214,6 +268,7 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
 }
 
 int64_t hyena_li_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype) {
+    TuningSnapshot snap;
     if (B < 0 || L < 0 || D < 0 || order < 1 || group < 1 || D % group != 0) return -1;
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
     if (empty(B, L, D)) return 0;
@@ -224,10 +279,8 @@ int64_t hyena_li_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order,
 hy_status hyena_li_fwd(const void* q, const void* k, const void* v, const float* R, const float* lambda, void* y,
                        void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D, int32_t order,
                        int32_t group, int32_t dtype, void* hip_stream) {
-    const void* ins[3] = {q, k, v};
-    void* outs[1] = {y};
-    const float* hs[2] = {R, lambda};
-    hy_status rc = validate(ins, 3, outs, 1, hs, 2, B, L, D, order, group, dtype);
+    TuningSnapshot snap;
+    hy_status rc = li_validate(q, k, v, R, lambda, y, B, L, D, order, group, dtype);
     if (rc != HY_OK) return rc;
     if (workspace_bytes < 0) return HY_ERR_SHAPE;
     if (order > 16) return HY_ERR_UNSUPPORTED;
@@ -236,24 +289,18 @@ hy_status hyena_li_fwd(const void* q, const void* k, const void* v, const float*
     LiPtrs p{q, k, v, R, lambda, y};
     LiShape s{B, L, D, order, group, static_cast<hy_dtype>(dtype)};
     if (li_mfma_supported(s)) {
-        const int64_t need = li_workspace_bytes(s);
-        if (need > 0) {
-            if (!workspace) return HY_ERR_NULL;
-            if (!aligned16(workspace)) return HY_ERR_ALIGN;
-            if (workspace_bytes < need) return HY_ERR_SHAPE;
-            const int64_t bytes = B * L * D * 2;
-            const void* all[4] = {q, k, v, y};
-            for (int i = 0; i < 4; ++i)
-                if (overlaps2(all[i], bytes, workspace, need)) return HY_ERR_ALIGN;
-            const int64_t nf = (D / group) * (int64_t)order * (int64_t)sizeof(float);
-            if (overlaps2(R, nf, workspace, need) || overlaps2(lambda, nf, workspace, need)) return HY_ERR_ALIGN;
-        }
+        const int64_t bytes = B * L * D * 2;
+        const int64_t nf = filter_bytes(D, group, order);
+        const Range others[6] = {{q, bytes}, {k, bytes}, {v, bytes}, {y, bytes}, {R, nf}, {lambda, nf}};
+        rc = check_workspace(workspace, workspace_bytes, li_workspace_bytes(s), others, 6);
+        if (rc != HY_OK) return rc;
         return launch_li_mfma(p, s, workspace, st);
     }
     return launch_li_direct(p, s, st);
 }
 
 int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
+    TuningSnapshot snap;
     if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1 || D % group != 0) return -1;
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
     if (empty(B, L, D)) return 0;
@@ -266,17 +313,22 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
 static hy_status gated_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,
                            void* dk, void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B,
                            int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+    TuningSnapshot snap;
     const void* ins[4] = {dy, q, k, v};
     void* outs[3] = {dq, dk, dv};
-    const float* hs[2] = {h, dh};
+    const FilterArg hs[2] = {{h, group, lh}, {dh, group, lh}};
     hy_status rc = validate(ins, 4, outs, 3, hs, 2, B, L, D, lh, group, dtype);
     if (rc != HY_OK) return rc;
     if (workspace_bytes < 0) return HY_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const int64_t nh = (D / group) * (int64_t)lh * (int64_t)sizeof(float);
-    if (overlaps2(h, nh, dh, nh)) return HY_ERR_ALIGN;
+    const int64_t nh = filter_bytes(D, group, lh);
+    const int64_t bytes = B * L * D * (dtype == HY_F32 ? 4 : 2);
+    // dh is written: disjoint from the filter and from every activation, read or written
+    const Range reads[8] = {{h, nh}, {dy, bytes}, {q, bytes}, {k, bytes}, {v, bytes}, {dq, bytes}, {dk, bytes}, {dv, bytes}};
+    const Range dh_range{dh, nh};
+    if (check_disjoint(reads, 8, &dh_range, 1) != HY_OK) return HY_ERR_ALIGN;
     if (empty(B, L, D)) {
-        // an empty batch has a zero filter gradient
+        // an empty batch has a zero filter gradient: one small fill launch, nothing else
         return launch_bwd_zero_dh(dh, D, lh, group, st);
     }
     BwdPtrs p{dy, q, k, v, h, dq, dk, dv, dh};
@@ -285,14 +337,10 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
     const bool mfma = !stencil && mr_bwd_supported(s);
     if (stencil || mfma) {
         const int64_t need = stencil ? bwd_stencil_workspace_bytes(s) : mr_bwd_workspace_bytes(s);
-        if (!workspace) return HY_ERR_NULL;
-        if (!aligned16(workspace)) return HY_ERR_ALIGN;
-        if (workspace_bytes < need) return HY_ERR_SHAPE;
-        const int64_t bytes = B * L * D * (dtype == HY_F32 ? 4 : 2);
-        const void* all[7] = {dy, q, k, v, dq, dk, dv};
-        for (int i = 0; i < 7; ++i)
-            if (overlaps2(all[i], bytes, workspace, need)) return HY_ERR_ALIGN;
-        if (overlaps2(h, nh, workspace, need) || overlaps2(dh, nh, workspace, need)) return HY_ERR_ALIGN;
+        const Range others[9] = {{dy, bytes}, {q, bytes}, {k, bytes}, {v, bytes}, {dq, bytes},
+                                 {dk, bytes}, {dv, bytes}, {h, nh}, {dh, nh}};
+        rc = check_workspace(workspace, workspace_bytes, need, others, 9);
+        if (rc != HY_OK) return rc;
         if (stencil) return launch_bwd_stencil(p, s, workspace, st);
         // medium grouped filters: dq is the forward operator applied to (dy, k, v); then dk, dv, dh
         ConvPtrs f{dy, k, v, h, dq};
@@ -325,15 +373,15 @@ hy_status hyena_stream_copy(const void* src, void* dst, int64_t bytes, void* hip
     const int64_t per_block = kCopyBlock * kCopyPerLane;
     const int64_t nb = (n16 + per_block - 1) / per_block;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(copy_kernel, dim3((uint32_t)nb), dim3(kCopyBlock), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
-    return launch_status();
+    return launch_kernel(copy_kernel, dim3((uint32_t)nb), dim3(kCopyBlock), static_cast<hipStream_t>(hip_stream),
+                         static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
 }
 
 hy_status hyena_set_option(const char* name, int32_t value) {
     if (!name) return HY_ERR_NULL;
     if (value < 0) return HY_ERR_SHAPE;
-    Tuning& t = tuning();
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    Tuning& t = g_tuning;
     if (strcmp(name, "se_vec") == 0) {
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return HY_ERR_SHAPE;
         t.se_vec = value;
@@ -348,9 +396,6 @@ hy_status hyena_set_option(const char* name, int32_t value) {
     } else if (strcmp(name, "se_walk") == 0) {
         if (value > 2) return HY_ERR_SHAPE;
         t.se_walk = value;
-    } else if (strcmp(name, "chain_valu") == 0) {
-        if (value > 1) return HY_ERR_SHAPE;
-        t.chain_valu = value;
     } else {
         return HY_ERR_UNSUPPORTED;
     }
@@ -363,13 +408,13 @@ const char* hyena_status_string(int32_t status) {
         case HY_ERR_NULL: return "null pointer argument";
         case HY_ERR_SHAPE: return "invalid shape or size argument";
         case HY_ERR_DTYPE: return "unknown dtype";
-        case HY_ERR_ALIGN: return "pointer not 16-byte aligned, or output aliases an input";
+        case HY_ERR_ALIGN: return "pointer not 16-byte aligned, or a written buffer overlaps another buffer of the call";
         case HY_ERR_UNSUPPORTED: return "no kernel for this problem";
         case HY_ERR_LAUNCH: return "HIP launch error";
     }
     return "unknown status";
 }
 
-int32_t hyena_version(void) { return 100; }
+int32_t hyena_version(void) { return 200; }
 
 }  // extern "C"

@@ -392,12 +392,12 @@ hy_status launch_stencil_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipSt
     a.nitems = s.B * a.tiles_per_seq * a.nvec;
     const int64_t nb = (a.nitems + kBlock - 1) / kBlock;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((bwd_stencil_kernel<T, VEC, LH, R>), dim3((uint32_t)nb), dim3(kBlock), 0, st, a);
+    const hy_status rc = launch_kernel((bwd_stencil_kernel<T, VEC, LH, R>), dim3((uint32_t)nb), dim3(kBlock), st, a);
+    if (rc != HY_OK) return rc;
     const int64_t nsets = s.B * a.tiles_per_seq;
     const int64_t nout = (s.D / s.group) * s.lh;
-    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), 0, st,
-                       a.partial, p.dh, nsets, s.D, s.lh, s.group);
-    return launch_status();
+    return launch_kernel(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), st,
+                         a.partial, p.dh, nsets, s.D, s.lh, s.group);
 }
 
 template <typename T>
@@ -424,10 +424,10 @@ hy_status launch_direct_t(const BwdPtrs& p, const BwdShape& s, hipStream_t st) {
     const int64_t gy = (s.L + kRows * kRowLanes - 1) / (kRows * kRowLanes);
     const int64_t G = s.D / s.group;
     if (gx > 0x7fffffffLL || gy > 65535 || s.B > 65535 || G > 0x7fffffffLL || s.lh > 65535) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((bwd_direct_kernel<T>), dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)s.B), dim3(kChan * kRowLanes), 0,
-                       st, a);
-    hipLaunchKernelGGL((dh_direct_kernel<T>), dim3((uint32_t)G, (uint32_t)s.lh), dim3(kBlock), 0, st, a);
-    return launch_status();
+    const hy_status rc = launch_kernel((bwd_direct_kernel<T>), dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)s.B),
+                                       dim3(kChan * kRowLanes), st, a);
+    if (rc != HY_OK) return rc;
+    return launch_kernel((dh_direct_kernel<T>), dim3((uint32_t)G, (uint32_t)s.lh), dim3(kBlock), st, a);
 }
 
 }  // namespace
@@ -453,9 +453,8 @@ hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64
                            hipStream_t st) {
     const int64_t nout = (n_rows / group) * lh;
     if (nout == 0) return HY_OK;
-    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), 0, st, partial, dh,
+    return launch_kernel(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), st, partial, dh,
                        nsets, n_rows, lh, group);
-    return launch_status();
 }
 
 hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st) {
@@ -463,9 +462,8 @@ hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hi
     if (nout == 0) return HY_OK;
     // a reduction over zero partial sets writes zeros (a fill kernel, not a memset, so that callers may
     // capture the call in a HIP graph)
-    hipLaunchKernelGGL(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), 0, st,
-                       static_cast<const float*>(dh), dh, (int64_t)0, D, lh, group);
-    return launch_status();
+    return launch_kernel(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), st,
+                         static_cast<const float*>(dh), dh, (int64_t)0, D, lh, group);
 }
 
 hy_status launch_bwd_direct(const BwdPtrs& p, const BwdShape& s, hipStream_t st) {

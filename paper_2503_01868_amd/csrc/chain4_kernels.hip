@@ -1,9 +1,9 @@
-// Fused Hyena-MR operator chain, forward (Sec. 2.1 Eq. 1 without the dense projections), second design:
+// Fused Hyena-MR operator chain, forward (Sec. 2.1 Eq. 1 without the dense projections):
 //     q' = hq * q,  k' = hk * k,  v' = hv * v          short per-channel featurizer convolutions
 //     y  = q' (.) ( h * (k' (.) v') )                  grouped medium convolution with both gates
-// with the featurizers on the matrix cores as well.  The kernel in chain_kernels.hip evaluates the three short
-// convolutions on the vector ALUs and is bound by vector instruction issue; here every convolution is a
-// Toeplitz product and the vector ALUs only gate, convert and transpose.
+// with the featurizers on the matrix cores as well.  (An earlier kernel that evaluated the three short
+// convolutions on the vector ALUs was bound by vector instruction issue and has been removed.)  Here every
+// convolution is a Toeplitz product and the vector ALUs only gate, convert and transpose.
 //
 //   featurizers  one filter per channel, so chunks of one channel go on the matrix tile (App. A.1) with the batched
 //                instruction v_mfma_f32_4x4x4_16B_bf16 as in cp4_kernels.hip: per tensor and 16 outputs of 16
@@ -362,8 +362,7 @@ hy_status launch_chain4_nkb(const ChainPtrs& p, const ChainShape& s, hipStream_t
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((chain4_kernel<NKB, PF>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), 0, st, a);
-    return launch_status();
+    return launch_kernel((chain4_kernel<NKB, PF>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), st, a);
 }
 
 }  // namespace

@@ -535,8 +535,7 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((cp4_kernel<NBK, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), 0, st, a);
-    return launch_status();
+    return launch_kernel((cp4_kernel<NBK, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
 }
 
 template <int NBK, int PF>
@@ -565,8 +564,7 @@ hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((cp4ws_kernel<NBK, PF>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), 0, st, a);
-    return launch_status();
+    return launch_kernel((cp4ws_kernel<NBK, PF>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), st, a);
 }
 
 template <int NBK>
@@ -576,12 +574,13 @@ hy_status launch_cp4_nbk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) 
     // fits the registers, but runs slower than 8 waves, 92 against 63 us at lh = 128.)
     if constexpr (NBK <= 17) {
         if (s.D % 256 == 0 && tuning().mr_waves != 8) return launch_cp4_nw<NBK, 16, 1>(p, s, st);
+        // (a second register stage of loads in flight, PF = 2, measured no faster here)
+        return launch_cp4_nw<NBK, 8, 1>(p, s, st);
+    } else {
+        // long filters: 8 multiplier waves + 4 mover waves (a kernel whose 8 waves load, multiply and store in turn
+        // ran at the same speed and was removed)
+        return launch_cp4_ws<NBK, 2>(p, s, st);
     }
-    // (a second register stage of loads in flight, PF = 2, measured no faster here)
-    if constexpr (NBK >= 25) {
-        if (tuning().mr_waves != 8) return launch_cp4_ws<NBK, 2>(p, s, st);
-    }
-    return launch_cp4_nw<NBK, 8, 1>(p, s, st);
 }
 
 }  // namespace

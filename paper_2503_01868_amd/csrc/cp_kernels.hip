@@ -285,8 +285,7 @@ hy_status launch_cp(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((cp_mfma_kernel<NKB>), dim3((uint32_t)nb), dim3(kThreads), 0, st, a);
-    return launch_status();
+    return launch_kernel((cp_mfma_kernel<NKB>), dim3((uint32_t)nb), dim3(kThreads), st, a);
 }
 
 }  // namespace

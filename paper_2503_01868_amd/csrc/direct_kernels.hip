@@ -87,9 +87,8 @@ hy_status launch_t(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t
     const int64_t gy = (s.L + kRows * kRowLanes - 1) / (kRows * kRowLanes);
     const int64_t gz = s.B * nprob;
     if (gx > 0x7fffffffLL || gy > 65535 || gz > 65535) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((direct_kernel<T, GATED>), dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)gz),
-                       dim3(kChan * kRowLanes), 0, st, a);
-    return launch_status();
+    return launch_kernel((direct_kernel<T, GATED>), dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)gz),
+                       dim3(kChan * kRowLanes), st, a);
 }
 
 }  // namespace

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "hyena.h"
 
 namespace hy {
@@ -82,9 +84,15 @@ struct Tuning {
     int mr_rows = 0;
     int mr_waves = 0;
     int se_walk = 0;  // 0: by size, 1: always the walking SE kernel where it applies, 2: never
-    int chain_valu = 0;  // 1: featurizers of the fused chain on the vector ALUs (the first design) even where the matrix-core kernel applies
 };
-Tuning& tuning();
+// The options as the calling thread's current entry point sees them.  Every extern "C" function that sizes or
+// launches anything starts with a TuningSnapshot, which copies the process-wide options under a lock into a
+// thread-local; all code below the ABI reads only that copy, so within one call the tile choice that sizes a
+// workspace and the one the launch uses cannot differ, whatever other threads set meanwhile.
+const Tuning& tuning();
+struct TuningSnapshot {
+    TuningSnapshot();
+};
 
 // Short-filter streaming stencil on the vector ALUs.  HY_ERR_UNSUPPORTED when lh is above its limit.
 hy_status launch_stencil(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
@@ -103,10 +111,8 @@ hy_status launch_cp_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // The same on the batched 4x4x4 MFMA: 256 channels per workgroup, lh <= 129.  HY_ERR_UNSUPPORTED outside cp4_supported().
 bool cp4_supported(const ConvShape& s);
 hy_status launch_cp4(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
-// Whole chain in one pass over q, k, v.  HY_ERR_UNSUPPORTED outside chain_fused_supported().
-bool chain_fused_supported(const ChainShape& s);
-hy_status launch_chain_fused(const ChainPtrs& p, const ChainShape& s, hipStream_t st);
-// The same chain with the featurizers on the matrix cores too (batched 4x4x4 products, taps as bf16 head + remainder).
+// Whole chain in one pass over q, k, v, featurizers on the matrix cores too (batched 4x4x4 products, taps as bf16
+// head + remainder).  HY_ERR_UNSUPPORTED outside chain4_supported().
 bool chain4_supported(const ChainShape& s);
 hy_status launch_chain4(const ChainPtrs& p, const ChainShape& s, hipStream_t st);
 // Hyena-LI as a two-pass chunked scan on bf16 MFMA (end-of-tile states in `ws`), and the plain recurrence.
@@ -132,6 +138,15 @@ hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64
 hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st);
 hy_status launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
 
-inline hy_status launch_status() { return hipGetLastError() == hipSuccess ? HY_OK : HY_ERR_LAUNCH; }
+// Launches `kernel` and returns the status of THIS launch as hipLaunchKernel reports it.  The thread's sticky
+// "last error" is neither read nor cleared: an error left behind by an earlier, unrelated HIP call of the caller
+// cannot make a healthy launch look failed, and stays there for the caller to find.
+template <typename... KArgs>
+inline hy_status launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t st,
+                               std::decay_t<KArgs>... args) {
+    void* ptrs[] = {static_cast<void*>(&args)...};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, st);
+    return e == hipSuccess ? HY_OK : HY_ERR_LAUNCH;
+}
 
 }  // namespace hy

@@ -414,11 +414,10 @@ hy_status launch_li_nw(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t 
     const int64_t nb1 = s.B * (a.tiles_per_seq - 1) * a.ncb;
     if (nb2 > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
     if (nb1 > 0) {
-        hipLaunchKernelGGL((li_mfma_kernel<NW, PF, true>), dim3((uint32_t)nb1), dim3(NW * 64), 0, st, a);
-        if (launch_status() != HY_OK) return HY_ERR_LAUNCH;
+        const hy_status rc = launch_kernel((li_mfma_kernel<NW, PF, true>), dim3((uint32_t)nb1), dim3(NW * 64), st, a);
+        if (rc != HY_OK) return rc;
     }
-    hipLaunchKernelGGL((li_mfma_kernel<NW, PF, false>), dim3((uint32_t)nb2), dim3(NW * 64), 0, st, a);
-    return launch_status();
+    return launch_kernel((li_mfma_kernel<NW, PF, false>), dim3((uint32_t)nb2), dim3(NW * 64), st, a);
 }
 
 }  // namespace
@@ -450,12 +449,10 @@ hy_status launch_li_direct(const LiPtrs& p, const LiShape& s, hipStream_t st) {
     const int64_t nb = (n + 63) / 64;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
     if (s.dtype == HY_F32)
-        hipLaunchKernelGGL((li_direct_kernel<F32>), dim3((uint32_t)nb), dim3(64), 0, st, p.q, p.k, p.v, p.R, p.lam, p.y,
+        return launch_kernel((li_direct_kernel<F32>), dim3((uint32_t)nb), dim3(64), st, p.q, p.k, p.v, p.R, p.lam, p.y,
                            s.B, s.L, s.D, s.order, s.group);
-    else
-        hipLaunchKernelGGL((li_direct_kernel<BF16>), dim3((uint32_t)nb), dim3(64), 0, st, p.q, p.k, p.v, p.R, p.lam, p.y,
-                           s.B, s.L, s.D, s.order, s.group);
-    return launch_status();
+    return launch_kernel((li_direct_kernel<BF16>), dim3((uint32_t)nb), dim3(64), st, p.q, p.k, p.v, p.R, p.lam, p.y,
+                         s.B, s.L, s.D, s.order, s.group);
 }
 
 }  // namespace hy

@@ -303,8 +303,7 @@ hy_status launch_nw(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t s
     *nsets = s.B * a.tiles_per_seq;
     const int64_t nb = *nsets * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((mr_bwd_kernel<NKB, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), 0, st, a);
-    return launch_status();
+    return launch_kernel((mr_bwd_kernel<NKB, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
 }
 
 template <int NKB>

@@ -171,8 +171,7 @@ hy_status launch_one(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream
     const int64_t nb = (a.nitems + kStencilBlock - 1) / kStencilBlock;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
     a.nblocks = (uint32_t)nb;
-    hipLaunchKernelGGL((stencil_kernel<T, VEC, LH, R, GATED>), dim3(a.nblocks, nprob), dim3(kStencilBlock), 0, st, a);
-    return launch_status();
+    return launch_kernel((stencil_kernel<T, VEC, LH, R, GATED>), dim3(a.nblocks, nprob), dim3(kStencilBlock), st, a);
 }
 
 template <typename T, int VEC, bool GATED>

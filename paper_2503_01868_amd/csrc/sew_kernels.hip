@@ -192,8 +192,7 @@ hy_status launch_sew_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((se_walk_kernel<LH, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), 0, st, a);
-    return launch_status();
+    return launch_kernel((se_walk_kernel<LH, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
 }
 
 template <int LH>

@@ -29,10 +29,12 @@ int main() {
     EXPECT(hyena_featurize_fwd(P[0], nullptr, P[1], 1, 8, 16, 7, 1, HY_F32, nullptr), HY_ERR_NULL);
     EXPECT(hyena_featurize3_fwd(P[0], P[1], P[2], H[0], H[1], H[2], P[3], P[4], P[3], 1, 8, 16, 7, 1, HY_F32, nullptr), HY_ERR_ALIGN);
     EXPECT(hyena_featurize3_fwd(P[0], P[1], P[2], H[0], H[1], H[2], P[3], P[4], P[5], 1, 8, 16, 7, 1, HY_F32, nullptr), HY_OK);
-    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], nullptr, 1, 8, 128, 7, 1, 128, 16, HY_BF16, nullptr), HY_OK);
-    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], nullptr, 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_ERR_NULL);
-    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], P[6], 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_OK);
-    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], P[2], 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_ERR_ALIGN);
+    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], nullptr, 0, 1, 8, 128, 7, 1, 128, 16, HY_BF16, nullptr), HY_OK);
+    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], nullptr, 0, 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_ERR_NULL);
+    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], P[6], 3 * 8 * 128 * 4, 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_OK);
+    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], P[6], 3 * 8 * 128 * 4 - 1, 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_ERR_SHAPE);
+    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], reinterpret_cast<const float*>(P[3]), P[3], P[6], 1 << 20, 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_ERR_ALIGN);
+    EXPECT(hyena_chain_fwd(P[0], P[1], P[2], H[0], H[1], H[2], H[3], P[3], P[2], 1 << 20, 1, 8, 128, 7, 1, 128, 16, HY_F32, nullptr), HY_ERR_ALIGN);
     if (hyena_chain_workspace_bytes(1, 8, 128, 7, 1, 128, 16, HY_F32) != 3 * 8 * 128 * 4) ++bad;
     if (hyena_chain_workspace_bytes(1, 8, 128, 7, 1, 128, 16, HY_BF16) != 0) ++bad;
     EXPECT(hyena_se_bwd(P[0], P[1], P[2], P[3], H[0], P[4], P[5], P[6], DH, P[7], 1 << 16, 1, 8, 16, 3, 1, HY_BF16, nullptr), HY_OK);
@@ -42,6 +44,9 @@ int main() {
     EXPECT(hyena_mr_bwd(P[0], P[1], P[2], P[3], H[0], P[4], P[5], P[4], DH, nullptr, 0, 1, 8, 40, 50, 1, HY_BF16, nullptr), HY_ERR_ALIGN);
     EXPECT(hyena_mr_bwd(P[0], P[1], P[2], P[3], H[0], P[4], P[5], P[6], DH, nullptr, 0, 0, 8, 40, 50, 1, HY_BF16, nullptr), HY_OK);
     if (hyena_bwd_workspace_bytes(1, 8, 16, 3, 1, HY_BF16) != 16 * 3 * 4) ++bad;
+    // a filter table or the filter gradient inside a written activation
+    EXPECT(hyena_se_fwd(P[0], P[1], P[2], reinterpret_cast<const float*>(P[3]), P[3], 1, 8, 16, 3, 1, HY_BF16, nullptr), HY_ERR_ALIGN);
+    EXPECT(hyena_se_bwd(P[0], P[1], P[2], P[3], H[0], P[4], P[5], P[6], reinterpret_cast<float*>(P[5]), P[7], 1 << 16, 1, 8, 16, 3, 1, HY_BF16, nullptr), HY_ERR_ALIGN);
     EXPECT(hyena_stream_copy(P[0], P[1], 24, nullptr), HY_ERR_SHAPE);
     EXPECT(hyena_stream_copy(P[0], P[1], 64, nullptr), HY_OK);
     EXPECT(hyena_set_option("se_vec", 3), HY_ERR_SHAPE);

@@ -74,6 +74,8 @@ def test_gated_entry_points_reject_bad_arguments(entry):
     assert conv(entry, h=P[3] + 8) == 4
     assert conv(entry, y=P[1]) == 4  # output aliases k
     assert conv(entry, y=P[1] + 16) == 4  # partial overlap
+    assert conv(entry, h=P[4] + 32) == 4  # the filter table lies inside the output
+    assert conv(entry, y=P[3] - 16) == 4  # the output's last bytes run into the filter table
     assert conv(entry, B=1 << 40, L=1 << 40, D=16) == 2  # size overflows 64-bit offsets
     # empty problems are valid and launch nothing
     assert conv(entry, B=0) == 0
@@ -126,11 +128,11 @@ def test_chain_entry_point_rejects_bad_arguments_and_sizes_its_workspace():
     lib = binding.lib()
 
     def ch(**kw):
-        a = dict(q=P[0], k=P[1], v=P[2], hq=P[3], hk=P[4], hv=P[5], h=P[6], y=P[7], ws=P[8],
+        a = dict(q=P[0], k=P[1], v=P[2], hq=P[3], hk=P[4], hv=P[5], h=P[6], y=P[7], ws=P[8], wsb=1 << 20,
                  B=1, L=8, D=128, lf=7, fg=1, lh=128, group=16, dtype=1)
         a.update(kw)
-        return lib.hyena_chain_fwd(*[a[n] for n in ("q", "k", "v", "hq", "hk", "hv", "h", "y", "ws", "B", "L", "D",
-                                                    "lf", "fg", "lh", "group", "dtype")], None)
+        return lib.hyena_chain_fwd(*[a[n] for n in ("q", "k", "v", "hq", "hk", "hv", "h", "y", "ws", "wsb", "B", "L",
+                                                    "D", "lf", "fg", "lh", "group", "dtype")], None)
 
     assert ch(q=None) == 1 and ch(hv=None) == 1 and ch(h=None) == 1 and ch(y=None) == 1
     assert ch(lf=0) == 2 and ch(fg=3) == 2 and ch(group=24) == 2 and ch(lh=0) == 2 and ch(dtype=9) == 3
@@ -139,12 +141,15 @@ def test_chain_entry_point_rejects_bad_arguments_and_sizes_its_workspace():
     # problems outside the single-kernel domain need a workspace
     assert ch(dtype=0, ws=None) == 1 and ch(D=64, group=16, ws=None) == 1 and ch(dtype=0, ws=P[8] + 2) == 4
     assert ch(dtype=0, ws=P[0]) == 4  # workspace overlaps an input
+    assert ch(dtype=0, wsb=3 * 8 * 128 * 4 - 1) == 2 and ch(wsb=-1) == 2  # workspace too small / negative size
+    assert ch(dtype=0, ws=P[4] - 4096) == 4  # workspace runs into a featurizer filter table
+    assert ch(h=P[7] + 64) == 4  # inner filter table inside the output
     wb = lib.hyena_chain_workspace_bytes
     assert wb(4, 32768, 4096, 7, 1, 128, 16, 1) == 0
     assert wb(1, 100, 64, 7, 1, 128, 16, 1) == 3 * 100 * 64 * 2
     assert wb(1, 100, 128, 7, 1, 128, 16, 0) == 3 * 100 * 128 * 4
     assert wb(1, 100, 128, 7, 1, 130, 16, 1) == 3 * 100 * 128 * 2
-    assert wb(1, 100, 128, 9, 1, 128, 16, 1) == 0   # nine taps: single kernel with matrix-core featurizers
+    assert wb(1, 100, 128, 9, 1, 128, 16, 1) == 0   # up to nine taps: single kernel
     assert wb(1, 100, 128, 10, 1, 128, 16, 1) == 3 * 100 * 128 * 2
     assert wb(1, 100, 128, 7, 1, 128, 24, 1) == -1 and wb(1, 100, 128, 0, 1, 128, 16, 1) == -1
     assert wb(0, 100, 128, 7, 1, 128, 16, 0) == 0
@@ -166,6 +171,7 @@ def test_backward_entry_points_reject_bad_arguments_and_size_their_workspace():
             assert bw(entry, **{name: None}) == 1
         assert bw(entry, lh=0) == 2 and bw(entry, group=3) == 2 and bw(entry, dtype=4) == 3 and bw(entry, wsb=-1) == 2
         assert bw(entry, dq=Q[1]) == 4 and bw(entry, dk=Q[5]) == 4 and bw(entry, dh=Q[4]) == 4 and bw(entry, dv=Q[7] + 2) == 4
+        assert bw(entry, dh=Q[6] + 64) == 4 and bw(entry, h=Q[5] + 64) == 4  # filter tables inside written tensors
         assert bw(entry, ws=None) == 1 and bw(entry, wsb=16) == 2 and bw(entry, ws=Q[9] + 4) == 4 and bw(entry, ws=Q[0]) == 4
     wb = lib.hyena_bwd_workspace_bytes
     assert wb(1, 8, 16, 3, 1, 1) == 1 * 1 * 16 * 3 * 4        # one tile
@@ -203,3 +209,32 @@ def test_long_implicit_entry_point_rejects_bad_arguments():
     assert lib.hyena_li_workspace_bytes(1, 64, 256, 16, 16, 1) == 0        # one tile
     assert lib.hyena_li_workspace_bytes(1, 64, 256, 0, 16, 1) == -1
     assert lib.hyena_li_workspace_bytes(1, 64, 250, 16, 16, 1) == -1
+
+
+def test_options_are_snapshotted_per_call_and_safe_to_set_from_other_threads():
+    """Workspace queries read one consistent snapshot of the options; setting options from other threads while
+    queries run never yields a size that belongs to neither setting."""
+    import threading
+
+    lib = binding.lib()
+    a = lib.hyena_li_workspace_bytes(1, 1 << 16, 256, 16, 16, 1)
+    assert lib.hyena_set_option(b"mr_rows", 1024) == 0
+    b = lib.hyena_li_workspace_bytes(1, 1 << 16, 256, 16, 16, 1)
+    assert lib.hyena_set_option(b"mr_rows", 0) == 0
+    assert a != b and a > 0 and b > 0
+    stop = threading.Event()
+
+    def flip():
+        while not stop.is_set():
+            lib.hyena_set_option(b"mr_rows", 1024)
+            lib.hyena_set_option(b"mr_rows", 0)
+
+    t = threading.Thread(target=flip)
+    t.start()
+    try:
+        seen = {lib.hyena_li_workspace_bytes(1, 1 << 16, 256, 16, 16, 1) for _ in range(20000)}
+    finally:
+        stop.set()
+        t.join()
+        lib.hyena_set_option(b"mr_rows", 0)
+    assert seen <= {a, b}

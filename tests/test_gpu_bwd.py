@@ -13,14 +13,14 @@ pytestmark = pytest.mark.gpu
 
 # dh is an fp32 sum over B*L*group products and is returned in fp32 for both storage types: its error is
 # accumulation rounding only (~sqrt(n) * 2^-24 relative to the sum's scale for the fp32 sums inside a tile; the
-# reduction over tiles and channels runs in fp64)
-DH_TOL = 2e-5
+# reduction over tiles and channels runs in fp64), so it is held to the fp32 bar
+DH_TOL = TOL["f32"]
 
 
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk", "chain_valu"):
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk"):
         binding.set_option(name, 0)
 
 

@@ -1,6 +1,7 @@
-"""GPU parity at the five benchmark configurations, in the launch configuration bench.py times.
-c0-c2 (and c2u, c2 with one filter per channel) are compared in full; c3 and c4 (half a billion outputs each)
-on sampled outputs the oracle evaluates one by one plus whole filter groups over all (b, t)."""
+"""GPU parity at the five benchmark configurations, in the launch configuration bench.py times, over EVERY output.
+c0-c2 (and c2u, c2 with one filter per channel) are compared in one piece; c3 and c4 (536 870 912 outputs each) in
+slabs of 256 channels (channels are independent given their filter group, so a slab of whole groups is an exact
+sub-problem for the oracle), folding max|y - y_ref| and max|y_ref| across slabs into the one acceptance metric."""
 import numpy as np
 import pytest
 import torch
@@ -29,62 +30,80 @@ def test_full_tensor_parity(name):
     assert err <= TOL[w["dtype"]]
 
 
-def subset_channels(w, groups):
-    """Slices of q, k, v and h that hold whole filter groups (channels are independent given their group)."""
-    dg = w["group"]
-    chans = np.concatenate([np.arange(g * dg, (g + 1) * dg) for g in groups])
-    idx = torch.from_numpy(chans)
-    sub = {key: w[key].index_select(2, idx).contiguous() for key in ("q", "k", "v")}
-    return chans, sub, w["h"][groups]
+SLAB = 256  # channels per oracle call: the fp64 reference of a slab of c3 / c4 is 268 MB
 
 
-def test_c3_long_context_sampled_and_group_subset():
+def slab_inputs(w, c0, c1, keys=("q", "k", "v")):
+    """Channels c0..c1-1 (whole filter groups) of the activations, contiguous."""
+    assert c0 % w["group"] == 0 and c1 % w["group"] == 0
+    return {key: w[key][:, :, c0:c1].contiguous() for key in keys}
+
+
+def fold_slabs(w, ys, ref_of_slab):
+    """max|y - y_ref| / max|y_ref| over the whole tensor for each device tensor in `ys` (a dict), the reference
+    computed slab by slab.  Returns {name: rel_err}; also checks that every output is finite."""
+    D = w["D"]
+    num = {name: 0.0 for name in ys}
+    den = 0.0
+    n_seen = 0
+    for c0 in range(0, D, SLAB):
+        c1 = min(D, c0 + SLAB)
+        ref = ref_of_slab(c0, c1)
+        den = max(den, float(np.abs(ref).max()))
+        for name, y_dev in ys.items():
+            got = y_dev[:, :, c0:c1].float().cpu().numpy().astype(np.float64)
+            assert np.isfinite(got).all(), (name, c0)
+            np.subtract(got, ref, out=got)
+            num[name] = max(num[name], float(np.abs(got).max()))
+        n_seen += ref.size
+        del ref
+    assert n_seen == w["B"] * w["L"] * D
+    return {name: num[name] / den for name in ys}, n_seen
+
+
+@pytest.mark.timeout(900)
+def test_c3_long_context_all_outputs():
+    """c3 (B=1, L=131072, D=4096, lh=128, groups of 16): all 536 870 912 outputs against the oracle."""
     say("config c3")
     w = synth.make("c3")
     y_dev = run_inner(w)
     torch.cuda.synchronize()
-    pts = synth.sample_points(7, w["B"], w["L"], w["D"], 20000, w["lh"])
-    ref = oracle.gated_conv_points(w["q"], w["k"], w["v"], w["h"], pts, group=w["group"])
-    got = y_dev[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
-    scale = np.abs(ref).max()
-    assert np.abs(got - ref).max() / scale <= TOL["bf16"]
-    groups = [0, 100, 255]
-    chans, sub, hsub = subset_channels(w, groups)
-    ref_sub = oracle.gated_conv(sub["q"], sub["k"], sub["v"], hsub, group=w["group"])
-    got_sub = y_dev.index_select(2, torch.from_numpy(chans).to(y_dev.device)).float().cpu().numpy().astype(np.float64)
-    err = oracle.rel_err(got_sub, ref_sub)
-    say("config c3 subset rel_err=%.3e" % err)
-    assert err <= TOL["bf16"]
+    dg = w["group"]
+
+    def ref_of_slab(c0, c1):
+        sub = slab_inputs(w, c0, c1)
+        return oracle.gated_conv(sub["q"], sub["k"], sub["v"], w["h"][c0 // dg:c1 // dg], group=dg)
+
+    errs, n = fold_slabs(w, {"mr": y_dev}, ref_of_slab)
+    say("config c3 all %d outputs rel_err=%.3e" % (n, errs["mr"]))
+    assert n == 536870912
+    assert errs["mr"] <= TOL["bf16"]
 
 
-def test_c4_operator_chain_sampled_and_group_subset():
+@pytest.mark.timeout(900)
+def test_c4_operator_chain_all_outputs():
+    """c4 (B=4, L=32768, D=4096; featurizers lf=7 per channel, inner lh=128 in groups of 16): all 536 870 912
+    outputs of the single-kernel chain (what bench.py times) and of the same chain run from its separate entry
+    points (featurized tensors rounded to bf16 in HBM) against the oracle's chain."""
     say("config c4")
     w = synth.make("c4")
     dq, dk, dv = dev(w["q"]), dev(w["k"]), dev(w["v"])
     dhq, dhk, dhv, dh = dev(w["hq"]), dev(w["hk"]), dev(w["hv"]), dev(w["h"])
-    # the single-kernel chain (what bench.py times) ...
     y_dev = binding.hyena_chain_fwd(dq, dk, dv, dhq, dhk, dhv, dh, w["group"], w["feat_group"])
-    # ... and the same chain from its separate entry points, featurized tensors rounded to bf16 in HBM
     qf, kf, vf = binding.hyena_featurize3_fwd(dq, dk, dv, dhq, dhk, dhv, w["feat_group"])
     del dq, dk, dv
     y_two = binding.hyena_mr_fwd(qf, kf, vf, dh, w["group"])
     torch.cuda.synchronize()
     del qf, kf, vf
-    pts = synth.sample_points(8, w["B"], w["L"], w["D"], 5000, w["lh"])
-    ref = oracle.chain_points(w["q"], w["k"], w["v"], w["hq"], w["hk"], w["hv"], w["h"], pts,
-                              group=w["group"], feat_group=w["feat_group"])
-    for name, yy in (("fused", y_dev), ("two-kernel", y_two)):
-        got = yy[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
-        err = np.abs(got - ref).max() / np.abs(ref).max()
-        say("config c4 %s sampled rel_err=%.3e" % (name, err))
-        assert err <= TOL["bf16"]
-    del y_two
-    groups = [0, 255]
-    chans, sub, hsub = subset_channels(w, groups)
-    idx = torch.from_numpy(chans)
-    ref_sub = oracle.chain(sub["q"], sub["k"], sub["v"], w["hq"][chans], w["hk"][chans], w["hv"][chans], hsub,
-                           group=w["group"], feat_group=1)
-    got_sub = y_dev.index_select(2, idx.to(y_dev.device)).float().cpu().numpy().astype(np.float64)
-    err = oracle.rel_err(got_sub, ref_sub)
-    say("config c4 subset rel_err=%.3e" % err)
-    assert err <= TOL["bf16"]
+    dg = w["group"]
+    assert w["feat_group"] == 1
+
+    def ref_of_slab(c0, c1):
+        sub = slab_inputs(w, c0, c1)
+        return oracle.chain(sub["q"], sub["k"], sub["v"], w["hq"][c0:c1], w["hk"][c0:c1], w["hv"][c0:c1],
+                            w["h"][c0 // dg:c1 // dg], group=dg, feat_group=1)
+
+    errs, n = fold_slabs(w, {"fused": y_dev, "two-kernel": y_two}, ref_of_slab)
+    say("config c4 all %d outputs rel_err fused=%.3e two-kernel=%.3e" % (n, errs["fused"], errs["two-kernel"]))
+    assert n == 536870912
+    assert errs["fused"] <= TOL["bf16"] and errs["two-kernel"] <= TOL["bf16"]

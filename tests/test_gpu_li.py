@@ -1,5 +1,6 @@
 """GPU parity of hyena_li_fwd (Hyena-LI, Sec. 2.1: filter = sum of real exponentials, as long as the sequence)
-against the oracle's definition: filter materialised in fp64 over the whole sequence, direct convolution."""
+against the oracle's definition: filter materialised in fp64 over the whole sequence, direct convolution.  The two
+full-size workloads are compared over every output against the oracle's recurrent form as well."""
 import numpy as np
 import pytest
 import torch
@@ -15,7 +16,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk", "chain_valu"):
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk"):
         binding.set_option(name, 0)
 
 
@@ -181,32 +182,69 @@ def test_guard_bands_determinism_and_no_leak_between_batch_items():
     assert oracle.rel_err(host(out[:1]), oracle.li_conv(q, k, v, R, lam, group=group)) <= TOL["bf16"]
 
 
-def test_full_size_config_on_sampled_outputs():
-    """li2 (B=1, L=8192, D=4096, 16 exponentials per group of 16) in the launch configuration bench.py times,
-    checked at sampled outputs the oracle computes one by one with the filter materialised over all 8192 steps."""
+def _all_outputs_against_the_recurrent_form(w, y, slab=256):
+    """max|y - y_ref| / max|y_ref| over every output, y_ref from the oracle's recurrent form in channel slabs."""
+    dg = w["group"]
+    num = den = 0.0
+    n = 0
+    for c0 in range(0, w["D"], slab):
+        c1 = min(w["D"], c0 + slab)
+        ref = oracle.li_recurrent(*(w[key][:, :, c0:c1].contiguous() for key in ("q", "k", "v")),
+                                  w["R"][c0 // dg:c1 // dg], w["lam"][c0 // dg:c1 // dg], group=dg)
+        got = y[:, :, c0:c1].float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        den = max(den, float(np.abs(ref).max()))
+        np.subtract(got, ref, out=got)
+        num = max(num, float(np.abs(got).max()))
+        n += ref.size
+    return num / den, n
+
+
+def _definition_at_points(w, y, seed, n_pts):
+    """Sampled outputs against the definition (filter materialised over the whole sequence, one direct sum per
+    output), and the recurrent-form oracle against the definition at the same outputs of the same inputs."""
+    pts = synth.sample_points(seed, w["B"], w["L"], w["D"], n_pts, 128)
+    ref = oracle.li_conv_points(w["q"], w["k"], w["v"], w["R"], w["lam"], pts, group=w["group"])
+    got = y[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= TOL["bf16"] * scale
+    # the channels the points fall in, through the recurrent form
+    chans = np.unique(pts[:, 2])
+    dg = w["group"]
+    idx = torch.from_numpy(chans)
+    sub = [w[key].index_select(2, idx).contiguous() for key in ("q", "k", "v")]
+    rec = oracle.li_recurrent(*sub, w["R"][chans // dg], w["lam"][chans // dg], group=1)
+    pos = np.searchsorted(chans, pts[:, 2])
+    assert np.abs(rec[pts[:, 0], pts[:, 1], pos] - ref).max() <= 1e-10 * scale
+
+
+@pytest.mark.timeout(600)
+def test_full_size_config_all_outputs():
+    """li2 (B=1, L=8192, D=4096, 16 exponentials per group of 16) in the launch configuration bench.py times: all
+    33 554 432 outputs against the oracle's recurrent form, and sampled outputs against the definition, which
+    also ties the recurrent form to the definition on these inputs."""
     w = synth.make("li2")
     say("li2 full size")
     y = binding.hyena_li_fwd(dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["R"]), dev(w["lam"]), w["group"])
     torch.cuda.synchronize()
-    pts = synth.sample_points(777, w["B"], w["L"], w["D"], 3000, 128)
-    ref = oracle.li_conv_points(w["q"], w["k"], w["v"], w["R"], w["lam"], pts, group=w["group"])
-    got = y[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
-    scale = np.abs(ref).max()
-    assert np.abs(got - ref).max() <= TOL["bf16"] * scale
-    assert torch.isfinite(y).all()
+    _definition_at_points(w, y, 777, 3000)
+    err, n = _all_outputs_against_the_recurrent_form(w, y)
+    say("li2 all %d outputs rel_err=%.3e" % (n, err))
+    assert n == 33554432 and err <= TOL["bf16"]
 
 
-def test_long_sequence_config_on_sampled_outputs():
-    """li3 (B=1, L=131072, D=4096): the running sums cross 15 tile boundaries and 4096 chunks; sampled outputs
-    against the filter materialised over all 131072 steps."""
+@pytest.mark.timeout(900)
+def test_long_sequence_config_all_outputs():
+    """li3 (B=1, L=131072, D=4096): the running sums cross 15 tile boundaries and 4096 chunks.  All 536 870 912
+    outputs against the oracle's recurrent form (the definition is quadratic in L: 3.5e13 multiply-adds for this
+    tensor), sampled outputs against the definition with the filter materialised over all 131072 steps."""
     w = synth.make("li3")
     say("li3 full size")
     y = binding.hyena_li_fwd(dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["R"]), dev(w["lam"]), w["group"])
     torch.cuda.synchronize()
-    pts = synth.sample_points(778, w["B"], w["L"], w["D"], 2000, 128)
-    ref = oracle.li_conv_points(w["q"], w["k"], w["v"], w["R"], w["lam"], pts, group=w["group"])
-    got = y[pts[:, 0], pts[:, 1], pts[:, 2]].float().cpu().numpy().astype(np.float64)
-    scale = np.abs(ref).max()
-    assert np.abs(got - ref).max() <= TOL["bf16"] * scale
+    _definition_at_points(w, y, 778, 2000)
+    err, n = _all_outputs_against_the_recurrent_form(w, y)
+    say("li3 all %d outputs rel_err=%.3e" % (n, err))
+    assert n == 536870912 and err <= TOL["bf16"]
     del y
     torch.cuda.empty_cache()

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_options():
     yield
-    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk", "chain_valu"):
+    for name in ("se_vec", "se_rows", "mr_rows", "mr_waves", "se_walk"):
         binding.set_option(name, 0)
 
 
@@ -246,10 +246,10 @@ def test_batched_small_tile_path_matches_oracle(case):
     check_gated(entry, 36, B, L, D, lh, group, "bf16", kind="mr")
 
 
-@pytest.mark.parametrize("case", [c for c in CP4_CASES if c[3] >= 66])
-def test_batched_small_tile_path_without_mover_waves_matches_oracle(case):
-    """Filters above 65 taps run with separate multiplier and mover waves by default; `mr_waves` = 8 selects the
-    kernel whose waves do both."""
+@pytest.mark.parametrize("case", [c for c in CP4_CASES if c[3] <= 65])
+def test_batched_small_tile_path_with_eight_waves_matches_oracle(case):
+    """Filters of up to 65 taps run 16 waves per workgroup where D allows; `mr_waves` = 8 selects the 128-channel
+    workgroup for them."""
     B, L, D, lh, group, rows = case
     binding.set_option("mr_rows", rows)
     binding.set_option("mr_waves", 8)
@@ -451,22 +451,18 @@ CHAIN_FUSED_CASES = [
 ]
 
 
-@pytest.mark.parametrize("valu", [0, 1], ids=["featurizers-mfma", "featurizers-valu"])
 @pytest.mark.parametrize("case", CHAIN_FUSED_CASES)
-def test_chain_single_kernel_path_matches_oracle(case, valu):
-    """Both single-kernel designs: featurizers as batched 4x4x4 matrix products (the default) and on the vector
-    ALUs (`chain_valu` = 1)."""
+def test_chain_single_kernel_path_matches_oracle(case):
+    """The single-kernel chain: featurizers and medium convolution as matrix products."""
     B, L, D, lf, fg, lh, group, rows = case
     binding.set_option("mr_rows", rows)
-    binding.set_option("chain_valu", valu)
     check_chain(61, B, L, D, lf, fg, lh, group, "bf16", expect_fused=True)
 
 
-def test_chain_nine_tap_featurizer_is_fused_only_on_the_matrix_cores():
+def test_chain_nine_tap_featurizer_is_the_longest_the_single_kernel_takes():
     binding.set_option("mr_rows", 96)
     check_chain(65, 2, 500, 128, 9, 1, 100, 16, "bf16", expect_fused=True)
-    binding.set_option("chain_valu", 1)
-    check_chain(65, 2, 500, 128, 9, 1, 100, 16, "bf16", expect_fused=False)
+    check_chain(65, 2, 500, 128, 10, 1, 100, 16, "bf16", expect_fused=False)
 
 
 @pytest.mark.parametrize("case", [
@@ -499,10 +495,8 @@ def test_chain_impulse_is_bit_exact():
         v[b, t0, c] = 1.0
     ref = oracle.chain(one, one, v, delta, delta, hv, h, group=group)
     assert np.array_equal(ref, torch.from_numpy(ref).bfloat16().double().numpy())
-    for valu in (0, 1):
-        binding.set_option("chain_valu", valu)
-        y = host(binding.hyena_chain_fwd(dev(one), dev(one), dev(v), dev(delta), dev(delta), dev(hv), dev(h), group, 1))
-        assert np.array_equal(y, ref), valu
+    y = host(binding.hyena_chain_fwd(dev(one), dev(one), dev(v), dev(delta), dev(delta), dev(hv), dev(h), group, 1))
+    assert np.array_equal(y, ref)
 
 
 def test_chain_guard_bands_and_determinism():
@@ -514,11 +508,8 @@ def test_chain_guard_bands_and_determinism():
     buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
     out = buf[guard:guard + n].view(B, L, D)
     args = [dev(x) for x in (q, k, v, hq, hk, hv, h)]
-    for valu in (0, 1):
-        binding.set_option("chain_valu", valu)
-        buf.fill_(float("nan"))
-        binding.hyena_chain_fwd(*args, 16, 1, out=out)
-        again = binding.hyena_chain_fwd(*args, 16, 1)
-        torch.cuda.synchronize()
-        assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all() and not torch.isnan(out).any()
-        assert torch.equal(out, again)
+    binding.hyena_chain_fwd(*args, 16, 1, out=out)
+    again = binding.hyena_chain_fwd(*args, 16, 1)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all() and not torch.isnan(out).any()
+    assert torch.equal(out, again)
