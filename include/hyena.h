@@ -37,7 +37,8 @@ typedef enum hy_status {
     HY_ERR_DTYPE = 3,       /* dtype is not one of hy_dtype */
     HY_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned, or a written buffer overlaps another buffer */
     HY_ERR_UNSUPPORTED = 5, /* valid problem, but no kernel in this build handles it */
-    HY_ERR_LAUNCH = 6       /* the HIP runtime reported an error at launch */
+    HY_ERR_LAUNCH = 6,      /* the HIP runtime reported an error at launch */
+    HY_ERR_SCRATCH = 7      /* the problem needs more scratch than the library's static buffer holds */
 } hy_status;
 
 /* Storage types.  Entry points take the value as a plain int32_t so that any integer a caller passes is
@@ -104,6 +105,25 @@ hy_status hyena_li_fwd(const void *q, const void *k, const void *v, const float 
  * problem.  Host-only. */
 int64_t hyena_li_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order, int32_t group,
                                  int32_t dtype);
+
+/*
+ * hyena_li_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and bit-identical
+ * results; the end-of-tile states of the scan go to a buffer of HYENA_LI_STATIC_SCRATCH_BYTES = 4 MiB that is
+ * part of the library's code object (one copy per GPU, held until the process ends) instead of a caller's
+ * workspace.  The call allocates nothing, frees nothing and calls no allocating routine.
+ * Limit: a problem whose hyena_li_workspace_bytes(...) exceeds that size returns HY_ERR_SCRATCH and launches
+ * nothing.  With the built-in tile choice the scan never needs more than 4 MiB (one workgroup per compute
+ * unit: B * tiles * D / 256 <= 256 records of 16 KiB), so this only happens with a small "mr_rows" option.
+ * All calls on one GPU share that GPU's buffer: two calls that overlap in time on the same GPU (different
+ * streams, or different threads) race on it and give wrong results; calls in stream order are safe, and no
+ * call depends on what an earlier one left behind.  The buffer's device address is looked up once per GPU,
+ * on the first call made while that GPU is current; make that first call outside graph capture.
+ */
+#define HYENA_LI_STATIC_SCRATCH_BYTES (4 * 1024 * 1024)
+hy_status hyena_li_fwd_static(const void *q, const void *k, const void *v, const float *R, const float *lambda,
+                              void *y, int64_t B, int64_t L, int64_t D, int32_t order, int32_t group,
+                              int32_t dtype, void *hip_stream);
 
 /*
  * Featurizer convolution, forward (Sec. 2.1 Eq. 1, first three lines: the short explicit filters

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     hyena_featurize3_fwd,
     hyena_featurize_fwd,
     hyena_li_fwd,
+    hyena_li_fwd_static,
     hyena_mr_bwd,
     hyena_mr_fwd,
     hyena_se_bwd,

@@ -48,13 +48,14 @@ def lib() -> ctypes.CDLL:
         L.hyena_bwd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_bwd_workspace_bytes.restype = i64
         L.hyena_li_fwd.argtypes = [vp] * 7 + [i64, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_li_fwd_static.argtypes = [vp] * 6 + [i64, i64, i64, i32, i32, ci, vp]
         L.hyena_li_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_li_workspace_bytes.restype = i64
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd",
-                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_stream_copy",
-                     "hyena_set_option"):
+                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_li_fwd_static",
+                     "hyena_stream_copy", "hyena_set_option"):
             getattr(L, name).restype = ci
         L.hyena_status_string.argtypes = [ci]
         L.hyena_status_string.restype = ctypes.c_char_p
@@ -370,6 +371,26 @@ def hyena_li_fwd(q, k, v, R, lam, group: int = 16, out=None, workspace=None, str
     """y = q * (h conv (k * v)) with h[g, j] = sum_n R[g, n] lam[g, n]^j; see ``hyena_li_fwd`` in hyena.h."""
     with torch.cuda.device(q.device):
         return plan_li(q, k, v, R, lam, group, out, workspace, stream)()
+
+
+def hyena_li_fwd_static(q, k, v, R, lam, group: int = 16, out=None, stream=None) -> torch.Tensor:
+    """``hyena_li_fwd`` with the scan's scratch inside the library (no workspace, no allocation in the call when
+    ``out`` is given); see ``hyena_li_fwd_static`` in hyena.h."""
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    order = _check_filter("R", R, q, group)
+    if _check_filter("lam", lam, q, group) != order:
+        raise ValueError("R and lam must share one [D // group, order] shape")
+    y = torch.empty_like(q) if out is None else out
+    _check_act("out", y, q)
+    B, L, D = q.shape
+    with torch.cuda.device(q.device):
+        rc = lib().hyena_li_fwd_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), R.data_ptr(), lam.data_ptr(),
+                                       y.data_ptr(), B, L, D, order, int(group), _dtype_code(q), _stream(q, stream))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_li_fwd_static")
+    return y
 
 
 def hyena_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.Tensor:

@@ -116,6 +116,30 @@ hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_ou
 
 bool empty(int64_t B, int64_t L, int64_t D) { return B == 0 || L == 0 || D == 0; }
 
+// ---- scratch of hyena_li_fwd_static: device memory that lives in the code object, one copy per GPU, held until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the device address
+// it yields (per device) is what kernels, copies and fills get.
+constexpr int64_t kLiStaticScratchBytes = HYENA_LI_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[kLiStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, resolved on first use there
+
+// Address of the current device's copy of `scratch` (resolved once per device, with that device current).
+hy_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HY_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return HY_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return HY_OK;
+}
+
 }  // namespace
 }  // namespace hy
 
@@ -299,6 +323,30 @@ hy_status hyena_li_fwd(const void* q, const void* k, const void* v, const float*
     return launch_li_direct(p, s, st);
 }
 
+hy_status hyena_li_fwd_static(const void* q, const void* k, const void* v, const float* R, const float* lambda,
+                              void* y, int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype,
+                              void* hip_stream) {
+    TuningSnapshot snap;
+    hy_status rc = li_validate(q, k, v, R, lambda, y, B, L, D, order, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (order > 16) return HY_ERR_UNSUPPORTED;
+    if (empty(B, L, D)) return HY_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    LiPtrs p{q, k, v, R, lambda, y};
+    LiShape s{B, L, D, order, group, static_cast<hy_dtype>(dtype)};
+    if (!li_mfma_supported(s)) return launch_li_direct(p, s, st);  // the plain recurrence needs no scratch
+    const int64_t need = li_workspace_bytes(s);
+    if (need > kLiStaticScratchBytes) return HY_ERR_SCRATCH;
+    void* ws = nullptr;
+    if (need > 0) {
+        rc = static_scratch(&ws);
+        if (rc != HY_OK) return rc;
+    }
+    // Nothing has to be cleared: pass 1 writes the end state of every tile but the last of each sequence, and pass 2
+    // reads exactly those records, so no byte is read that this call has not written.
+    return launch_li_mfma(p, s, ws, st);
+}
+
 int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
     TuningSnapshot snap;
     if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1 || D % group != 0) return -1;
@@ -411,6 +459,7 @@ const char* hyena_status_string(int32_t status) {
         case HY_ERR_ALIGN: return "pointer not 16-byte aligned, or a written buffer overlaps another buffer of the call";
         case HY_ERR_UNSUPPORTED: return "no kernel for this problem";
         case HY_ERR_LAUNCH: return "HIP launch error";
+        case HY_ERR_SCRATCH: return "problem needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }

@@ -47,12 +47,23 @@ int main() {
     // a filter table or the filter gradient inside a written activation
     EXPECT(hyena_se_fwd(P[0], P[1], P[2], reinterpret_cast<const float*>(P[3]), P[3], 1, 8, 16, 3, 1, HY_BF16, nullptr), HY_ERR_ALIGN);
     EXPECT(hyena_se_bwd(P[0], P[1], P[2], P[3], H[0], P[4], P[5], P[6], reinterpret_cast<float*>(P[5]), P[7], 1 << 16, 1, 8, 16, 3, 1, HY_BF16, nullptr), HY_ERR_ALIGN);
+    // Hyena-LI with the library's own scratch: same checks, no workspace argument; a scan that needs more than the
+    // static buffer is refused before anything is launched
+    EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], H[1], P[3], 1, 8, 64, 16, 16, HY_BF16, nullptr), HY_OK);
+    EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], nullptr, P[3], 1, 8, 64, 16, 16, HY_BF16, nullptr), HY_ERR_NULL);
+    EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], H[1], P[3], 1, 8, 64, 17, 16, HY_BF16, nullptr), HY_ERR_UNSUPPORTED);
+    EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], H[1], P[3], 1, 8, 64, 16, 16, HY_F32, nullptr), HY_OK);
+    {
+        char* const far = reinterpret_cast<char*>(1ull << 40);  // 128 MiB tensors, 4 GiB apart
+        EXPECT(hyena_li_fwd_static(far, far + (1ull << 32), far + (2ull << 32), H[0], H[1], far + (3ull << 32), 1, 1 << 14,
+                                   4096, 16, 16, HY_BF16, nullptr), HY_ERR_SCRATCH);
+    }
     EXPECT(hyena_stream_copy(P[0], P[1], 24, nullptr), HY_ERR_SHAPE);
     EXPECT(hyena_stream_copy(P[0], P[1], 64, nullptr), HY_OK);
     EXPECT(hyena_set_option("se_vec", 3), HY_ERR_SHAPE);
     EXPECT(hyena_set_option("nope", 1), HY_ERR_UNSUPPORTED);
     EXPECT(hyena_set_option(nullptr, 1), HY_ERR_NULL);
-    for (int s = 0; s < 8; ++s)
+    for (int s = 0; s < 9; ++s)
         if (!hyena_status_string(s)) ++bad;
     std::printf("abi selftest: %d problem(s), version %d\n", bad, hyena_version());
     return bad != 0;

@@ -38,14 +38,14 @@ def test_binding_exposes_the_same_names():
     import paper_2503_01868_amd as pkg
 
     for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd", "hyena_chain_fwd",
-                 "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_stream_copy"):
+                 "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_li_fwd_static", "hyena_stream_copy"):
         assert callable(getattr(pkg, name))
 
 
 def test_version_and_status_strings():
     assert binding.version() >= 100
-    seen = {binding.status_string(c) for c in range(7)}
-    assert len(seen) == 7 and "ok" in seen
+    seen = {binding.status_string(c) for c in range(8)}
+    assert len(seen) == 8 and "ok" in seen
 
 
 # fake but well-formed device addresses: validation must finish before any of them is dereferenced
@@ -209,6 +209,30 @@ def test_long_implicit_entry_point_rejects_bad_arguments():
     assert lib.hyena_li_workspace_bytes(1, 64, 256, 16, 16, 1) == 0        # one tile
     assert lib.hyena_li_workspace_bytes(1, 64, 256, 0, 16, 1) == -1
     assert lib.hyena_li_workspace_bytes(1, 64, 250, 16, 16, 1) == -1
+
+
+def li_static(q=P[0], k=P[1], v=P[2], R=P[3], lam=P[5], y=P[4], B=1, L=8, D=16, order=4, group=1, dtype=0):
+    return binding.lib().hyena_li_fwd_static(q, k, v, R, lam, y, B, L, D, order, group, dtype, None)
+
+
+def test_static_scratch_entry_point_rejects_bad_arguments_and_oversized_scans():
+    lib = binding.lib()
+    assert li_static(q=None) == 1 and li_static(lam=None) == 1 and li_static(y=None) == 1
+    assert li_static(order=0) == 2 and li_static(D=16, group=3) == 2 and li_static(dtype=9) == 3
+    assert li_static(R=P[3] + 4) == 4 and li_static(y=P[2]) == 4 and li_static(order=17) == 5
+    assert li_static(B=0) == 0 and li_static(L=0) == 0
+    # the scan of this problem needs more end-of-tile records than the static buffer holds: refused, nothing launched
+    far = 1 << 40
+    big = dict(q=far, k=2 * far, v=3 * far, y=4 * far, B=1, L=1 << 16, D=256, order=16, group=16, dtype=1)
+    assert lib.hyena_set_option(b"mr_rows", 32) == 0
+    try:
+        assert lib.hyena_li_workspace_bytes(1, 1 << 16, 256, 16, 16, 1) > 4 * 1024 * 1024
+        assert li_static(**big) == 7
+    finally:
+        assert lib.hyena_set_option(b"mr_rows", 0) == 0
+    # with the built-in tile choice no shape needs more than the buffer holds
+    for B, L, D in ((1, 131072, 4096), (4, 32768, 4096), (3, 100000, 1024), (1, 1 << 20, 256), (7, 5000, 128), (1, 1 << 22, 64)):
+        assert 0 <= lib.hyena_li_workspace_bytes(B, L, D, 16, 16, 1) <= 4 * 1024 * 1024, (B, L, D)
 
 
 def test_options_are_snapshotted_per_call_and_safe_to_set_from_other_threads():
