@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the Hyena-SE / Hyena-MR forward path on one MI355X, against the HBM roofline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|...]
 
 A step is one pass of the hot path over one synthetic batch that already sits in HBM:
   c1  Hyena-SE  bf16 B1 L8192   D4096 lh7            hyena_se_fwd            (default; the headline case)
@@ -12,8 +12,12 @@ A step is one pass of the hot path over one synthetic batch that already sits in
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
   c2u c2 with one filter per channel; li2 / li3: Hyena-LI at the shapes of c2 / c3
+  stream / strip64 / strip128 / strip256: the bandwidth yardstick hyena_stream_gate (y = q*k*v: the operator's
+      3-read/1-write traffic without its arithmetic) on c1's shape, streamed linearly or walked in column strips
+      of 64 / 128 / 256 channels (128 / 256 / 512-byte row pieces) the way the matrix-core kernels move their data
 Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded slice of the same workload.  With the default
-workload the line also carries, under "also", a short timing of c2, c3, c4, c2u and li2 (a quarter of the steps each).
+workload the line also carries, under "also", the same roofline figures for c2, c3, c4, c2u, li2 and both backward
+workloads (a quarter of the steps each, after a warm-up of their own, which each entry states).
 """
 import argparse
 import json
@@ -30,6 +34,9 @@ if ROOT not in sys.path:
 METRIC = "Hyena-SE/MR fwd tokens/s at D=4096; achieved HBM GB/s and MFMA % of peak"
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# bandwidth yardsticks: workload name -> channels per workgroup strip (0 = linear stream)
+YARDSTICKS = {"stream": 0, "strip64": 64, "strip128": 128, "strip256": 256}
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic.json")
 
 
 def parse():
@@ -37,17 +44,24 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "copy"],
+    ap.add_argument("--workload", default="c1",
+                    choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "
                          "width 4096); the JSON line then names the changed shape and carries no stored traffic figure")
     ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
+    ap.add_argument("--depth", type=int, default=0,
+                    help="strip yardsticks only: 32-row chunks of loads in flight per lane (0 = 2, as in the operator kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle slice")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
                     help="library tuning knob (hyena_set_option), may repeat; results never depend on these")
-    ap.add_argument("--also", default="c2,c3,c4,c2u,li2", help="comma list of further workloads to time briefly (c1 only)")
+    ap.add_argument("--also", default="c2,c3,c4,c2u,li2,c1_bwd,c2_bwd",
+                    help="comma list of further workloads to time briefly (c1 only)")
+    ap.add_argument("--also-warmup", type=int, default=200,
+                    help="untimed launches before each --also workload (at least --warmup): the matrix-heavy kernels run "
+                         "several percent slower until the clocks have settled after an idle period")
     return ap.parse_args()
 
 
@@ -73,11 +87,14 @@ def upload(w, torch):
 class Workload:
     """Device-resident rotating buffer sets plus the pre-marshalled launches of one configuration."""
 
-    def __init__(self, name, nsets, torch, pkg, synth, seq_len=0):
+    def __init__(self, name, nsets, torch, pkg, synth, seq_len=0, depth=0):
         self.name, self.torch, self.pkg = name, torch, pkg
         self.bwd = name.endswith("_bwd")
+        self.strip = YARDSTICKS.get(name)
         name = name[:-4] if self.bwd else name
         over = {"L": seq_len} if seq_len > 0 else {}
+        if self.strip is not None:
+            name = "c1"  # the yardsticks run on c1's tensors (its filter is not used)
         self.cfg = synth.config(name, **over)
         c = self.cfg
         self.n_out = c["B"] * c["L"] * c["D"]
@@ -86,7 +103,7 @@ class Workload:
         if nsets <= 0:
             nsets = max(1, min(6, int((1.5 * 2 ** 30) // bytes_set) + 1))
         self.host0 = None
-        self.sets, self.pre, self.main = [], [], []
+        self.sets, self.main = [], []
         for i in range(nsets):
             w = synth.make(name, variant=i, **over)
             if i == 0:
@@ -105,6 +122,8 @@ class Workload:
                 self.main.append(pkg.plan_bwd("hyena_se_bwd" if c["kind"] == "se" else "hyena_mr_bwd", d["dy"], d["q"],
                                               d["k"], d["v"], d["h"], c["group"],
                                               out=(d["dq"], d["dk"], d["dv"], d["dh"])))
+            elif self.strip is not None:
+                self.main.append(pkg.plan_stream_gate(d["q"], d["k"], d["v"], self.strip, 0, depth, out=d["y"]))
             elif c["kind"] == "li":
                 self.main.append(pkg.plan_li(d["q"], d["k"], d["v"], d["R"], d["lam"], c["group"], out=d["y"]))
             elif c["kind"] == "chain":
@@ -119,8 +138,6 @@ class Workload:
     def step(self):
         j = self.i % len(self.sets)
         self.i += 1
-        if self.pre:
-            self.pre[j]()
         self.main[j]()
 
     def run(self, steps, warmup):
@@ -130,31 +147,17 @@ class Workload:
         for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
-        if not self.pre:
-            # one kernel per step: bracket the whole timed region with two events on the launch stream;
-            # (elapsed / steps) is the average launch period, an upper bound of the kernel's duration
-            e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
-            t0 = time.perf_counter()
-            e0.record()
-            for _ in range(steps):
-                self.step()
-            e1.record()
-            torch.cuda.synchronize()
-            wall = time.perf_counter() - t0
-            return wall, e0.elapsed_time(e1) / steps
-        # two kernels per step: an event pair around every launch of the dominant one (milliseconds long)
-        pairs = [(ev(enable_timing=True), ev(enable_timing=True)) for _ in range(steps)]
+        # bracket the whole timed region with two events on the launch stream; (elapsed / steps) is the average
+        # launch period of the entry point's kernel(s), an upper bound of their duration
+        e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
         t0 = time.perf_counter()
-        for a, b in pairs:
-            j = self.i % len(self.sets)
-            self.i += 1
-            self.pre[j]()
-            a.record()
-            self.main[j]()
-            b.record()
+        e0.record()
+        for _ in range(steps):
+            self.step()
+        e1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        return wall, sum(a.elapsed_time(b) for a, b in pairs) / steps
+        return wall, e0.elapsed_time(e1) / steps
 
     def launch_stats(self, n=60):
         """Outside the timed region: an event pair around every one of n launches rotating through the buffer
@@ -167,8 +170,6 @@ class Workload:
             pairs = [(ev(enable_timing=True), ev(enable_timing=True)) for _ in range(n)]
             for i, (a, b) in enumerate(pairs):
                 j = pick(i)
-                if self.pre:
-                    self.pre[j]()
                 a.record()
                 self.main[j]()
                 b.record()
@@ -256,17 +257,49 @@ def gpu_clocks():
     return out
 
 
+def stored_traffic(workload, seq_len):
+    """HBM bytes per step as hardware counters saw them in an EARLIER profiled run of this workload (this run takes
+    no counters): (bytes or None, where the figure comes from)."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
+    if seq_len > 0 or not os.path.exists(path):
+        return None, None
+    with open(path) as f:
+        entry = json.load(f).get(workload)
+    if not entry:
+        return None, None
+    return entry.get("bytes_per_launch"), ("stored: %s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                                           "workload, scaled by the copy-kernel calibration; see profiles/%s)"
+                                           % (TRAFFIC_FILE, entry.get("profile", "")))
+
+
+def entry_point(wl):
+    if wl.strip is not None:
+        return "hyena_stream_gate (strip_channels=%d)" % wl.strip
+    name = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd",
+            "li": "hyena_li_fwd (both passes of the scan)"}[wl.cfg["kind"]]
+    return name.replace("_fwd", "_bwd (all launches of the entry point)") if wl.bwd else name
+
+
 def measure(name, args, torch, pkg, synth, steps, warmup):
-    wl = Workload(name, args.sets, torch, pkg, synth, args.seq_len)
+    """Times one workload; returns it with the figures every line and every "also" entry carries."""
+    wl = Workload(name, args.sets, torch, pkg, synth, args.seq_len, args.depth)
     wall, kern_ms = wl.run(steps, warmup)
+    ms_step = 1e3 * wall / steps
+    gbs = wl.algo_bytes() / (kern_ms * 1e-3) / 1e9
+    traffic, source = stored_traffic(name, args.seq_len)
     res = {
-        "tokens_per_s": wl.tokens * steps / wall,
-        "ms_per_step": 1e3 * wall / steps,
-        "kernel_ms_avg": kern_ms,
-        "hbm_gbs": wl.algo_bytes() / (kern_ms * 1e-3) / 1e9,
-        "tflops_algorithmic": wl.algo_flops() / (kern_ms * 1e-3) / 1e12,
-        "sets": len(wl.sets),
+        "tokens_per_s": wl.tokens * steps / wall, "ms_per_step": ms_step, "steps": steps, "warmup": warmup,
+        "buffer_sets": len(wl.sets),
+        "roofline": {"bound": "hbm", "kernel": entry_point(wl), "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
+                     "kernel_ms_avg": kern_ms, "algorithmic_bytes_per_launch": wl.algo_bytes(),
+                     # the same fraction from the wall clock of the timed region (launch overhead included)
+                     "frac_wall_clock": wl.algo_bytes() / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    if wl.cfg["kind"] != "se" and wl.strip is None:
+        tf = wl.algo_flops() / (kern_ms * 1e-3) / 1e12
+        res["mfma"] = {"tflops_algorithmic": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": tf / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops_per_launch": wl.algo_flops()}
     return wl, res
 
 
@@ -307,38 +340,24 @@ def main():
 
     wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup)
     cfg = wl.cfg
-    kernel = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd",
-              "li": "hyena_li_fwd (both passes of the scan)"}[cfg["kind"]]
-    if wl.bwd:
-        kernel = kernel.replace("_fwd", "_bwd")
-
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get(args.workload, {}).get("bytes_per_launch") if args.seq_len <= 0 else None
-
+    what = "bandwidth yardstick y=q*k*v," if wl.strip is not None else {
+        "se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,", "li": "Hyena-LI"}[cfg["kind"]]
     out = {
         "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %s%s bf16 B=%d L=%d D=%d %s=%d group=%d" % (
-            args.workload, {"se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,",
-                            "li": "Hyena-LI"}[cfg["kind"]],
-            " backward (all launches of the entry point)" if wl.bwd else "",
+            args.workload, what, " backward" if wl.bwd else "",
             cfg["B"], cfg["L"], cfg["D"], "order" if cfg["kind"] == "li" else "lh",
-            cfg["order"] if cfg["kind"] == "li" else cfg["lh"], cfg["group"]), "buffer_sets": res["sets"]},
-        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": res["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": res["hbm_gbs"] / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel_ms_avg": res["kernel_ms_avg"], "algorithmic_bytes_per_launch": wl.algo_bytes()},
+            cfg["order"] if cfg["kind"] == "li" else cfg["lh"], cfg["group"]), "buffer_sets": res["buffer_sets"]},
+        "roofline": res["roofline"],
     }
     out["launch_stats"] = wl.launch_stats()
     out["launch_stats"]["clocks_after_run"] = gpu_clocks()
-    if cfg["kind"] != "se":
-        out["mfma"] = {"tflops_algorithmic": res["tflops_algorithmic"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                       "frac": res["tflops_algorithmic"] / MFMA_BF16_PEAK_TFLOPS}
+    if "mfma" in res:
+        out["mfma"] = res["mfma"]
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and wl.strip is None:
         import oracle
 
         base, rows, y_ref = cpu_baseline(wl, args.cpu_seconds, np, oracle)
@@ -356,11 +375,7 @@ def main():
         torch.cuda.empty_cache()
         out["also"] = {}
         for name in [s for s in args.also.split(",") if s]:
-            # 200 untimed launches first: the matrix-heavy kernels run several percent slower until the clocks have
-            # settled after an idle period (the ungrouped kernel by 10% over its first ~150 launches)
-            wl2, r2 = measure(name, args, torch, pkg, synth, max(10, args.steps // 4), max(200, args.warmup))
-            r2["hbm_frac"] = r2["hbm_gbs"] / HBM_PEAK_GBS
-            r2["mfma_frac_algorithmic"] = r2["tflops_algorithmic"] / MFMA_BF16_PEAK_TFLOPS
+            wl2, r2 = measure(name, args, torch, pkg, synth, max(10, args.steps // 4), max(args.also_warmup, args.warmup))
             out["also"][name] = r2
             del wl2
             torch.cuda.empty_cache()

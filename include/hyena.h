@@ -62,7 +62,7 @@ hy_status hyena_se_fwd(const void *q, const void *k, const void *v, const float 
 /*
  * Hyena-MR inner operator, forward: same formula as hyena_se_fwd, meant for filters of length in
  * the hundreds shared by groups of channels (paper default lh = 128, group = 16).  For HY_BF16 with
- * group a multiple of 16, D a multiple of 64 and lh <= 257 the convolution is evaluated as the
+ * group a multiple of 16, D a multiple of 64 and lh <= 513 the convolution is evaluated as the
  * block-Toeplitz contraction of Sec. 3.1 (hat y_n = sum_k H_k hat x_{n-k}) on bf16 matrix cores with
  * fp32 accumulation: u = k*v is rounded once to bf16, h is rounded once to bf16, the output is
  * rounded once at the store.  For HY_BF16 with any other group size (down to one filter per
@@ -212,6 +212,20 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
  * hardware byte counters; not part of the operator.
  */
 hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip_stream);
+
+/*
+ * Bandwidth yardstick with the operator's traffic and none of its arithmetic: y = q * k * v elementwise on bf16
+ * [B, L, D] tensors (the gated convolution of Eq. 1 with a one-tap unit filter), three tensors read once and one
+ * written once with the streaming hints the operator kernels use.  strip_channels = 0 streams the tensors
+ * linearly; 64, 128 or 256 makes a workgroup walk a column strip of that many channels (128, 256 or 512 bytes
+ * per row) down `rows` time steps (0 = tile length that gives one workgroup per compute unit), which is how the
+ * matrix-core kernels move their data, with `depth` 32-row chunks of loads in flight per lane (1, 2, 3, 4 or 6;
+ * 0 = 2, what the operator kernels use; ignored by the linear stream).  D must be a multiple of 8 and of
+ * strip_channels.  Not part of the
+ * operator: it measures the practical ceiling a kernel with that access pattern can reach.
+ */
+hy_status hyena_stream_gate(const void *q, const void *k, const void *v, void *y, int64_t B, int64_t L, int64_t D,
+                            int32_t strip_channels, int64_t rows, int32_t depth, void *hip_stream);
 
 /*
  * Tuning knobs (process-wide; 0 restores the built-in choice).  Thread-safe: every entry point takes one

@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     hyena_se_bwd,
     hyena_se_fwd,
     hyena_stream_copy,
+    hyena_stream_gate,
+    plan_stream_gate,
     set_option,
     status_string,
     version,

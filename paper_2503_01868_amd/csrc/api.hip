@@ -425,6 +425,21 @@ hy_status hyena_stream_copy(const void* src, void* dst, int64_t bytes, void* hip
                          static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
 }
 
+hy_status hyena_stream_gate(const void* q, const void* k, const void* v, void* y, int64_t B, int64_t L, int64_t D,
+                            int32_t strip_channels, int64_t rows, int32_t depth, void* hip_stream) {
+    const void* ins[3] = {q, k, v};
+    void* outs[1] = {y};
+    hy_status rc = validate(ins, 3, outs, 1, nullptr, 0, B, L, D, 1, 1, HY_BF16);
+    if (rc != HY_OK) return rc;
+    if (rows < 0 || rows > 0x7fff0000LL || D % 8 != 0) return HY_ERR_SHAPE;
+    if (strip_channels != 0 && strip_channels != 64 && strip_channels != 128 && strip_channels != 256)
+        return HY_ERR_UNSUPPORTED;
+    if (strip_channels != 0 && D % strip_channels != 0) return HY_ERR_SHAPE;
+    if (depth != 0 && depth != 1 && depth != 2 && depth != 3 && depth != 4 && depth != 6) return HY_ERR_UNSUPPORTED;
+    if (empty(B, L, D)) return HY_OK;
+    return launch_stream_gate(q, k, v, y, B, L, D, strip_channels, rows, depth, static_cast<hipStream_t>(hip_stream));
+}
+
 hy_status hyena_set_option(const char* name, int32_t value) {
     if (!name) return HY_ERR_NULL;
     if (value < 0) return HY_ERR_SHAPE;

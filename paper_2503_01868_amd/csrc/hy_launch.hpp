@@ -136,7 +136,10 @@ hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64
                            hipStream_t st);
 // dh := 0 (the filter gradient of an empty batch).
 hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st);
-hy_status launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t st);
+// Bandwidth yardstick y = q*k*v (bf16): strip = 0 streams linearly, 64 / 128 / 256 walks column strips of that many
+// channels down time in `rows`-step tiles (0 = one workgroup per compute unit), `depth` chunks of loads in flight.
+hy_status launch_stream_gate(const void* q, const void* k, const void* v, void* y, int64_t B, int64_t L, int64_t D,
+                             int32_t strip, int64_t rows, int32_t depth, hipStream_t st);
 
 // Launches `kernel` and returns the status of THIS launch as hipLaunchKernel reports it.  The thread's sticky
 // "last error" is neither read nor cleared: an error left behind by an earlier, unrelated HIP call of the caller

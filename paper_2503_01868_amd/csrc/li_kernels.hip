@@ -86,19 +86,20 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
 
     const int lr = tid / PPR, lp = tid % PPR;
     const int64_t ld_off = cblock0 + 8 * lp;
-    // unconditional, clamped loads (see mr_kernels.hip): rows past the end of the tile re-read its last row
+    // unconditional, clamped loads (see mr_kernels.hip): rows past the end of the tile re-read its last row; loads
+    // for chunk indices past the last chunk (results unused) all go to one 16-byte location of the tile
+    const int64_t idle_off = (t_end - 1) * D + cblock0;
     auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
-        const int cic = ci < nchunks ? ci : nchunks - 1;
-        int64_t t = t_start + (int64_t)cic * kChunk + lr;
+        int64_t t = t_start + (int64_t)ci * kChunk + lr;
         t = t < t_end ? t : t_end - 1;
-        kk = load_words_nt<4>(a.k + seq0 + t * D + ld_off);
-        vv = load_words_nt<4>(a.v + seq0 + t * D + ld_off);
+        const int64_t off = ci < nchunks ? t * D + ld_off : idle_off;
+        kk = load_words_nt<4>(a.k + seq0 + off);
+        vv = load_words_nt<4>(a.v + seq0 + off);
     };
     auto load_q = [&](int ci, Words<4>& qq) {
-        const int cic = ci < nchunks ? ci : nchunks - 1;
-        int64_t t = t_start + (int64_t)cic * kChunk + lr;
+        int64_t t = t_start + (int64_t)ci * kChunk + lr;
         t = t < t_end ? t : t_end - 1;
-        qq = load_words_nt<4>(a.q + seq0 + t * D + ld_off);
+        qq = load_words_nt<4>(a.q + seq0 + (ci < nchunks ? t * D + ld_off : idle_off));
     };
 
     Words<4> kpre[kPrefetch], vpre[kPrefetch], qpre[kPrefetch];

@@ -80,16 +80,17 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
         tau = tau < t_end ? tau : t_end - 1;
         return seq0 + (L - 1 - tau) * D + ld_off;
     };
+    // loads whose result is never used (chunk indices past the last chunk; k and v of warm-up chunks) all go to one
+    // 16-byte location of the tile, the same for every lane of the workgroup: one cache line per wave
+    const int64_t idle_off = seq0 + (L - t_end) * D + cblock0;
     auto load_g = [&](int ci, Words<4>& yy, Words<4>& qq) {
-        const int cic = ci < nchunks ? ci : nchunks - 1;
-        const int64_t off = row_off(t_begin + (int64_t)cic * kChunk + lr);
+        const int64_t off = ci < nchunks ? row_off(t_begin + (int64_t)ci * kChunk + lr) : idle_off;
         yy = load_words_nt<4>(a.dy + off);
         qq = load_words_nt<4>(a.q + off);
     };
-    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {  // warm-up chunks need no k, v: read the first real rows
-        const int cic = ci < nchunks ? ci : nchunks - 1;
-        const int64_t t0 = t_begin + (int64_t)cic * kChunk;
-        const int64_t off = row_off((t0 >= t_start ? t0 : t_start) + lr);
+    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {  // warm-up chunks need no k, v
+        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
+        const int64_t off = (ci < nchunks && t0 >= t_start) ? row_off(t0 + lr) : idle_off;
         kk = load_words_nt<4>(a.k + off);
         vv = load_words_nt<4>(a.v + off);
     };

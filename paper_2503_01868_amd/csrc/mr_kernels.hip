@@ -42,9 +42,11 @@ struct MrArgs {
 
 constexpr int kChunk = 32;
 
-// kPrefetch = chunks of k, v and q in flight per lane (registers).  Two waves per SIMD must fit.
+// kPrefetch = chunks of k, v and q in flight per lane (registers).  Two waves per SIMD must fit (NKB = 13: 247
+// registers); filters beyond 385 taps (NKB = 17: 34 operands and a window of 17 blocks, ~320 registers) run one wave
+// per SIMD.
 template <int NKB, int NW, int kPrefetch>
-__global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void mr_mfma_kernel(MrArgs a) {
+__global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr_mfma_kernel(MrArgs a) {
     constexpr int PPR = 2 * NW;              // 16-byte pieces per staged row of u (bf16)
     constexpr int kTaps = 32 * NKB;          // >= lh
     constexpr int ZROW = 16 * NW * 4 + 16;   // bytes per staged row of z (fp32), padded against bank conflicts
@@ -85,22 +87,24 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void mr_mfma_kernel(MrAr
     // kPrefetch chunks in flight without ever draining the queue.  Addresses are clamped instead:
     //  - rows past the end of the tile read the tile's last row (a source step >= t_end only reaches
     //    outputs >= t_end, which are never stored);
-    //  - chunk indices past the last chunk re-read the last chunk (result unused);
-    //  - warm-up chunks, which need no q, read the q rows of the first real chunk (cache hits, unused).
+    //  - loads whose result is never used (chunk indices past the last chunk; q of warm-up chunks) all go to ONE
+    //    16-byte location of the tile, the same for every lane of the workgroup, so that they cost one cache line
+    //    per wave instead of a row piece per lane (with the streaming hint such re-reads may otherwise go all the
+    //    way to memory: 2 of 20 chunk loads of a 512-step tile).
+    const uint64_t idle_off = (uint64_t)(uint32_t)(te32 - 1) * D32 + (uint32_t)cblock0;
     auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
-        const int cic = ci < nchunks ? ci : nchunks - 1;
-        int t = tb32 + cic * kChunk + lr;
+        int t = tb32 + ci * kChunk + lr;
         t = t < te32 ? t : te32 - 1;
-        const uint64_t off = (uint64_t)(uint32_t)t * D32 + ld_off;
+        const uint64_t off = ci < nchunks ? (uint64_t)(uint32_t)t * D32 + ld_off : idle_off;
         kk = load_words_nt<4>(a.k + seq0 + off);
         vv = load_words_nt<4>(a.v + seq0 + off);
     };
     auto load_q = [&](int ci, Words<4>& qq) {
-        const int cic = ci < nchunks ? ci : nchunks - 1;
-        const int t0 = tb32 + cic * kChunk;
-        int tq = (t0 >= ts32 ? t0 : ts32) + lr;
+        const int t0 = tb32 + ci * kChunk;
+        int tq = t0 + lr;
         tq = tq < te32 ? tq : te32 - 1;
-        qq = load_words_nt<4>(a.q + seq0 + ((uint64_t)(uint32_t)tq * D32 + ld_off));
+        const uint64_t off = (ci < nchunks && t0 >= ts32) ? (uint64_t)(uint32_t)tq * D32 + ld_off : idle_off;
+        qq = load_words_nt<4>(a.q + seq0 + off);
     };
 
     // start the first loads before anything else so their latency overlaps the filter set-up
@@ -269,18 +273,22 @@ template <int NKB>
 hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     // Widest row piece per workgroup the width allows: 16 waves = 256 channels = 512 bytes of every row,
     // then 8, then 4.  Measured on MI355X (L = 131072): 694 us with 16 waves against 787 us with 8.
-    const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 16;
-    if constexpr (NKB <= 5) {  // 16 waves only where the kernel fits 128 registers without spilling
-        if (nw == 16 && s.D % 256 == 0) return launch_nkb_nw<NKB, 16>(p, s, st);
+    if constexpr (NKB > 13) {
+        return launch_nkb_nw<NKB, 4>(p, s, st);  // one wave per SIMD: 64 channels per workgroup
+    } else {
+        const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 16;
+        if constexpr (NKB <= 5) {  // 16 waves only where the kernel fits 128 registers without spilling
+            if (nw == 16 && s.D % 256 == 0) return launch_nkb_nw<NKB, 16>(p, s, st);
+        }
+        if (nw >= 8 && s.D % 128 == 0) return launch_nkb_nw<NKB, 8>(p, s, st);
+        return launch_nkb_nw<NKB, 4>(p, s, st);
     }
-    if (nw >= 8 && s.D % 128 == 0) return launch_nkb_nw<NKB, 8>(p, s, st);
-    return launch_nkb_nw<NKB, 4>(p, s, st);
 }
 
 }  // namespace
 
 hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
-    if (s.dtype != HY_BF16 || !s.gated || s.group % 16 != 0 || s.D % 64 != 0 || s.lh > 257 || s.L > 0x7fff0000LL ||
+    if (s.dtype != HY_BF16 || !s.gated || s.group % 16 != 0 || s.D % 64 != 0 || s.lh > 513 || s.L > 0x7fff0000LL ||
         s.D > 0x7fff0000LL)
         return HY_ERR_UNSUPPORTED;
     const int nkb = (s.lh - 1 + 31) / 32 + 1;  // 32-step source blocks that can meet a 16-step output tile
@@ -294,6 +302,8 @@ hy_status launch_mr_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st) 
         case 7: return launch_nkb<7>(p, s, st);
         case 8: return launch_nkb<8>(p, s, st);
         case 9: return launch_nkb<9>(p, s, st);
+        case 10: case 11: case 12: case 13: return launch_nkb<13>(p, s, st);  // lh <= 385
+        case 14: case 15: case 16: case 17: return launch_nkb<17>(p, s, st);  // lh <= 513
         default: return HY_ERR_UNSUPPORTED;
     }
 }

@@ -64,23 +64,24 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
     const uint32_t ld_off = (uint32_t)(cblock0 + 8 * lp);
     const int t_lo = warm ? ts32 - kLook : 0;  // oldest row ever needed
 
-    // unconditional, clamped loads: rows before the needed history re-read its first row, rows past the end of the
-    // tile its last row, chunk indices past the last chunk the last chunk (all unused or harmless, see mr_kernels.hip)
-    auto row_of = [&](int ci) {
-        const int cic = ci < nchunks ? ci : nchunks - 1;
-        int t = tb32 + cic * kChunk + lr;
-        t = t < te32 ? t : te32 - 1;
-        return t > t_lo ? t : t_lo;
-    };
+    // unconditional, clamped loads: rows past the end of the tile re-read its last row; loads whose result is never
+    // used (rows before the needed history, chunk indices past the last chunk, q of the warm-up chunk) all go to one
+    // 16-byte location of the tile, the same for every lane of the workgroup (one cache line per wave; see
+    // mr_kernels.hip)
+    const uint64_t idle_off = (uint64_t)(uint32_t)(te32 - 1) * D32 + (uint32_t)cblock0;
     auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
-        const uint64_t off = (uint64_t)(uint32_t)row_of(ci) * D32 + ld_off;
+        int t = tb32 + ci * kChunk + lr;
+        const bool used = ci < nchunks && t >= t_lo;
+        t = t < te32 ? t : te32 - 1;
+        const uint64_t off = used ? (uint64_t)(uint32_t)t * D32 + ld_off : idle_off;
         kk = load_words_nt<4>(a.k + seq0 + off);
         vv = load_words_nt<4>(a.v + seq0 + off);
     };
     auto load_q = [&](int ci, Words<4>& qq) {
-        int t = row_of(ci);
-        t = t > ts32 ? t : ts32;
-        qq = load_words_nt<4>(a.q + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off));
+        int t = tb32 + ci * kChunk + lr;
+        const bool used = ci < nchunks && t >= ts32;
+        t = t < te32 ? t : te32 - 1;
+        qq = load_words_nt<4>(a.q + seq0 + (used ? (uint64_t)(uint32_t)t * D32 + ld_off : idle_off));
     };
 
     Words<4> kpre[kPrefetch], vpre[kPrefetch], qpre[kPrefetch];

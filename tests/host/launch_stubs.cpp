@@ -5,7 +5,7 @@ namespace hy {
 hy_status launch_stencil(const ConvPtrs*, int, const ConvShape& s, hipStream_t) { return s.lh > 8 ? HY_ERR_UNSUPPORTED : HY_OK; }
 hy_status launch_direct(const ConvPtrs*, int, const ConvShape&, hipStream_t) { return HY_OK; }
 hy_status launch_mr_mfma(const ConvPtrs&, const ConvShape& s, hipStream_t) {
-    return (s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.lh <= 257) ? HY_OK : HY_ERR_UNSUPPORTED;
+    return (s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.lh <= 513) ? HY_OK : HY_ERR_UNSUPPORTED;
 }
 bool se_walk_preferred(const ConvShape&) { return false; }
 hy_status launch_se_walk(const ConvPtrs&, const ConvShape&, hipStream_t) { return HY_OK; }
@@ -30,5 +30,7 @@ int64_t mr_bwd_rows(const BwdShape& s) { return (s.L + 31) / 32 * 32; }
 int64_t mr_bwd_workspace_bytes(const BwdShape& s) { return s.B * (s.D / 16) * s.lh * 4; }
 hy_status launch_mr_bwd(const BwdPtrs&, const BwdShape&, void*, hipStream_t) { return HY_OK; }
 hy_status launch_dh_reduce(const float*, float*, int64_t, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
+hy_status launch_stream_gate(const void*, const void*, const void*, void*, int64_t, int64_t, int64_t, int32_t, int64_t,
+                             int32_t, hipStream_t) { return HY_OK; }
 hy_status launch_bwd_zero_dh(float*, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
 }  // namespace hy

@@ -116,6 +116,16 @@ def test_stream_copy_and_options_reject_bad_arguments():
     assert lib.hyena_set_option(b"se_vec", 0) == 0
 
 
+def test_bandwidth_yardstick_rejects_bad_arguments():
+    lib = binding.lib()
+    g = lambda q=P[0], k=P[1], v=P[2], y=P[3], B=1, L=8, D=256, strip=0, rows=0, depth=0: lib.hyena_stream_gate(
+        q, k, v, y, B, L, D, strip, rows, depth, None)
+    assert g(depth=5) == 5 and g(depth=6, strip=64, B=0) == 0
+    assert g(q=None) == 1 and g(y=None) == 1 and g(L=-1) == 2 and g(D=12) == 2 and g(rows=-1) == 2
+    assert g(strip=32) == 5 and g(strip=128, D=192) == 2 and g(y=P[1]) == 4 and g(k=P[1] + 8) == 4
+    assert g(B=0) == 0 and g(L=0, strip=256) == 0
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
 

@@ -18,7 +18,7 @@ def run_bench(*args):
 
 
 def test_one_json_line_with_roofline_and_cpu_baseline():
-    proc = run_bench("--steps", "5", "--warmup", "2", "--cpu-seconds", "1", "--also", "c2")
+    proc = run_bench("--steps", "5", "--warmup", "2", "--cpu-seconds", "1", "--also", "c2,c1_bwd", "--also-warmup", "3")
     assert proc.returncode == 0, proc.stderr[-2000:]
     lines = [ln for ln in proc.stdout.splitlines() if ln.strip()]
     assert len(lines) == 1
@@ -36,7 +36,24 @@ def test_one_json_line_with_roofline_and_cpu_baseline():
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "tokens/s" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
     assert d["parity_rel_err"] <= 2e-2
-    assert set(d["also"]) == {"c2"} and d["also"]["c2"]["kernel_ms_avg"] > 0
+    assert r["frac_wall_clock"] <= r["frac"] * 1.001 and r["traffic_source"].startswith("stored")
+    # every further workload carries the same roofline object, its own step and warm-up counts, and (where the
+    # matrix cores are used) the MFMA figure
+    assert set(d["also"]) == {"c2", "c1_bwd"}
+    for name, e in d["also"].items():
+        ro = e["roofline"]
+        for key in ("bound", "kernel", "achieved", "peak", "unit", "frac", "traffic", "kernel_ms_avg"):
+            assert key in ro, (name, key)
+        assert ro["kernel_ms_avg"] > 0 and 0.0 < ro["frac"] < 1.0 and e["warmup"] == 3 and e["steps"] == 10
+    assert 0.0 < d["also"]["c2"]["mfma"]["frac"] < 1.0 and "mfma" not in d["also"]["c1_bwd"]
+
+
+def test_yardstick_workload_prints_a_roofline_line_without_cpu_baseline():
+    proc = run_bench("--workload", "strip128", "--steps", "5", "--warmup", "2")
+    assert proc.returncode == 0, proc.stderr[-2000:]
+    d = json.loads(proc.stdout.strip())
+    assert "hyena_stream_gate" in d["roofline"]["kernel"] and 0.0 < d["roofline"]["frac"] < 1.0
+    assert "cpu_baseline" not in d and d["config"]["workload"].startswith("strip128")
 
 
 def test_more_than_one_gpu_is_refused_with_a_message():

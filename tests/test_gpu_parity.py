@@ -164,8 +164,14 @@ MR_MFMA_CASES = [
     (1, 300, 64, 1, 16, 64),        # lh = 1
     (1, 700, 64, 129, 16, 128),     # one tap past 128
     (1, 900, 64, 200, 16, 224),
-    (1, 1100, 64, 257, 64, 288),    # longest filter of the matrix-core path
+    (1, 1100, 64, 257, 64, 288),    # longest filter at two waves per SIMD
     (3, 256, 256, 128, 16, 128),
+    (1, 1300, 64, 258, 16, 0),      # filters in the hundreds (one wave per SIMD, 13 source blocks)
+    (2, 1500, 128, 384, 16, 512),   # several tiles, each with 12 warm-up chunks
+    (1, 900, 64, 385, 32, 416),     # last filter of 13 source blocks
+    (1, 2000, 64, 386, 16, 576),    # first of 17 source blocks
+    (1, 2500, 192, 513, 16, 1024),  # longest filter of the matrix-core path
+    (1, 300, 64, 513, 64, 0),       # L < lh
 ]
 
 
@@ -189,7 +195,7 @@ def test_mr_every_workgroup_width(case, waves):
     (1, 300, 64, 128, 16, "f32"),   # fp32: exact-to-1e-5 check of the Toeplitz indexing on the general kernel
     (2, 257, 48, 128, 8, "bf16"),   # group smaller than a matrix tile
     (1, 200, 40, 50, 1, "bf16"),    # ungrouped medium filter
-    (1, 400, 64, 300, 16, "bf16"),  # filter longer than the matrix-core path takes
+    (1, 700, 64, 514, 16, "bf16"),  # filter longer than the matrix-core path takes
     (2, 130, 64, 128, 16, "f32"),
     (1, 64, 16, 128, 16, "bf16"),   # D below the 64-channel block
 ])
@@ -513,3 +519,26 @@ def test_chain_guard_bands_and_determinism():
     torch.cuda.synchronize()
     assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all() and not torch.isnan(out).any()
     assert torch.equal(out, again)
+
+
+@pytest.mark.parametrize("case", [
+    # B, L, D, strip_channels, rows, depth
+    (1, 1000, 256, 0, 0, 0), (2, 333, 256, 64, 0, 1), (1, 700, 256, 128, 96, 3), (3, 129, 512, 256, 32, 4),
+    (1, 1, 256, 256, 0, 6), (2, 77, 64, 64, 0, 6), (1, 50, 24, 0, 0, 0), (1, 900, 128, 128, 64, 2),
+])
+def test_bandwidth_yardstick_computes_the_elementwise_gate(case):
+    """hyena_stream_gate is the operator with a one-tap unit filter: y = q*k*v, compared with the oracle as such,
+    for the linear stream and every strip width, with ragged tiles."""
+    B, L, D, strip, rows, depth = case
+    say("hyena_stream_gate B=%d L=%d D=%d strip=%d rows=%d depth=%d" % case)
+    rng = np.random.Generator(np.random.PCG64(90 + strip + L))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3))
+    n = B * L * D
+    guard = 2048
+    buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    out = buf[guard:guard + n].view(B, L, D)
+    binding.hyena_stream_gate(dev(q), dev(k), dev(v), strip, rows, depth, out=out)
+    y = host(out)
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all()
+    ref = oracle.gated_conv(q, k, v, np.ones((D, 1), dtype=np.float32), group=1)
+    assert np.isfinite(y).all() and oracle.rel_err(y, ref) <= TOL["bf16"]
