@@ -187,9 +187,10 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
  * Arithmetic is fp32 throughout with one rounding per stored element; dh is summed in fp32, first within a
  * tile in time order, then over tiles and channels in index order (deterministic, no atomics).
  * Short filters (lh <= 8) run a fused streaming stencil.  Medium grouped bf16 filters (group a multiple of 16,
- * D a multiple of 64, 8 < lh <= 129) run on the matrix cores: dq is the forward operator applied to (dy, k, v);
- * dk, dv come from the same block-Toeplitz scheme walked in reversed time; dh is a second MFMA contraction
- * over the channels of a group (u and g = dy*q are rounded to bf16 for it, partial sums stay fp32).
+ * D a multiple of 64, 8 < lh <= 129) run on the matrix cores in ONE pass over dy, q, k, v that walks the sequence
+ * from its end: dk, dv come from the block-Toeplitz scheme of the forward operator, causal in reversed time; dq
+ * from the same Toeplitz operands applied to a window of u blocks, a few chunks late; dh is a second MFMA
+ * contraction over the channels of a group (u and g = dy*q are rounded to bf16 for it, partial sums stay fp32).
  * Everything else runs a general fp32 kernel.
  * hyena_se_bwd and hyena_mr_bwd are the same operation and differ only in which shapes they are tuned for.
  */

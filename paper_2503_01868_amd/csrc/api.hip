@@ -390,12 +390,7 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
         rc = check_workspace(workspace, workspace_bytes, need, others, 9);
         if (rc != HY_OK) return rc;
         if (stencil) return launch_bwd_stencil(p, s, workspace, st);
-        // medium grouped filters: dq is the forward operator applied to (dy, k, v); then dk, dv, dh
-        ConvPtrs f{dy, k, v, h, dq};
-        ConvShape fs{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
-        rc = launch_mr_mfma(f, fs, st);
-        if (rc != HY_OK) return rc;
-        return launch_mr_bwd(p, s, workspace, st);
+        return launch_mr_bwd(p, s, workspace, st);  // medium grouped filters: one pass on the matrix cores
     }
     return launch_bwd_direct(p, s, st);
 }

@@ -126,7 +126,7 @@ int64_t bwd_stencil_workspace_bytes(const BwdShape& s);
 hy_status launch_bwd_stencil(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
 // Backward, any shape (no workspace).
 hy_status launch_bwd_direct(const BwdPtrs& p, const BwdShape& s, hipStream_t st);
-// Backward on the matrix cores for medium grouped bf16 filters: dk, dv, dh (dq is the forward kernel with q := dy).
+// Backward on the matrix cores for medium grouped bf16 filters: dq, dk, dv and dh in one pass over dy, q, k, v.
 bool mr_bwd_supported(const BwdShape& s);
 int64_t mr_bwd_rows(const BwdShape& s);
 int64_t mr_bwd_workspace_bytes(const BwdShape& s);

@@ -1,13 +1,21 @@
-// Hyena-MR backward on the gfx950 matrix cores (bf16 operands, fp32 accumulation).
+// Hyena-MR backward on the gfx950 matrix cores (bf16 operands, fp32 accumulation), ONE pass over the tensors.
 //
 // With u = k*v and g = dy*q the gradients of y = q (.) (h * u) are (Sec. 2.1 Eq. 1, Sec. 3.1 Eq. 2):
-//     dq = dy (.) (h * u)                                   -> the forward kernel itself, called with q := dy
+//     dq[t] = dy[t] * z[t],   z[t] = sum_j h[j] u[t-j]
 //     du[s] = sum_j h[j] g[s+j],  dk = du (.) v,  dv = du (.) k
 //     dh[j] = sum_{b, c in group, s} u[s] g[s+j]
-// This file holds the kernel for the last two lines.  In reversed time tau = L-1-t the transposed
-// convolution is again causal, du'[tau] = sum_j h[j] g'[tau-j], so the kernel IS the forward block-Toeplitz
-// scheme of mr_kernels.hip (same Toeplitz operands in registers, same source window, same LDS transposition,
-// same clamped prefetch) walking the sequence from its end, with g in the role of u and two post-gates.
+// The kernel walks the sequence from its end, tau = L-1-t.  In tau the transposed convolution is causal,
+// du'[tau] = sum_j h[j] g'[tau-j], so du is the forward block-Toeplitz scheme of mr_kernels.hip (Toeplitz operands
+// in registers, register window of the last NKB source blocks, LDS transposition) with g in the role of u and two
+// post-gates.  The forward sum is anti-causal in tau, z'[tau] = sum_j h[j] u'[tau+j]: the outputs of a chunk are
+// complete once the NKB-1 chunks after it have arrived, so z (and dq) come out NKB-1 chunks late, from a second
+// register window that holds the u blocks.  No second set of operands is needed: with the 32 source steps of a
+// block fed in reversed order and the 16 output steps written in reversed order, the operand of the anti-causal
+// product for output tile tau0 and source block sigma0 has the element h[(sigma0 - tau0 + 16) + n - k], which is the
+// causal operand for the offset sigma0 - tau0 + 16.  dy waits NKB chunks for its z in a lane-private LDS ring.
+// So dy, q, k, v are each read once and dq, dk, dv written once (7 tensor passes; with the forward kernel computing
+// dq in a launch of its own it was 10).  A tile needs NKB-1 chunks of dy, q before it (for du) and NKB-1 chunks of
+// k, v after it (for z).
 // The filter gradient is a second contraction over the 16 channels of a group,
 //     C_x[i][n] = sum_c u[tau_s + i, c] * g[tau_s - 16 x + n, c],    dh[16 x + i - n] += C_x[i][n],
 // which is what v_mfma_f32_16x16x16_bf16 computes from plain row-major operands (4 adjacent channels of
@@ -15,6 +23,8 @@
 // for the whole tile.  At the end of the tile each wave folds the diagonals of its accumulators into one
 // partial dh row and writes it to the workspace (App. A.4: partial accumulation by block, written out
 // contiguously); dh_reduce_kernel sums the partials.
+// Four waves (64 channels) per workgroup, one wave per SIMD: operands, two windows, the filter-gradient
+// accumulators and a deep prefetch need ~300 registers per lane.
 #include "hy_common.hpp"
 #include "hy_launch.hpp"
 
@@ -29,6 +39,7 @@ struct MrBwdArgs {
     const uint16_t* k;
     const uint16_t* v;
     const float* h;
+    uint16_t* dq;
     uint16_t* dk;
     uint16_t* dv;
     float* partial;  // [B * tiles_per_seq][D / 16][lh]: one row per (tile, 16-channel slice)
@@ -40,17 +51,23 @@ struct MrBwdArgs {
 constexpr int kChunk = 32;
 
 template <int NKB, int NW, int PF>
-__global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
+__global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
     constexpr int PPR = 2 * NW;              // 16-byte pieces per staged row
     constexpr int CPR = 2 * PPR;             // 8-byte chunks per staged row
     constexpr int kTaps = 32 * NKB;
     constexpr int ZROW = 16 * NW * 4 + 16;
     constexpr int ND = 2 * NKB - 1;          // 16-step offsets x with a tap 16 x + i - n inside [0, lh)
     constexpr int NSLOT = NKB + 1;           // chunks of g kept for the filter gradient (+1: no write/read overlap)
+    constexpr int NR = NKB + 1;              // chunks of dy waiting for their z
+    constexpr int LAG = NKB - 1;             // chunks between a chunk's arrival and its complete z
+    static_assert(NW % 4 == 0, "the LDS swizzle needs 8 pieces per row");
     __shared__ uint4 gst[2][kChunk * PPR];             // g of the newest chunk, swizzled for the transposed read
+    __shared__ uint4 utr[2][kChunk * PPR];             // u of the newest chunk, same layout (source of z)
     __shared__ uint2 gring[NSLOT][kChunk * CPR];       // g rows, 8-byte chunks XOR-swizzled by row
-    __shared__ uint2 ust[2][kChunk * CPR];             // u rows of the current chunk, same layout
-    __shared__ __attribute__((aligned(16))) char zst[2][kChunk * ZROW];
+    __shared__ uint2 ust[2][kChunk * CPR];             // u rows of the current chunk, same layout (filter gradient)
+    __shared__ uint4 dyring[NR][kChunk * PPR];         // raw dy pieces, written and read back by the same lane
+    __shared__ __attribute__((aligned(16))) char zst[2][kChunk * ZROW];   // du, fp32 rows
+    __shared__ __attribute__((aligned(16))) char zst2[2][kChunk * ZROW];  // z, fp32 rows
     __shared__ float hs[NW][kTaps];
 
     const int tid = threadIdx.x;
@@ -65,9 +82,11 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
     // everything below is in reversed time tau = L - 1 - t
     const int64_t t_start = (tile % a.tiles_per_seq) * (int64_t)a.rows;
     const int64_t t_end = (t_start + a.rows < L) ? t_start + a.rows : L;
-    int64_t t_begin = t_start - (int64_t)kChunk * (NKB - 1);
+    int64_t t_begin = t_start - (int64_t)kChunk * LAG;   // dy, q of the chunks before the tile feed its du
     if (t_begin < 0) t_begin = 0;
-    const int nchunks = (int)((t_end - t_begin + kChunk - 1) / kChunk);
+    // k, v of the LAG chunks after the tile feed its z; the walk always runs LAG chunks past the tile, also where
+    // the sequence ends first (those chunks then hold zeros and load nothing)
+    const int ntot = (int)((t_end - t_begin + kChunk - 1) / kChunk) + LAG;
 
     const int64_t cblock0 = (int64_t)cb * 16 * NW;
     const int64_t c0 = cblock0 + 16 * w;
@@ -75,22 +94,30 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
 
     const int lr = tid / PPR, lp = tid % PPR;
     const int64_t ld_off = cblock0 + 8 * lp;
-    // element offset of reversed step tau (clamped into the tile) for this lane
-    auto row_off = [&](int64_t tau) {
-        tau = tau < t_end ? tau : t_end - 1;
-        return seq0 + (L - 1 - tau) * D + ld_off;
+    // element offset of reversed step tau for this lane
+    auto row_off = [&](int64_t tau) { return seq0 + (L - 1 - tau) * D + ld_off; };
+    auto chunk_start = [&](int ci) { return t_begin + (int64_t)ci * kChunk; };
+    auto in_tile = [&](int ci) {
+        const int64_t t0 = chunk_start(ci);
+        return ci >= 0 && t0 >= t_start && t0 < t_end;
     };
-    // loads whose result is never used (chunk indices past the last chunk; k and v of warm-up chunks) all go to one
-    // 16-byte location of the tile, the same for every lane of the workgroup: one cache line per wave
+    // loads whose result is never used (chunk indices past the last chunk; k and v before the tile, dy and q after
+    // it) all go to one 16-byte location of the tile, the same for every lane of the workgroup: one cache line per
+    // wave
     const int64_t idle_off = seq0 + (L - t_end) * D + cblock0;
     auto load_g = [&](int ci, Words<4>& yy, Words<4>& qq) {
-        const int64_t off = ci < nchunks ? row_off(t_begin + (int64_t)ci * kChunk + lr) : idle_off;
+        const int64_t t0 = chunk_start(ci);
+        int64_t tau = t0 + lr;
+        tau = tau < t_end ? tau : t_end - 1;
+        const int64_t off = (ci < ntot && t0 < t_end) ? row_off(tau) : idle_off;
         yy = load_words_nt<4>(a.dy + off);
         qq = load_words_nt<4>(a.q + off);
     };
-    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {  // warm-up chunks need no k, v
-        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-        const int64_t off = (ci < nchunks && t0 >= t_start) ? row_off(t0 + lr) : idle_off;
+    auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
+        const int64_t t0 = chunk_start(ci);
+        int64_t tau = t0 + lr;
+        tau = tau < L ? tau : L - 1;
+        const int64_t off = (ci < ntot && t0 >= t_start && t0 < L) ? row_off(tau) : idle_off;
         kk = load_words_nt<4>(a.k + off);
         vv = load_words_nt<4>(a.v + off);
     };
@@ -124,11 +151,16 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
             tz[i] = __builtin_bit_cast(bf16x8_t, wds);
         }
     }
-    bf16x8_t gw[NKB];
+    // gw[m]: g block of chunk ci - m, source steps in walk order; uw[m]: u block of chunk ci - m, source steps in
+    // reversed order (element e of octet lq = step 31 - 8 lq - e of the chunk)
+    bf16x8_t gw[NKB], uw[NKB];
     {
         Words<4> z = zero_words<4>();
 #pragma unroll
-        for (int m = 0; m < NKB; ++m) gw[m] = __builtin_bit_cast(bf16x8_t, z);
+        for (int m = 0; m < NKB; ++m) {
+            gw[m] = __builtin_bit_cast(bf16x8_t, z);
+            uw[m] = __builtin_bit_cast(bf16x8_t, z);
+        }
     }
     f32x4_t cacc[ND];
 #pragma unroll
@@ -136,18 +168,20 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
 
     const int swz = ((lr >> 3) & 3) << 1;
     const int st_idx = lr * PPR + (lp ^ swz);
-    const int rd_piece = (2 * w + (li >> 3)) ^ (lq << 1);
-    const int zwr_off = li * ZROW + (16 * w + 4 * lq) * 4;
+    const int rd_piece = (2 * w + (li >> 3)) ^ (lq << 1);          // rows 8 lq .. 8 lq + 7
+    const int rd_piece_rev = (2 * w + (li >> 3)) ^ ((3 - lq) << 1);  // rows 31 - 8 lq - 7 .. 31 - 8 lq
+    const int zwr_off = li * ZROW + (16 * w + 4 * lq) * 4;           // du: step li of a 16-step tile
+    const int zwr_off_rev = (15 - li) * ZROW + (16 * w + 4 * lq) * 4;  // z: step 15 - li
     const int zrd_off = lr * ZROW + 8 * lp * 4;
     // 8-byte chunk layout: logical chunk c8 of row r sits at c8 ^ (r & 15)
     const int x8 = lr & 15;
     const int wr8a = lr * CPR + ((2 * lp) ^ x8), wr8b = lr * CPR + ((2 * lp + 1) ^ x8);
     const int rd8 = (4 * w + lq) ^ li;  // this lane's chunk in a row whose index is li (mod 16)
 
-    auto gate_store = [&](int ci, const Words<4>& kk, const Words<4>& vv) {
-        const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-        const int64_t tau = t0 + lr;
-        if (t0 >= t_start && tau < t_end) {
+    // dk, dv of chunk ci (du staged one iteration earlier)
+    auto gate_store_du = [&](int ci, const Words<4>& kk, const Words<4>& vv) {
+        const int64_t tau = chunk_start(ci) + lr;
+        if (in_tile(ci) && tau < t_end) {
             const char* zp = zst[ci & 1] + zrd_off;
             const float4 za = *reinterpret_cast<const float4*>(zp);
             const float4 zb = *reinterpret_cast<const float4*>(zp + 16);
@@ -160,21 +194,39 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
                 o1[e] = du[e] * vf[e];
                 o2[e] = du[e] * kf[e];
             }
-            const int64_t off = seq0 + (L - 1 - tau) * D + ld_off;
+            const int64_t off = row_off(tau);
             store_words_nt<4>(a.dk + off, Pack<BF16, 8>::pack(o1));
             store_words_nt<4>(a.dv + off, Pack<BF16, 8>::pack(o2));
         }
     };
+    // dq of chunk cq, whose z was staged in iteration cq + LAG (buffer parity of that iteration)
+    auto gate_store_dq = [&](int cq) {
+        const int64_t tau = chunk_start(cq) + lr;
+        if (in_tile(cq) && tau < t_end) {
+            const char* zp = zst2[(cq + LAG) & 1] + zrd_off;
+            const float4 za = *reinterpret_cast<const float4*>(zp);
+            const float4 zb = *reinterpret_cast<const float4*>(zp + 16);
+            const uint4 raw = dyring[cq % NR][tid];
+            Words<4> yy;
+            yy.w[0] = raw.x; yy.w[1] = raw.y; yy.w[2] = raw.z; yy.w[3] = raw.w;
+            float yf[8];
+            Pack<BF16, 8>::unpack(yy, yf);
+            float o[8] = {za.x * yf[0], za.y * yf[1], za.z * yf[2], za.w * yf[3],
+                          zb.x * yf[4], zb.y * yf[5], zb.z * yf[6], zb.w * yf[7]};
+            store_words_nt<4>(a.dq + row_off(tau), Pack<BF16, 8>::pack(o));
+        }
+    };
 
-    for (int base = 0; base < nchunks; base += PF) {
+    // one more iteration than chunks: the last chunk's du and the last finished z are gated one iteration late
+    for (int base = 0; base < ntot + 1; base += PF) {
 #pragma unroll
         for (int sgi = 0; sgi < PF; ++sgi) {
             const int ci = base + sgi;
-            const int64_t t0 = t_begin + (int64_t)ci * kChunk;
-            const bool main_chunk = t0 >= t_start && ci < nchunks;
+            const int64_t t0 = chunk_start(ci);
+            const bool main_chunk = in_tile(ci) && ci < ntot;
             const int slot = __builtin_amdgcn_readfirstlane(ci % NSLOT);
 
-            // g = dy*q and u = k*v of this lane's row piece, rounded to bf16, into LDS
+            // g = dy*q and u = k*v of this lane's row piece, rounded to bf16, into LDS; dy itself into its ring
             {
                 float a8[8], b8[8];
                 Pack<BF16, 8>::unpack(ypre[sgi], a8);
@@ -185,34 +237,46 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
                 gst[ci & 1][st_idx] = make_uint4(gg.w[0], gg.w[1], gg.w[2], gg.w[3]);
                 gring[slot][wr8a] = make_uint2(gg.w[0], gg.w[1]);
                 gring[slot][wr8b] = make_uint2(gg.w[2], gg.w[3]);
+                dyring[ci % NR][tid] = make_uint4(ypre[sgi].w[0], ypre[sgi].w[1], ypre[sgi].w[2], ypre[sgi].w[3]);
                 Pack<BF16, 8>::unpack(kpre[sgi], a8);
                 Pack<BF16, 8>::unpack(vpre[sgi], b8);
-                // u of steps past the end of the tile must not reach the filter gradient
-                const bool live = t0 + lr < t_end;
                 Words<4> uu;
 #pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2)
-                    uu.w[e2] = live ? pack_bf16x2(a8[2 * e2] * b8[2 * e2], a8[2 * e2 + 1] * b8[2 * e2 + 1]) : 0u;
-                ust[ci & 1][wr8a] = make_uint2(uu.w[0], uu.w[1]);
-                ust[ci & 1][wr8b] = make_uint2(uu.w[2], uu.w[3]);
+                for (int e2 = 0; e2 < 4; ++e2) uu.w[e2] = pack_bf16x2(a8[2 * e2] * b8[2 * e2], a8[2 * e2 + 1] * b8[2 * e2 + 1]);
+                // z reaches over the end of the tile but not over the end of the sequence; the filter gradient
+                // takes u of the tile only
+                const bool in_seq = t0 + lr < L;
+                const bool in_own = t0 + lr < t_end;
+                utr[ci & 1][st_idx] = in_seq ? make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]) : make_uint4(0u, 0u, 0u, 0u);
+                ust[ci & 1][wr8a] = in_own ? make_uint2(uu.w[0], uu.w[1]) : make_uint2(0u, 0u);
+                ust[ci & 1][wr8b] = in_own ? make_uint2(uu.w[2], uu.w[3]) : make_uint2(0u, 0u);
             }
             load_g(ci + PF, ypre[sgi], qpre[sgi]);
 
             __syncthreads();
 
 #pragma unroll
-            for (int m = NKB - 1; m > 0; --m) gw[m] = gw[m - 1];
+            for (int m = NKB - 1; m > 0; --m) {
+                gw[m] = gw[m - 1];
+                uw[m] = uw[m - 1];
+            }
             {
                 const uint16_t* s16 = reinterpret_cast<const uint16_t*>(gst[ci & 1]);
-                Words<4> wds;
+                const uint16_t* u16 = reinterpret_cast<const uint16_t*>(utr[ci & 1]);
+                Words<4> wds, wdu;
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) {
                     const int r0 = 8 * lq + 2 * e2;
                     const uint32_t lo = s16[((r0 * PPR + rd_piece) << 3) + (li & 7)];
                     const uint32_t hi = s16[(((r0 + 1) * PPR + rd_piece) << 3) + (li & 7)];
                     wds.w[e2] = lo | (hi << 16);
+                    const int rr = 31 - 8 * lq - 2 * e2;  // reversed: element 2 e2 = row rr, element 2 e2 + 1 = row rr - 1
+                    const uint32_t ulo = u16[((rr * PPR + rd_piece_rev) << 3) + (li & 7)];
+                    const uint32_t uhi = u16[(((rr - 1) * PPR + rd_piece_rev) << 3) + (li & 7)];
+                    wdu.w[e2] = ulo | (uhi << 16);
                 }
                 gw[0] = __builtin_bit_cast(bf16x8_t, wds);
+                uw[0] = __builtin_bit_cast(bf16x8_t, wdu);
             }
 
             if (main_chunk) {
@@ -243,14 +307,27 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
                     }
                 }
             }
+            // z of chunk ci - LAG: its source blocks ci - LAG .. ci are all in the window now.  Source block
+            // ci - LAG + s sits s chunks after the output chunk: offset 32 s + 16 for the first 16 outputs,
+            // 32 s for the second 16.
+            if (ci < ntot && in_tile(ci - LAG)) {
+                f32x4_t acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int s = 0; s < NKB; ++s) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw[LAG - s], tz[2 * s + 1], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(uw[LAG - s], tz[2 * s], acc1, 0, 0, 0);
+                }
+                char* zp = zst2[ci & 1] + zwr_off_rev;
+                *reinterpret_cast<float4*>(zp) = make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
+                *reinterpret_cast<float4*>(zp + 16 * ZROW) = make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
+            }
             const int prev = (sgi + PF - 1) % PF;  // static after unrolling
-            if (ci > 0 && ci <= nchunks) gate_store(ci - 1, kpre[prev], vpre[prev]);
+            if (ci > 0 && ci <= ntot) {
+                gate_store_du(ci - 1, kpre[prev], vpre[prev]);
+                gate_store_dq(ci - 1 - LAG);
+            }
             load_kv(ci - 1 + PF, kpre[prev], vpre[prev]);
         }
-    }
-    if (nchunks % PF == 0) {
-        __syncthreads();
-        gate_store(nchunks - 1, kpre[PF - 1], vpre[PF - 1]);
     }
 
     // ---- fold the diagonals: dh[16 x + i - n] += C_x[i][n]; the lane holds C_x[4 lq + r][li], r = 0..3
@@ -282,15 +359,18 @@ __global__ __launch_bounds__(NW * 64, 2) void mr_bwd_kernel(MrBwdArgs a) {
     for (int j = lane; j < a.lh; j += 64) out[j] = dhw[j];
 }
 
+constexpr int kBwdWaves = 4;  // waves (16-channel slices) per workgroup
+
 template <int NKB, int NW>
 hy_status launch_nw(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st, int64_t* nsets) {
-    constexpr int PF = 3;
+    constexpr int PF = 4;  // chunks of dy, q, k, v in flight per lane (measured: 3 and 6 are 2-8% slower)
     MrBwdArgs a;
     a.dy = static_cast<const uint16_t*>(p.dy);
     a.q = static_cast<const uint16_t*>(p.q);
     a.k = static_cast<const uint16_t*>(p.k);
     a.v = static_cast<const uint16_t*>(p.v);
     a.h = p.h;
+    a.dq = static_cast<uint16_t*>(p.dq);
     a.dk = static_cast<uint16_t*>(p.dk);
     a.dv = static_cast<uint16_t*>(p.dv);
     a.partial = static_cast<float*>(ws);
@@ -309,8 +389,7 @@ hy_status launch_nw(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t s
 
 template <int NKB>
 hy_status launch_nkb(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st, int64_t* nsets) {
-    if (s.D % 128 == 0) return launch_nw<NKB, 8>(p, s, ws, st, nsets);
-    return launch_nw<NKB, 4>(p, s, ws, st, nsets);
+    return launch_nw<NKB, kBwdWaves>(p, s, ws, st, nsets);
 }
 
 }  // namespace
@@ -321,8 +400,7 @@ bool mr_bwd_supported(const BwdShape& s) {
 
 // time steps per workgroup: one workgroup per CU where the sequence allows it (same rule as the forward kernel)
 int64_t mr_bwd_rows(const BwdShape& s) {
-    const int nw = s.D % 128 == 0 ? 8 : 4;
-    const int64_t ncb = s.D / (16 * nw);
+    const int64_t ncb = s.D / (16 * kBwdWaves);
     const int nkb = (s.lh - 1 + 31) / 32 + 1;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
@@ -343,7 +421,7 @@ int64_t mr_bwd_workspace_bytes(const BwdShape& s) {
     return s.B * tiles * (s.D / 16) * s.lh * (int64_t)sizeof(float);
 }
 
-// dk, dv and dh (dq comes from the forward kernel).  `ws` holds the partial filter gradients.
+// dq, dk, dv and dh in one pass.  `ws` holds the partial filter gradients.
 hy_status launch_mr_bwd(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st) {
     if (!mr_bwd_supported(s)) return HY_ERR_UNSUPPORTED;
     const int nkb = (s.lh - 1 + 31) / 32 + 1;
