@@ -59,6 +59,11 @@ def parse():
                     help="library tuning knob (hyena_set_option), may repeat; results never depend on these")
     ap.add_argument("--also", default="c2,c3,c4,c2u,li2,c1_bwd,c2_bwd",
                     help="comma list of further workloads to time briefly (c1 only)")
+    ap.add_argument("--settle", type=int, default=300,
+                    help="launches issued right after set-up, before the --warmup steps, so that the clocks have left "
+                         "their idle state when warm-up and timing begin (uploading the inputs leaves the GPU idle for "
+                         "seconds; measured: the first few hundred launches after that run up to 5%% slower); part "
+                         "of set-up, never timed, stated in the JSON line")
     ap.add_argument("--also-warmup", type=int, default=200,
                     help="untimed launches before each --also workload (at least --warmup): the matrix-heavy kernels run "
                          "several percent slower until the clocks have settled after an idle period")
@@ -140,10 +145,13 @@ class Workload:
         self.i += 1
         self.main[j]()
 
-    def run(self, steps, warmup):
+    def run(self, steps, warmup, settle=0):
         """Returns (wall seconds for `steps` steps, average duration in ms of the dominant kernel)."""
         torch = self.torch
         ev = torch.cuda.Event
+        for _ in range(settle):  # set-up: brings the clocks out of idle (see --settle)
+            self.step()
+        torch.cuda.synchronize()
         for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
@@ -280,16 +288,16 @@ def entry_point(wl):
     return name.replace("_fwd", "_bwd (all launches of the entry point)") if wl.bwd else name
 
 
-def measure(name, args, torch, pkg, synth, steps, warmup):
+def measure(name, args, torch, pkg, synth, steps, warmup, settle=0):
     """Times one workload; returns it with the figures every line and every "also" entry carries."""
     wl = Workload(name, args.sets, torch, pkg, synth, args.seq_len, args.depth)
-    wall, kern_ms = wl.run(steps, warmup)
+    wall, kern_ms = wl.run(steps, warmup, settle)
     ms_step = 1e3 * wall / steps
     gbs = wl.algo_bytes() / (kern_ms * 1e-3) / 1e9
     traffic, source = stored_traffic(name, args.seq_len)
     res = {
         "tokens_per_s": wl.tokens * steps / wall, "ms_per_step": ms_step, "steps": steps, "warmup": warmup,
-        "buffer_sets": len(wl.sets),
+        "settle_launches_before_warmup": settle, "buffer_sets": len(wl.sets),
         "roofline": {"bound": "hbm", "kernel": entry_point(wl), "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
                      "kernel_ms_avg": kern_ms, "algorithmic_bytes_per_launch": wl.algo_bytes(),
@@ -338,7 +346,7 @@ def main():
         calibrate_copy(args, torch, pkg)
         return
 
-    wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup)
+    wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup, args.settle)
     cfg = wl.cfg
     what = "bandwidth yardstick y=q*k*v," if wl.strip is not None else {
         "se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,", "li": "Hyena-LI"}[cfg["kind"]]
@@ -349,7 +357,8 @@ def main():
         "config": {"workload": "%s: %s%s bf16 B=%d L=%d D=%d %s=%d group=%d" % (
             args.workload, what, " backward" if wl.bwd else "",
             cfg["B"], cfg["L"], cfg["D"], "order" if cfg["kind"] == "li" else "lh",
-            cfg["order"] if cfg["kind"] == "li" else cfg["lh"], cfg["group"]), "buffer_sets": res["buffer_sets"]},
+            cfg["order"] if cfg["kind"] == "li" else cfg["lh"], cfg["group"]), "buffer_sets": res["buffer_sets"],
+            "settle_launches_before_warmup": args.settle},
         "roofline": res["roofline"],
     }
     out["launch_stats"] = wl.launch_stats()

@@ -288,7 +288,10 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
                     // two instruction shapes matters beyond rounding: a 16x16x16 product that accumulates onto the
                     // result of a 16x16x32 product issued fewer than 5 wait states earlier reads the register's
                     // previous contents on gfx950 (measured), and the compiler does not always leave that distance;
-                    // 16x16x16 results feeding a 16x16x32 product are interlocked by the hardware.
+                    // 16x16x16 results feeding a 16x16x32 product are interlocked by the hardware.  Every 16x16x16
+                    // product below accumulates onto zero or onto another 16x16x16 result, so the unsafe pair cannot
+                    // arise from this source by data dependence; tests/test_isa_hazards.py checks the generated code
+                    // of this file for the pair on every build.
                     f32x4_t acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
                     acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop_lo[0], acc0, 0, 0, 0);
                     acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(shi, qop_lo[1], acc1, 0, 0, 0);
