@@ -8,7 +8,8 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c2  Hyena-MR  bf16 B1 L8192   D4096 lh128 group16  hyena_mr_fwd
   c3  Hyena-MR  bf16 B1 L131072 D4096 lh128 group16  hyena_mr_fwd
   c4  chain     bf16 B4 L32768  D4096                hyena_chain_fwd (featurizers + MR in one kernel)
-  c1_bwd / c2_bwd / c3_bwd: the backward entry points (hyena_se_bwd / hyena_mr_bwd) on the shapes of c1 / c2 / c3
+  c1_bwd / c2_bwd / c3_bwd / c2u_bwd: the backward entry points (hyena_se_bwd / hyena_mr_bwd) on the shapes of
+      c1 / c2 / c3 / c2u
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
   c2u c2 with one filter per channel; li2 / li3: Hyena-LI at the shapes of c2 / c3
@@ -45,7 +46,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
-                    choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "copy"] + list(YARDSTICKS),
+                    choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "

@@ -191,6 +191,10 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
  * from its end: dk, dv come from the block-Toeplitz scheme of the forward operator, causal in reversed time; dq
  * from the same Toeplitz operands applied to a window of u blocks, a few chunks late; dh is a second MFMA
  * contraction over the channels of a group (u and g = dy*q are rounded to bf16 for it, partial sums stay fp32).
+ * Medium bf16 filters that are not shared by 16 channels (any other group size, D a multiple of 128, 8 < lh <= 129)
+ * run chunk-parallel on the matrix cores (App. A.1): dq is the forward operator applied to (dy, k, v), dk and dv the
+ * same kernel walking towards the past on g = dy*q (one launch each), dh a per-channel correlation of g and u on
+ * the batched 4x4 matrix instruction (g and u rounded to bf16, partial sums fp32).
  * Everything else runs a general fp32 kernel.
  * hyena_se_bwd and hyena_mr_bwd are the same operation and differ only in which shapes they are tuned for.
  */

@@ -355,6 +355,7 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
     BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
     if (bwd_stencil_supported(s)) return bwd_stencil_workspace_bytes(s);
     if (mr_bwd_supported(s)) return mr_bwd_workspace_bytes(s);
+    if (cp4_bwd_supported(s)) return cp4_bwd_workspace_bytes(s);
     return 0;
 }
 
@@ -383,14 +384,17 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
     BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
     const bool stencil = bwd_stencil_supported(s);
     const bool mfma = !stencil && mr_bwd_supported(s);
-    if (stencil || mfma) {
-        const int64_t need = stencil ? bwd_stencil_workspace_bytes(s) : mr_bwd_workspace_bytes(s);
+    const bool cp4 = !stencil && !mfma && cp4_bwd_supported(s);
+    if (stencil || mfma || cp4) {
+        const int64_t need = stencil ? bwd_stencil_workspace_bytes(s)
+                                     : (mfma ? mr_bwd_workspace_bytes(s) : cp4_bwd_workspace_bytes(s));
         const Range others[9] = {{dy, bytes}, {q, bytes}, {k, bytes}, {v, bytes}, {dq, bytes},
                                  {dk, bytes}, {dv, bytes}, {h, nh}, {dh, nh}};
         rc = check_workspace(workspace, workspace_bytes, need, others, 9);
         if (rc != HY_OK) return rc;
         if (stencil) return launch_bwd_stencil(p, s, workspace, st);
-        return launch_mr_bwd(p, s, workspace, st);  // medium grouped filters: one pass on the matrix cores
+        if (mfma) return launch_mr_bwd(p, s, workspace, st);  // medium grouped filters: one pass on the matrix cores
+        return launch_cp4_bwd(p, s, workspace, st);           // medium filters of single channels or small groups
     }
     return launch_bwd_direct(p, s, st);
 }

@@ -45,6 +45,8 @@ struct Cp4Args {
     int32_t rows;           // time steps per workgroup, multiple of 64
     int32_t tiles_per_seq;  // ceil(L / rows)
     int32_t ncb;            // channel blocks = D / (16 NW)
+    int32_t rev;            // 1: step t of the kernel is row L - 1 - t of the tensors (the convolution then runs
+                            // towards the past: the transposed operator of the backward pass)
 };
 
 constexpr int kT = 64;    // steps per iteration
@@ -82,6 +84,9 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
     const int64_t seq0 = b * a.L * D;
 
     auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
+    // step -> row of the tensors: t, or L - 1 - t = (t ^ -1) + L in reversed time
+    const int rxor = a.rev ? -1 : 0, radd = a.rev ? (int)a.L : 0;
+    auto phys = [&](int t) { return (uint32_t)((t ^ rxor) + radd); };
 
     // ---- row layout: rows 2 rp, 2 rp + 1 of an iteration, channels 8 lp .. 8 lp + 7 of the block
     const int lp = tid % PPR, rp = tid / PPR;
@@ -93,7 +98,7 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
     auto row_addr = [&](int t) {  // clamped into the rows this tile may touch
         t = t < te32 ? t : te32 - 1;
         t = t > 0 ? t : 0;
-        return seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off);
+        return seq0 + ((uint64_t)phys(t) * D32 + ld_off);
     };
     auto load_rows = [&](int it, Words<4> (&kk)[2], Words<4> (&vv)[2], Words<4> (&qq)[2]) {
         const int t0 = ts32 + (it - 1) * kT + 2 * rp;  // iteration it >= 1 covers steps ts32 + 64 (it - 1) ...
@@ -240,8 +245,8 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
                 row1.w[p] = (yc[2 * p] >> 16) | (yc[2 * p + 1] & 0xffff0000u);
             }
             const int t = ts + 2 * rp;
-            if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), row0);
-            if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)(t + 1) * D32 + ld_off), row1);
+            if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t) * D32 + ld_off), row0);
+            if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
         }
     };
 
@@ -304,6 +309,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
     const int64_t cblock0 = (int64_t)cb * C;
     const int64_t seq0 = b * a.L * a.D;
     auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
+    const int rxor = a.rev ? -1 : 0, radd = a.rev ? (int)a.L : 0;  // step -> row, see cp4_kernel
+    auto phys = [&](int t) { return (uint32_t)((t ^ rxor) + radd); };
     using std::integral_constant;
 
     if (w < kWM) {
@@ -389,7 +396,7 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
         auto row_addr = [&](int t) {  // clamped into the rows this tile may touch
             t = t < te32 ? t : te32 - 1;
             t = t > 0 ? t : 0;
-            return seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off);
+            return seq0 + ((uint64_t)phys(t) * D32 + ld_off);
         };
         // u of 2 rows x 8 channels, transposed: one dword (2 steps) per channel at ring position `pos` + 2 rp
         auto write_u = [&](const Words<4> (&kk)[2], const Words<4> (&vv)[2], bool keep0, bool keep1, int pos) {
@@ -447,8 +454,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
                     row1.w[p] = (yc[2 * p] >> 16) | (yc[2 * p + 1] & 0xffff0000u);
                 }
                 const int t = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
-                if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), row0);
-                if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)(t + 1) * D32 + ld_off), row1);
+                if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t) * D32 + ld_off), row0);
+                if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
             }
         };
 
@@ -522,6 +529,7 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * NW));
+    a.rev = s.reversed ? 1 : 0;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
         int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
@@ -551,6 +559,7 @@ hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * kWM));
+    a.rev = s.reversed ? 1 : 0;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
         int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU

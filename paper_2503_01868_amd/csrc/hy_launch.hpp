@@ -23,6 +23,9 @@ struct ConvShape {
     int32_t lh, group;
     hy_dtype dtype;
     bool gated;
+    // true: the convolution runs towards the past, y[t] = q[t] * sum_j h[j] k[t+j] v[t+j] (terms with t+j >= L
+    // vanish): the transposed operator the backward pass needs.  Only launch_cp4 implements it.
+    bool reversed = false;
 };
 
 // The operator chain: featurize q, k, v (filters hq, hk, hv), then the gated medium convolution with h.
@@ -131,6 +134,12 @@ bool mr_bwd_supported(const BwdShape& s);
 int64_t mr_bwd_rows(const BwdShape& s);
 int64_t mr_bwd_workspace_bytes(const BwdShape& s);
 hy_status launch_mr_bwd(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
+// Backward on the matrix cores for medium bf16 filters not shared by 16 channels (any group): dq and dk, dv from the
+// chunk-parallel forward kernel (forwards, and twice towards the past), dh as a per-channel correlation on the
+// batched 4x4x4 products; `ws` holds the partial filter gradients.
+bool cp4_bwd_supported(const BwdShape& s);
+int64_t cp4_bwd_workspace_bytes(const BwdShape& s);
+hy_status launch_cp4_bwd(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
 // dh[g][j] = sum over nsets partial sets and over `group` adjacent rows of a set; a set is [n_rows][lh].
 hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64_t n_rows, int32_t lh, int32_t group,
                            hipStream_t st);

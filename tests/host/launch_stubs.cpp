@@ -29,6 +29,9 @@ bool mr_bwd_supported(const BwdShape& s) { return s.dtype == HY_BF16 && s.group 
 int64_t mr_bwd_rows(const BwdShape& s) { return (s.L + 31) / 32 * 32; }
 int64_t mr_bwd_workspace_bytes(const BwdShape& s) { return s.B * (s.D / 16) * s.lh * 4; }
 hy_status launch_mr_bwd(const BwdPtrs&, const BwdShape&, void*, hipStream_t) { return HY_OK; }
+bool cp4_bwd_supported(const BwdShape& s) { return s.dtype == HY_BF16 && s.D % 128 == 0 && s.lh > 8 && s.lh <= 129; }
+int64_t cp4_bwd_workspace_bytes(const BwdShape& s) { return s.B * s.D * s.lh * 4; }
+hy_status launch_cp4_bwd(const BwdPtrs&, const BwdShape&, void*, hipStream_t) { return HY_OK; }
 hy_status launch_dh_reduce(const float*, float*, int64_t, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
 hy_status launch_stream_gate(const void*, const void*, const void*, void*, int64_t, int64_t, int64_t, int32_t, int64_t,
                              int32_t, hipStream_t) { return HY_OK; }

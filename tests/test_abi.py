@@ -188,6 +188,7 @@ def test_backward_entry_points_reject_bad_arguments_and_size_their_workspace():
     assert wb(2, 1000, 256, 7, 1, 1) % (256 * 7 * 4) == 0 and wb(2, 1000, 256, 7, 1, 1) > 0
     assert wb(1, 100, 64, 128, 16, 1) == 1 * 1 * (64 // 16) * 128 * 4   # matrix-core path: one row per tile and slice
     assert wb(1, 100, 64, 128, 16, 0) == 0 and wb(1, 100, 40, 50, 1, 1) == 0  # general kernel: no workspace
+    assert wb(1, 100, 128, 50, 1, 1) == 1 * 1 * 128 * 50 * 4   # chunk-parallel matrix-core path: one row per tile and channel
     assert wb(0, 100, 64, 7, 1, 1) == 0 and wb(1, 100, 64, 0, 1, 1) == -1 and wb(1, 100, 64, 7, 5, 1) == -1
 
 

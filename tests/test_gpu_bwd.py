@@ -117,6 +117,66 @@ def test_matrix_core_backward_matches_oracle(case):
         assert err <= tol, (name, err)
 
 
+CP4_BWD_CASES = [
+    # B, L, D, lh, group, mr_rows: filters not shared by 16 channels -> chunk-parallel matrix-core backward
+    (1, 512, 128, 128, 1, 0),
+    (2, 1000, 128, 128, 1, 256),    # several tiles: history of k, v before a tile, 3 look-ahead steps of dy, q after it
+    (1, 333, 128, 100, 2, 64),      # one-iteration tiles, ragged end
+    (2, 97, 128, 128, 8, 0),        # L < lh
+    (1, 1, 128, 64, 1, 0),
+    (1, 700, 256, 129, 1, 192),     # longest filter (nine lag blocks), tiles of three iterations
+    (1, 640, 128, 9, 4, 128),       # shortest filter of this path
+    (1, 450, 128, 48, 1, 64),       # three lag blocks exactly
+    (1, 450, 128, 49, 1, 128),      # one tap into the fourth
+    (1, 900, 384, 80, 2, 320),      # five lag blocks; tile length that is not a multiple of the ring
+    (3, 260, 128, 33, 32, 0),       # groups of 32 channels through hyena_se_bwd... (see the entry chosen below)
+    (1, 2100, 128, 128, 1, 1024),
+]
+
+
+@pytest.mark.parametrize("case", CP4_BWD_CASES)
+def test_chunk_parallel_backward_matches_oracle(case):
+    B, L, D, lh, group, rows = case
+    binding.set_option("mr_rows", rows)
+    say("cp4 bwd B=%d L=%d D=%d lh=%d group=%d rows=%d" % case)
+    dy, q, k, v, h = draw(78, B, L, D, lh, group, "bf16", "mr")
+    assert binding.lib().hyena_bwd_workspace_bytes(B, L, D, lh, group, binding.HY_BF16) > 0
+    entry = binding.hyena_se_bwd if group == 32 else binding.hyena_mr_bwd
+    # groups of 32 channels are a multiple of 16: that case runs the grouped kernel and only checks that the two
+    # matrix-core paths agree on what they take
+    outs = entry(dev(dy), dev(q), dev(k), dev(v), dev(h), group)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for name, got, want, tol in zip(("dq", "dk", "dv", "dh"), outs, ref, (TOL["bf16"],) * 3 + (DH_TOL_MFMA,)):
+        g = host(got)
+        assert np.isfinite(g).all(), name
+        err = oracle.rel_err(g, want)
+        assert err <= tol, (name, err)
+
+
+def test_chunk_parallel_backward_exact_case():
+    """One filter per channel, sparse signed inputs and dyadic taps: every product and partial sum is exactly
+    representable, so dq, dk, dv and dh must match the oracle bit for bit (indexing of the reversed-time launches and
+    of the lag blocks of the filter gradient, through tile boundaries)."""
+    B, L, D, lh, group = 2, 700, 128, 100, 1
+    say("cp4 bwd exact")
+    binding.set_option("mr_rows", 192)
+    rng = np.random.Generator(np.random.PCG64(79))
+    h = ((rng.integers(-8, 9, size=(D // group, lh)) / 8.0) * (rng.random((D // group, lh)) < 0.25)).astype(np.float32)
+
+    def sparse(p, lo, hi):
+        x = rng.integers(lo, hi + 1, (B, L, D)) * (rng.random((B, L, D)) < p)
+        return torch.from_numpy(x.astype(np.float32)).bfloat16()
+
+    dy, q, k, v = sparse(0.3, -2, 2), sparse(0.5, -1, 1), sparse(0.5, -1, 1), sparse(0.3, -1, 1)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for r in ref[:3]:
+        assert np.array_equal(r, torch.from_numpy(r).bfloat16().double().numpy())
+    assert np.abs(ref[3]).max() < 2 ** 20 and np.array_equal(ref[3], np.round(ref[3]))
+    outs = binding.hyena_mr_bwd(dev(dy), dev(q), dev(k), dev(v), dev(h), group)
+    for name, got, want in zip(("dq", "dk", "dv", "dh"), outs, ref):
+        assert np.array_equal(host(got), want), name
+
+
 def test_matrix_core_backward_exact_case():
     """Sparse signed inputs and dyadic taps: every product and partial sum is exactly representable, so
     dq, dk, dv and dh must match the oracle bit for bit."""
