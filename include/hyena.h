@@ -88,8 +88,9 @@ hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float 
  * fp32 accumulation (HY_BF16, group a multiple of 16, D a multiple of 64); u = k*v and the first 32
  * filter values are rounded once to bf16; the running sums stay in fp32 and, like the powers of the
  * poles that feed and read them, enter the products with 16 significant bits (two bf16 parts), so that
- * filters whose exponentials nearly cancel keep their accuracy.  Other valid combinations run the
- * plain fp32 recurrence, one lane per channel.  1 <= order <= 16, else HY_ERR_UNSUPPORTED.
+ * filters whose exponentials nearly cancel keep their accuracy.  Other valid combinations (fp32 storage, other
+ * group sizes or widths, more than 16 exponentials) run the plain recurrence, one lane per channel, with its
+ * running sums in fp64.  1 <= order <= 64, else HY_ERR_UNSUPPORTED; the matrix-core scan takes order <= 16.
  * q,k,v,y: [B,L,D] of `dtype` (device); R, lambda: fp32 [D/group, order] (device).  |lambda| <= 1 is the
  * caller's business: larger poles overflow like the definition does.
  * workspace: device memory of at least hyena_li_workspace_bytes(...) bytes, 16-byte aligned, disjoint

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libhyena.so")
 
-SOURCES = ["api.hip", "se_kernels.hip", "sew_kernels.hip", "direct_kernels.hip", "mr_kernels.hip", "cp_kernels.hip", "cp4_kernels.hip", "li_kernels.hip", "chain4_kernels.hip", "bwd_kernels.hip", "mr_bwd_kernels.hip", "cp4_bwd_kernels.hip", "yardstick_kernels.hip"]
+SOURCES = ["api.hip", "se_kernels.hip", "sew_kernels.hip", "direct_kernels.hip", "mr_kernels.hip", "cp_kernels.hip", "cp4_kernels.hip", "li_kernels.hip", "chain4_kernels.hip", "bwd_kernels.hip", "bwdw_kernels.hip", "mr_bwd_kernels.hip", "cp4_bwd_kernels.hip", "yardstick_kernels.hip"]
 
 # Packed-fp32 instruction selection is switched off for all device code in this library.
 HIPCC_FLAGS = [

@@ -307,7 +307,7 @@ hy_status hyena_li_fwd(const void* q, const void* k, const void* v, const float*
     hy_status rc = li_validate(q, k, v, R, lambda, y, B, L, D, order, group, dtype);
     if (rc != HY_OK) return rc;
     if (workspace_bytes < 0) return HY_ERR_SHAPE;
-    if (order > 16) return HY_ERR_UNSUPPORTED;
+    if (order > 64) return HY_ERR_UNSUPPORTED;
     if (empty(B, L, D)) return HY_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     LiPtrs p{q, k, v, R, lambda, y};
@@ -329,7 +329,7 @@ hy_status hyena_li_fwd_static(const void* q, const void* k, const void* v, const
     TuningSnapshot snap;
     hy_status rc = li_validate(q, k, v, R, lambda, y, B, L, D, order, group, dtype);
     if (rc != HY_OK) return rc;
-    if (order > 16) return HY_ERR_UNSUPPORTED;
+    if (order > 64) return HY_ERR_UNSUPPORTED;
     if (empty(B, L, D)) return HY_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     LiPtrs p{q, k, v, R, lambda, y};
@@ -353,7 +353,7 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
     if (dtype != HY_F32 && dtype != HY_BF16) return -1;
     if (empty(B, L, D)) return 0;
     BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
-    if (bwd_stencil_supported(s)) return bwd_stencil_workspace_bytes(s);
+    if (bwd_stencil_supported(s)) return bwd_walk_preferred(s) ? bwd_walk_workspace_bytes(s) : bwd_stencil_workspace_bytes(s);
     if (mr_bwd_supported(s)) return mr_bwd_workspace_bytes(s);
     if (cp4_bwd_supported(s)) return cp4_bwd_workspace_bytes(s);
     return 0;
@@ -385,13 +385,16 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
     const bool stencil = bwd_stencil_supported(s);
     const bool mfma = !stencil && mr_bwd_supported(s);
     const bool cp4 = !stencil && !mfma && cp4_bwd_supported(s);
+    const bool walk = stencil && bwd_walk_preferred(s);
     if (stencil || mfma || cp4) {
-        const int64_t need = stencil ? bwd_stencil_workspace_bytes(s)
-                                     : (mfma ? mr_bwd_workspace_bytes(s) : cp4_bwd_workspace_bytes(s));
+        const int64_t need = walk ? bwd_walk_workspace_bytes(s)
+                                  : (stencil ? bwd_stencil_workspace_bytes(s)
+                                             : (mfma ? mr_bwd_workspace_bytes(s) : cp4_bwd_workspace_bytes(s)));
         const Range others[9] = {{dy, bytes}, {q, bytes}, {k, bytes}, {v, bytes}, {dq, bytes},
                                  {dk, bytes}, {dv, bytes}, {h, nh}, {dh, nh}};
         rc = check_workspace(workspace, workspace_bytes, need, others, 9);
         if (rc != HY_OK) return rc;
+        if (walk) return launch_bwd_walk(p, s, workspace, st);
         if (stencil) return launch_bwd_stencil(p, s, workspace, st);
         if (mfma) return launch_mr_bwd(p, s, workspace, st);  // medium grouped filters: one pass on the matrix cores
         return launch_cp4_bwd(p, s, workspace, st);           // medium filters of single channels or small groups

@@ -127,6 +127,11 @@ hy_status launch_li_direct(const LiPtrs& p, const LiShape& s, hipStream_t st);
 bool bwd_stencil_supported(const BwdShape& s);
 int64_t bwd_stencil_workspace_bytes(const BwdShape& s);
 hy_status launch_bwd_stencil(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
+// Backward, short bf16 filters on long stretches of time: the same arithmetic on the tile-walking data movement
+// (256 channels per workgroup, 16-row chunks through LDS); bwd_walk_preferred() says when the dispatcher takes it.
+bool bwd_walk_preferred(const BwdShape& s);
+int64_t bwd_walk_workspace_bytes(const BwdShape& s);
+hy_status launch_bwd_walk(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st);
 // Backward, any shape (no workspace).
 hy_status launch_bwd_direct(const BwdPtrs& p, const BwdShape& s, hipStream_t st);
 // Backward on the matrix cores for medium grouped bf16 filters: dq, dk, dv and dh in one pass over dy, q, k, v.

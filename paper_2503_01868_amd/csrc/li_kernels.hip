@@ -332,26 +332,31 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// General kernel: the recurrence itself, one lane per (batch item, channel).  Any dtype, any group; slow
-// (B * D lanes in all), the correctness path for what the matrix-core kernel does not take.  The running sums
-// and the output sum are kept in fp64: a slow pole (lambda close to 1) carries thousands of steps, and in fp32
-// one rounding per step and exponential would add up past the 1e-5 that fp32 storage is held to; in fp64 the
-// only roundings left are the final conversion of z and the gate.
-template <typename T>
+// General kernel: the recurrence itself, one lane per (batch item, channel).  Any dtype, any group, up to
+// kMaxOrderDirect exponentials; slow (B * D lanes in all), the correctness path for what the matrix-core kernel
+// does not take.  The running sums and the output sum are kept in fp64: a slow pole (lambda close to 1) carries
+// thousands of steps, and in fp32 one rounding per step and exponential would add up past the 1e-5 that fp32
+// storage is held to; in fp64 the only roundings left are the final conversion of z and the gate.  The running
+// sums live in registers (MAXO of them); residues and poles of the lane's group sit in LDS.
+constexpr int kMaxOrderDirect = 64;
+
+template <typename T, int MAXO>
 __global__ __launch_bounds__(64) void li_direct_kernel(const void* qv, const void* kv, const void* vv, const float* R,
                                                        const float* lam, void* yv, int64_t B, int64_t L, int64_t D,
                                                        int32_t order, int32_t group) {
+    __shared__ float rtab[MAXO][64], ltab[MAXO][64];  // [exponential][lane]: conflict-free per-lane columns
     const int64_t idx = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (idx >= B * D) return;
-    const int64_t b = idx / D, c = idx % D;
+    const bool live = idx < B * D;
+    const int64_t b = live ? idx / D : 0, c = live ? idx % D : 0;
     const int64_t g = c / group;
-    double rn[kMaxOrder], ln[kMaxOrder], sn[kMaxOrder];
+    double sn[MAXO];
 #pragma unroll
-    for (int n = 0; n < kMaxOrder; ++n) {
-        rn[n] = n < order ? (double)R[g * order + n] : 0.0;
-        ln[n] = n < order ? (double)lam[g * order + n] : 0.0;
+    for (int n = 0; n < MAXO; ++n) {
+        rtab[n][threadIdx.x] = n < order ? R[g * order + n] : 0.0f;
+        ltab[n][threadIdx.x] = n < order ? lam[g * order + n] : 0.0f;
         sn[n] = 0.0;
     }
+    if (!live) return;  // (each lane reads only its own column of the tables: no barrier needed)
     const char* qp = static_cast<const char*>(qv);
     const char* kp = static_cast<const char*>(kv);
     const char* vp = static_cast<const char*>(vv);
@@ -365,9 +370,9 @@ __global__ __launch_bounds__(64) void li_direct_kernel(const void* qv, const voi
         const double u = (double)kf[0] * (double)vf[0];
         double z = 0.0;
 #pragma unroll
-        for (int n = 0; n < kMaxOrder; ++n) {
-            sn[n] = __builtin_fma(ln[n], sn[n], u);
-            z = __builtin_fma(rn[n], sn[n], z);
+        for (int n = 0; n < MAXO; ++n) {
+            sn[n] = __builtin_fma((double)ltab[n][threadIdx.x], sn[n], u);
+            z = __builtin_fma((double)rtab[n][threadIdx.x], sn[n], z);
         }
         float y1[1] = {(float)((double)qf[0] * z)};
         Pack<T, 1>::store(yp + off, Pack<T, 1>::pack(y1));
@@ -448,15 +453,24 @@ hy_status launch_li_mfma(const LiPtrs& p, const LiShape& s, void* ws, hipStream_
 }
 
 hy_status launch_li_direct(const LiPtrs& p, const LiShape& s, hipStream_t st) {
-    if (s.order < 1 || s.order > kMaxOrder) return HY_ERR_UNSUPPORTED;
+    if (s.order < 1 || s.order > kMaxOrderDirect) return HY_ERR_UNSUPPORTED;
     const int64_t n = s.B * s.D;
     const int64_t nb = (n + 63) / 64;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    if (s.dtype == HY_F32)
-        return launch_kernel((li_direct_kernel<F32>), dim3((uint32_t)nb), dim3(64), st, p.q, p.k, p.v, p.R, p.lam, p.y,
-                           s.B, s.L, s.D, s.order, s.group);
-    return launch_kernel((li_direct_kernel<BF16>), dim3((uint32_t)nb), dim3(64), st, p.q, p.k, p.v, p.R, p.lam, p.y,
-                         s.B, s.L, s.D, s.order, s.group);
+    const dim3 grid((uint32_t)nb), block(64);
+    const bool small = s.order <= kMaxOrder;
+    if (s.dtype == HY_F32) {
+        if (small)
+            return launch_kernel((li_direct_kernel<F32, kMaxOrder>), grid, block, st, p.q, p.k, p.v, p.R, p.lam, p.y, s.B,
+                                 s.L, s.D, s.order, s.group);
+        return launch_kernel((li_direct_kernel<F32, kMaxOrderDirect>), grid, block, st, p.q, p.k, p.v, p.R, p.lam, p.y,
+                             s.B, s.L, s.D, s.order, s.group);
+    }
+    if (small)
+        return launch_kernel((li_direct_kernel<BF16, kMaxOrder>), grid, block, st, p.q, p.k, p.v, p.R, p.lam, p.y, s.B,
+                             s.L, s.D, s.order, s.group);
+    return launch_kernel((li_direct_kernel<BF16, kMaxOrderDirect>), grid, block, st, p.q, p.k, p.v, p.R, p.lam, p.y, s.B,
+                         s.L, s.D, s.order, s.group);
 }
 
 }  // namespace hy

@@ -51,7 +51,7 @@ int main() {
     // static buffer is refused before anything is launched
     EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], H[1], P[3], 1, 8, 64, 16, 16, HY_BF16, nullptr), HY_OK);
     EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], nullptr, P[3], 1, 8, 64, 16, 16, HY_BF16, nullptr), HY_ERR_NULL);
-    EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], H[1], P[3], 1, 8, 64, 17, 16, HY_BF16, nullptr), HY_ERR_UNSUPPORTED);
+    EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], H[1], P[3], 1, 8, 64, 65, 16, HY_BF16, nullptr), HY_ERR_UNSUPPORTED);
     EXPECT(hyena_li_fwd_static(P[0], P[1], P[2], H[0], H[1], P[3], 1, 8, 64, 16, 16, HY_F32, nullptr), HY_OK);
     {
         char* const far = reinterpret_cast<char*>(1ull << 40);  // 128 MiB tensors, 4 GiB apart

@@ -203,7 +203,7 @@ def test_long_implicit_entry_point_rejects_bad_arguments():
     assert li(B=-1) == 2 and li(order=0) == 2 and li(group=0) == 2 and li(D=16, group=3) == 2
     assert li(dtype=9) == 3
     assert li(lam=P[5] + 4) == 4 and li(y=P[2]) == 4
-    assert li(order=17) == 5                      # more exponentials than the kernels hold
+    assert li(order=65) == 5                      # more exponentials than the kernels hold
     assert li(ws_bytes=-1) == 2
     assert li(B=0) == 0 and li(L=0) == 0          # empty problems launch nothing
     # matrix-core shapes that span several tiles need the workspace: present, aligned, large enough, disjoint
@@ -230,7 +230,7 @@ def test_static_scratch_entry_point_rejects_bad_arguments_and_oversized_scans():
     lib = binding.lib()
     assert li_static(q=None) == 1 and li_static(lam=None) == 1 and li_static(y=None) == 1
     assert li_static(order=0) == 2 and li_static(D=16, group=3) == 2 and li_static(dtype=9) == 3
-    assert li_static(R=P[3] + 4) == 4 and li_static(y=P[2]) == 4 and li_static(order=17) == 5
+    assert li_static(R=P[3] + 4) == 4 and li_static(y=P[2]) == 4 and li_static(order=65) == 5
     assert li_static(B=0) == 0 and li_static(L=0) == 0
     # the scan of this problem needs more end-of-tile records than the static buffer holds: refused, nothing launched
     far = 1 << 40

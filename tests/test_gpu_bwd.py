@@ -68,6 +68,37 @@ def test_short_filter_backward_every_tile_length(rows):
         check("hyena_se_bwd", 72, 2, 203, 192, 7, 1, dtype)
 
 
+WALK_CASES = [
+    # B, L, D, lh, group, se_rows (0 = the library's tile length)
+    (1, 1024, 256, 7, 1, 0), (2, 777, 512, 7, 1, 128), (3, 100, 256, 4, 1, 16), (1, 5, 256, 7, 1, 0), (1, 1, 256, 3, 1, 0),
+    (2, 333, 256, 1, 1, 48), (2, 400, 256, 6, 4, 80), (1, 300, 768, 5, 2, 32), (2, 129, 256, 2, 64, 0), (1, 513, 256, 3, 1, 256),
+    (1, 2000, 256, 7, 256, 160),
+]
+
+
+@pytest.mark.parametrize("case", WALK_CASES)
+def test_short_filter_backward_tile_walker_matches_oracle_and_the_stencil(case):
+    """The walking kernel (`se_walk` = 1 forces it at these small sizes): against the oracle, and dq, dk, dv bit for
+    bit against the stencil, whose arithmetic it repeats; dh differs only in the order of its fp32 partial sums."""
+    B, L, D, lh, group, rows = case
+    say("bwd walker B=%d L=%d D=%d lh=%d group=%d rows=%d" % case)
+    dy, q, k, v, h = draw(80, B, L, D, lh, group, "bf16", "se")
+    args = [dev(x) for x in (dy, q, k, v, h)]
+    binding.set_option("se_rows", rows)
+    binding.set_option("se_walk", 1)
+    walked = binding.hyena_se_bwd(*args, group)
+    binding.set_option("se_walk", 2)
+    plain = binding.hyena_se_bwd(*args, group)
+    torch.cuda.synchronize()
+    for a, b in zip(walked[:3], plain[:3]):
+        assert torch.equal(a, b)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for name, got, want, tol in zip(("dq", "dk", "dv", "dh"), walked, ref, (TOL["bf16"],) * 3 + (DH_TOL,)):
+        g = host(got)
+        assert np.isfinite(g).all(), name
+        assert oracle.rel_err(g, want) <= tol, name
+
+
 @pytest.mark.parametrize("case", [
     (1, 300, 48, 128, 16, "bf16"), (2, 130, 64, 128, 16, "f32"), (1, 200, 40, 50, 1, "bf16"),
     (2, 150, 72, 13, 1, "f32"), (1, 90, 48, 40, 8, "bf16"), (1, 64, 33, 3, 1, "bf16"),  # odd D: general kernel

@@ -132,6 +132,17 @@ def test_general_recurrence_matches_the_definition(case):
     check_li(64, B, L, D, order, group, dtype)
 
 
+@pytest.mark.parametrize("case", [
+    (1, 400, 64, 17, 16, "bf16"),   # one exponential more than the matrix-core scan takes
+    (2, 300, 48, 40, 8, "bf16"),
+    (1, 257, 64, 64, 16, "f32"),    # the most the general kernel holds
+    (1, 100, 32, 33, 1, "f32"),
+])
+def test_more_than_sixteen_exponentials_run_the_general_recurrence(case):
+    B, L, D, order, group, dtype = case
+    check_li(66, B, L, D, order, group, dtype)
+
+
 def test_impulse_response_is_bit_exact_across_chunks_and_tiles():
     """Dyadic residues and poles +-1/2: every coefficient, state and product is a power of two times a small
     integer, so the response to unit impulses must equal sum_n R_n lambda_n^j bit for bit, through chunk
