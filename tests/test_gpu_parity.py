@@ -241,6 +241,11 @@ CP4_CASES = [
     (1, 256, 384, 64, 3, 0),
     (3, 256, 128, 128, 32, 0),      # through hyena_se_fwd
     (1, 1000, 256, 100, 1, 320),    # tile length that is not a multiple of the ring
+    (1, 2300, 256, 129, 1, 512),    # long filters, two and more channel blocks per tile
+    (2, 513, 512, 113, 2, 256),
+    (1, 777, 256, 81, 8, 256),
+    (1, 3, 256, 128, 1, 0),
+    (1, 130, 768, 97, 3, 0),
 ]
 
 
@@ -274,13 +279,22 @@ def test_chunk_parallel_path_matches_oracle(case):
 def test_chunk_parallel_impulse_and_tile_boundaries_are_bit_exact():
     """Ungrouped dyadic taps, q = k = 1, v = unit impulses placed so that responses cross iteration and tile
     boundaries and the ring's wrap-around: y must reproduce each channel's own taps exactly."""
-    B, L, D, lh = 2, 1500, 128, 100
-    say("impulse chunk-parallel")
+    _chunk_parallel_impulse(128)
+
+
+def test_chunk_parallel_impulse_with_256_channel_workgroups_is_bit_exact():
+    _chunk_parallel_impulse(256)
+
+
+def _chunk_parallel_impulse(D):
+    B, L, lh = 2, 1500, 100
+    say("impulse chunk-parallel D=%d" % D)
     binding.set_option("mr_rows", 512)
     h = dyadic_filter(D, lh, 44)
     one = torch.ones(B, L, D, dtype=torch.bfloat16)
     v = torch.zeros(B, L, D, dtype=torch.bfloat16)
-    hits = [(0, 0, 0), (0, 200, 17), (0, 500, 63), (1, 511, 64), (1, 1023, 127), (1, 1450, 5), (0, 1499, 9), (0, 255, 70)]
+    hits = [(0, 0, 0), (0, 200, 17), (0, 500, 63), (1, 511, 64), (1, 1023, 127), (1, 1450, 5), (0, 1499, 9), (0, 255, 70),
+            (1, 31, D - 1), (0, 32, D - 17), (1, 63, D - 16), (0, 992, D - 33)]
     expect = np.zeros((B, L, D))
     for b, t0, c in hits:
         v[b, t0, c] = 1.0
