@@ -15,7 +15,8 @@ HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 25
   c2u c2 with one filter per channel; li2 / li3: Hyena-LI at the shapes of c2 / c3
   stream / strip64 / strip128 / strip256: the bandwidth yardstick hyena_stream_gate (y = q*k*v: the operator's
       3-read/1-write traffic without its arithmetic) on c1's shape, streamed linearly or walked in column strips
-      of 64 / 128 / 256 channels (128 / 256 / 512-byte row pieces) the way the matrix-core kernels move their data
+      of 64 / 128 / 256 channels (128 / 256 / 512-byte row pieces) the way the matrix-core kernels move their data;
+      strip256w8 / strip256w4: 512-byte strips walked by 8 / 4 waves with 4 / 8 chunks in flight per lane
 Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded slice of the same workload.  With the default
 workload the line also carries, under "also", the same roofline figures for c2, c3, c4, c2u, li2 and both backward
 workloads (a quarter of the steps each, after a warm-up of their own, which each entry states).
@@ -35,8 +36,11 @@ if ROOT not in sys.path:
 METRIC = "Hyena-SE/MR fwd tokens/s at D=4096; achieved HBM GB/s and MFMA % of peak"
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# bandwidth yardsticks: workload name -> channels per workgroup strip (0 = linear stream)
-YARDSTICKS = {"stream": 0, "strip64": 64, "strip128": 128, "strip256": 256}
+# bandwidth yardsticks: workload name -> (channels per workgroup strip (0 = linear stream), waves per workgroup
+# (0 = one per 16 channels), chunks of loads in flight per lane (0 = 2)); the first four have the shape of the
+# operator kernels, the last two keep the same bytes in flight with fewer, fatter streams
+YARDSTICKS = {"stream": (0, 0, 0), "strip64": (64, 0, 0), "strip128": (128, 0, 0), "strip256": (256, 0, 0),
+              "strip256w8": (256, 8, 4), "strip256w4": (256, 4, 8)}
 TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic.json")
 
 
@@ -53,7 +57,7 @@ def parse():
                          "width 4096); the JSON line then names the changed shape and carries no stored traffic figure")
     ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
     ap.add_argument("--depth", type=int, default=0,
-                    help="strip yardsticks only: 32-row chunks of loads in flight per lane (0 = 2, as in the operator kernels)")
+                    help="strip yardsticks only: chunks of loads in flight per lane (0 = the workload's own: 2 as in the operator kernels, 4 / 8 for strip256w8 / strip256w4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle slice")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
@@ -96,7 +100,8 @@ class Workload:
     def __init__(self, name, nsets, torch, pkg, synth, seq_len=0, depth=0):
         self.name, self.torch, self.pkg = name, torch, pkg
         self.bwd = name.endswith("_bwd")
-        self.strip = YARDSTICKS.get(name)
+        self.strip, self.ywaves, ydepth = YARDSTICKS.get(name, (None, 0, 0))
+        depth = depth or ydepth
         name = name[:-4] if self.bwd else name
         over = {"L": seq_len} if seq_len > 0 else {}
         if self.strip is not None:
@@ -129,7 +134,8 @@ class Workload:
                                               d["k"], d["v"], d["h"], c["group"],
                                               out=(d["dq"], d["dk"], d["dv"], d["dh"])))
             elif self.strip is not None:
-                self.main.append(pkg.plan_stream_gate(d["q"], d["k"], d["v"], self.strip, 0, depth, out=d["y"]))
+                self.main.append(pkg.plan_stream_gate(d["q"], d["k"], d["v"], self.strip, 0, depth, self.ywaves,
+                                                      out=d["y"]))
             elif c["kind"] == "li":
                 self.main.append(pkg.plan_li(d["q"], d["k"], d["v"], d["R"], d["lam"], c["group"], out=d["y"]))
             elif c["kind"] == "chain":
@@ -283,7 +289,7 @@ def stored_traffic(workload, seq_len):
 
 def entry_point(wl):
     if wl.strip is not None:
-        return "hyena_stream_gate (strip_channels=%d)" % wl.strip
+        return "hyena_stream_gate (strip_channels=%d, waves=%d)" % (wl.strip, wl.ywaves or wl.strip // 16)
     name = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd",
             "li": "hyena_li_fwd (both passes of the scan)"}[wl.cfg["kind"]]
     return name.replace("_fwd", "_bwd (all launches of the entry point)") if wl.bwd else name

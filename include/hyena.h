@@ -225,13 +225,16 @@ hy_status hyena_stream_copy(const void *src, void *dst, int64_t bytes, void *hip
  * written once with the streaming hints the operator kernels use.  strip_channels = 0 streams the tensors
  * linearly; 64, 128 or 256 makes a workgroup walk a column strip of that many channels (128, 256 or 512 bytes
  * per row) down `rows` time steps (0 = tile length that gives one workgroup per compute unit), which is how the
- * matrix-core kernels move their data, with `depth` 32-row chunks of loads in flight per lane (1, 2, 3, 4 or 6;
- * 0 = 2, what the operator kernels use; ignored by the linear stream).  D must be a multiple of 8 and of
- * strip_channels.  Not part of the
- * operator: it measures the practical ceiling a kernel with that access pattern can reach.
+ * matrix-core kernels move their data, with `depth` chunks of loads in flight per lane (1, 2, 3, 4, 6 or 8;
+ * 0 = 2, what the operator kernels use; ignored by the linear stream) and one workgroup barrier per chunk.
+ * `waves` = waves per workgroup: 0 = strip_channels / 16 (one wave per 16 channels, 32-row chunks: the operator
+ * kernels' shape), or 4, 8, 16 with 16 * waves <= strip_channels (a chunk is then 512 * waves / strip_channels
+ * rows: fewer, fatter streams per compute unit); must be 0 for the linear stream.  D must be a multiple of 8 and
+ * of strip_channels.  Unsupported combinations return HY_ERR_UNSUPPORTED.  Not part of the operator: it measures
+ * the practical ceiling a kernel with that access pattern can reach.
  */
 hy_status hyena_stream_gate(const void *q, const void *k, const void *v, void *y, int64_t B, int64_t L, int64_t D,
-                            int32_t strip_channels, int64_t rows, int32_t depth, void *hip_stream);
+                            int32_t strip_channels, int64_t rows, int32_t depth, int32_t waves, void *hip_stream);
 
 /*
  * Tuning knobs (process-wide; 0 restores the built-in choice).  Thread-safe: every entry point takes one

@@ -52,7 +52,7 @@ def lib() -> ctypes.CDLL:
         L.hyena_li_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_li_workspace_bytes.restype = i64
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
-        L.hyena_stream_gate.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i64, i32, vp]
+        L.hyena_stream_gate.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i64, i32, i32, vp]
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd",
                      "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_li_fwd_static",
@@ -408,7 +408,8 @@ def hyena_stream_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torc
     return dst
 
 
-def plan_stream_gate(q, k, v, strip_channels: int = 0, rows: int = 0, depth: int = 0, out=None, stream=None) -> Plan:
+def plan_stream_gate(q, k, v, strip_channels: int = 0, rows: int = 0, depth: int = 0, waves: int = 0, out=None,
+                     stream=None) -> Plan:
     """Marshal one ``hyena_stream_gate`` call (y = q*k*v, the bandwidth yardstick) for repeated issue."""
     _check_act("q", q)
     _check_act("k", k, q)
@@ -421,11 +422,12 @@ def plan_stream_gate(q, k, v, strip_channels: int = 0, rows: int = 0, depth: int
     c = ctypes
     args = tuple(c.c_void_p(t.data_ptr()) for t in (q, k, v, y)) + (
         c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(int(strip_channels)), c.c_int64(int(rows)),
-        c.c_int32(int(depth)), c.c_void_p(_stream(q, stream)))
+        c.c_int32(int(depth)), c.c_int32(int(waves)), c.c_void_p(_stream(q, stream)))
     return Plan(lib().hyena_stream_gate, args, "hyena_stream_gate", (q, k, v, y), y)
 
 
-def hyena_stream_gate(q, k, v, strip_channels: int = 0, rows: int = 0, depth: int = 0, out=None, stream=None) -> torch.Tensor:
+def hyena_stream_gate(q, k, v, strip_channels: int = 0, rows: int = 0, depth: int = 0, waves: int = 0, out=None,
+                      stream=None) -> torch.Tensor:
     """y = q*k*v elementwise, linearly or through column strips; see ``hyena_stream_gate`` in hyena.h."""
     with torch.cuda.device(q.device):
-        return plan_stream_gate(q, k, v, strip_channels, rows, depth, out, stream)()
+        return plan_stream_gate(q, k, v, strip_channels, rows, depth, waves, out, stream)()

@@ -428,7 +428,7 @@ hy_status hyena_stream_copy(const void* src, void* dst, int64_t bytes, void* hip
 }
 
 hy_status hyena_stream_gate(const void* q, const void* k, const void* v, void* y, int64_t B, int64_t L, int64_t D,
-                            int32_t strip_channels, int64_t rows, int32_t depth, void* hip_stream) {
+                            int32_t strip_channels, int64_t rows, int32_t depth, int32_t waves, void* hip_stream) {
     const void* ins[3] = {q, k, v};
     void* outs[1] = {y};
     hy_status rc = validate(ins, 3, outs, 1, nullptr, 0, B, L, D, 1, 1, HY_BF16);
@@ -437,9 +437,14 @@ hy_status hyena_stream_gate(const void* q, const void* k, const void* v, void* y
     if (strip_channels != 0 && strip_channels != 64 && strip_channels != 128 && strip_channels != 256)
         return HY_ERR_UNSUPPORTED;
     if (strip_channels != 0 && D % strip_channels != 0) return HY_ERR_SHAPE;
-    if (depth != 0 && depth != 1 && depth != 2 && depth != 3 && depth != 4 && depth != 6) return HY_ERR_UNSUPPORTED;
+    if (depth != 0 && depth != 1 && depth != 2 && depth != 3 && depth != 4 && depth != 6 && depth != 8)
+        return HY_ERR_UNSUPPORTED;
+    // 4, 8 or 16 waves, at most one wave per 16 channels of the strip (the linear stream has no such choice)
+    if (waves != 0 && (strip_channels == 0 || (waves != 4 && waves != 8 && waves != 16) || waves * 16 > strip_channels))
+        return HY_ERR_UNSUPPORTED;
     if (empty(B, L, D)) return HY_OK;
-    return launch_stream_gate(q, k, v, y, B, L, D, strip_channels, rows, depth, static_cast<hipStream_t>(hip_stream));
+    return launch_stream_gate(q, k, v, y, B, L, D, strip_channels, rows, depth, waves,
+                              static_cast<hipStream_t>(hip_stream));
 }
 
 hy_status hyena_set_option(const char* name, int32_t value) {

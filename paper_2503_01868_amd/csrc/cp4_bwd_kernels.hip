@@ -278,10 +278,16 @@ hy_status launch_cp4_bwd(const BwdPtrs& p, const BwdShape& s, void* ws, hipStrea
     ConvShape rev{s.B, s.L, s.D, s.lh, s.group, s.dtype, true, true};
     hy_status rc = launch_cp4(ConvPtrs{p.dy, p.k, p.v, p.h, p.dq}, fwd, st);
     if (rc != HY_OK) return rc;
-    rc = launch_cp4(ConvPtrs{p.v, p.dy, p.q, p.h, p.dk}, rev, st);
-    if (rc != HY_OK) return rc;
-    rc = launch_cp4(ConvPtrs{p.k, p.dy, p.q, p.h, p.dv}, rev, st);
-    if (rc != HY_OK) return rc;
+    if (cp4_dual_supported(rev)) {
+        // filters of 66 taps and more: dk and dv from one launch with two post-gates
+        rc = launch_cp4(ConvPtrs{p.v, p.dy, p.q, p.h, p.dk, p.k, p.dv}, rev, st);
+        if (rc != HY_OK) return rc;
+    } else {
+        rc = launch_cp4(ConvPtrs{p.v, p.dy, p.q, p.h, p.dk}, rev, st);
+        if (rc != HY_OK) return rc;
+        rc = launch_cp4(ConvPtrs{p.k, p.dy, p.q, p.h, p.dv}, rev, st);
+        if (rc != HY_OK) return rc;
+    }
     const int na = (s.lh + 15) / 16;
     if (na <= 3) return launch_dh_na<3>(p, s, ws, st);
     if (na <= 5) return launch_dh_na<5>(p, s, ws, st);

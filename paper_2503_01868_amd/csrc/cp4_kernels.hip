@@ -40,6 +40,8 @@ struct Cp4Args {
     const uint16_t* v;
     const float* h;
     uint16_t* y;
+    const uint16_t* q2;  // second post-gate and output of the same convolution (dual kernels only)
+    uint16_t* y2;
     int64_t L, D;
     int32_t lh, group;
     int32_t rows;           // time steps per workgroup, multiple of 64
@@ -284,7 +286,9 @@ constexpr int kR4 = 256;   // ring length in steps, 4 kT
 constexpr int kLS4 = 544;  // bytes per ring line (2 kR4 + 32: 8 banks per channel)
 constexpr int kQS4 = 288;  // bytes per q/y line (2 slots x 2 kT + 32)
 
-template <int NBK, int PF>
+// DUAL: two post-gates and two outputs from one convolution, y = q * z and y2 = q2 * z (the backward pass needs
+// dk = v * du and dv = k * du): a second q/y buffer, one more tensor loaded and one more stored per step.
+template <int NBK, int PF, bool DUAL>
 __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
     constexpr int kH = 4 * (NBK - 1);
     static_assert(kH <= 2 * kT, "history must fit two ring slots");
@@ -293,6 +297,7 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
     constexpr int PPR = C / 8;   // 16-byte pieces per row
     __shared__ __attribute__((aligned(16))) char ring[C * kLS4 + (C / 8) * 8];
     __shared__ __attribute__((aligned(16))) char qy[C * kQS4 + (C / 8) * 8];
+    __shared__ __attribute__((aligned(16))) char qy2[DUAL ? C * kQS4 + (C / 8) * 8 : 16];
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -343,6 +348,7 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
         const char* const mix2 = rl + 2 * ((4 * l4 - 8 + kR4) % kR4);
         const char* const mix3 = rl + 2 * ((4 * l4 - 12 + kR4) % kR4);
         char* const qy_lane = qy + line_off(cw, kQS4) + 8 * l4;
+        char* const qy2_lane = qy2 + line_off(cw, kQS4) + 8 * l4;
 
         auto mstep = [&](auto j4_c) {
             constexpr int J4 = decltype(j4_c)::value;  // iteration mod 4 = ring slot
@@ -374,6 +380,13 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
                 *reinterpret_cast<uint2*>(ql) =
                     make_uint2(pack_bf16x2(bf16_lo(q4.x) * acc[g][0], bf16_hi(q4.x) * acc[g][1]),
                                pack_bf16x2(bf16_lo(q4.y) * acc[g][2], bf16_hi(q4.y) * acc[g][3]));
+                if constexpr (DUAL) {
+                    char* ql2 = qy2_lane + SL + 32 * g;
+                    const uint2 p4 = *reinterpret_cast<const uint2*>(ql2);
+                    *reinterpret_cast<uint2*>(ql2) =
+                        make_uint2(pack_bf16x2(bf16_lo(p4.x) * acc[g][0], bf16_hi(p4.x) * acc[g][1]),
+                                   pack_bf16x2(bf16_lo(p4.y) * acc[g][2], bf16_hi(p4.y) * acc[g][3]));
+                }
             }
             __syncthreads();
         };
@@ -392,6 +405,7 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
         const uint32_t ld_off = (uint32_t)(cblock0 + 8 * lp);
         char* const u_lines = ring + line_off(8 * lp, kLS4) + 4 * rp;
         char* const q_lines = qy + line_off(8 * lp, kQS4) + 4 * rp;
+        char* const q2_lines = qy2 + line_off(8 * lp, kQS4) + 4 * rp;
 
         auto row_addr = [&](int t) {  // clamped into the rows this tile may touch
             t = t < te32 ? t : te32 - 1;
@@ -412,7 +426,9 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
         };
 
         Words<4> kw[PF][2][2], vw[PF][2][2], qw[PF][2][2];  // [stage][half of the iteration][row of the pair]
-        auto load_rows = [&](int it, Words<4> (&kk)[2][2], Words<4> (&vv)[2][2], Words<4> (&qq)[2][2]) {
+        Words<4> pw[DUAL ? PF : 1][2][2];                  // the second gate
+        auto load_rows = [&](int it, Words<4> (&kk)[2][2], Words<4> (&vv)[2][2], Words<4> (&qq)[2][2],
+                             Words<4> (&pp)[2][2]) {
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const int t0 = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
@@ -422,29 +438,35 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
                     kk[hf][r] = load_words_nt<4>(a.k + off);
                     vv[hf][r] = load_words_nt<4>(a.v + off);
                     qq[hf][r] = load_words_nt<4>(a.q + off);
+                    if constexpr (DUAL) pp[hf][r] = load_words_nt<4>(a.q2 + off);
                 }
             }
         };
+        // a gate's 2 rows x 8 channels, transposed into its [channel][time] buffer
+        auto write_gate = [&](char* ql, const Words<4> (&qq)[2]) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t q0 = qq[0].w[p], q1 = qq[1].w[p];
+                *reinterpret_cast<uint32_t*>(ql + (2 * p) * kQS4) = (q0 & 0xffffu) | (q1 << 16);
+                *reinterpret_cast<uint32_t*>(ql + (2 * p + 1) * kQS4) = (q0 >> 16) | (q1 & 0xffff0000u);
+            }
+        };
         // iteration `it` out of its register stage into ring position wb and q/y slot offset sl
-        auto prepare = [&](int it, int wb, int sl, Words<4> (&kk)[2][2], Words<4> (&vv)[2][2], Words<4> (&qq)[2][2]) {
+        auto prepare = [&](int it, int wb, int sl, Words<4> (&kk)[2][2], Words<4> (&vv)[2][2], Words<4> (&qq)[2][2],
+                           Words<4> (&pp)[2][2]) {
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const int t = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
                 write_u(kk[hf], vv[hf], t < te32, t + 1 < te32, wb + 32 * hf);
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const uint32_t q0 = qq[hf][0].w[p], q1 = qq[hf][1].w[p];
-                    char* ql = q_lines + sl + 64 * hf;
-                    *reinterpret_cast<uint32_t*>(ql + (2 * p) * kQS4) = (q0 & 0xffffu) | (q1 << 16);
-                    *reinterpret_cast<uint32_t*>(ql + (2 * p + 1) * kQS4) = (q0 >> 16) | (q1 & 0xffff0000u);
-                }
+                write_gate(q_lines + sl + 64 * hf, qq[hf]);
+                if constexpr (DUAL) write_gate(q2_lines + sl + 64 * hf, pp[hf]);
             }
         };
-        auto store_y = [&](int it, int sl) {
+        auto store_one = [&](int it, int sl, const char* lines, uint16_t* dst) {
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 uint32_t yc[8];
-                const char* ql = q_lines + sl + 64 * hf;
+                const char* ql = lines + sl + 64 * hf;
 #pragma unroll
                 for (int c8 = 0; c8 < 8; ++c8) yc[c8] = *reinterpret_cast<const uint32_t*>(ql + c8 * kQS4);
                 Words<4> row0, row1;
@@ -454,9 +476,13 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
                     row1.w[p] = (yc[2 * p] >> 16) | (yc[2 * p + 1] & 0xffff0000u);
                 }
                 const int t = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
-                if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t) * D32 + ld_off), row0);
-                if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
+                if (t < te32) store_words_nt<4>(dst + seq0 + ((uint64_t)phys(t) * D32 + ld_off), row0);
+                if (t + 1 < te32) store_words_nt<4>(dst + seq0 + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
             }
+        };
+        auto store_y = [&](int it, int sl) {
+            store_one(it, sl, q_lines, a.y);
+            if constexpr (DUAL) store_one(it, sl, q2_lines, a.y2);
         };
 
         // history: steps ts32 - 128 .. ts32 - 65 into slot 3, ts32 - 64 .. ts32 - 1 into slot 0; its loads go out
@@ -479,7 +505,7 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
                     }
                 }
             }
-            load_rows(1, kw[0], vw[0], qw[0]);
+            load_rows(1, kw[0], vw[0], qw[0], pw[0]);
 #pragma unroll
             for (int hb = (kH <= kT ? 1 : 0); hb < 2; ++hb) {
 #pragma unroll
@@ -490,10 +516,10 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
             }
         }
         if constexpr (PF == 2) {
-            if (2 <= nit) load_rows(2, kw[1], vw[1], qw[1]);
+            if (2 <= nit) load_rows(2, kw[1], vw[1], qw[1], pw[DUAL ? 1 : 0]);
         }
-        prepare(1, kT, 2 * kT, kw[0], vw[0], qw[0]);
-        if (1 + PF <= nit) load_rows(1 + PF, kw[0], vw[0], qw[0]);
+        prepare(1, kT, 2 * kT, kw[0], vw[0], qw[0], pw[0]);
+        if (1 + PF <= nit) load_rows(1 + PF, kw[0], vw[0], qw[0], pw[0]);
         __syncthreads();
 
         auto vstep = [&](auto j4_c, int j) {
@@ -501,8 +527,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
             constexpr int ST = J4 % PF;                // stage of iteration j + 1
             if (j >= 2) store_y(j - 1, ((J4 + 3) & 1) * 2 * kT);
             if (j + 1 <= nit) {
-                prepare(j + 1, kT * ((J4 + 1) & 3), ((J4 + 1) & 1) * 2 * kT, kw[ST], vw[ST], qw[ST]);
-                if (j + 1 + PF <= nit) load_rows(j + 1 + PF, kw[ST], vw[ST], qw[ST]);
+                prepare(j + 1, kT * ((J4 + 1) & 3), ((J4 + 1) & 1) * 2 * kT, kw[ST], vw[ST], qw[ST], pw[DUAL ? ST : 0]);
+                if (j + 1 + PF <= nit) load_rows(j + 1 + PF, kw[ST], vw[ST], qw[ST], pw[DUAL ? ST : 0]);
             }
             __syncthreads();
         };
@@ -524,6 +550,8 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.v = static_cast<const uint16_t*>(p.v);
     a.h = p.h;
     a.y = static_cast<uint16_t*>(p.y);
+    a.q2 = nullptr;
+    a.y2 = nullptr;
     a.L = s.L;
     a.D = s.D;
     a.lh = s.lh;
@@ -548,12 +576,15 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
 
 template <int NBK, int PF>
 hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
+    const bool dual = p.q2 != nullptr;
     Cp4Args a;
     a.q = static_cast<const uint16_t*>(p.q);
     a.k = static_cast<const uint16_t*>(p.k);
     a.v = static_cast<const uint16_t*>(p.v);
     a.h = p.h;
     a.y = static_cast<uint16_t*>(p.y);
+    a.q2 = static_cast<const uint16_t*>(p.q2);
+    a.y2 = static_cast<uint16_t*>(p.y2);
     a.L = s.L;
     a.D = s.D;
     a.lh = s.lh;
@@ -573,7 +604,8 @@ hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    return launch_kernel((cp4ws_kernel<NBK, PF>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), st, a);
+    if (dual) return launch_kernel((cp4ws_kernel<NBK, PF, true>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), st, a);
+    return launch_kernel((cp4ws_kernel<NBK, PF, false>), dim3((uint32_t)nb), dim3((kWM + kWV) * 64), st, a);
 }
 
 template <int NBK>
@@ -594,6 +626,8 @@ hy_status launch_cp4_nbk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) 
 
 }  // namespace
 
+bool cp4_dual_supported(const ConvShape& s) { return cp4_supported(s) && (s.lh + 2) / 4 + 1 > 17; }
+
 bool cp4_supported(const ConvShape& s) {
     return s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh >= 1 && s.lh <= 129 && s.L <= 0x7fff0000LL &&
            s.D <= 0x7fff0000LL;
@@ -601,6 +635,8 @@ bool cp4_supported(const ConvShape& s) {
 
 hy_status launch_cp4(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     if (!cp4_supported(s)) return HY_ERR_UNSUPPORTED;
+    if ((p.q2 != nullptr || p.y2 != nullptr) && !(p.q2 != nullptr && p.y2 != nullptr && cp4_dual_supported(s)))
+        return HY_ERR_UNSUPPORTED;
     const int nbk = (s.lh + 2) / 4 + 1;  // products per 16 outputs; instantiated in steps of 8 (except the smallest)
     if (nbk <= 5) return launch_cp4_nbk<5>(p, s, st);
     if (nbk <= 9) return launch_cp4_nbk<9>(p, s, st);

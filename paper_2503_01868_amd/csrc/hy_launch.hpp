@@ -16,6 +16,10 @@ struct ConvPtrs {
     const void* v;   // pre-gate operand, unused when not gated
     const float* h;  // [D/group, lh] fp32
     void* y;
+    // optional second post-gate and output, y2 = q2 * (h * (k*v)), from the same convolution (only where
+    // cp4_dual_supported says so)
+    const void* q2 = nullptr;
+    void* y2 = nullptr;
 };
 
 struct ConvShape {
@@ -113,6 +117,8 @@ bool cp_mfma_supported(const ConvShape& s);
 hy_status launch_cp_mfma(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // The same on the batched 4x4x4 MFMA: 256 channels per workgroup, lh <= 129.  HY_ERR_UNSUPPORTED outside cp4_supported().
 bool cp4_supported(const ConvShape& s);
+// whether launch_cp4 also takes ConvPtrs::q2 / y2 for this shape (the long-filter kernel does)
+bool cp4_dual_supported(const ConvShape& s);
 hy_status launch_cp4(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
 // Whole chain in one pass over q, k, v, featurizers on the matrix cores too (batched 4x4x4 products, taps as bf16
 // head + remainder).  HY_ERR_UNSUPPORTED outside chain4_supported().
@@ -151,9 +157,10 @@ hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64
 // dh := 0 (the filter gradient of an empty batch).
 hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st);
 // Bandwidth yardstick y = q*k*v (bf16): strip = 0 streams linearly, 64 / 128 / 256 walks column strips of that many
-// channels down time in `rows`-step tiles (0 = one workgroup per compute unit), `depth` chunks of loads in flight.
+// channels down time in `rows`-step tiles (0 = one workgroup per compute unit), `depth` chunks of loads in flight,
+// `waves` waves per workgroup (0 = strip / 16).
 hy_status launch_stream_gate(const void* q, const void* k, const void* v, void* y, int64_t B, int64_t L, int64_t D,
-                             int32_t strip, int64_t rows, int32_t depth, hipStream_t st);
+                             int32_t strip, int64_t rows, int32_t depth, int32_t waves, hipStream_t st);
 
 // Launches `kernel` and returns the status of THIS launch as hipLaunchKernel reports it.  The thread's sticky
 // "last error" is neither read nor cleared: an error left behind by an earlier, unrelated HIP call of the caller

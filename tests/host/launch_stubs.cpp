@@ -37,6 +37,6 @@ int64_t cp4_bwd_workspace_bytes(const BwdShape& s) { return s.B * s.D * s.lh * 4
 hy_status launch_cp4_bwd(const BwdPtrs&, const BwdShape&, void*, hipStream_t) { return HY_OK; }
 hy_status launch_dh_reduce(const float*, float*, int64_t, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
 hy_status launch_stream_gate(const void*, const void*, const void*, void*, int64_t, int64_t, int64_t, int32_t, int64_t,
-                             int32_t, hipStream_t) { return HY_OK; }
+                             int32_t, int32_t, hipStream_t) { return HY_OK; }
 hy_status launch_bwd_zero_dh(float*, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
 }  // namespace hy

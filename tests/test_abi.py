@@ -118,9 +118,10 @@ def test_stream_copy_and_options_reject_bad_arguments():
 
 def test_bandwidth_yardstick_rejects_bad_arguments():
     lib = binding.lib()
-    g = lambda q=P[0], k=P[1], v=P[2], y=P[3], B=1, L=8, D=256, strip=0, rows=0, depth=0: lib.hyena_stream_gate(
-        q, k, v, y, B, L, D, strip, rows, depth, None)
-    assert g(depth=5) == 5 and g(depth=6, strip=64, B=0) == 0
+    g = lambda q=P[0], k=P[1], v=P[2], y=P[3], B=1, L=8, D=256, strip=0, rows=0, depth=0, waves=0: lib.hyena_stream_gate(
+        q, k, v, y, B, L, D, strip, rows, depth, waves, None)
+    assert g(depth=5) == 5 and g(depth=6, strip=64, B=0) == 0 and g(depth=8, strip=256, waves=4, B=0) == 0
+    assert g(waves=8) == 5 and g(strip=64, waves=8) == 5 and g(strip=256, waves=12) == 5
     assert g(q=None) == 1 and g(y=None) == 1 and g(L=-1) == 2 and g(D=12) == 2 and g(rows=-1) == 2
     assert g(strip=32) == 5 and g(strip=128, D=192) == 2 and g(y=P[1]) == 4 and g(k=P[1] + 8) == 4
     assert g(B=0) == 0 and g(L=0, strip=256) == 0

@@ -261,3 +261,26 @@ def test_backward_guard_bands_determinism_and_empty_batch():
     rc = binding.lib().hyena_se_bwd(*ptr, None, 0, B, 0, D, lh, 1, binding.HY_BF16, None)
     torch.cuda.synchronize()
     assert rc == 0 and torch.count_nonzero(dh) == 0
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["c1", "c2", "c2u"])
+def test_backward_at_the_bench_shapes_all_outputs(name):
+    """The backward workloads bench.py times (c1_bwd, c2_bwd, c2u_bwd: tile walker, one-pass matrix-core kernel,
+    chunk-parallel ungrouped kernels) with bench.py's inputs and launch configuration, every element of dq, dk, dv
+    and dh against the oracle."""
+    w = synth.make(name)
+    B, L, D, lh, group = (w[x] for x in ("B", "L", "D", "lh", "group"))
+    say("backward at bench shape %s B=%d L=%d D=%d lh=%d group=%d" % (name, B, L, D, lh, group))
+    rng = np.random.Generator(np.random.PCG64(synth.seed_for(name, 0) + 500000))
+    dy = synth.normal_tensor(rng, (B, L, D), w["dtype"])
+    entry = binding.hyena_se_bwd if w["kind"] == "se" else binding.hyena_mr_bwd
+    outs = entry(dev(dy), dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["h"]), group)
+    ref = oracle.gated_conv_bwd(dy, w["q"], w["k"], w["v"], w["h"], group=group)
+    dh_tol = DH_TOL if w["kind"] == "se" else DH_TOL_MFMA
+    for nm, got, want, tol in zip(("dq", "dk", "dv", "dh"), outs, ref, (TOL[w["dtype"]],) * 3 + (dh_tol,)):
+        g = host(got)
+        assert g.shape == want.shape and np.isfinite(g).all(), nm
+        err = oracle.rel_err(g, want)
+        say("  %s rel_err=%.3e" % (nm, err))
+        assert err <= tol, (nm, err)

@@ -536,22 +536,23 @@ def test_chain_guard_bands_and_determinism():
 
 
 @pytest.mark.parametrize("case", [
-    # B, L, D, strip_channels, rows, depth
-    (1, 1000, 256, 0, 0, 0), (2, 333, 256, 64, 0, 1), (1, 700, 256, 128, 96, 3), (3, 129, 512, 256, 32, 4),
-    (1, 1, 256, 256, 0, 6), (2, 77, 64, 64, 0, 6), (1, 50, 24, 0, 0, 0), (1, 900, 128, 128, 64, 2),
+    # B, L, D, strip_channels, rows, depth, waves
+    (1, 1000, 256, 0, 0, 0, 0), (2, 333, 256, 64, 0, 1, 0), (1, 700, 256, 128, 96, 3, 0), (3, 129, 512, 256, 32, 4, 0),
+    (1, 1, 256, 256, 0, 6, 0), (2, 77, 64, 64, 0, 6, 4), (1, 50, 24, 0, 0, 0, 0), (1, 900, 128, 128, 64, 2, 8),
+    (2, 555, 512, 256, 0, 4, 8), (1, 1001, 256, 256, 40, 8, 4), (1, 301, 384, 128, 0, 4, 4), (1, 7, 256, 256, 0, 8, 8),
 ])
 def test_bandwidth_yardstick_computes_the_elementwise_gate(case):
     """hyena_stream_gate is the operator with a one-tap unit filter: y = q*k*v, compared with the oracle as such,
     for the linear stream and every strip width, with ragged tiles."""
-    B, L, D, strip, rows, depth = case
-    say("hyena_stream_gate B=%d L=%d D=%d strip=%d rows=%d depth=%d" % case)
+    B, L, D, strip, rows, depth, waves = case
+    say("hyena_stream_gate B=%d L=%d D=%d strip=%d rows=%d depth=%d waves=%d" % case)
     rng = np.random.Generator(np.random.PCG64(90 + strip + L))
     q, k, v = (synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3))
     n = B * L * D
     guard = 2048
     buf = torch.full((n + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
     out = buf[guard:guard + n].view(B, L, D)
-    binding.hyena_stream_gate(dev(q), dev(k), dev(v), strip, rows, depth, out=out)
+    binding.hyena_stream_gate(dev(q), dev(k), dev(v), strip, rows, depth, waves, out=out)
     y = host(out)
     assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all()
     ref = oracle.gated_conv(q, k, v, np.ones((D, 1), dtype=np.float32), group=1)
