@@ -284,3 +284,27 @@ def test_backward_at_the_bench_shapes_all_outputs(name):
         err = oracle.rel_err(g, want)
         say("  %s rel_err=%.3e" % (nm, err))
         assert err <= tol, (nm, err)
+
+
+@pytest.mark.timeout(600)
+def test_backward_at_the_long_context_shape_on_channel_slabs():
+    """c3_bwd as bench.py times it (B=1, L=131072, D=4096, lh=128, groups of 16; one-pass matrix-core kernel, four
+    tiles of 32768 steps per channel block): the whole problem runs on the GPU; dq, dk, dv and the dh rows of the
+    first and the last 256 channels (whole filter groups are exact sub-problems for the oracle: 100 663 296 of the
+    1.6 G gradient elements, every tile boundary of those channels included) are compared element by element."""
+    w = synth.make("c3")
+    B, L, D, lh, group = (w[x] for x in ("B", "L", "D", "lh", "group"))
+    say("backward at c3's shape B=%d L=%d D=%d lh=%d group=%d" % (B, L, D, lh, group))
+    rng = np.random.Generator(np.random.PCG64(synth.seed_for("c3", 0) + 500000))
+    dy = synth.normal_tensor(rng, (B, L, D), w["dtype"])
+    outs = binding.hyena_mr_bwd(dev(dy), dev(w["q"]), dev(w["k"]), dev(w["v"]), dev(w["h"]), group)
+    torch.cuda.synchronize()
+    for c0, c1 in ((0, 256), (D - 256, D)):
+        sub = [x[:, :, c0:c1].contiguous() for x in (dy, w["q"], w["k"], w["v"])]
+        ref = oracle.gated_conv_bwd(*sub, w["h"][c0 // group:c1 // group], group=group)
+        got = [host(o[:, :, c0:c1]) for o in outs[:3]] + [host(outs[3][c0 // group:c1 // group])]
+        for nm, g, want, tol in zip(("dq", "dk", "dv", "dh"), got, ref, (TOL["bf16"],) * 3 + (DH_TOL_MFMA,)):
+            assert g.shape == want.shape and np.isfinite(g).all(), nm
+            err = oracle.rel_err(g, want)
+            say("  channels %d..%d %s rel_err=%.3e" % (c0, c1 - 1, nm, err))
+            assert err <= tol, (nm, err)
