@@ -119,6 +119,38 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
         }
     }
     __syncthreads();
+    // ---- start state: zero at the start of a sequence, else the Horner sum over the earlier tiles' end states,
+    // sixteen records per round (the loads do not depend on the running sum, only the FMAs do; indices past the
+    // last record are clamped so that the loads stay unconditional), so that up to sixteen earlier tiles cost one
+    // memory latency.  Done before the operands are built, while few registers are live.
+    // state layout: lane (li = channel, lq) holds s[n = 4lq + r][channel], r = 0..3
+    f32x4_t s = {0.0f, 0.0f, 0.0f, 0.0f};
+    const int64_t ws_wave = ((c0 / 16) * 64 + lane) * 4;  // this lane's 4 floats inside one (b, tile) record set
+    const int64_t ws_tile = (D / 16) * 256;               // floats per (b, tile)
+    if constexpr (!kStateOnly) {
+        float lam_rows[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) lam_rows[r] = powi(ls[w][4 * lq + r], a.rows);
+        const float* wp = a.ws + b * (a.tiles_per_seq - 1) * ws_tile + ws_wave;
+        for (int tau0 = 0; tau0 < tile; tau0 += 16) {
+            float4 st[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int tau = tau0 + i < tile ? tau0 + i : tile - 1;
+                st[i] = *reinterpret_cast<const float4*>(wp + tau * ws_tile);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (tau0 + i < tile) {
+                    s[0] = lam_rows[0] * s[0] + st[i].x;
+                    s[1] = lam_rows[1] * s[1] + st[i].y;
+                    s[2] = lam_rows[2] * s[2] + st[i].z;
+                    s[3] = lam_rows[3] * s[3] + st[i].w;
+                }
+            }
+        }
+    }
+
     if (lane < kChunk) {
         float hj = 0.0f;
         for (int n = 0; n < kMaxOrder; ++n) hj += rs[w][n] * powi(ls[w][n], lane);
@@ -167,13 +199,9 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
         pop = __builtin_bit_cast(bf16x8_t, wds);
         pop_lo = __builtin_bit_cast(bf16x8_t, wlo);
     }
-    // state layout: lane (li = channel, lq) holds s[n = 4lq + r][channel], r = 0..3
-    float lam32[4], lam_rows[4];
+    float lam32[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        lam32[r] = powi(ls[w][4 * lq + r], kChunk);
-        lam_rows[r] = powi(ls[w][4 * lq + r], a.rows);
-    }
+    for (int r = 0; r < 4; ++r) lam32[r] = powi(ls[w][4 * lq + r], kChunk);
     // Q operands: lane (li = step of tile x, lq), element e = R_n lambda_n^(16x + li + 1), n = 4lq + e
     s16x4_t qop[2], qop_lo[2];
     if constexpr (!kStateOnly) {
@@ -189,33 +217,6 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
             wlo.w[1] = pack_bf16x2(qe[2] - bf16_lo(wds.w[1]), qe[3] - bf16_hi(wds.w[1]));
             qop[x] = __builtin_bit_cast(s16x4_t, wds);
             qop_lo[x] = __builtin_bit_cast(s16x4_t, wlo);
-        }
-    }
-
-    // ---- start state: zero at the start of a sequence, else the Horner sum over the earlier tiles' end states
-    f32x4_t s = {0.0f, 0.0f, 0.0f, 0.0f};
-    const int64_t ws_wave = ((c0 / 16) * 64 + lane) * 4;  // this lane's 4 floats inside one (b, tile) record set
-    const int64_t ws_tile = (D / 16) * 256;               // floats per (b, tile)
-    if constexpr (!kStateOnly) {
-        // eight records in flight at a time (the loads do not depend on the running sum, only the FMAs do);
-        // indices past the last record are clamped so that the loads stay unconditional
-        const float* wp = a.ws + b * (a.tiles_per_seq - 1) * ws_tile + ws_wave;
-        for (int tau0 = 0; tau0 < tile; tau0 += 8) {
-            float4 st[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int tau = tau0 + i < tile ? tau0 + i : tile - 1;
-                st[i] = *reinterpret_cast<const float4*>(wp + tau * ws_tile);
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (tau0 + i < tile) {
-                    s[0] = lam_rows[0] * s[0] + st[i].x;
-                    s[1] = lam_rows[1] * s[1] + st[i].y;
-                    s[2] = lam_rows[2] * s[2] + st[i].z;
-                    s[3] = lam_rows[3] * s[3] + st[i].w;
-                }
-            }
         }
     }
 
@@ -395,6 +396,10 @@ int64_t li_rows(const LiShape& s, int nw) {
 
 int li_waves(const LiShape& s) {
     const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 16;
+    // Left to itself, a problem that gives a 256-channel workgroup fewer than 512 steps takes 128-channel workgroups
+    // (half as many tiles per sequence, twice as long): measured at B = 1, D = 4096: L = 2048 29.8 against 32.5 us,
+    // L = 4096 45.8 against 48.6; from L = 8192 on the wide workgroup wins (76.2 against 79.2 us).
+    if (tuning().mr_waves == 0 && tuning().mr_rows == 0 && s.D % 256 == 0 && li_rows(s, 16) < 512) return 8;
     if (nw == 16 && s.D % 256 == 0) return 16;
     if (nw >= 8 && s.D % 128 == 0) return 8;
     return 4;

@@ -235,6 +235,27 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr
     }
 }
 
+// Time steps per workgroup of NW waves and the number of workgroups that gives.
+template <int NKB>
+int64_t tile_rows(const ConvShape& s, int nw, int64_t* workgroups) {
+    const int64_t ncb = s.D / (16 * nw);
+    int64_t rows = tuning().mr_rows;
+    if (rows <= 0) {
+        // One workgroup per CU: measured on MI355X, few large workgroups that each stream a wide piece of
+        // every row beat many small ones, and each extra tile costs (NKB-1)*32 halo steps of k and v.
+        const int64_t want = 256;
+        int64_t tiles = want / (s.B * ncb);
+        if (tiles < 1) tiles = 1;
+        rows = (s.L + tiles - 1) / tiles;
+        const int64_t min_rows = 4LL * kChunk * (NKB > 1 ? NKB - 1 : 1);
+        if (rows < min_rows) rows = min_rows;
+    }
+    rows = (rows + kChunk - 1) / kChunk * kChunk;
+    if (rows > (s.L + kChunk - 1) / kChunk * kChunk) rows = (s.L + kChunk - 1) / kChunk * kChunk;
+    *workgroups = s.B * ((s.L + rows - 1) / rows) * ncb;
+    return rows;
+}
+
 template <int NKB, int NW>
 hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     constexpr int PF = 2;  // chunks of k, v, q in flight per lane: measured best on MI355X (deeper queues ran slower)
@@ -249,22 +270,10 @@ hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * NW));
-    int64_t rows = tuning().mr_rows;
-    if (rows <= 0) {
-        // One workgroup per CU: measured on MI355X, few large workgroups that each stream a wide piece of
-        // every row beat many small ones, and each extra tile costs (NKB-1)*32 halo steps of k and v.
-        const int64_t want = 256;
-        int64_t tiles = want / (s.B * a.ncb);
-        if (tiles < 1) tiles = 1;
-        rows = (s.L + tiles - 1) / tiles;
-        const int64_t min_rows = 4LL * kChunk * (NKB > 1 ? NKB - 1 : 1);
-        if (rows < min_rows) rows = min_rows;
-    }
-    rows = (rows + kChunk - 1) / kChunk * kChunk;
-    if (rows > (s.L + kChunk - 1) / kChunk * kChunk) rows = (s.L + kChunk - 1) / kChunk * kChunk;
+    int64_t nb = 0;
+    const int64_t rows = tile_rows<NKB>(s, NW, &nb);
     a.rows = (int32_t)rows;
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
-    const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
     return launch_kernel((mr_mfma_kernel<NKB, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
 }
@@ -276,7 +285,21 @@ hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     if constexpr (NKB > 13) {
         return launch_nkb_nw<NKB, 4>(p, s, st);  // one wave per SIMD: 64 channels per workgroup
     } else {
-        const int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 16;
+        int nw = tuning().mr_waves > 0 ? tuning().mr_waves : 16;
+        if (tuning().mr_waves == 0 && tuning().mr_rows == 0) {
+            // Small problems: a tile cannot be shorter than four times its halo, so wide workgroups may leave
+            // compute units idle.  Take the widest workgroup that still gives every compute unit one (measured
+            // at B = 1, D = 4096, lh = 128: L = 4096 28.9 us with 8 waves against 33.0 with 16; L = 2048 16.3 us
+            // with 4 waves against 19.8 / 28.3; L = 512 11.9 against 14.3 / 22.5; from L = 8192 on 16 waves win).
+            int64_t wg = 0;
+            const bool wide_ok = NKB <= 5 && s.D % 256 == 0;
+            if (wide_ok) tile_rows<NKB>(s, 16, &wg);
+            if (!wide_ok || wg < 256) {
+                nw = 8;
+                if (s.D % 128 == 0) tile_rows<NKB>(s, 8, &wg);
+                if (s.D % 128 != 0 || wg < 256) nw = 4;
+            }
+        }
         if constexpr (NKB <= 5) {  // 16 waves only where the kernel fits 128 registers without spilling
             if (nw == 16 && s.D % 256 == 0) return launch_nkb_nw<NKB, 16>(p, s, st);
         }
