@@ -174,3 +174,52 @@ def test_every_tuning_knob_combination_leaves_the_result_within_tolerance(case):
                         ("se_vec", se_vec)):
         binding.set_option(name, value)
     check_gated(entry, 7000 + i, B, L, D, lh, group, "bf16", kind="mr" if lh > 8 else "se")
+
+
+def bwd_cases(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        group = pick(rng, [1, 1, 2, 4, 8, 16, 16, 32, 64])
+        D = group * int(rng.integers(1, 5)) * pick(rng, [1, 2, 4, 8, 16])
+        D = min(D, 512)
+        D -= D % group
+        D = max(D, group)
+        if rng.random() < 0.4:  # widths the matrix-core and tile-walking paths take
+            D = pick(rng, [128, 256, 384, 512])
+            group = pick(rng, [g for g in (1, 2, 4, 8, 16, 32, 64) if D % g == 0])
+        lh = pick(rng, [1, 2, 3, 7, 8, 9, 13, 17, 33, 48, 50, 64, 65, 66, 100, 128, 129, 130, 140])
+        L = int(rng.integers(1, 1200))
+        B = int(rng.integers(1, 4))
+        dtype = pick(rng, ["bf16", "bf16", "bf16", "f32"])
+        entry = pick(rng, ["hyena_se_bwd", "hyena_mr_bwd"])
+        rows = pick(rng, [0, 0, 64, 128, 256, 512])
+        walk = pick(rng, [0, 0, 1])
+        out.append((i, entry, B, L, D, lh, group, dtype, rows, walk))
+    return out
+
+
+@pytest.mark.parametrize("case", bwd_cases(40, 2026), ids=lambda c: "%d-%s-B%dL%dD%dlh%dg%d%s-r%d-w%d" % c)
+def test_backward_entry_points_on_random_shapes(case):
+    """Whichever backward path a shape lands on (stencil, tile walker, one-pass matrix-core kernel, chunk-parallel
+    ungrouped kernels with one or two gates, general kernels): dq, dk, dv within the storage type's tolerance; dh
+    at the fp32 bar where it is summed in fp32 from unrounded products, at the matrix-core bar where u and g enter
+    the contraction rounded to bf16."""
+    i, entry, B, L, D, lh, group, dtype, rows, walk = case
+    binding.set_option("mr_rows", rows)
+    binding.set_option("se_rows", rows)
+    binding.set_option("se_walk", walk)
+    say("%s #%d B=%d L=%d D=%d lh=%d group=%d %s rows=%d walk=%d" % (entry, i, B, L, D, lh, group, dtype, rows, walk))
+    rng = np.random.Generator(np.random.PCG64(7000 + i))
+    dy, q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(4))
+    h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
+    outs = getattr(binding, entry)(dev(dy), dev(q), dev(k), dev(v), dev(h), group)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    on_matrix_cores = dtype == "bf16" and 8 < lh <= 129 and (
+        (group % 16 == 0 and D % 64 == 0) or (group % 16 != 0 and D % 128 == 0))
+    dh_tol = 1e-2 if on_matrix_cores else TOL["f32"]
+    for name, got, want, tol in zip(("dq", "dk", "dv", "dh"), outs, ref, (TOL[dtype],) * 3 + (dh_tol,)):
+        g = host(got)
+        assert g.shape == want.shape and np.isfinite(g).all(), name
+        err = oracle.rel_err(g, want)
+        assert err <= tol, (name, err)
