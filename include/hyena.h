@@ -80,6 +80,35 @@ hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float 
                        void *hip_stream);
 
 /*
+ * One rank's share of a sequence-sharded forward call (Sec. 4, the point-to-point scheme for FIR filters: a
+ * rank needs, beyond its own steps, only the last lh - 1 steps of k and v of its left neighbour).  Same
+ * operator as hyena_se_fwd / hyena_mr_fwd on the shard's L steps,
+ *     y[b,t,c] = q[b,t,c] * sum_{j<lh} h[c/group, j] * k[b,t-j,c] * v[b,t-j,c],   t = 0 .. L-1,
+ * except that rows t - j < 0 are not all zero: the `history` rows in front of row 0 of k and v (device memory
+ * at negative offsets from the pointers, i.e. the neighbour's rows received in front of the shard, or simply
+ * the preceding rows when the shard is a window of a longer tensor) hold real steps; rows before those are
+ * zero.  history = 0 is the start of a sequence; history >= lh - 1 an interior shard; values in between are
+ * a shard that begins fewer than lh - 1 steps into the sequence.
+ * Layout: row t of batch item b of k and v is at element offset b * batch_stride_kv + t * D from the pointer,
+ * of q and y at b * batch_stride_qy + t * D (D contiguous as everywhere); the strides are ignored when B = 1,
+ * else batch_stride_kv >= (L + history) * D, batch_stride_qy >= L * D (HY_ERR_SHAPE) and both a multiple of
+ * 16 bytes (HY_ERR_ALIGN).  The overlap rules apply to the memory really touched (history rows included).
+ * Kernels: the short-filter stencil and tile walker, the grouped matrix-core kernel, and the general kernel
+ * for every other shape (the chunk-parallel kernels for ungrouped medium filters do not take shards yet).
+ * Results of a sequence computed in shards equal the unsharded call's up to the rounding order of the fp32
+ * sums (bit for bit on the short-filter paths, whose tap order is fixed).
+ * No collective is issued here: exchanging the halo rows is the caller's business.
+ */
+hy_status hyena_se_fwd_shard(const void *q, const void *k, const void *v, const float *h, void *y,
+                             int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
+                             int64_t batch_stride_kv, int64_t batch_stride_qy, int32_t history,
+                             void *hip_stream);
+hy_status hyena_mr_fwd_shard(const void *q, const void *k, const void *v, const float *h, void *y,
+                             int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
+                             int64_t batch_stride_kv, int64_t batch_stride_qy, int32_t history,
+                             void *hip_stream);
+
+/*
  * Hyena-LI inner operator, forward (Sec. 2.1, the "long implicit" filter; gates as in Eq. 1 / Algorithm 1):
  *     y[b,t,c] = q[b,t,c] * sum_{j=0}^{t} h[c/group, j] * k[b,t-j,c] * v[b,t-j,c],
  *     h[g, j]  = sum_{n=0}^{order-1} R[g,n] * lambda[g,n]^j         (the paper's h_t with t = j + 1)

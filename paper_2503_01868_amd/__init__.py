@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     plan_chain,
     plan_featurize3,
     plan_gated,
+    plan_gated_shard,
     plan_li,
     hyena_chain_fwd,
     hyena_featurize3_fwd,
@@ -18,8 +19,10 @@ from .binding import (  # noqa: F401
     hyena_li_fwd_static,
     hyena_mr_bwd,
     hyena_mr_fwd,
+    hyena_mr_fwd_shard,
     hyena_se_bwd,
     hyena_se_fwd,
+    hyena_se_fwd_shard,
     hyena_stream_copy,
     hyena_stream_gate,
     plan_stream_gate,

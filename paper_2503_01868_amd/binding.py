@@ -37,6 +37,9 @@ def lib() -> ctypes.CDLL:
         conv_args = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_se_fwd.argtypes = conv_args
         L.hyena_mr_fwd.argtypes = conv_args
+        shard_args = [vp] * 5 + [i64, i64, i64, i32, i32, ci, i64, i64, i32, vp]
+        L.hyena_se_fwd_shard.argtypes = shard_args
+        L.hyena_mr_fwd_shard.argtypes = shard_args
         L.hyena_featurize_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_featurize3_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, ci, vp]
         L.hyena_chain_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i64, i32, i32, i32, i32, ci, vp]
@@ -54,7 +57,8 @@ def lib() -> ctypes.CDLL:
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
         L.hyena_stream_gate.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i64, i32, i32, vp]
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
-        for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_featurize_fwd", "hyena_featurize3_fwd",
+        for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_se_fwd_shard", "hyena_mr_fwd_shard", "hyena_featurize_fwd",
+                     "hyena_featurize3_fwd",
                      "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_li_fwd_static",
                      "hyena_stream_copy", "hyena_stream_gate", "hyena_set_option"):
             getattr(L, name).restype = ci
@@ -161,6 +165,51 @@ def plan_gated(entry: str, q, k, v, h, group: int, out=None, stream=None) -> Pla
             c.c_void_p(y.data_ptr()), c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lh), c.c_int32(int(group)),
             c.c_int(_dtype_code(q)), c.c_void_p(_stream(q, stream)))
     return Plan(getattr(lib(), entry), args, entry, (q, k, v, h, y), y)
+
+
+def _check_rows(name: str, t: torch.Tensor, ref: torch.Tensor | None = None) -> None:
+    """A [B, L, D] window of rows: D contiguous, rows D apart, any distance between batch items."""
+    if not isinstance(t, torch.Tensor) or t.device.type != "cuda":
+        raise ValueError("%s must be a tensor on the GPU" % name)
+    if t.dim() != 3 or t.stride(2) != 1 or t.stride(1) != t.shape[2]:
+        raise ValueError("%s must be a [B, L, D] tensor or view with contiguous rows" % name)
+    if ref is not None and (t.shape != ref.shape or t.dtype != ref.dtype or t.device != ref.device):
+        raise ValueError("%s must match the shape, dtype and device of the first activation" % name)
+
+
+def plan_gated_shard(entry: str, q, k, v, h, group: int, history: int, out=None, stream=None) -> Plan:
+    """Marshal one ``hyena_se_fwd_shard`` / ``hyena_mr_fwd_shard`` call.  q, k, v (and out) are [B, L, D] windows
+    with contiguous rows, e.g. ``x[:, t0:t0 + L]`` of a longer tensor; k and v must have ``history`` valid rows in
+    front of their first row in memory and share one batch stride, q and out another."""
+    if entry not in ("hyena_se_fwd_shard", "hyena_mr_fwd_shard"):
+        raise ValueError("entry must be hyena_se_fwd_shard or hyena_mr_fwd_shard")
+    _check_rows("q", q)
+    _check_rows("k", k, q)
+    _check_rows("v", v, q)
+    lh = _check_filter("h", h, q, group)
+    y = torch.empty_like(q, memory_format=torch.contiguous_format) if out is None else out
+    _check_rows("out", y, q)
+    B, L, D = q.shape
+    if B > 1 and (k.stride(0) != v.stride(0) or q.stride(0) != y.stride(0)):
+        raise ValueError("k and v must share a batch stride, q and out too")
+    c = ctypes
+    args = (c.c_void_p(q.data_ptr()), c.c_void_p(k.data_ptr()), c.c_void_p(v.data_ptr()), c.c_void_p(h.data_ptr()),
+            c.c_void_p(y.data_ptr()), c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lh), c.c_int32(int(group)),
+            c.c_int(_dtype_code(q)), c.c_int64(k.stride(0)), c.c_int64(q.stride(0)), c.c_int32(int(history)),
+            c.c_void_p(_stream(q, stream)))
+    return Plan(getattr(lib(), entry), args, entry, (q, k, v, h, y), y)
+
+
+def hyena_se_fwd_shard(q, k, v, h, group: int = 1, history: int = 0, out=None, stream=None) -> torch.Tensor:
+    """One sequence shard of ``hyena_se_fwd``; see ``hyena_se_fwd_shard`` in hyena.h."""
+    with torch.cuda.device(q.device):
+        return plan_gated_shard("hyena_se_fwd_shard", q, k, v, h, group, history, out, stream)()
+
+
+def hyena_mr_fwd_shard(q, k, v, h, group: int = 1, history: int = 0, out=None, stream=None) -> torch.Tensor:
+    """One sequence shard of ``hyena_mr_fwd``; see ``hyena_mr_fwd_shard`` in hyena.h."""
+    with torch.cuda.device(q.device):
+        return plan_gated_shard("hyena_mr_fwd_shard", q, k, v, h, group, history, out, stream)()
 
 
 def plan_featurize3(q, k, v, hq, hk, hv, group: int = 1, out=None, stream=None) -> Plan:

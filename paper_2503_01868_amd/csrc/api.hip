@@ -147,17 +147,52 @@ using namespace hy;
 
 namespace {
 
+// Extra checks of the sequence-shard entry points: the layout arguments, and the overlap rules on what a shard call
+// really touches (batch items a stride apart; k and v from `history` rows before their pointer).
+hy_status validate_shard(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
+                         int64_t D, int32_t lh, int32_t group, int32_t dtype, int64_t stride_kv, int64_t stride_qy,
+                         int32_t history) {
+    if (history < 0 || stride_kv < 0 || stride_qy < 0) return HY_ERR_SHAPE;
+    if (empty(B, L, D)) return HY_OK;
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    if (history > (INT64_MAX / esz - L * D) / D) return HY_ERR_SHAPE;
+    const int64_t item_kv = (L + history) * D, item_qy = L * D;  // elements of one batch item's rows
+    if (B > 1 && (stride_kv < item_kv || stride_qy < item_qy)) return HY_ERR_SHAPE;
+    // every batch item starts on a 16-byte boundary
+    if (B > 1 && ((stride_kv * esz) % 16 != 0 || (stride_qy * esz) % 16 != 0)) return HY_ERR_ALIGN;
+    if (B > 1 && (stride_kv > (INT64_MAX / esz - item_kv) / (B - 1) || stride_qy > (INT64_MAX / esz - item_qy) / (B - 1)))
+        return HY_ERR_SHAPE;
+    const int64_t span_kv = ((B - 1) * stride_kv + L * D) * esz, span_qy = ((B - 1) * stride_qy + L * D) * esz;
+    const int64_t back = (int64_t)history * D * esz;
+    const Range rd[4] = {{q, span_qy},
+                         {static_cast<const char*>(k) - back, span_kv + back},
+                         {static_cast<const char*>(v) - back, span_kv + back},
+                         {h, filter_bytes(D, group, lh)}};
+    const Range wr[1] = {{y, span_qy}};
+    return check_disjoint(rd, 4, wr, 1);
+}
+
 hy_status gated_fwd(bool mr_first, const void* q, const void* k, const void* v, const float* h, void* y, int64_t B,
-                    int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+                    int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream,
+                    bool shard = false, int64_t stride_kv = 0, int64_t stride_qy = 0, int32_t history = 0) {
     TuningSnapshot snap;
     const void* ins[3] = {q, k, v};
     void* outs[1] = {y};
     const FilterArg hs[1] = {{h, group, lh}};
     hy_status rc = validate(ins, 3, outs, 1, hs, 1, B, L, D, lh, group, dtype);
     if (rc != HY_OK) return rc;
+    if (shard) {
+        rc = validate_shard(q, k, v, h, y, B, L, D, lh, group, dtype, stride_kv, stride_qy, history);
+        if (rc != HY_OK) return rc;
+    }
     if (empty(B, L, D)) return HY_OK;
     ConvPtrs p{q, k, v, h, y};
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), true};
+    if (shard) {
+        s.bstride_kv = B > 1 ? stride_kv : L * D;
+        s.bstride_qy = B > 1 ? stride_qy : L * D;
+        s.history = history;
+    }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     rc = mr_first ? launch_mr_mfma(p, s, st) : HY_ERR_UNSUPPORTED;
     // short filters (that the grouped matrix-core path does not take) are the SE kernels' business
@@ -197,6 +232,20 @@ extern "C" {
 hy_status hyena_se_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,
                        int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     return gated_fwd(false, q, k, v, h, y, B, L, D, lh, group, dtype, hip_stream);
+}
+
+hy_status hyena_se_fwd_shard(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B,
+                             int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, int64_t batch_stride_kv,
+                             int64_t batch_stride_qy, int32_t history, void* hip_stream) {
+    return gated_fwd(false, q, k, v, h, y, B, L, D, lh, group, dtype, hip_stream, true, batch_stride_kv,
+                     batch_stride_qy, history);
+}
+
+hy_status hyena_mr_fwd_shard(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B,
+                             int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, int64_t batch_stride_kv,
+                             int64_t batch_stride_qy, int32_t history, void* hip_stream) {
+    return gated_fwd(true, q, k, v, h, y, B, L, D, lh, group, dtype, hip_stream, true, batch_stride_kv,
+                     batch_stride_qy, history);
 }
 
 hy_status hyena_mr_fwd(const void* q, const void* k, const void* v, const float* h, void* y, int64_t B, int64_t L,

@@ -629,7 +629,7 @@ hy_status launch_cp4_nbk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) 
 bool cp4_dual_supported(const ConvShape& s) { return cp4_supported(s) && (s.lh + 2) / 4 + 1 > 17; }
 
 bool cp4_supported(const ConvShape& s) {
-    return s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh >= 1 && s.lh <= 129 && s.L <= 0x7fff0000LL &&
+    return !s.sharded() && s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh >= 1 && s.lh <= 129 && s.L <= 0x7fff0000LL &&
            s.D <= 0x7fff0000LL;
 }
 

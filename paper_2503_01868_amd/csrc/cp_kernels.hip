@@ -291,7 +291,7 @@ hy_status launch_cp(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
 }  // namespace
 
 bool cp_mfma_supported(const ConvShape& s) {
-    return s.dtype == HY_BF16 && s.gated && s.D % kC == 0 && s.lh >= 1 && s.lh <= 32 * 5 - 15 &&
+    return !s.sharded() && s.dtype == HY_BF16 && s.gated && s.D % kC == 0 && s.lh >= 1 && s.lh <= 32 * 5 - 15 &&
            s.L <= 0x7fffffffLL - 2 * kT;
 }
 

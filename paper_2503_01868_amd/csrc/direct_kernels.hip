@@ -17,6 +17,8 @@ constexpr int kRowLanes = 4;  // block = kChan x kRowLanes lanes, covers kChan c
 struct DirectArgs {
     ConvPtrs p[3];
     int64_t B, L, D;
+    int64_t bstride_kv, bstride_qy;  // elements between batch items in k, v / in q, y
+    int32_t hist;     // rows of k (and v) in front of row 0 that hold data
     int32_t lh, group;
 };
 
@@ -34,10 +36,10 @@ __global__ __launch_bounds__(kChan* kRowLanes) void direct_kernel(DirectArgs a) 
     const float* hp = pr.h + (c / a.group) * (int64_t)lh;
     const char* kp = static_cast<const char*>(pr.k);
     const char* vp = static_cast<const char*>(pr.v);
-    const int64_t seq0 = b * a.L * a.D + c;
+    const int64_t seq0 = b * a.bstride_qy + c, seq0kv = b * a.bstride_kv + c;
 
     int64_t s = tf - (lh - 1);
-    if (s < 0) s = 0;
+    if (s < -(int64_t)a.hist) s = -(int64_t)a.hist;
     // tw[r] = tap that links output row tf + r with source s: index (tf + r - s), zero outside [0, lh)
     float tw[kRows], acc[kRows];
 #pragma unroll
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(kChan* kRowLanes) void direct_kernel(DirectArgs a) 
         acc[r] = 0.0f;
     }
     for (; s <= tl; ++s) {
-        const int64_t off = (seq0 + s * a.D) * T::kBytes;
+        const int64_t off = (seq0kv + s * a.D) * T::kBytes;
         float kf[1], vf[1];
         P::unpack(P::load(kp + off), kf);
         float u = kf[0];
@@ -83,6 +85,9 @@ hy_status launch_t(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t
     DirectArgs a;
     for (int i = 0; i < 3; ++i) a.p[i] = p[i < nprob ? i : 0];
     a.B = s.B; a.L = s.L; a.D = s.D; a.lh = s.lh; a.group = s.group;
+    a.bstride_kv = s.stride_kv();
+    a.bstride_qy = s.stride_qy();
+    a.hist = s.history;
     const int64_t gx = (s.D + kChan - 1) / kChan;
     const int64_t gy = (s.L + kRows * kRowLanes - 1) / (kRows * kRowLanes);
     const int64_t gz = s.B * nprob;

@@ -30,6 +30,16 @@ struct ConvShape {
     // true: the convolution runs towards the past, y[t] = q[t] * sum_j h[j] k[t+j] v[t+j] (terms with t+j >= L
     // vanish): the transposed operator the backward pass needs.  Only launch_cp4 implements it.
     bool reversed = false;
+    // One rank's share of a sequence-sharded call (Sec. 4, point-to-point scheme): consecutive batch items are
+    // `bstride_kv` elements apart in k and v and `bstride_qy` in q and y (0: L * D, dense), and `history` rows of
+    // k and v in front of row 0 hold the steps that precede the shard (the left neighbour's last rows); what lies
+    // before them is zero.  Implemented by launch_stencil, launch_se_walk (history 0 or >= 8), launch_mr_mfma and
+    // launch_direct.
+    int64_t bstride_kv = 0, bstride_qy = 0;
+    int32_t history = 0;
+    int64_t stride_kv() const { return bstride_kv > 0 ? bstride_kv : L * D; }
+    int64_t stride_qy() const { return bstride_qy > 0 ? bstride_qy : L * D; }
+    bool sharded() const { return history != 0 || stride_kv() != L * D || stride_qy() != L * D; }
 };
 
 // The operator chain: featurize q, k, v (filters hq, hk, hv), then the gated medium convolution with h.

@@ -34,6 +34,8 @@ struct MrArgs {
     const float* h;
     uint16_t* y;
     int64_t L, D;
+    int64_t bstride_kv, bstride_qy;  // elements between batch items in k, v / in q, y
+    int32_t hist;           // rows of k and v in front of row 0 that hold data (a sequence shard's left halo)
     int32_t lh, group;
     int32_t rows;           // time steps per workgroup, multiple of 32
     int32_t tiles_per_seq;  // ceil(L / rows)
@@ -67,14 +69,16 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr
     const int64_t b = tile / a.tiles_per_seq;
     const int64_t t_start = (tile % a.tiles_per_seq) * (int64_t)a.rows;
     const int64_t t_end = (t_start + a.rows < a.L) ? t_start + a.rows : a.L;
+    // warm-up chunks reach back to the first chunk boundary at or below the oldest row that holds data
     int64_t t_begin = t_start - (int64_t)kChunk * (NKB - 1);
-    if (t_begin < 0) t_begin = 0;
+    const int64_t t_floor = -(((int64_t)a.hist + kChunk - 1) / kChunk) * kChunk;
+    if (t_begin < t_floor) t_begin = t_floor;
     const int nchunks = (int)((t_end - t_begin + kChunk - 1) / kChunk);
 
     const int64_t D = a.D;
     const int64_t cblock0 = (int64_t)cb * 16 * NW;  // first channel of the workgroup
     const int64_t c0 = cblock0 + 16 * w;            // first channel of this wave
-    const int64_t seq0 = b * a.L * D;
+    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv;
 
     // cooperative coordinates of this lane: row lr of the chunk, 16-byte piece lp (8 channels) of the row;
     // used for the k, v, q loads and the y store, all of them whole 32*NW-byte row pieces
@@ -92,12 +96,16 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr
     //    per wave instead of a row piece per lane (with the streaming hint such re-reads may otherwise go all the
     //    way to memory: 2 of 20 chunk loads of a 512-step tile).
     const uint64_t idle_off = (uint64_t)(uint32_t)(te32 - 1) * D32 + (uint32_t)cblock0;
+    //  - rows before the oldest row that holds data (a shard whose halo does not fill its first warm-up chunk) read
+    //    that oldest row; their u is zeroed before it is staged.
+    const int t_old = -a.hist;
     auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
         int t = tb32 + ci * kChunk + lr;
         t = t < te32 ? t : te32 - 1;
-        const uint64_t off = ci < nchunks ? (uint64_t)(uint32_t)t * D32 + ld_off : idle_off;
-        kk = load_words_nt<4>(a.k + seq0 + off);
-        vv = load_words_nt<4>(a.v + seq0 + off);
+        t = t > t_old ? t : t_old;
+        const int64_t off = ci < nchunks ? (int64_t)t * (int64_t)D32 + ld_off : (int64_t)idle_off;
+        kk = load_words_nt<4>(a.k + seq0kv + off);
+        vv = load_words_nt<4>(a.v + seq0kv + off);
     };
     auto load_q = [&](int ci, Words<4>& qq) {
         const int t0 = tb32 + ci * kChunk;
@@ -189,6 +197,7 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2)
                     uu.w[e2] = pack_bf16x2(kf[2 * e2] * vf[2 * e2], kf[2 * e2 + 1] * vf[2 * e2 + 1]);
+                if (tb32 + ci * kChunk + lr < t_old) uu = zero_words<4>();  // before the data: zeros
                 stage[ci & 1][st_idx] = make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]);
             }
             // refill this register stage with the chunk kPrefetch ahead
@@ -267,6 +276,9 @@ hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.y = static_cast<uint16_t*>(p.y);
     a.L = s.L;
     a.D = s.D;
+    a.bstride_kv = s.stride_kv();
+    a.bstride_qy = s.stride_qy();
+    a.hist = s.history;
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * NW));

@@ -17,6 +17,8 @@ namespace {
 struct StencilArgs {
     ConvPtrs p[3];
     int64_t L, D;
+    int64_t bstride_kv, bstride_qy;  // elements between batch items in k, v / in q, y
+    int32_t hist;     // rows of k (and v) in front of row 0 that hold data
     int64_t nvec;    // D / VEC
     int64_t nitems;  // B * tiles_per_seq * nvec lanes of work
     int32_t group;
@@ -46,7 +48,8 @@ __global__ __launch_bounds__(kStencilBlock) void stencil_kernel(StencilArgs a) {
     const char* vp = static_cast<const char*>(pr.v);
     const char* qp = static_cast<const char*>(pr.q);
     char* yp = static_cast<char*>(pr.y);
-    const int64_t seq0 = (b * a.L) * D + c;  // element offset of (b, 0, c)
+    const int64_t seq0 = b * a.bstride_qy + c;    // element offset of (b, 0, c) in q and y
+    const int64_t seq0kv = b * a.bstride_kv + c;  // and in k and v
 
     // taps of this lane's channels
     float taps[VEC][LH];
@@ -63,8 +66,8 @@ __global__ __launch_bounds__(kStencilBlock) void stencil_kernel(StencilArgs a) {
     for (int i = 0; i < LH - 1; ++i) {
         const int64_t t = t0 - (LH - 1) + i;
         float kf[VEC], vf[VEC];
-        if (t >= 0) {
-            const int64_t off = (seq0 + t * D) * T::kBytes;
+        if (t >= -(int64_t)a.hist) {
+            const int64_t off = (seq0kv + t * D) * T::kBytes;
             P::unpack(P::load(kp + off), kf);
             if constexpr (GATED) P::unpack(P::load(vp + off), vf);
 #pragma unroll
@@ -80,11 +83,11 @@ __global__ __launch_bounds__(kStencilBlock) void stencil_kernel(StencilArgs a) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (t + r < t1) {
-                const int64_t off = (seq0 + (t + r) * D) * T::kBytes;
+                const int64_t off = (seq0kv + (t + r) * D) * T::kBytes;
                 kr[r] = P::load_nt(kp + off);
                 if constexpr (GATED) {
                     vr[r] = P::load_nt(vp + off);
-                    qr[r] = P::load_nt(qp + off);
+                    qr[r] = P::load_nt(qp + (seq0 + (t + r) * D) * T::kBytes);
                 }
             } else {
                 kr[r] = zero_words<P::kWords>();
@@ -152,6 +155,9 @@ hy_status launch_one(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream
     for (int i = 0; i < 3; ++i) a.p[i] = p[i < nprob ? i : 0];
     a.L = s.L;
     a.D = s.D;
+    a.bstride_kv = s.stride_kv();
+    a.bstride_qy = s.stride_qy();
+    a.hist = s.history;
     a.group = s.group;
     a.nvec = s.D / VEC;
     int rows = tuning().se_rows;

@@ -27,6 +27,8 @@ struct SewArgs {
     const float* h;
     uint16_t* y;
     int64_t L, D;
+    int64_t bstride_kv, bstride_qy;  // elements between batch items in k, v / in q, y
+    int32_t hist;           // rows of k and v in front of row 0 that hold data: 0 or >= kLook
     int32_t lh, group;
     int32_t rows;           // time steps per workgroup, multiple of 32
     int32_t tiles_per_seq;  // ceil(L / rows)
@@ -52,14 +54,14 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
     const int ts32 = (int)((tile % a.tiles_per_seq) * (int64_t)a.rows);
     const int te32 = (ts32 + a.rows < a.L) ? ts32 + a.rows : (int)a.L;
     // one warm-up chunk in front of a tile that does not start the sequence; only its last 8 rows are real loads
-    const bool warm = ts32 > 0;
+    const bool warm = ts32 > 0 || a.hist > 0;
     const int tb32 = warm ? ts32 - kChunk : 0;
     const int nchunks = (te32 - tb32 + kChunk - 1) / kChunk;
 
     const int64_t D = a.D;
     const uint32_t D32 = (uint32_t)D;
     const int64_t cblock0 = (int64_t)cb * 16 * NW;
-    const int64_t seq0 = b * a.L * D;
+    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv;
     const int lr = tid / PPR, lp = tid % PPR;
     const uint32_t ld_off = (uint32_t)(cblock0 + 8 * lp);
     const int t_lo = warm ? ts32 - kLook : 0;  // oldest row ever needed
@@ -73,9 +75,9 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
         int t = tb32 + ci * kChunk + lr;
         const bool used = ci < nchunks && t >= t_lo;
         t = t < te32 ? t : te32 - 1;
-        const uint64_t off = used ? (uint64_t)(uint32_t)t * D32 + ld_off : idle_off;
-        kk = load_words_nt<4>(a.k + seq0 + off);
-        vv = load_words_nt<4>(a.v + seq0 + off);
+        const int64_t off = used ? (int64_t)t * (int64_t)D32 + ld_off : (int64_t)idle_off;
+        kk = load_words_nt<4>(a.k + seq0kv + off);
+        vv = load_words_nt<4>(a.v + seq0kv + off);
     };
     auto load_q = [&](int ci, Words<4>& qq) {
         int t = tb32 + ci * kChunk + lr;
@@ -178,6 +180,9 @@ hy_status launch_sew_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.y = static_cast<uint16_t*>(p.y);
     a.L = s.L;
     a.D = s.D;
+    a.bstride_kv = s.stride_kv();
+    a.bstride_qy = s.stride_qy();
+    a.hist = s.history;
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * NW));
@@ -207,6 +212,7 @@ hy_status launch_sew_lh(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
 // The walking kernel pays off once every workgroup has a long stretch of time to walk.
 bool se_walk_preferred(const ConvShape& s) {
     if (s.dtype != HY_BF16 || !s.gated || s.lh < 1 || s.lh > 8 || s.D % 128 != 0) return false;
+    if (s.history != 0 && s.history < kLook) return false;  // a halo shorter than the look-back rows: the stencil's case
     if (s.L > 0x7fff0000LL || s.D > 0x7fff0000LL) return false;
     const int force = tuning().se_walk;
     if (force == 1) return true;
