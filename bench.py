@@ -10,6 +10,9 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c4  chain     bf16 B4 L32768  D4096                hyena_chain_fwd (featurizers + MR in one kernel)
   c1_bwd / c2_bwd / c3_bwd / c2u_bwd: the backward entry points (hyena_se_bwd / hyena_mr_bwd) on the shapes of
       c1 / c2 / c3 / c2u
+  c1_shards / c2_shards / c3_shards: c1 / c2 / c3 computed as four consecutive sequence shards (hyena_se_fwd_shard /
+      hyena_mr_fwd_shard: each call sees its quarter of the steps plus the lh - 1 rows of k and v before it), the
+      compute half of a sequence-sharded run on one GPU; a step is the four launches
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
   c2u c2 with one filter per channel; li2 / li3: Hyena-LI at the shapes of c2 / c3
@@ -50,7 +53,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
-                    choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "copy"] + list(YARDSTICKS),
+                    choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "c1_shards",
+                             "c2_shards", "c3_shards", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "
@@ -100,6 +104,8 @@ class Workload:
     def __init__(self, name, nsets, torch, pkg, synth, seq_len=0, depth=0):
         self.name, self.torch, self.pkg = name, torch, pkg
         self.bwd = name.endswith("_bwd")
+        self.shards = 4 if name.endswith("_shards") else 0
+        name = name[:-7] if self.shards else name
         self.strip, self.ywaves, ydepth = YARDSTICKS.get(name, (None, 0, 0))
         depth = depth or ydepth
         name = name[:-4] if self.bwd else name
@@ -141,6 +147,15 @@ class Workload:
             elif c["kind"] == "chain":
                 self.main.append(pkg.plan_chain(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"], d["h"],
                                                 c["group"], c["feat_group"], out=d["y"]))
+            elif self.shards:
+                # the sequence as `shards` consecutive shard calls, each with the lh - 1 rows before it as history
+                entry = "hyena_se_fwd_shard" if c["kind"] == "se" else "hyena_mr_fwd_shard"
+                n = c["L"] // self.shards
+                plans = [pkg.plan_gated_shard(entry, d["q"][:, i * n:(i + 1) * n], d["k"][:, i * n:(i + 1) * n],
+                                              d["v"][:, i * n:(i + 1) * n], d["h"], c["group"],
+                                              min(i * n, c["lh"] - 1), out=d["y"][:, i * n:(i + 1) * n])
+                         for i in range(self.shards)]
+                self.main.append(lambda plans=plans: [p() for p in plans])
             else:
                 entry = "hyena_se_fwd" if c["kind"] == "se" else "hyena_mr_fwd"
                 self.main.append(pkg.plan_gated(entry, d["q"], d["k"], d["v"], d["h"], c["group"], out=d["y"]))
@@ -292,6 +307,8 @@ def entry_point(wl):
         return "hyena_stream_gate (strip_channels=%d, waves=%d)" % (wl.strip, wl.ywaves or wl.strip // 16)
     name = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd",
             "li": "hyena_li_fwd (both passes of the scan)"}[wl.cfg["kind"]]
+    if wl.shards:
+        return "%s_shard x %d (the sequence in consecutive shards, one launch each)" % (name, wl.shards)
     return name.replace("_fwd", "_bwd (all launches of the entry point)") if wl.bwd else name
 
 

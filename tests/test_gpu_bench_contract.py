@@ -56,6 +56,14 @@ def test_yardstick_workload_prints_a_roofline_line_without_cpu_baseline():
     assert "cpu_baseline" not in d and d["config"]["workload"].startswith("strip128")
 
 
+def test_sharded_workload_times_the_shard_entry_point_and_keeps_parity():
+    proc = run_bench("--workload", "c2_shards", "--steps", "5", "--warmup", "2", "--settle", "0", "--cpu-seconds", "1")
+    assert proc.returncode == 0, proc.stderr[-2000:]
+    d = json.loads(proc.stdout.strip())
+    assert "hyena_mr_fwd_shard x 4" in d["roofline"]["kernel"] and 0.0 < d["roofline"]["frac"] < 1.0
+    assert d["roofline"]["traffic"] is None and d["parity_rel_err"] <= 2e-2
+
+
 def test_more_than_one_gpu_is_refused_with_a_message():
     proc = run_bench("--gpus", "2")
     assert proc.returncode != 0
