@@ -137,6 +137,28 @@ int64_t hyena_li_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order,
                                  int32_t dtype);
 
 /*
+ * hyena_li_fwd on one stretch of a longer sequence (Sec. 2.1: the filter is a sum of real exponentials, so
+ * everything before a step acts on it through `order` running sums per channel; a sequence cut into stretches,
+ * in time on one GPU or across ranks, hands those sums from one stretch to the next).  The outputs are those
+ * of hyena_li_fwd on the whole sequence restricted to this stretch, up to rounding.
+ * state_in:  running sums s[n] = sum_{i < first step} lambda_n^(first step - 1 - i) * k[i] * v[i] left by the steps
+ *            before this call, or NULL at the start of a sequence (zeros).
+ * state_out: where to leave the sums after this call's last step, or NULL; requires L to be a multiple of 32.
+ * Both are device arrays of hyena_li_state_bytes(B, D) bytes, fp32 [B][D/16][64][4]: element
+ * [b][g][16*lq + li][r] belongs to exponential n = 4*lq + r (0 for n >= order) of channel 16*g + li; 16-byte
+ * aligned, disjoint from every other argument (HY_ERR_ALIGN).  state_out of one call is state_in of the next.
+ * Matrix-core scan only: HY_BF16, group a multiple of 16, D a multiple of 64, order <= 16, B, L, D >= 1; anything
+ * else returns HY_ERR_UNSUPPORTED.  workspace as for hyena_li_fwd (same size query).
+ */
+hy_status hyena_li_fwd_carry(const void *q, const void *k, const void *v, const float *R, const float *lambda,
+                             void *y, const float *state_in, float *state_out, void *workspace,
+                             int64_t workspace_bytes, int64_t B, int64_t L, int64_t D, int32_t order, int32_t group,
+                             int32_t dtype, void *hip_stream);
+
+/* Bytes of a Hyena-LI state for hyena_li_fwd_carry: B * D * 64; -1 if D is not a multiple of 16.  Host-only. */
+int64_t hyena_li_state_bytes(int64_t B, int64_t D);
+
+/*
  * hyena_li_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and bit-identical
  * results; the end-of-tile states of the scan go to a buffer of HYENA_LI_STATIC_SCRATCH_BYTES = 4 MiB that is

@@ -251,6 +251,35 @@ def li_filter(R, lam, L: int) -> np.ndarray:
     return h
 
 
+def _wide(x) -> np.ndarray:
+    """The values of ``x`` in fp64, widened exactly from its stored bits (bf16 bit patterns become the fp32 with
+    the same upper half)."""
+    a, code = _arr(x)
+    if code == BF16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def li_state(k, v, lam, group: int = 1) -> np.ndarray:
+    """Running sums of the Hyena-LI recurrent form (Sec. 2.1) after the last step of the sequence:
+    ``s[b, c, n] = sum_{i=0}^{L-1} lam[c // group, n] ** (L - 1 - i) * k[b, i, c] * v[b, i, c]``: what a sequence cut
+    after step L - 1 hands to its continuation.  fp64 [B, D, d]."""
+    ka, va = _wide(k), _wide(v)
+    lam = np.asarray(lam, dtype=np.float64)
+    if ka.shape != va.shape or ka.ndim != 3 or lam.ndim != 2:
+        raise ValueError("k, v must share one [B, L, D] shape and lam be [G, d]")
+    B, L, D = ka.shape
+    if group < 1 or D % group != 0 or lam.shape[0] != D // group:
+        raise ValueError("lam must have one row per group of channels")
+    u = ka * va
+    e = np.arange(L - 1, -1, -1, dtype=np.int64)  # exponent of step i
+    out = np.empty((B, D, lam.shape[1]), dtype=np.float64)
+    for n in range(lam.shape[1]):  # one exponential at a time: [L, D] temporaries only
+        w = np.power(np.repeat(lam[:, n], group)[None, :], e[:, None])  # [L, D]
+        out[:, :, n] = np.einsum("bld,ld->bd", u, w)
+    return out
+
+
 def li_conv(q, k, v, R, lam, group: int = 1) -> np.ndarray:
     """Hyena-LI inner operator: ``gated_conv`` with the filter of ``li_filter`` as long as the sequence."""
     return gated_conv(q, k, v, li_filter(R, lam, int(q.shape[1])), group=group)

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     hyena_featurize_fwd,
     hyena_li_fwd,
     hyena_li_fwd_static,
+    hyena_li_fwd_carry,
     hyena_mr_bwd,
     hyena_mr_fwd,
     hyena_mr_fwd_shard,

@@ -52,6 +52,9 @@ def lib() -> ctypes.CDLL:
         L.hyena_bwd_workspace_bytes.restype = i64
         L.hyena_li_fwd.argtypes = [vp] * 7 + [i64, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_li_fwd_static.argtypes = [vp] * 6 + [i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_li_fwd_carry.argtypes = [vp] * 9 + [i64, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_li_state_bytes.argtypes = [i64, i64]
+        L.hyena_li_state_bytes.restype = i64
         L.hyena_li_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_li_workspace_bytes.restype = i64
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
@@ -59,7 +62,7 @@ def lib() -> ctypes.CDLL:
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_se_fwd_shard", "hyena_mr_fwd_shard", "hyena_featurize_fwd",
                      "hyena_featurize3_fwd",
-                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_li_fwd_static",
+                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_li_fwd_static", "hyena_li_fwd_carry",
                      "hyena_stream_copy", "hyena_stream_gate", "hyena_set_option"):
             getattr(L, name).restype = ci
         L.hyena_status_string.argtypes = [ci]
@@ -421,6 +424,45 @@ def hyena_li_fwd(q, k, v, R, lam, group: int = 16, out=None, workspace=None, str
     """y = q * (h conv (k * v)) with h[g, j] = sum_n R[g, n] lam[g, n]^j; see ``hyena_li_fwd`` in hyena.h."""
     with torch.cuda.device(q.device):
         return plan_li(q, k, v, R, lam, group, out, workspace, stream)()
+
+
+def hyena_li_fwd_carry(q, k, v, R, lam, group: int = 16, state_in=None, want_state: bool = True, out=None,
+                       stream=None):
+    """One stretch of a longer sequence: returns (y, state_out); ``state_in`` is the state the previous stretch
+    returned (None at the start of a sequence); see ``hyena_li_fwd_carry`` in hyena.h."""
+    _check_act("q", q)
+    _check_act("k", k, q)
+    _check_act("v", v, q)
+    order = _check_filter("R", R, q, group)
+    if _check_filter("lam", lam, q, group) != order:
+        raise ValueError("R and lam must share one [D // group, order] shape")
+    y = torch.empty_like(q) if out is None else out
+    _check_act("out", y, q)
+    B, L, D = q.shape
+    code = _dtype_code(q)
+    nstate = int(lib().hyena_li_state_bytes(B, D))
+    if nstate < 0:
+        raise ValueError("D must be a multiple of 16")
+    if state_in is not None and (state_in.dtype != torch.float32 or state_in.numel() * 4 != nstate or
+                                 not state_in.is_contiguous() or state_in.device != q.device):
+        raise ValueError("state_in must be the float32 state a previous call returned")
+    state_out = torch.empty(nstate // 4, dtype=torch.float32, device=q.device) if want_state else None
+    need = int(lib().hyena_li_workspace_bytes(B, L, D, order, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid Hyena-LI problem")
+    workspace = torch.empty(need, dtype=torch.uint8, device=q.device) if need > 0 else None
+    c = ctypes
+    with torch.cuda.device(q.device):
+        rc = lib().hyena_li_fwd_carry(
+            *(c.c_void_p(t.data_ptr()) for t in (q, k, v, R, lam, y)),
+            c.c_void_p(state_in.data_ptr() if state_in is not None else None),
+            c.c_void_p(state_out.data_ptr() if state_out is not None else None),
+            c.c_void_p(workspace.data_ptr() if workspace is not None else None), c.c_int64(need), c.c_int64(B),
+            c.c_int64(L), c.c_int64(D), c.c_int32(order), c.c_int32(int(group)), c.c_int(code),
+            c.c_void_p(_stream(q, stream)))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_li_fwd_carry")
+    return y, state_out
 
 
 def hyena_li_fwd_static(q, k, v, R, lam, group: int = 16, out=None, stream=None) -> torch.Tensor:

@@ -372,6 +372,36 @@ hy_status hyena_li_fwd(const void* q, const void* k, const void* v, const float*
     return launch_li_direct(p, s, st);
 }
 
+hy_status hyena_li_fwd_carry(const void* q, const void* k, const void* v, const float* R, const float* lambda, void* y,
+                             const float* state_in, float* state_out, void* workspace, int64_t workspace_bytes,
+                             int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype,
+                             void* hip_stream) {
+    TuningSnapshot snap;
+    hy_status rc = li_validate(q, k, v, R, lambda, y, B, L, D, order, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (workspace_bytes < 0) return HY_ERR_SHAPE;
+    if ((state_in && !aligned16(state_in)) || (state_out && !aligned16(state_out))) return HY_ERR_ALIGN;
+    LiPtrs p{q, k, v, R, lambda, y, state_in, state_out};
+    LiShape s{B, L, D, order, group, static_cast<hy_dtype>(dtype)};
+    // states exist in the matrix-core scan only; an empty call would have to copy state_in to state_out
+    if (!li_mfma_supported(s) || empty(B, L, D)) return HY_ERR_UNSUPPORTED;
+    if (state_out && L % 32 != 0) return HY_ERR_UNSUPPORTED;
+    const int64_t bytes = B * L * D * 2;
+    const int64_t nf = filter_bytes(D, group, order);
+    const int64_t sb = B * D * 64;  // bytes of a state: B * (D / 16) records of 256 floats
+    const Range rd[6] = {{q, bytes}, {k, bytes}, {v, bytes}, {R, nf}, {lambda, nf}, {state_in, state_in ? sb : 0}};
+    const Range wr[2] = {{y, bytes}, {state_out, state_out ? sb : 0}};
+    rc = check_disjoint(rd, 6, wr, 2);
+    if (rc != HY_OK) return rc;
+    const Range others[8] = {{q, bytes}, {k, bytes}, {v, bytes}, {y, bytes}, {R, nf}, {lambda, nf},
+                             {state_in, state_in ? sb : 0}, {state_out, state_out ? sb : 0}};
+    rc = check_workspace(workspace, workspace_bytes, li_workspace_bytes(s), others, 8);
+    if (rc != HY_OK) return rc;
+    return launch_li_mfma(p, s, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int64_t hyena_li_state_bytes(int64_t B, int64_t D) { return (B < 0 || D < 0 || D % 16 != 0) ? -1 : B * D * 64; }
+
 hy_status hyena_li_fwd_static(const void* q, const void* k, const void* v, const float* R, const float* lambda,
                               void* y, int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype,
                               void* hip_stream) {

@@ -87,6 +87,11 @@ struct LiPtrs {
     const float* R;
     const float* lam;
     void* y;
+    // optional (matrix-core scan only): the running sums at the step before the call's first step, and where to
+    // leave them after its last step; fp32 [B][D/16][64][4], element [b][g][16 lq + li][r] = sum of exponential
+    // n = 4 lq + r of channel 16 g + li
+    const float* state_in = nullptr;
+    float* state_out = nullptr;
 };
 
 struct LiShape {

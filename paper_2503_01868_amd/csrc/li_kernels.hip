@@ -35,6 +35,8 @@ struct LiArgs {
     const float* lam;
     uint16_t* y;
     float* ws;              // [B][tiles_per_seq - 1][D / 16][64 lanes][4] end-of-tile states
+    const float* s_in;      // [B][D / 16][64 lanes][4] running sums before the first step (nullptr: zero)
+    float* s_out;           // same layout: running sums after the last step (nullptr: not wanted)
     int64_t L, D;
     int32_t order, group;
     int32_t rows;           // time steps per workgroup, multiple of 32
@@ -128,6 +130,10 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
     const int64_t ws_wave = ((c0 / 16) * 64 + lane) * 4;  // this lane's 4 floats inside one (b, tile) record set
     const int64_t ws_tile = (D / 16) * 256;               // floats per (b, tile)
     if constexpr (!kStateOnly) {
+        if (a.s_in) {  // a call that continues a sequence: what the steps before it left behind decays like any state
+            const float4 c4 = *reinterpret_cast<const float4*>(a.s_in + b * ws_tile + ws_wave);
+            s = f32x4_t{c4.x, c4.y, c4.z, c4.w};
+        }
         float lam_rows[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) lam_rows[r] = powi(ls[w][4 * lq + r], a.rows);
@@ -326,6 +332,8 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
             __syncthreads();
             gate_store(nchunks - 1, qpre[kPrefetch - 1]);
         }
+        if (a.s_out && tile == a.tiles_per_seq - 1)  // (the launcher admits this only for L % 32 == 0: no padded rows)
+            *reinterpret_cast<float4*>(a.s_out + b * ws_tile + ws_wave) = make_float4(s[0], s[1], s[2], s[3]);
     } else {
         float* wp = a.ws + (b * (a.tiles_per_seq - 1) + tile) * ws_tile + ws_wave;
         *reinterpret_cast<float4*>(wp) = make_float4(s[0], s[1], s[2], s[3]);
@@ -416,6 +424,8 @@ hy_status launch_li_nw(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t 
     a.lam = p.lam;
     a.y = static_cast<uint16_t*>(p.y);
     a.ws = static_cast<float*>(ws);
+    a.s_in = p.state_in;
+    a.s_out = p.state_out;
     a.L = s.L;
     a.D = s.D;
     a.order = s.order;
@@ -450,6 +460,8 @@ int64_t li_workspace_bytes(const LiShape& s) {
 
 hy_status launch_li_mfma(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st) {
     if (!li_mfma_supported(s)) return HY_ERR_UNSUPPORTED;
+    // a last chunk with rows past the end would carry them into the state it leaves behind
+    if (p.state_out && s.L % kChunk != 0) return HY_ERR_UNSUPPORTED;
     switch (li_waves(s)) {
         case 16: return launch_li_nw<16>(p, s, ws, st);
         case 8: return launch_li_nw<8>(p, s, ws, st);

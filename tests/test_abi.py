@@ -274,3 +274,40 @@ def test_options_are_snapshotted_per_call_and_safe_to_set_from_other_threads():
         t.join()
         lib.hyena_set_option(b"mr_rows", 0)
     assert seen <= {a, b}
+
+
+@pytest.mark.parametrize("entry", ["hyena_se_fwd_shard", "hyena_mr_fwd_shard"])
+def test_shard_entry_points_reject_bad_layouts(entry):
+    lib = binding.lib()
+
+    def call(q=P[0], k=P[1], v=P[2], h=P[3], y=P[4], B=2, L=8, D=16, lh=3, group=1, dtype=1, skv=10 * 16, sqy=8 * 16,
+             hist=2):
+        return getattr(lib, entry)(q, k, v, h, y, B, L, D, lh, group, dtype, skv, sqy, hist, None)
+
+    assert call(hist=-1) == 2 and call(skv=-16) == 2 and call(sqy=-16) == 2
+    assert call(skv=9 * 16) == 2          # k, v stride shorter than history + L rows
+    assert call(sqy=7 * 16) == 2          # q, y stride shorter than L rows
+    assert call(skv=10 * 16 + 4) == 4     # batch items of bf16 rows must start on 16-byte boundaries
+    assert call(q=None) == 1 and call(L=-1) == 2 and call(dtype=9) == 3
+    # overlap is judged on what is really touched: y inside the history rows in front of k
+    assert call(y=P[1] - 2 * 16 * 2) == 4
+    # and across the batch stride: y between k's two batch items is inside k's span
+    assert call(y=P[1] + 8 * 16 * 2, skv=64 * 16) == 4
+    assert call(B=0) == 0 and call(L=0) == 0   # empty problems: nothing to do, nothing launched
+    assert call(B=1, skv=0, sqy=0, L=0) == 0   # strides are ignored for a single batch item
+
+
+def test_long_implicit_carry_entry_point_rejects_bad_arguments():
+    lib = binding.lib()
+
+    def call(q=P[0], k=P[1], v=P[2], R=P[3], lam=P[4], y=P[5], s_in=P[6], s_out=P[7], ws=P[8], ws_bytes=1 << 20, B=1,
+             L=64, D=64, order=4, group=16, dtype=1):
+        return lib.hyena_li_fwd_carry(q, k, v, R, lam, y, s_in, s_out, ws, ws_bytes, B, L, D, order, group, dtype, None)
+
+    assert call(q=None) == 1 and call(L=-1) == 2 and call(dtype=7) == 3
+    assert call(s_in=P[6] + 4) == 4 and call(s_out=P[7] + 8) == 4      # states are 16-byte aligned
+    assert call(s_out=P[5]) == 4 and call(s_in=P[7]) == 4              # and disjoint from y and from each other
+    assert call(L=40) == 5                                             # a state after a ragged last chunk
+    assert call(dtype=0) == 5 and call(group=8) == 5 and call(order=17) == 5 and call(D=48, group=16) == 5
+    assert call(L=0) == 5                                              # an empty stretch has no state of its own
+    assert lib.hyena_li_state_bytes(2, 64) == 2 * 64 * 64 and lib.hyena_li_state_bytes(1, 24) == -1

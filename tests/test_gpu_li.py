@@ -259,3 +259,56 @@ def test_long_sequence_config_all_outputs():
     assert n == 536870912 and err <= TOL["bf16"]
     del y
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ a sequence handed on in stretches
+def _state_as_oracle(state, B, D, order):
+    """[B][D/16][lq 4][li 16][r 4] floats -> [B, D, order]: element (b, 16 g + li, 4 lq + r)."""
+    s = state.float().cpu().numpy().astype(np.float64).reshape(B, D // 16, 4, 16, 4)
+    return s.transpose(0, 1, 3, 2, 4).reshape(B, D, 16)[:, :, :order]
+
+
+@pytest.mark.parametrize("case", [
+    # B, L, D, order, group, cuts, mr_rows
+    (2, 1024, 128, 16, 16, (512,), 0),
+    (1, 2048, 256, 7, 32, (256, 1280), 128),       # stretches of several tiles each
+    (3, 960, 64, 16, 16, (32, 64, 480), 32),       # one-chunk stretches and one-chunk tiles
+    (1, 4096, 256, 16, 16, (1024, 2048, 3072), 0),
+])
+def test_sequence_in_stretches_with_carried_state_equals_the_whole_sequence(case):
+    """hyena_li_fwd_carry: y of every stretch against the oracle on the whole sequence, the state handed on after
+    every stretch against the definition of the running sums, and the chained result against one hyena_li_fwd call."""
+    B, L, D, order, group, cuts, rows = case
+    say("li carry B=%d L=%d D=%d order=%d group=%d cuts=%s rows=%d" % case)
+    binding.set_option("mr_rows", rows)
+    rng = np.random.Generator(np.random.PCG64(600 + L))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3))
+    R, lam = synth.li_params(rng, D // group, order)
+    dq, dk, dv, dR, dl = dev(q), dev(k), dev(v), dev(R), dev(lam)
+    edges = [0] + list(cuts) + [L]
+    state, parts = None, []
+    for t0, t1 in zip(edges[:-1], edges[1:]):
+        y, state = binding.hyena_li_fwd_carry(dq[:, t0:t1].contiguous(), dk[:, t0:t1].contiguous(),
+                                              dv[:, t0:t1].contiguous(), dR, dl, group, state_in=state)
+        parts.append(y)
+        want = oracle.li_state(k[:, :t1], v[:, :t1], lam, group=group)
+        got = _state_as_oracle(state, B, D, order)
+        assert np.isfinite(got).all() and oracle.rel_err(got, want) <= TOL["bf16"], (t1, oracle.rel_err(got, want))
+    y_cat = torch.cat(parts, dim=1)
+    ref = oracle.li_recurrent(q, k, v, R, lam, group=group)
+    assert oracle.rel_err(host(y_cat), ref) <= TOL["bf16"]
+    whole = binding.hyena_li_fwd(dq, dk, dv, dR, dl, group)
+    assert oracle.rel_err(host(y_cat), host(whole)) <= TOL["bf16"]
+
+
+def test_carry_without_states_is_the_plain_call_and_bad_requests_are_refused():
+    B, L, D, order, group = 2, 640, 128, 16, 16
+    rng = np.random.Generator(np.random.PCG64(611))
+    q, k, v = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(3))
+    R, lam = (dev(x) for x in synth.li_params(rng, D // group, order))
+    y, none = binding.hyena_li_fwd_carry(q, k, v, R, lam, group, want_state=False)
+    assert none is None and torch.equal(y, binding.hyena_li_fwd(q, k, v, R, lam, group))
+    with pytest.raises(binding.HyenaError):   # a state after a length that is no multiple of 32
+        binding.hyena_li_fwd_carry(q[:, :100].contiguous(), k[:, :100].contiguous(), v[:, :100].contiguous(), R, lam, group)
+    with pytest.raises(binding.HyenaError):   # the general kernel keeps no such state
+        binding.hyena_li_fwd_carry(q.float(), k.float(), v.float(), R, lam, group)

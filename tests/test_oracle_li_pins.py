@@ -206,3 +206,46 @@ def test_recurrent_form_against_scipy_and_closed_forms():
     y = oracle.li_recurrent(np.ones_like(imp), np.ones_like(imp), imp, np.array([[2.0]]), np.array([[0.97]]))
     assert y[0, 199, 0] == pytest.approx(2.0 * 0.97 ** 199, rel=1e-12)
     assert np.all(y[1] == 0.0)
+
+
+# ------------------------------------------------------------------ the state a cut sequence hands on (oracle.li_state)
+def test_end_state_reproduces_the_last_output_and_the_continuation():
+    """Three things the running sums must satisfy, none of which uses their own formula: (1) weighted by the
+    residues they give the last output of the definition; (2) they obey the first-order recursion in L (SciPy's
+    recursive filter evaluated at its last step); (3) a sequence continued from them equals the uncut sequence:
+    y[t >= L0] = q[t] * (sum_n R_n lam_n^(t - L0 + 1) s_n  +  the definition on the steps from L0 on)."""
+    rng = rng_for(70)
+    B, L, D, group, d = 2, 120, 6, 2, 3
+    q, k, v = (rng.standard_normal((B, L, D)) for _ in range(3))
+    R = rng.standard_normal((D // group, d))
+    lam = rng.uniform(-0.95, 0.95, (D // group, d))
+    s = oracle.li_state(k, v, lam, group=group)
+    assert s.shape == (B, D, d)
+    Rc, lc = np.repeat(R, group, axis=0), np.repeat(lam, group, axis=0)  # per channel
+    one = np.ones_like(q)
+    assert np.allclose((s * Rc[None]).sum(-1), oracle.li_conv(one, k, v, R, lam, group=group)[:, -1, :], rtol=1e-12, atol=1e-12)
+    u = k * v
+    for c in range(D):
+        for n in range(d):
+            rec = scipy.signal.lfilter([1.0], [1.0, -lc[c, n]], u[:, :, c], axis=1)[:, -1]
+            assert np.allclose(s[:, c, n], rec, rtol=1e-11, atol=1e-11)
+    L0 = 70
+    s0 = oracle.li_state(k[:, :L0], v[:, :L0], lam, group=group)
+    tail = oracle.li_conv(q[:, L0:], k[:, L0:], v[:, L0:], R, lam, group=group)
+    j = np.arange(1, L - L0 + 1)
+    carry = np.einsum("bcn,cnj->bjc", s0, Rc[:, :, None] * np.power(lc[:, :, None], j[None, None, :]))
+    whole = oracle.li_conv(q, k, v, R, lam, group=group)
+    assert np.allclose(tail + q[:, L0:] * carry, whole[:, L0:], rtol=1e-11, atol=1e-11)
+
+
+def test_end_state_closed_forms_and_stored_bits():
+    import torch
+
+    one = np.ones((1, 40, 2))
+    s = oracle.li_state(one, one, np.array([[0.5, 1.0, 0.0]]), group=2)
+    assert np.allclose(s[0, 0], [(1 - 0.5 ** 40) / 0.5, 40.0, 1.0], rtol=1e-13) and np.array_equal(s[0, 0], s[0, 1])
+    rng = rng_for(71)
+    k, v = (torch.from_numpy(rng.standard_normal((1, 30, 4)).astype(np.float32)).bfloat16() for _ in range(2))
+    lam = rng.uniform(0, 1, (4, 2)).astype(np.float32)
+    want = oracle.li_state(k.float().numpy().astype(np.float64), v.float().numpy().astype(np.float64), lam, group=1)
+    assert np.array_equal(oracle.li_state(k, v, lam, group=1), want)
