@@ -264,6 +264,36 @@ hy_status hyena_mr_bwd(const void *dy, const void *q, const void *k, const void 
 int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype);
 
 /*
+ * One rank's share of a sequence-sharded backward call (Sec. 4, point-to-point scheme; App. A.4).  Same
+ * gradients as hyena_se_bwd / hyena_mr_bwd on the shard's L steps, with the neighbours' steps where the chain
+ * rule reaches across the cuts: dq needs k and v of the `history` rows in front of row 0 (as the forward shard
+ * call does), dk and dv need dy and q of the `future` rows behind row L - 1 (device memory directly after the
+ * shard's rows of dy and q: the right neighbour's first rows); rows beyond those are zero.  history = 0 /
+ * future = 0 mark the first / last shard of a sequence; interior shards pass lh - 1 for both.
+ * dh receives THIS shard's share of the filter gradient: the shares of all shards of a sequence add up to the
+ * gradient of the unsharded call (products that straddle a cut are counted by exactly one of the two shards;
+ * which one depends on the kernel, the same for every shard of a given problem shape and dtype).
+ * Layout: row t of batch item b is at element offset b * stride + t * D from the pointer, with
+ * batch_stride_kv for k and v (>= (L + history) * D), batch_stride_gq for dy and q (>= (L + future) * D) and
+ * batch_stride_out for dq, dk, dv (>= L * D); ignored when B = 1; multiples of 16 bytes (HY_ERR_ALIGN), too
+ * small: HY_ERR_SHAPE.  The overlap rules apply to the memory really touched.
+ * workspace: hyena_bwd_shard_workspace_bytes(...) bytes (the shard calls take the short-filter stencil, the
+ * one-pass grouped matrix-core kernel or the general kernels, never the paths that do not know shards, so
+ * their size differs from hyena_bwd_workspace_bytes).
+ */
+hy_status hyena_se_bwd_shard(const void *dy, const void *q, const void *k, const void *v, const float *h, void *dq,
+                             void *dk, void *dv, float *dh, void *workspace, int64_t workspace_bytes, int64_t B,
+                             int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
+                             int64_t batch_stride_kv, int64_t batch_stride_gq, int64_t batch_stride_out,
+                             int32_t history, int32_t future, void *hip_stream);
+hy_status hyena_mr_bwd_shard(const void *dy, const void *q, const void *k, const void *v, const float *h, void *dq,
+                             void *dk, void *dv, float *dh, void *workspace, int64_t workspace_bytes, int64_t B,
+                             int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype,
+                             int64_t batch_stride_kv, int64_t batch_stride_gq, int64_t batch_stride_out,
+                             int32_t history, int32_t future, void *hip_stream);
+int64_t hyena_bwd_shard_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype);
+
+/*
  * Plain device-to-device streaming copy of `bytes` bytes (a multiple of 16) with the same launch
  * shape as the streaming kernels.  Used to measure the practical HBM ceiling and to calibrate
  * hardware byte counters; not part of the operator.

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     HyenaError,
     Plan,
     plan_bwd,
+    plan_bwd_shard,
     plan_chain,
     plan_featurize3,
     plan_gated,
@@ -19,9 +20,11 @@ from .binding import (  # noqa: F401
     hyena_li_fwd_static,
     hyena_li_fwd_carry,
     hyena_mr_bwd,
+    hyena_mr_bwd_shard,
     hyena_mr_fwd,
     hyena_mr_fwd_shard,
     hyena_se_bwd,
+    hyena_se_bwd_shard,
     hyena_se_fwd,
     hyena_se_fwd_shard,
     hyena_stream_copy,

@@ -50,6 +50,11 @@ def lib() -> ctypes.CDLL:
         L.hyena_mr_bwd.argtypes = bwd_args
         L.hyena_bwd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_bwd_workspace_bytes.restype = i64
+        bwd_shard_args = [vp] * 10 + [i64, i64, i64, i64, i32, i32, ci, i64, i64, i64, i32, i32, vp]
+        L.hyena_se_bwd_shard.argtypes = bwd_shard_args
+        L.hyena_mr_bwd_shard.argtypes = bwd_shard_args
+        L.hyena_bwd_shard_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
+        L.hyena_bwd_shard_workspace_bytes.restype = i64
         L.hyena_li_fwd.argtypes = [vp] * 7 + [i64, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_li_fwd_static.argtypes = [vp] * 6 + [i64, i64, i64, i32, i32, ci, vp]
         L.hyena_li_fwd_carry.argtypes = [vp] * 9 + [i64, i64, i64, i64, i32, i32, ci, vp]
@@ -62,7 +67,8 @@ def lib() -> ctypes.CDLL:
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_se_fwd_shard", "hyena_mr_fwd_shard", "hyena_featurize_fwd",
                      "hyena_featurize3_fwd",
-                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_li_fwd", "hyena_li_fwd_static", "hyena_li_fwd_carry",
+                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_se_bwd_shard", "hyena_mr_bwd_shard", "hyena_li_fwd",
+                     "hyena_li_fwd_static", "hyena_li_fwd_carry",
                      "hyena_stream_copy", "hyena_stream_gate", "hyena_set_option"):
             getattr(L, name).restype = ci
         L.hyena_status_string.argtypes = [ci]
@@ -356,6 +362,53 @@ def plan_bwd(entry: str, dy, q, k, v, h, group: int, out=None, workspace=None, s
                                                   c.c_int64(D), c.c_int32(lh), c.c_int32(int(group)), c.c_int(code),
                                                   c.c_void_p(_stream(dy, stream)))
     return Plan(getattr(lib(), entry), args, entry, (dy, q, k, v, h, workspace) + tuple(out), tuple(out))
+
+
+def plan_bwd_shard(entry: str, dy, q, k, v, h, group: int, history: int, future: int, out=None, stream=None) -> Plan:
+    """Marshal one ``hyena_se_bwd_shard`` / ``hyena_mr_bwd_shard`` call; dy, q, k, v are [B, L, D] windows with
+    contiguous rows (k, v with ``history`` valid rows in front of them in memory, dy, q with ``future`` valid rows
+    behind them); ``out`` = (dq, dk, dv, dh), the first three windows too, dh this shard's share."""
+    if entry not in ("hyena_se_bwd_shard", "hyena_mr_bwd_shard"):
+        raise ValueError("entry must be hyena_se_bwd_shard or hyena_mr_bwd_shard")
+    _check_rows("dy", dy)
+    _check_rows("q", q, dy)
+    _check_rows("k", k, dy)
+    _check_rows("v", v, dy)
+    lh = _check_filter("h", h, dy, group)
+    B, L, D = dy.shape
+    code = _dtype_code(dy)
+    need = int(lib().hyena_bwd_shard_workspace_bytes(B, L, D, lh, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid backward problem")
+    workspace = torch.empty(need, dtype=torch.uint8, device=dy.device) if need > 0 else None
+    if out is None:
+        out = tuple(torch.empty_like(dy, memory_format=torch.contiguous_format) for _ in range(3)) + (torch.empty_like(h),)
+    for name, o in zip(("dq", "dk", "dv"), out[:3]):
+        _check_rows(name, o, dy)
+    _check_filter("dh", out[3], dy, group)
+    if B > 1 and (k.stride(0) != v.stride(0) or dy.stride(0) != q.stride(0) or
+                  out[0].stride(0) != out[1].stride(0) or out[0].stride(0) != out[2].stride(0)):
+        raise ValueError("k, v / dy, q / dq, dk, dv must each share a batch stride")
+    c = ctypes
+    ptrs = [t.data_ptr() for t in (dy, q, k, v, h) + tuple(out)]
+    args = tuple(c.c_void_p(p) for p in ptrs) + (
+        c.c_void_p(workspace.data_ptr() if need > 0 else None), c.c_int64(need), c.c_int64(B), c.c_int64(L),
+        c.c_int64(D), c.c_int32(lh), c.c_int32(int(group)), c.c_int(code), c.c_int64(k.stride(0)),
+        c.c_int64(dy.stride(0)), c.c_int64(out[0].stride(0)), c.c_int32(int(history)), c.c_int32(int(future)),
+        c.c_void_p(_stream(dy, stream)))
+    return Plan(getattr(lib(), entry), args, entry, (dy, q, k, v, h, workspace) + tuple(out), tuple(out))
+
+
+def hyena_se_bwd_shard(dy, q, k, v, h, group: int = 1, history: int = 0, future: int = 0, out=None, stream=None):
+    """One sequence shard of ``hyena_se_bwd``: (dq, dk, dv, this shard's share of dh)."""
+    with torch.cuda.device(dy.device):
+        return plan_bwd_shard("hyena_se_bwd_shard", dy, q, k, v, h, group, history, future, out, stream)()
+
+
+def hyena_mr_bwd_shard(dy, q, k, v, h, group: int = 1, history: int = 0, future: int = 0, out=None, stream=None):
+    """One sequence shard of ``hyena_mr_bwd``: (dq, dk, dv, this shard's share of dh)."""
+    with torch.cuda.device(dy.device):
+        return plan_bwd_shard("hyena_mr_bwd_shard", dy, q, k, v, h, group, history, future, out, stream)()
 
 
 def _bwd(entry: str, dy, q, k, v, h, group, workspace, stream):

@@ -438,9 +438,29 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
     return 0;
 }
 
+int64_t hyena_bwd_shard_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
+    TuningSnapshot snap;
+    if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1 || D % group != 0) return -1;
+    if (dtype != HY_F32 && dtype != HY_BF16) return -1;
+    if (empty(B, L, D)) return 0;
+    BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
+    s.shard_call = true;
+    if (bwd_stencil_supported(s)) return bwd_stencil_workspace_bytes(s);
+    if (mr_bwd_supported(s)) return mr_bwd_workspace_bytes(s);
+    return 0;
+}
+
+// Layout of a sequence-shard backward call (all zero: the plain dense call).
+struct BwdShard {
+    int64_t stride_kv = 0, stride_gq = 0, stride_out = 0;
+    int32_t history = 0, future = 0;
+    bool on = false;
+};
+
 static hy_status gated_bwd(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,
                            void* dk, void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B,
-                           int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
+                           int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, void* hip_stream,
+                           const BwdShard& sh = BwdShard()) {
     TuningSnapshot snap;
     const void* ins[4] = {dy, q, k, v};
     void* outs[3] = {dq, dk, dv};
@@ -450,9 +470,39 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
     if (workspace_bytes < 0) return HY_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int64_t nh = filter_bytes(D, group, lh);
-    const int64_t bytes = B * L * D * (dtype == HY_F32 ? 4 : 2);
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    int64_t bytes = B * L * D * esz;
+    // what the call really touches: [front, front + span) around each pointer
+    int64_t back_kv = 0, span_kv = bytes, span_gq = bytes, span_out = bytes;
+    if (sh.on) {
+        if (sh.history < 0 || sh.future < 0 || sh.stride_kv < 0 || sh.stride_gq < 0 || sh.stride_out < 0) return HY_ERR_SHAPE;
+        if (!empty(B, L, D)) {
+            const int64_t lim = (INT64_MAX / esz - L * D) / D;
+            if (sh.history > lim || sh.future > lim) return HY_ERR_SHAPE;
+            const int64_t item_kv = (L + sh.history) * D, item_gq = (L + sh.future) * D, item_out = L * D;
+            if (B > 1) {
+                if (sh.stride_kv < item_kv || sh.stride_gq < item_gq || sh.stride_out < item_out) return HY_ERR_SHAPE;
+                if ((sh.stride_kv * esz) % 16 != 0 || (sh.stride_gq * esz) % 16 != 0 || (sh.stride_out * esz) % 16 != 0)
+                    return HY_ERR_ALIGN;
+                const int64_t cap = (INT64_MAX / esz - item_kv - item_gq) / (B - 1);
+                if (sh.stride_kv > cap || sh.stride_gq > cap || sh.stride_out > cap) return HY_ERR_SHAPE;
+            }
+            back_kv = (int64_t)sh.history * D * esz;
+            span_kv = ((B - 1) * (B > 1 ? sh.stride_kv : 0) + item_kv) * esz;
+            span_gq = ((B - 1) * (B > 1 ? sh.stride_gq : 0) + item_gq) * esz;
+            span_out = ((B - 1) * (B > 1 ? sh.stride_out : 0) + item_out) * esz;
+            const Range rd[5] = {{dy, span_gq}, {q, span_gq}, {static_cast<const char*>(k) - back_kv, span_kv},
+                                 {static_cast<const char*>(v) - back_kv, span_kv}, {h, nh}};
+            const Range wr[3] = {{dq, span_out}, {dk, span_out}, {dv, span_out}};
+            rc = check_disjoint(rd, 5, wr, 3);
+            if (rc != HY_OK) return rc;
+        }
+    }
+    const void* k_front = static_cast<const char*>(k) - back_kv;
+    const void* v_front = static_cast<const char*>(v) - back_kv;
     // dh is written: disjoint from the filter and from every activation, read or written
-    const Range reads[8] = {{h, nh}, {dy, bytes}, {q, bytes}, {k, bytes}, {v, bytes}, {dq, bytes}, {dk, bytes}, {dv, bytes}};
+    const Range reads[8] = {{h, nh}, {dy, span_gq}, {q, span_gq}, {k_front, span_kv}, {v_front, span_kv},
+                            {dq, span_out}, {dk, span_out}, {dv, span_out}};
     const Range dh_range{dh, nh};
     if (check_disjoint(reads, 8, &dh_range, 1) != HY_OK) return HY_ERR_ALIGN;
     if (empty(B, L, D)) {
@@ -461,6 +511,14 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
     }
     BwdPtrs p{dy, q, k, v, h, dq, dk, dv, dh};
     BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
+    if (sh.on) {
+        s.bstride_kv = B > 1 ? sh.stride_kv : 0;
+        s.bstride_gq = B > 1 ? sh.stride_gq : 0;
+        s.bstride_out = B > 1 ? sh.stride_out : 0;
+        s.history = sh.history;
+        s.future = sh.future;
+        s.shard_call = true;
+    }
     const bool stencil = bwd_stencil_supported(s);
     const bool mfma = !stencil && mr_bwd_supported(s);
     const bool cp4 = !stencil && !mfma && cp4_bwd_supported(s);
@@ -469,8 +527,8 @@ static hy_status gated_bwd(const void* dy, const void* q, const void* k, const v
         const int64_t need = walk ? bwd_walk_workspace_bytes(s)
                                   : (stencil ? bwd_stencil_workspace_bytes(s)
                                              : (mfma ? mr_bwd_workspace_bytes(s) : cp4_bwd_workspace_bytes(s)));
-        const Range others[9] = {{dy, bytes}, {q, bytes}, {k, bytes}, {v, bytes}, {dq, bytes},
-                                 {dk, bytes}, {dv, bytes}, {h, nh}, {dh, nh}};
+        const Range others[9] = {{dy, span_gq}, {q, span_gq}, {k_front, span_kv}, {v_front, span_kv}, {dq, span_out},
+                                 {dk, span_out}, {dv, span_out}, {h, nh}, {dh, nh}};
         rc = check_workspace(workspace, workspace_bytes, need, others, 9);
         if (rc != HY_OK) return rc;
         if (walk) return launch_bwd_walk(p, s, workspace, st);
@@ -491,6 +549,26 @@ hy_status hyena_mr_bwd(const void* dy, const void* q, const void* k, const void*
                        void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D,
                        int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     return gated_bwd(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype, hip_stream);
+}
+
+hy_status hyena_se_bwd_shard(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,
+                             void* dk, void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B,
+                             int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, int64_t batch_stride_kv,
+                             int64_t batch_stride_gq, int64_t batch_stride_out, int32_t history, int32_t future,
+                             void* hip_stream) {
+    BwdShard sh;
+    sh.stride_kv = batch_stride_kv; sh.stride_gq = batch_stride_gq; sh.stride_out = batch_stride_out;
+    sh.history = history; sh.future = future; sh.on = true;
+    return gated_bwd(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype, hip_stream, sh);
+}
+
+hy_status hyena_mr_bwd_shard(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,
+                             void* dk, void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B,
+                             int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype, int64_t batch_stride_kv,
+                             int64_t batch_stride_gq, int64_t batch_stride_out, int32_t history, int32_t future,
+                             void* hip_stream) {
+    return hyena_se_bwd_shard(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype,
+                              batch_stride_kv, batch_stride_gq, batch_stride_out, history, future, hip_stream);
 }
 
 hy_status hyena_stream_copy(const void* src, void* dst, int64_t bytes, void* hip_stream) {

@@ -26,6 +26,8 @@ struct BwdStencilArgs {
     BwdPtrs p;
     float* partial;  // [B * tiles_per_seq][D * LH]
     int64_t L, D;
+    int64_t skv, sgq, sout;  // elements between batch items in k, v / dy, q / dq, dk, dv
+    int32_t hist, fut;       // rows of k, v in front of row 0 / of dy, q behind row L - 1 that hold data
     int64_t nvec, nitems;
     int32_t group, rows, tiles_per_seq;
 };
@@ -46,7 +48,7 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
     const int64_t t1 = (t0 + a.rows < a.L) ? t0 + a.rows : a.L;
     const int64_t L = a.L, D = a.D;
     const int64_t c = cv * VEC;
-    const int64_t seq0 = (b * L) * D + c;
+    const int64_t seq0 = b * a.sout + c, seq0kv = b * a.skv + c, seq0gq = b * a.sgq + c;
     const char* dyp = static_cast<const char*>(a.p.dy);
     const char* qp = static_cast<const char*>(a.p.q);
     const char* kp = static_cast<const char*>(a.p.k);
@@ -72,8 +74,8 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
     for (int i = 0; i < LH - 1; ++i) {
         const int64_t t = t0 - (LH - 1) + i;
         float kf[VEC], vf[VEC];
-        if (t >= 0) {
-            const int64_t off = (seq0 + t * D) * T::kBytes;
+        if (t >= -(int64_t)a.hist) {
+            const int64_t off = (seq0kv + t * D) * T::kBytes;
             P::unpack(P::load(kp + off), kf);
             P::unpack(P::load(vp + off), vf);
         } else {
@@ -90,7 +92,8 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
     }
 
     // the walk covers the tile plus the LH-1 steps after it whose g still reaches into the tile
-    const int64_t t_walk = (t1 + (LH - 1) < L) ? t1 + (LH - 1) : L;
+    const int64_t t_stop = L + a.fut;  // dy and q hold data up to here
+    const int64_t t_walk = (t1 + (LH - 1) < t_stop) ? t1 + (LH - 1) : t_stop;
     Raw kr[R], vr[R], qr[R], gr[R];
     auto issue = [&](int64_t t) {
 #pragma unroll
@@ -100,12 +103,13 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
             qr[r] = zero_words<P::kWords>();
             gr[r] = zero_words<P::kWords>();
             if (t + r < t_walk) {
-                const int64_t off = (seq0 + (t + r) * D) * T::kBytes;
+                const int64_t off = (seq0gq + (t + r) * D) * T::kBytes;
                 qr[r] = P::load_nt(qp + off);
                 gr[r] = P::load_nt(dyp + off);
                 if (t + r < t1) {
-                    kr[r] = P::load_nt(kp + off);
-                    vr[r] = P::load_nt(vp + off);
+                    const int64_t offkv = (seq0kv + (t + r) * D) * T::kBytes;
+                    kr[r] = P::load_nt(kp + offkv);
+                    vr[r] = P::load_nt(vp + offkv);
                 }
             }
         }
@@ -247,6 +251,8 @@ constexpr int kRowLanes = 4;
 struct BwdDirectArgs {
     BwdPtrs p;
     int64_t B, L, D;
+    int64_t skv, sgq, sout;  // elements between batch items in k, v / dy, q / dq, dk, dv
+    int32_t hist, fut;       // rows of k, v in front of row 0 / of dy, q behind row L - 1 that hold data
     int32_t lh, group;
 };
 
@@ -267,17 +273,17 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
     const char* qp = static_cast<const char*>(a.p.q);
     const char* kp = static_cast<const char*>(a.p.k);
     const char* vp = static_cast<const char*>(a.p.v);
-    const int64_t seq0 = b * L * a.D + c;
-    auto ld = [&](const char* base, int64_t t) {
+    const int64_t seq0 = b * a.sout + c, seq0kv = b * a.skv + c, seq0gq = b * a.sgq + c;
+    auto ld = [&](const char* base, int64_t s0, int64_t t) {
         float f[1];
-        P::unpack(P::load(base + (seq0 + t * a.D) * T::kBytes), f);
+        P::unpack(P::load(base + (s0 + t * a.D) * T::kBytes), f);
         return f[0];
     };
 
     float tw[kRows], acc[kRows];
     // z[tf + r] = sum_s h[tf + r - s] u[s], s ascending
     int64_t s = tf - (lh - 1);
-    if (s < 0) s = 0;
+    if (s < -(int64_t)a.hist) s = -(int64_t)a.hist;
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
         const int64_t j = tf + r - s;
@@ -285,7 +291,7 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
         acc[r] = 0.0f;
     }
     for (; s <= tl; ++s) {
-        const float u = ld(kp, s) * ld(vp, s);
+        const float u = ld(kp, seq0kv, s) * ld(vp, seq0kv, s);
 #pragma unroll
         for (int r = 0; r < kRows; ++r) acc[r] = __builtin_fmaf(tw[r], u, acc[r]);
 #pragma unroll
@@ -300,7 +306,7 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
     // du[tf + r] = sum_t h[t - tf - r] g[t], t ascending from tf to tl + lh - 1
     int64_t t = tf;
     int64_t t_last = tl + (lh - 1);
-    if (t_last > L - 1) t_last = L - 1;
+    if (t_last > L + a.fut - 1) t_last = L + a.fut - 1;
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
         const int64_t j = t - tf - r;
@@ -308,7 +314,7 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
         acc[r] = 0.0f;
     }
     for (; t <= t_last; ++t) {
-        const float g = ld(dyp, t) * ld(qp, t);
+        const float g = ld(dyp, seq0gq, t) * ld(qp, seq0gq, t);
 #pragma unroll
         for (int r = 0; r < kRows; ++r) acc[r] = __builtin_fmaf(tw[r], g, acc[r]);
         // next source: every tap index grows by one
@@ -321,7 +327,7 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
     for (int r = 0; r < kRows; ++r) {
         if (tf + r <= tl) {
             const int64_t off = (seq0 + (tf + r) * a.D) * T::kBytes;
-            const float kf = ld(kp, tf + r), vf = ld(vp, tf + r), dyf = ld(dyp, tf + r);
+            const float kf = ld(kp, seq0kv, tf + r), vf = ld(vp, seq0kv, tf + r), dyf = ld(dyp, seq0gq, tf + r);
             float o[1];
             o[0] = dyf * zz[r];
             P::store(static_cast<char*>(a.p.dq) + off, P::pack(o));
@@ -352,13 +358,15 @@ __global__ __launch_bounds__(kBlock) void dh_direct_kernel(BwdDirectArgs a) {
         P::unpack(P::load(base + e * T::kBytes), f);
         return f[0];
     };
-    const int64_t span = (L - j) * group;  // (t, cc) pairs per batch item, channel fastest
+    // this call's share: g of its own steps against u up to `hist` steps before them
+    const int64_t t_first = j > a.hist ? j - a.hist : 0;
+    const int64_t span = (L - t_first) * group;  // (t, cc) pairs per batch item, channel fastest
     double s = 0.0;
     for (int64_t b = 0; b < a.B; ++b) {
         for (int64_t i = threadIdx.x; i < span; i += kBlock) {
-            const int64_t t = j + i / group;
+            const int64_t t = t_first + i / group;
             const int64_t c = g * group + i % group;
-            const int64_t at = (b * L + t) * D + c, src = (b * L + (t - j)) * D + c;
+            const int64_t at = b * a.sgq + t * D + c, src = b * a.skv + (t - j) * D + c;
             s = __builtin_fma((double)ld(dyp, at) * (double)ld(qp, at), (double)ld(kp, src) * (double)ld(vp, src), s);
         }
     }
@@ -397,6 +405,11 @@ hy_status launch_stencil_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipSt
     a.partial = static_cast<float*>(ws);
     a.L = s.L;
     a.D = s.D;
+    a.skv = s.stride_kv();
+    a.sgq = s.stride_gq();
+    a.sout = s.stride_out();
+    a.hist = s.history;
+    a.fut = s.future;
     a.group = s.group;
     a.nvec = s.D / VEC;
     a.rows = stencil_rows(s, a.nvec);
@@ -432,6 +445,11 @@ hy_status launch_direct_t(const BwdPtrs& p, const BwdShape& s, hipStream_t st) {
     BwdDirectArgs a;
     a.p = p;
     a.B = s.B; a.L = s.L; a.D = s.D; a.lh = s.lh; a.group = s.group;
+    a.skv = s.stride_kv();
+    a.sgq = s.stride_gq();
+    a.sout = s.stride_out();
+    a.hist = s.history;
+    a.fut = s.future;
     const int64_t gx = (s.D + kChan - 1) / kChan;
     const int64_t gy = (s.L + kRows * kRowLanes - 1) / (kRows * kRowLanes);
     const int64_t G = s.D / s.group;

@@ -44,6 +44,8 @@ struct MrBwdArgs {
     uint16_t* dv;
     float* partial;  // [B * tiles_per_seq][D / 16][lh]: one row per (tile, 16-channel slice)
     int64_t L, D;
+    int64_t skv, sgq, sout;  // elements between batch items in k, v / dy, q / dq, dk, dv
+    int32_t hist, fut;       // rows of k, v in front of row 0 / of dy, q behind row L - 1 that hold data
     int32_t lh, group;
     int32_t rows, tiles_per_seq, ncb;
 };
@@ -82,20 +84,25 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
     // everything below is in reversed time tau = L - 1 - t
     const int64_t t_start = (tile % a.tiles_per_seq) * (int64_t)a.rows;
     const int64_t t_end = (t_start + a.rows < L) ? t_start + a.rows : L;
-    int64_t t_begin = t_start - (int64_t)kChunk * LAG;   // dy, q of the chunks before the tile feed its du
-    if (t_begin < 0) t_begin = 0;
+    // dy, q of the chunks before the tile feed its du; before tau = 0 lie the `fut` rows behind the sequence's end
+    // that hold data (a shard's right halo), down to the first chunk boundary at or below them
+    int64_t t_begin = t_start - (int64_t)kChunk * LAG;
+    const int64_t t_floor = -(((int64_t)a.fut + kChunk - 1) / kChunk) * kChunk;
+    if (t_begin < t_floor) t_begin = t_floor;
+    const int64_t tau_lo = -(int64_t)a.fut;     // smallest reversed step at which dy and q hold data
+    const int64_t tau_hi = L + (int64_t)a.hist;  // k and v hold data below this reversed step
     // k, v of the LAG chunks after the tile feed its z; the walk always runs LAG chunks past the tile, also where
     // the sequence ends first (those chunks then hold zeros and load nothing)
     const int ntot = (int)((t_end - t_begin + kChunk - 1) / kChunk) + LAG;
 
     const int64_t cblock0 = (int64_t)cb * 16 * NW;
     const int64_t c0 = cblock0 + 16 * w;
-    const int64_t seq0 = b * L * D;
+    const int64_t seq0 = b * a.sout, seq0kv = b * a.skv, seq0gq = b * a.sgq;
 
     const int lr = tid / PPR, lp = tid % PPR;
     const int64_t ld_off = cblock0 + 8 * lp;
-    // element offset of reversed step tau for this lane
-    auto row_off = [&](int64_t tau) { return seq0 + (L - 1 - tau) * D + ld_off; };
+    // element offset of reversed step tau for this lane, without the batch item's offset
+    auto row_off = [&](int64_t tau) { return (L - 1 - tau) * D + ld_off; };
     auto chunk_start = [&](int ci) { return t_begin + (int64_t)ci * kChunk; };
     auto in_tile = [&](int ci) {
         const int64_t t0 = chunk_start(ci);
@@ -104,20 +111,21 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
     // loads whose result is never used (chunk indices past the last chunk; k and v before the tile, dy and q after
     // it) all go to one 16-byte location of the tile, the same for every lane of the workgroup: one cache line per
     // wave
-    const int64_t idle_off = seq0 + (L - t_end) * D + cblock0;
+    const int64_t idle_off = (L - t_end) * D + cblock0;
     auto load_g = [&](int ci, Words<4>& yy, Words<4>& qq) {
         const int64_t t0 = chunk_start(ci);
         int64_t tau = t0 + lr;
         tau = tau < t_end ? tau : t_end - 1;
-        const int64_t off = (ci < ntot && t0 < t_end) ? row_off(tau) : idle_off;
+        tau = tau > tau_lo ? tau : tau_lo;  // rows past the data read its last row; their g is zeroed below
+        const int64_t off = seq0gq + ((ci < ntot && t0 < t_end) ? row_off(tau) : idle_off);
         yy = load_words_nt<4>(a.dy + off);
         qq = load_words_nt<4>(a.q + off);
     };
     auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
         const int64_t t0 = chunk_start(ci);
         int64_t tau = t0 + lr;
-        tau = tau < L ? tau : L - 1;
-        const int64_t off = (ci < ntot && t0 >= t_start && t0 < L) ? row_off(tau) : idle_off;
+        tau = tau < tau_hi ? tau : tau_hi - 1;
+        const int64_t off = seq0kv + ((ci < ntot && t0 >= t_start && t0 < tau_hi) ? row_off(tau) : idle_off);
         kk = load_words_nt<4>(a.k + off);
         vv = load_words_nt<4>(a.v + off);
     };
@@ -194,7 +202,7 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
                 o1[e] = du[e] * vf[e];
                 o2[e] = du[e] * kf[e];
             }
-            const int64_t off = row_off(tau);
+            const int64_t off = seq0 + row_off(tau);
             store_words_nt<4>(a.dk + off, Pack<BF16, 8>::pack(o1));
             store_words_nt<4>(a.dv + off, Pack<BF16, 8>::pack(o2));
         }
@@ -213,7 +221,7 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
             Pack<BF16, 8>::unpack(yy, yf);
             float o[8] = {za.x * yf[0], za.y * yf[1], za.z * yf[2], za.w * yf[3],
                           zb.x * yf[4], zb.y * yf[5], zb.z * yf[6], zb.w * yf[7]};
-            store_words_nt<4>(a.dq + row_off(tau), Pack<BF16, 8>::pack(o));
+            store_words_nt<4>(a.dq + seq0 + row_off(tau), Pack<BF16, 8>::pack(o));
         }
     };
 
@@ -234,6 +242,7 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
                 Words<4> gg;
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) gg.w[e2] = pack_bf16x2(a8[2 * e2] * b8[2 * e2], a8[2 * e2 + 1] * b8[2 * e2 + 1]);
+                if (t0 + lr < tau_lo) gg = zero_words<4>();  // past the rows that hold data: zeros
                 gst[ci & 1][st_idx] = make_uint4(gg.w[0], gg.w[1], gg.w[2], gg.w[3]);
                 gring[slot][wr8a] = make_uint2(gg.w[0], gg.w[1]);
                 gring[slot][wr8b] = make_uint2(gg.w[2], gg.w[3]);
@@ -245,7 +254,7 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
                 for (int e2 = 0; e2 < 4; ++e2) uu.w[e2] = pack_bf16x2(a8[2 * e2] * b8[2 * e2], a8[2 * e2 + 1] * b8[2 * e2 + 1]);
                 // z reaches over the end of the tile but not over the end of the sequence; the filter gradient
                 // takes u of the tile only
-                const bool in_seq = t0 + lr < L;
+                const bool in_seq = t0 + lr < tau_hi;
                 const bool in_own = t0 + lr < t_end;
                 utr[ci & 1][st_idx] = in_seq ? make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]) : make_uint4(0u, 0u, 0u, 0u);
                 ust[ci & 1][wr8a] = in_own ? make_uint2(uu.w[0], uu.w[1]) : make_uint2(0u, 0u);
@@ -376,6 +385,11 @@ hy_status launch_nw(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t s
     a.partial = static_cast<float*>(ws);
     a.L = s.L;
     a.D = s.D;
+    a.skv = s.stride_kv();
+    a.sgq = s.stride_gq();
+    a.sout = s.stride_out();
+    a.hist = s.history;
+    a.fut = s.future;
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * NW));

@@ -311,3 +311,25 @@ def test_long_implicit_carry_entry_point_rejects_bad_arguments():
     assert call(dtype=0) == 5 and call(group=8) == 5 and call(order=17) == 5 and call(D=48, group=16) == 5
     assert call(L=0) == 5                                              # an empty stretch has no state of its own
     assert lib.hyena_li_state_bytes(2, 64) == 2 * 64 * 64 and lib.hyena_li_state_bytes(1, 24) == -1
+
+
+@pytest.mark.parametrize("entry", ["hyena_se_bwd_shard", "hyena_mr_bwd_shard"])
+def test_backward_shard_entry_points_reject_bad_layouts(entry):
+    lib = binding.lib()
+    Q = [0x100000 * (i + 1) for i in range(10)]
+
+    def call(dy=Q[0], q=Q[1], k=Q[2], v=Q[3], h=Q[4], dq=Q[5], dk=Q[6], dv=Q[7], dh=Q[8], ws=Q[9], wsb=1 << 20, B=2, L=8,
+             D=16, lh=3, group=1, dtype=1, skv=10 * 16, sgq=10 * 16, sout=8 * 16, hist=2, fut=2):
+        return getattr(lib, entry)(dy, q, k, v, h, dq, dk, dv, dh, ws, wsb, B, L, D, lh, group, dtype, skv, sgq, sout,
+                                   hist, fut, None)
+
+    assert call(hist=-1) == 2 and call(fut=-1) == 2 and call(skv=-16) == 2
+    assert call(skv=9 * 16) == 2 and call(sgq=9 * 16) == 2 and call(sout=7 * 16) == 2   # strides shorter than the rows
+    assert call(sgq=10 * 16 + 4) == 4
+    assert call(dy=None) == 1 and call(L=-1) == 2 and call(dtype=9) == 3 and call(wsb=-1) == 2
+    assert call(dk=Q[2] - 2 * 16 * 2) == 4      # an output inside the history rows in front of k
+    assert call(dq=Q[0] + 8 * 16 * 2) == 4      # an output inside the future rows behind dy
+    assert call(dh=Q[1] + 9 * 16 * 2) == 4      # the filter gradient inside q's future rows
+    assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 256, 7, 1, 1) > 0
+    assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 128, 100, 1, 1) == 0    # ungrouped medium: general kernels
+    assert lib.hyena_bwd_shard_workspace_bytes(1, 64, 30, 3, 4, 1) == -1

@@ -100,3 +100,55 @@ def test_zero_history_is_the_plain_call():
     assert torch.equal(binding.hyena_mr_fwd_shard(q, k, v, h, group, 0), binding.hyena_mr_fwd(q, k, v, h, group))
     hs = dev(synth.short_filter(rng, D, 7))
     assert torch.equal(binding.hyena_se_fwd_shard(q, k, v, hs, 1, 0), binding.hyena_se_fwd(q, k, v, hs, 1))
+
+
+# ------------------------------------------------------------------------------------------------ backward
+def run_bwd_sharded(entry, dy, q, k, v, h, group, cuts, lh):
+    """dq, dk, dv over [B, L, D] and the sum of the shards' filter-gradient shares, one shard call per stretch;
+    every tensor of a shard is a window of the full tensor."""
+    B, L, D = q.shape
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    dh = torch.zeros_like(h, dtype=torch.float64)
+    edges = [0] + list(cuts) + [L]
+    for t0, t1 in zip(edges[:-1], edges[1:]):
+        hist, fut = min(t0, lh - 1), min(L - t1, lh - 1)
+        w = slice(t0, t1)
+        outs = getattr(binding, entry)(dy[:, w], q[:, w], k[:, w], v[:, w], h, group, hist, fut,
+                                       out=(dq[:, w], dk[:, w], dv[:, w], torch.empty_like(h)))
+        dh += outs[3].double()
+    torch.cuda.synchronize()
+    return dq, dk, dv, dh
+
+
+BWD_CASES = [
+    # entry, B, L, D, lh, group, dtype, cuts, options
+    ("hyena_se_bwd_shard", 2, 1000, 256, 7, 1, "bf16", (300, 301, 640), {}),        # stencil; a one-step shard
+    ("hyena_se_bwd_shard", 1, 900, 64, 4, 2, "f32", (3, 500, 898), {}),             # halos shorter than lh - 1
+    ("hyena_se_bwd_shard", 2, 700, 128, 8, 4, "bf16", (350,), {"se_rows": 64}),
+    ("hyena_mr_bwd_shard", 2, 1500, 128, 128, 16, "bf16", (400, 1000), {}),         # one-pass matrix-core kernel
+    ("hyena_mr_bwd_shard", 1, 2000, 64, 128, 16, "bf16", (50, 90, 1024, 1950), {"mr_rows": 256}),  # partial halo chunks
+    ("hyena_mr_bwd_shard", 3, 700, 64, 33, 32, "bf16", (128, 129), {}),
+    ("hyena_mr_bwd_shard", 2, 800, 48, 100, 1, "bf16", (333,), {}),                 # general kernels (ungrouped)
+    ("hyena_mr_bwd_shard", 1, 600, 128, 128, 16, "f32", (200, 400), {}),            # general kernels (fp32)
+    ("hyena_mr_bwd_shard", 1, 640, 128, 100, 1, "bf16", (320,), {}),                # ungrouped at D % 128 == 0
+]
+
+
+@pytest.mark.parametrize("case", BWD_CASES, ids=lambda c: "%s-B%dL%dD%dlh%dg%d%s" % c[:7])
+def test_sharded_backward_equals_the_whole_sequence(case):
+    entry, B, L, D, lh, group, dtype, cuts, opts = case
+    say("%s B=%d L=%d D=%d lh=%d group=%d %s cuts=%s" % (entry, B, L, D, lh, group, dtype, cuts))
+    rng = np.random.Generator(np.random.PCG64(4500 + L + lh))
+    dy, q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(4))
+    h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
+    for name, value in opts.items():
+        binding.set_option(name, value)
+    got = run_bwd_sharded(entry, dev(dy), dev(q), dev(k), dev(v), dev(h), group, cuts, lh)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    on_matrix_cores = dtype == "bf16" and 8 < lh <= 129 and group % 16 == 0 and D % 64 == 0
+    for name, g, want, tol in zip(("dq", "dk", "dv", "dh"), got, ref,
+                                  (TOL[dtype],) * 3 + (1e-2 if on_matrix_cores else TOL["f32"],)):
+        gh = host(g)
+        assert np.isfinite(gh).all(), name
+        err = oracle.rel_err(gh, want)
+        assert err <= tol, (name, err)
