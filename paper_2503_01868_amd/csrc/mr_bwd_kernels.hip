@@ -52,7 +52,9 @@ struct MrBwdArgs {
 
 constexpr int kChunk = 32;
 
-template <int NKB, int NW, int PF>
+// kShard: the call is one rank's share of a sequence (halo rows next to the tensors, batch strides); the plain
+// call's instantiation carries none of that arithmetic.
+template <int NKB, int NW, int PF, bool kShard>
 __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
     constexpr int PPR = 2 * NW;              // 16-byte pieces per staged row
     constexpr int CPR = 2 * PPR;             // 8-byte chunks per staged row
@@ -87,17 +89,18 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
     // dy, q of the chunks before the tile feed its du; before tau = 0 lie the `fut` rows behind the sequence's end
     // that hold data (a shard's right halo), down to the first chunk boundary at or below them
     int64_t t_begin = t_start - (int64_t)kChunk * LAG;
-    const int64_t t_floor = -(((int64_t)a.fut + kChunk - 1) / kChunk) * kChunk;
+    const int64_t t_floor = kShard ? -(((int64_t)a.fut + kChunk - 1) / kChunk) * kChunk : 0;
     if (t_begin < t_floor) t_begin = t_floor;
-    const int64_t tau_lo = -(int64_t)a.fut;     // smallest reversed step at which dy and q hold data
-    const int64_t tau_hi = L + (int64_t)a.hist;  // k and v hold data below this reversed step
+    const int64_t tau_lo = kShard ? -(int64_t)a.fut : 0;     // smallest reversed step at which dy and q hold data
+    const int64_t tau_hi = kShard ? L + (int64_t)a.hist : L;  // k and v hold data below this reversed step
     // k, v of the LAG chunks after the tile feed its z; the walk always runs LAG chunks past the tile, also where
     // the sequence ends first (those chunks then hold zeros and load nothing)
     const int ntot = (int)((t_end - t_begin + kChunk - 1) / kChunk) + LAG;
 
     const int64_t cblock0 = (int64_t)cb * 16 * NW;
     const int64_t c0 = cblock0 + 16 * w;
-    const int64_t seq0 = b * a.sout, seq0kv = b * a.skv, seq0gq = b * a.sgq;
+    const int64_t seq0 = kShard ? b * a.sout : b * L * D;
+    const int64_t seq0kv = kShard ? b * a.skv : seq0, seq0gq = kShard ? b * a.sgq : seq0;
 
     const int lr = tid / PPR, lp = tid % PPR;
     const int64_t ld_off = cblock0 + 8 * lp;
@@ -116,7 +119,7 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
         const int64_t t0 = chunk_start(ci);
         int64_t tau = t0 + lr;
         tau = tau < t_end ? tau : t_end - 1;
-        tau = tau > tau_lo ? tau : tau_lo;  // rows past the data read its last row; their g is zeroed below
+        if constexpr (kShard) tau = tau > tau_lo ? tau : tau_lo;  // rows past the data read its last row; their g is zeroed below
         const int64_t off = seq0gq + ((ci < ntot && t0 < t_end) ? row_off(tau) : idle_off);
         yy = load_words_nt<4>(a.dy + off);
         qq = load_words_nt<4>(a.q + off);
@@ -242,7 +245,8 @@ __global__ __launch_bounds__(NW * 64, 1) void mr_bwd_kernel(MrBwdArgs a) {
                 Words<4> gg;
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) gg.w[e2] = pack_bf16x2(a8[2 * e2] * b8[2 * e2], a8[2 * e2 + 1] * b8[2 * e2 + 1]);
-                if (t0 + lr < tau_lo) gg = zero_words<4>();  // past the rows that hold data: zeros
+                if constexpr (kShard)
+                    if (t0 + lr < tau_lo) gg = zero_words<4>();  // past the rows that hold data: zeros
                 gst[ci & 1][st_idx] = make_uint4(gg.w[0], gg.w[1], gg.w[2], gg.w[3]);
                 gring[slot][wr8a] = make_uint2(gg.w[0], gg.w[1]);
                 gring[slot][wr8b] = make_uint2(gg.w[2], gg.w[3]);
@@ -398,7 +402,8 @@ hy_status launch_nw(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t s
     *nsets = s.B * a.tiles_per_seq;
     const int64_t nb = *nsets * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    return launch_kernel((mr_bwd_kernel<NKB, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
+    if (s.sharded()) return launch_kernel((mr_bwd_kernel<NKB, NW, PF, true>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
+    return launch_kernel((mr_bwd_kernel<NKB, NW, PF, false>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
 }
 
 template <int NKB>

@@ -47,7 +47,9 @@ constexpr int kChunk = 32;
 // kPrefetch = chunks of k, v and q in flight per lane (registers).  Two waves per SIMD must fit (NKB = 13: 247
 // registers); filters beyond 385 taps (NKB = 17: 34 operands and a window of 17 blocks, ~320 registers) run one wave
 // per SIMD.
-template <int NKB, int NW, int kPrefetch>
+// kShard: the call is one rank's share of a sequence (history rows in front of k and v, batch strides); the plain
+// call's instantiation carries none of that arithmetic.
+template <int NKB, int NW, int kPrefetch, bool kShard>
 __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr_mfma_kernel(MrArgs a) {
     constexpr int PPR = 2 * NW;              // 16-byte pieces per staged row of u (bf16)
     constexpr int kTaps = 32 * NKB;          // >= lh
@@ -71,14 +73,14 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr
     const int64_t t_end = (t_start + a.rows < a.L) ? t_start + a.rows : a.L;
     // warm-up chunks reach back to the first chunk boundary at or below the oldest row that holds data
     int64_t t_begin = t_start - (int64_t)kChunk * (NKB - 1);
-    const int64_t t_floor = -(((int64_t)a.hist + kChunk - 1) / kChunk) * kChunk;
+    const int64_t t_floor = kShard ? -(((int64_t)a.hist + kChunk - 1) / kChunk) * kChunk : 0;
     if (t_begin < t_floor) t_begin = t_floor;
     const int nchunks = (int)((t_end - t_begin + kChunk - 1) / kChunk);
 
     const int64_t D = a.D;
     const int64_t cblock0 = (int64_t)cb * 16 * NW;  // first channel of the workgroup
     const int64_t c0 = cblock0 + 16 * w;            // first channel of this wave
-    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv;
+    const int64_t seq0 = kShard ? b * a.bstride_qy : b * a.L * D, seq0kv = kShard ? b * a.bstride_kv : seq0;
 
     // cooperative coordinates of this lane: row lr of the chunk, 16-byte piece lp (8 channels) of the row;
     // used for the k, v, q loads and the y store, all of them whole 32*NW-byte row pieces
@@ -98,11 +100,11 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr
     const uint64_t idle_off = (uint64_t)(uint32_t)(te32 - 1) * D32 + (uint32_t)cblock0;
     //  - rows before the oldest row that holds data (a shard whose halo does not fill its first warm-up chunk) read
     //    that oldest row; their u is zeroed before it is staged.
-    const int t_old = -a.hist;
+    const int t_old = kShard ? -a.hist : 0;
     auto load_kv = [&](int ci, Words<4>& kk, Words<4>& vv) {
         int t = tb32 + ci * kChunk + lr;
         t = t < te32 ? t : te32 - 1;
-        t = t > t_old ? t : t_old;
+        if constexpr (kShard) t = t > t_old ? t : t_old;
         const int64_t off = ci < nchunks ? (int64_t)t * (int64_t)D32 + ld_off : (int64_t)idle_off;
         kk = load_words_nt<4>(a.k + seq0kv + off);
         vv = load_words_nt<4>(a.v + seq0kv + off);
@@ -197,7 +199,8 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : (NKB > 13 ? 1 : 2)) void mr
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2)
                     uu.w[e2] = pack_bf16x2(kf[2 * e2] * vf[2 * e2], kf[2 * e2 + 1] * vf[2 * e2 + 1]);
-                if (tb32 + ci * kChunk + lr < t_old) uu = zero_words<4>();  // before the data: zeros
+                if constexpr (kShard)
+                    if (tb32 + ci * kChunk + lr < t_old) uu = zero_words<4>();  // before the data: zeros
                 stage[ci & 1][st_idx] = make_uint4(uu.w[0], uu.w[1], uu.w[2], uu.w[3]);
             }
             // refill this register stage with the chunk kPrefetch ahead
@@ -287,7 +290,8 @@ hy_status launch_nkb_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.rows = (int32_t)rows;
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    return launch_kernel((mr_mfma_kernel<NKB, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
+    if (s.sharded()) return launch_kernel((mr_mfma_kernel<NKB, NW, PF, true>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
+    return launch_kernel((mr_mfma_kernel<NKB, NW, PF, false>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
 }
 
 template <int NKB>
