@@ -225,6 +225,23 @@ int64_t hyena_chain_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf,
                                     int32_t lh, int32_t group, int32_t dtype);
 
 /*
+ * One rank's share of a sequence-sharded hyena_chain_fwd call (Sec. 4, point-to-point scheme, for the whole
+ * operator of Eq. 1): the shard's L steps, with `history` rows of q, k AND v in front of row 0 of each (device
+ * memory at negative offsets) that hold the steps before the shard; rows before those are zero.  An interior
+ * shard passes history >= (lh - 1) + (lf - 1): the medium filter reaches lh - 1 steps back into k' v', each of
+ * which reaches lf - 1 steps further back into k and v (q' needs lf - 1); the first shard passes 0.
+ * Row t of batch item b of q, k, v is at element offset b * batch_stride_in + t * D (>= (L + history) * D), of y
+ * at b * batch_stride_y + t * D (>= L * D); ignored for B = 1; multiples of 16 bytes.
+ * Single-kernel path only (HY_BF16, group a multiple of 16, D a multiple of 128, lh <= 129, lf <= 9): other
+ * shapes return HY_ERR_UNSUPPORTED.  No workspace.
+ */
+hy_status hyena_chain_fwd_shard(const void *q, const void *k, const void *v, const float *hq, const float *hk,
+                                const float *hv, const float *h, void *y, int64_t B, int64_t L, int64_t D,
+                                int32_t lf, int32_t feat_group, int32_t lh, int32_t group, int32_t dtype,
+                                int64_t batch_stride_in, int64_t batch_stride_y, int32_t history,
+                                void *hip_stream);
+
+/*
  * Backward of hyena_se_fwd / hyena_mr_fwd: gradients of y = q (.) (h * (k (.) v)) given dy = dLoss/dy.
  * With u = k*v, z = h * u (the forward sum of Sec. 3.1 Eq. 2) and g = dy*q:
  *     dq[b,t,c] = dy[b,t,c] * z[b,t,c]

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     plan_gated_shard,
     plan_li,
     hyena_chain_fwd,
+    hyena_chain_fwd_shard,
     hyena_featurize3_fwd,
     hyena_featurize_fwd,
     hyena_li_fwd,

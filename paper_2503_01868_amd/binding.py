@@ -43,6 +43,7 @@ def lib() -> ctypes.CDLL:
         L.hyena_featurize_fwd.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_featurize3_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i32, i32, ci, vp]
         L.hyena_chain_fwd.argtypes = [vp] * 9 + [i64, i64, i64, i64, i32, i32, i32, i32, ci, vp]
+        L.hyena_chain_fwd_shard.argtypes = [vp] * 8 + [i64, i64, i64, i32, i32, i32, i32, ci, i64, i64, i32, vp]
         L.hyena_chain_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, i32, i32, ci]
         L.hyena_chain_workspace_bytes.restype = i64
         bwd_args = [vp] * 10 + [i64, i64, i64, i64, i32, i32, ci, vp]
@@ -67,7 +68,7 @@ def lib() -> ctypes.CDLL:
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_se_fwd_shard", "hyena_mr_fwd_shard", "hyena_featurize_fwd",
                      "hyena_featurize3_fwd",
-                     "hyena_chain_fwd", "hyena_se_bwd", "hyena_mr_bwd", "hyena_se_bwd_shard", "hyena_mr_bwd_shard", "hyena_li_fwd",
+                     "hyena_chain_fwd", "hyena_chain_fwd_shard", "hyena_se_bwd", "hyena_mr_bwd", "hyena_se_bwd_shard", "hyena_mr_bwd_shard", "hyena_li_fwd",
                      "hyena_li_fwd_static", "hyena_li_fwd_carry",
                      "hyena_stream_copy", "hyena_stream_gate", "hyena_set_option"):
             getattr(L, name).restype = ci
@@ -331,6 +332,33 @@ def plan_chain(q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, out
     """Marshal one ``hyena_chain_fwd`` call for repeated issue."""
     args, keep, y = _chain_args(q, k, v, hq, hk, hv, h, group, feat_group, out, workspace, stream)
     return Plan(lib().hyena_chain_fwd, args, "hyena_chain_fwd", keep, y)
+
+
+def hyena_chain_fwd_shard(q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, history: int = 0, out=None,
+                          stream=None) -> torch.Tensor:
+    """One sequence shard of ``hyena_chain_fwd``: q, k, v are [B, L, D] windows with contiguous rows and ``history``
+    valid rows in front of each in memory; see ``hyena_chain_fwd_shard`` in hyena.h."""
+    _check_rows("q", q)
+    _check_rows("k", k, q)
+    _check_rows("v", v, q)
+    lf = _check_filter("hq", hq, q, feat_group)
+    if _check_filter("hk", hk, q, feat_group) != lf or _check_filter("hv", hv, q, feat_group) != lf:
+        raise ValueError("the three featurizer filters must share one length")
+    lh = _check_filter("h", h, q, group)
+    y = torch.empty_like(q, memory_format=torch.contiguous_format) if out is None else out
+    _check_rows("out", y, q)
+    B, L, D = q.shape
+    if B > 1 and (q.stride(0) != k.stride(0) or q.stride(0) != v.stride(0)):
+        raise ValueError("q, k, v must share a batch stride")
+    c = ctypes
+    with torch.cuda.device(q.device):
+        rc = lib().hyena_chain_fwd_shard(
+            *(c.c_void_p(t.data_ptr()) for t in (q, k, v, hq, hk, hv, h, y)), c.c_int64(B), c.c_int64(L), c.c_int64(D),
+            c.c_int32(lf), c.c_int32(int(feat_group)), c.c_int32(lh), c.c_int32(int(group)), c.c_int(_dtype_code(q)),
+            c.c_int64(q.stride(0)), c.c_int64(y.stride(0)), c.c_int32(int(history)), c.c_void_p(_stream(q, stream)))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_chain_fwd_shard")
+    return y
 
 
 def plan_bwd(entry: str, dy, q, k, v, h, group: int, out=None, workspace=None, stream=None) -> Plan:

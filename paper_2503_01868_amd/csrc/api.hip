@@ -340,6 +340,47 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
     return rc;
 }
 
+hy_status hyena_chain_fwd_shard(const void* q, const void* k, const void* v, const float* hq, const float* hk,
+                                const float* hv, const float* h, void* y, int64_t B, int64_t L, int64_t D, int32_t lf,
+                                int32_t feat_group, int32_t lh, int32_t group, int32_t dtype, int64_t batch_stride_in,
+                                int64_t batch_stride_y, int32_t history, void* hip_stream) {
+    TuningSnapshot snap;
+    const void* ins[3] = {q, k, v};
+    void* outs[1] = {y};
+    const FilterArg hs[4] = {{hq, feat_group, lf}, {hk, feat_group, lf}, {hv, feat_group, lf}, {h, group, lh}};
+    hy_status rc = validate(ins, 3, outs, 1, hs, 4, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (lf < 1 || feat_group < 1 || D % feat_group != 0) return HY_ERR_SHAPE;
+    if (history < 0 || batch_stride_in < 0 || batch_stride_y < 0) return HY_ERR_SHAPE;
+    if (empty(B, L, D)) return HY_OK;
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    if (history > (INT64_MAX / esz - L * D) / D) return HY_ERR_SHAPE;
+    const int64_t item_in = (L + history) * D, item_y = L * D;
+    if (B > 1) {
+        if (batch_stride_in < item_in || batch_stride_y < item_y) return HY_ERR_SHAPE;
+        if ((batch_stride_in * esz) % 16 != 0 || (batch_stride_y * esz) % 16 != 0) return HY_ERR_ALIGN;
+        if (batch_stride_in > (INT64_MAX / esz - item_in) / (B - 1) || batch_stride_y > (INT64_MAX / esz - item_y) / (B - 1))
+            return HY_ERR_SHAPE;
+    }
+    const int64_t back = (int64_t)history * D * esz;
+    const int64_t span_in = ((B - 1) * (B > 1 ? batch_stride_in : 0) + L * D) * esz + back;
+    const int64_t span_y = ((B - 1) * (B > 1 ? batch_stride_y : 0) + L * D) * esz;
+    const Range rd[7] = {{static_cast<const char*>(q) - back, span_in}, {static_cast<const char*>(k) - back, span_in},
+                         {static_cast<const char*>(v) - back, span_in}, {hq, filter_bytes(D, feat_group, lf)},
+                         {hk, filter_bytes(D, feat_group, lf)}, {hv, filter_bytes(D, feat_group, lf)},
+                         {h, filter_bytes(D, group, lh)}};
+    const Range wr[1] = {{y, span_y}};
+    rc = check_disjoint(rd, 7, wr, 1);
+    if (rc != HY_OK) return rc;
+    ChainShape cs{B, L, D, lf, feat_group, lh, group, static_cast<hy_dtype>(dtype)};
+    cs.bstride_in = B > 1 ? batch_stride_in : 0;
+    cs.bstride_y = B > 1 ? batch_stride_y : 0;
+    cs.history = history;
+    if (!chain4_supported(cs)) return HY_ERR_UNSUPPORTED;  // shards exist on the single-kernel path only
+    ChainPtrs cp{q, k, v, hq, hk, hv, h, y};
+    return launch_chain4(cp, cs, static_cast<hipStream_t>(hip_stream));
+}
+
 int64_t hyena_li_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype) {
     TuningSnapshot snap;
     if (B < 0 || L < 0 || D < 0 || order < 1 || group < 1 || D % group != 0) return -1;

@@ -41,6 +41,8 @@ struct Chain4Args {
     const float* h;
     uint16_t* y;
     int64_t L, D;
+    int64_t bstride_in, bstride_y;  // elements between batch items in q, k, v / in y
+    int32_t hist;                   // rows of q, k, v in front of row 0 that hold data
     int32_t lh, lf, group, feat_group;
     int32_t rows;           // time steps per workgroup, multiple of 32
     int32_t tiles_per_seq;  // ceil(L / rows)
@@ -87,7 +89,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void chain4_kernel(Chain4Args 
 
     const uint32_t D32 = (uint32_t)a.D;
     const int64_t cblock0 = (int64_t)cb * kC;
-    const int64_t seq0 = b * a.L * a.D;
+    const int64_t seq0 = b * a.bstride_in, seq0y = b * a.bstride_y;
+    const int t_old = -a.hist;  // oldest row that holds data; what lies before it counts as zeros
     using std::integral_constant;
 
     if (w < kWM) {
@@ -251,8 +254,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void chain4_kernel(Chain4Args 
 
         auto row_addr = [&](int t) {  // clamped into the rows this tile may touch
             t = t < te32 ? t : te32 - 1;
-            t = t > 0 ? t : 0;
-            return seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off);
+            t = t > t_old ? t : t_old;
+            return seq0 + ((int64_t)t * (int64_t)D32 + ld_off);
         };
         Words<4> kw[PF][2], vw[PF][2], qw[PF][2];
         auto load_rows = [&](int idx, Words<4> (&kk)[2], Words<4> (&vv)[2], Words<4> (&qq)[2]) {
@@ -277,9 +280,9 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void chain4_kernel(Chain4Args 
         auto prepare = [&](int idx, int sl, Words<4> (&kk)[2], Words<4> (&vv)[2], Words<4> (&qq)[2]) {
             const int t = ts32 + (idx - NKB) * kT + 2 * rp;
             const int off = raw_wr + 2 * kT * sl;
-            write_raw(raw[0] + off, kk, t >= 0, t + 1 >= 0);
-            write_raw(raw[1] + off, vv, t >= 0, t + 1 >= 0);
-            if (idx >= NKB - 1) write_raw(raw[2] + off, qq, t >= 0, t + 1 >= 0);
+            write_raw(raw[0] + off, kk, t >= t_old, t + 1 >= t_old);
+            write_raw(raw[1] + off, vv, t >= t_old, t + 1 >= t_old);
+            if (idx >= NKB - 1) write_raw(raw[2] + off, qq, t >= t_old, t + 1 >= t_old);
         };
         auto store_y = [&](int idx, int ys) {
             uint32_t yc[8];
@@ -293,8 +296,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void chain4_kernel(Chain4Args 
                 row1.w[p] = (yc[2 * p] >> 16) | (yc[2 * p + 1] & 0xffff0000u);
             }
             const int t = ts32 + (idx - NKB) * kT + 2 * rp;
-            if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), row0);
-            if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)(t + 1) * D32 + ld_off), row1);
+            if (t < te32) store_words_nt<4>(a.y + seq0y + ((uint64_t)(uint32_t)t * D32 + ld_off), row0);
+            if (t + 1 < te32) store_words_nt<4>(a.y + seq0y + ((uint64_t)(uint32_t)(t + 1) * D32 + ld_off), row1);
         };
 
 #pragma unroll
@@ -343,6 +346,9 @@ hy_status launch_chain4_nkb(const ChainPtrs& p, const ChainShape& s, hipStream_t
     a.y = static_cast<uint16_t*>(p.y);
     a.L = s.L;
     a.D = s.D;
+    a.bstride_in = s.stride_in();
+    a.bstride_y = s.stride_y();
+    a.hist = s.history;
     a.lh = s.lh;
     a.lf = s.lf;
     a.group = s.group;

@@ -58,6 +58,13 @@ struct ChainShape {
     int64_t B, L, D;
     int32_t lf, feat_group, lh, group;
     hy_dtype dtype;
+    // One rank's share of a sequence-sharded call: `history` rows of q, k and v in front of row 0 hold data (zeros
+    // before them); batch items are `bstride_in` elements apart in q, k, v and `bstride_y` in y (0: L * D).
+    // Only launch_chain4 implements it.
+    int64_t bstride_in = 0, bstride_y = 0;
+    int32_t history = 0;
+    int64_t stride_in() const { return bstride_in > 0 ? bstride_in : L * D; }
+    int64_t stride_y() const { return bstride_y > 0 ? bstride_y : L * D; }
 };
 
 // Backward of the gated convolution.

@@ -333,3 +333,18 @@ def test_backward_shard_entry_points_reject_bad_layouts(entry):
     assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 256, 7, 1, 1) > 0
     assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 128, 100, 1, 1) == 0    # ungrouped medium: general kernels
     assert lib.hyena_bwd_shard_workspace_bytes(1, 64, 30, 3, 4, 1) == -1
+
+
+def test_chain_shard_entry_point_rejects_bad_layouts():
+    lib = binding.lib()
+    Q = [0x100000 * (i + 1) for i in range(8)]
+
+    def call(q=Q[0], k=Q[1], v=Q[2], hq=Q[3], hk=Q[4], hv=Q[5], h=Q[6], y=Q[7], B=2, L=64, D=128, lf=7, fg=1, lh=128,
+             group=16, dtype=1, sin=200 * 128, sy=64 * 128, hist=133):
+        return lib.hyena_chain_fwd_shard(q, k, v, hq, hk, hv, h, y, B, L, D, lf, fg, lh, group, dtype, sin, sy, hist, None)
+
+    assert call(hist=-1) == 2 and call(sin=-1) == 2 and call(sin=196 * 128) == 2 and call(sy=63 * 128) == 2
+    assert call(sin=200 * 128 + 4) == 4 and call(q=None) == 1 and call(lf=0) == 2 and call(fg=3) == 2
+    assert call(y=Q[0] - 133 * 128 * 2) == 4          # y inside q's history rows
+    assert call(dtype=0) == 5 and call(group=8) == 5 and call(lh=130) == 5 and call(lf=10) == 5   # single-kernel path only
+    assert call(B=0) == 0 and call(L=0) == 0

@@ -152,3 +152,37 @@ def test_sharded_backward_equals_the_whole_sequence(case):
         assert np.isfinite(gh).all(), name
         err = oracle.rel_err(gh, want)
         assert err <= tol, (name, err)
+
+
+# ------------------------------------------------------------------------------------------------ fused chain
+@pytest.mark.parametrize("case", [
+    # B, L, D, lf, lh, group, cuts, mr_rows
+    (2, 1500, 128, 7, 128, 16, (400, 1000), 0),
+    (1, 2048, 256, 7, 128, 16, (60, 100, 1024), 256),   # histories shorter than (lh - 1) + (lf - 1) near the start
+    (3, 700, 128, 9, 33, 32, (128, 129), 0),            # a one-step shard; longest featurizer
+    (1, 1000, 128, 3, 129, 16, (500,), 0),
+])
+def test_sharded_operator_chain_equals_the_whole_sequence(case):
+    """hyena_chain_fwd_shard: every shard call sees its own steps of q, k, v plus (lh - 1) + (lf - 1) rows of each in
+    front of them; the shards' outputs against the oracle's chain on the whole sequence and against one call."""
+    B, L, D, lf, lh, group, cuts, rows = case
+    say("chain shards B=%d L=%d D=%d lf=%d lh=%d group=%d cuts=%s rows=%d" % case)
+    binding.set_option("mr_rows", rows)
+    rng = np.random.Generator(np.random.PCG64(4700 + L + lh))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3))
+    hq, hk, hv = (synth.short_filter(rng, D, lf) for _ in range(3))
+    h = synth.decay_filter(rng, D // group, lh)
+    dq, dk, dv = dev(q), dev(k), dev(v)
+    dhq, dhk, dhv, dh = dev(hq), dev(hk), dev(hv), dev(h)
+    y = torch.full_like(dq, float("nan"))
+    edges = [0] + list(cuts) + [L]
+    for t0, t1 in zip(edges[:-1], edges[1:]):
+        hist = min(t0, lh - 1 + lf - 1)
+        binding.hyena_chain_fwd_shard(dq[:, t0:t1], dk[:, t0:t1], dv[:, t0:t1], dhq, dhk, dhv, dh, group, 1, hist,
+                                      out=y[:, t0:t1])
+    torch.cuda.synchronize()
+    ref = oracle.chain(q, k, v, hq, hk, hv, h, group=group, feat_group=1)
+    got = host(y)
+    assert np.isfinite(got).all() and oracle.rel_err(got, ref) <= TOL["bf16"]
+    whole = binding.hyena_chain_fwd(dq, dk, dv, dhq, dhk, dhv, dh, group, 1)
+    assert oracle.rel_err(got, host(whole)) <= TOL["bf16"]
