@@ -93,8 +93,9 @@ hy_status hyena_mr_fwd(const void *q, const void *k, const void *v, const float 
  * of q and y at b * batch_stride_qy + t * D (D contiguous as everywhere); the strides are ignored when B = 1,
  * else batch_stride_kv >= (L + history) * D, batch_stride_qy >= L * D (HY_ERR_SHAPE) and both a multiple of
  * 16 bytes (HY_ERR_ALIGN).  The overlap rules apply to the memory really touched (history rows included).
- * Kernels: the short-filter stencil and tile walker, the grouped matrix-core kernel, and the general kernel
- * for every other shape (the chunk-parallel kernels for ungrouped medium filters do not take shards yet).
+ * Kernels: the short-filter stencil and tile walker, the grouped matrix-core kernel, the batched 4x4x4
+ * chunk-parallel kernel for medium filters that are not shared by 16 channels, and the general kernel for every
+ * other shape.
  * Results of a sequence computed in shards equal the unsharded call's up to the rounding order of the fp32
  * sums (bit for bit on the short-filter paths, whose tap order is fixed).
  * No collective is issued here: exchanging the halo rows is the caller's business.

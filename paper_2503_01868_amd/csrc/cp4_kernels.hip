@@ -49,6 +49,9 @@ struct Cp4Args {
     int32_t ncb;            // channel blocks = D / (16 NW)
     int32_t rev;            // 1: step t of the kernel is row L - 1 - t of the tensors (the convolution then runs
                             // towards the past: the transposed operator of the backward pass)
+    int64_t bstride_kv, bstride_qy;  // elements between batch items in k, v / in q, y (and q2, y2)
+    int32_t hist;           // rows of k and v in front of row 0 that hold data (a sequence shard's left halo;
+                            // forward direction only)
 };
 
 constexpr int kT = 64;    // steps per iteration
@@ -83,7 +86,8 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
     const int64_t D = a.D;
     const uint32_t D32 = (uint32_t)D;
     const int64_t cblock0 = (int64_t)cb * C;
-    const int64_t seq0 = b * a.L * D;
+    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv;
+    const int t_old = -a.hist;  // oldest row that holds data; what lies before it counts as zeros
 
     auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
     // step -> row of the tensors: t, or L - 1 - t = (t ^ -1) + L in reversed time
@@ -99,17 +103,17 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
     Words<4> kw[PF][2], vw[PF][2], qw[PF][2];
     auto row_addr = [&](int t) {  // clamped into the rows this tile may touch
         t = t < te32 ? t : te32 - 1;
-        t = t > 0 ? t : 0;
-        return seq0 + ((uint64_t)phys(t) * D32 + ld_off);
+        t = t > t_old ? t : t_old;
+        return (int64_t)((t ^ rxor) + radd) * (int64_t)D32 + ld_off;  // without the batch item's offset
     };
     auto load_rows = [&](int it, Words<4> (&kk)[2], Words<4> (&vv)[2], Words<4> (&qq)[2]) {
         const int t0 = ts32 + (it - 1) * kT + 2 * rp;  // iteration it >= 1 covers steps ts32 + 64 (it - 1) ...
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int64_t off = row_addr(t0 + r);
-            kk[r] = load_words_nt<4>(a.k + off);
-            vv[r] = load_words_nt<4>(a.v + off);
-            qq[r] = load_words_nt<4>(a.q + off);
+            kk[r] = load_words_nt<4>(a.k + seq0kv + off);
+            vv[r] = load_words_nt<4>(a.v + seq0kv + off);
+            qq[r] = load_words_nt<4>(a.q + seq0 + off);
         }
     };
     // u of 2 rows x 8 channels, transposed: one dword (2 steps) per channel into the ring at step position `pos`
@@ -166,10 +170,10 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
                 int t = t0 + r;
                 t = t > t_lo ? t : t_lo;
                 const int64_t off = row_addr(t);
-                kh[r] = load_words_nt<4>(a.k + off);
-                vh[r] = load_words_nt<4>(a.v + off);
+                kh[r] = load_words_nt<4>(a.k + seq0kv + off);
+                vh[r] = load_words_nt<4>(a.v + seq0kv + off);
             }
-            write_u(kh, vh, t0 >= 0, t0 + 1 >= 0, hp2 == 0 ? 2 * kT : 0);
+            write_u(kh, vh, t0 >= t_old, t0 + 1 >= t_old, hp2 == 0 ? 2 * kT : 0);
         }
     }
 
@@ -312,7 +316,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
 
     const uint32_t D32 = (uint32_t)a.D;
     const int64_t cblock0 = (int64_t)cb * C;
-    const int64_t seq0 = b * a.L * a.D;
+    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv;
+    const int t_old = -a.hist;  // oldest row that holds data; what lies before it counts as zeros
     auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
     const int rxor = a.rev ? -1 : 0, radd = a.rev ? (int)a.L : 0;  // step -> row, see cp4_kernel
     auto phys = [&](int t) { return (uint32_t)((t ^ rxor) + radd); };
@@ -409,8 +414,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
 
         auto row_addr = [&](int t) {  // clamped into the rows this tile may touch
             t = t < te32 ? t : te32 - 1;
-            t = t > 0 ? t : 0;
-            return seq0 + ((uint64_t)phys(t) * D32 + ld_off);
+            t = t > t_old ? t : t_old;
+            return (int64_t)((t ^ rxor) + radd) * (int64_t)D32 + ld_off;  // without the batch item's offset
         };
         // u of 2 rows x 8 channels, transposed: one dword (2 steps) per channel at ring position `pos` + 2 rp
         auto write_u = [&](const Words<4> (&kk)[2], const Words<4> (&vv)[2], bool keep0, bool keep1, int pos) {
@@ -435,10 +440,10 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
                     const int64_t off = row_addr(t0 + r);
-                    kk[hf][r] = load_words_nt<4>(a.k + off);
-                    vv[hf][r] = load_words_nt<4>(a.v + off);
-                    qq[hf][r] = load_words_nt<4>(a.q + off);
-                    if constexpr (DUAL) pp[hf][r] = load_words_nt<4>(a.q2 + off);
+                    kk[hf][r] = load_words_nt<4>(a.k + seq0kv + off);
+                    vv[hf][r] = load_words_nt<4>(a.v + seq0kv + off);
+                    qq[hf][r] = load_words_nt<4>(a.q + seq0 + off);
+                    if constexpr (DUAL) pp[hf][r] = load_words_nt<4>(a.q2 + seq0 + off);
                 }
             }
         };
@@ -500,8 +505,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
                         int t = t0 + r;
                         t = t > t_lo ? t : t_lo;
                         const int64_t off = row_addr(t);
-                        kh[hb][hf][r] = load_words_nt<4>(a.k + off);
-                        vh[hb][hf][r] = load_words_nt<4>(a.v + off);
+                        kh[hb][hf][r] = load_words_nt<4>(a.k + seq0kv + off);
+                        vh[hb][hf][r] = load_words_nt<4>(a.v + seq0kv + off);
                     }
                 }
             }
@@ -511,7 +516,7 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf) {
                     const int t0 = ts32 - 2 * kT + hb * kT + 32 * hf + 2 * rp;
-                    write_u(kh[hb][hf], vh[hb][hf], t0 >= 0, t0 + 1 >= 0, (hb == 0 ? 3 * kT : 0) + 32 * hf);
+                    write_u(kh[hb][hf], vh[hb][hf], t0 >= t_old, t0 + 1 >= t_old, (hb == 0 ? 3 * kT : 0) + 32 * hf);
                 }
             }
         }
@@ -558,6 +563,9 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * NW));
     a.rev = s.reversed ? 1 : 0;
+    a.bstride_kv = s.stride_kv();
+    a.bstride_qy = s.stride_qy();
+    a.hist = s.history;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
         int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
@@ -591,6 +599,9 @@ hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.group = s.group;
     a.ncb = (int32_t)(s.D / (16 * kWM));
     a.rev = s.reversed ? 1 : 0;
+    a.bstride_kv = s.stride_kv();
+    a.bstride_qy = s.stride_qy();
+    a.hist = s.history;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
         int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
@@ -629,7 +640,7 @@ hy_status launch_cp4_nbk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) 
 bool cp4_dual_supported(const ConvShape& s) { return cp4_supported(s) && (s.lh + 2) / 4 + 1 > 17; }
 
 bool cp4_supported(const ConvShape& s) {
-    return !s.sharded() && s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh >= 1 && s.lh <= 129 && s.L <= 0x7fff0000LL &&
+    return !(s.sharded() && s.reversed) && s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh >= 1 && s.lh <= 129 && s.L <= 0x7fff0000LL &&
            s.D <= 0x7fff0000LL;
 }
 

@@ -33,8 +33,8 @@ struct ConvShape {
     // One rank's share of a sequence-sharded call (Sec. 4, point-to-point scheme): consecutive batch items are
     // `bstride_kv` elements apart in k and v and `bstride_qy` in q and y (0: L * D, dense), and `history` rows of
     // k and v in front of row 0 hold the steps that precede the shard (the left neighbour's last rows); what lies
-    // before them is zero.  Implemented by launch_stencil, launch_se_walk (history 0 or >= 8), launch_mr_mfma and
-    // launch_direct.
+    // before them is zero.  Implemented by launch_stencil, launch_se_walk (history 0 or >= 8), launch_mr_mfma,
+    // launch_cp4 (forward direction) and launch_direct.
     int64_t bstride_kv = 0, bstride_qy = 0;
     int32_t history = 0;
     int64_t stride_kv() const { return bstride_kv > 0 ? bstride_kv : L * D; }

@@ -46,6 +46,10 @@ CASES = [
     ("hyena_mr_fwd_shard", 2, 800, 48, 100, 1, "bf16", (333,), {}),                      # general kernel (ungrouped)
     ("hyena_mr_fwd_shard", 1, 600, 256, 128, 16, "f32", (200, 400), {}),                 # general kernel (fp32)
     ("hyena_mr_fwd_shard", 1, 640, 128, 7, 16, "bf16", (320,), {}),                      # short grouped filter
+    ("hyena_mr_fwd_shard", 2, 1500, 128, 128, 1, "bf16", (400, 1000), {}),               # ungrouped: 4x4x4 kernel, long filter
+    ("hyena_mr_fwd_shard", 1, 1000, 256, 40, 2, "bf16", (30, 64, 500), {"mr_rows": 256}),  # 16 waves; short histories
+    ("hyena_mr_fwd_shard", 3, 700, 128, 20, 1, "bf16", (350, 351), {}),                  # 8 waves, 9 products
+    ("hyena_se_fwd_shard", 2, 900, 384, 100, 8, "bf16", (450,), {}),                     # through the SE entry point
 ]
 
 
