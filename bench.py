@@ -12,7 +12,8 @@ A step is one pass of the hot path over one synthetic batch that already sits in
       c1 / c2 / c3 / c2u
   c1_shards / c2_shards / c3_shards: c1 / c2 / c3 computed as four consecutive sequence shards (hyena_se_fwd_shard /
       hyena_mr_fwd_shard: each call sees its quarter of the steps plus the lh - 1 rows of k and v before it), the
-      compute half of a sequence-sharded run on one GPU; a step is the four launches
+      compute half of a sequence-sharded run on one GPU; a step is the four launches.  c3_bwd_shards: the same for
+      the backward pass (hyena_mr_bwd_shard: halos on both sides, every shard its share of the filter gradient)
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
   c2u c2 with one filter per channel; li2 / li3: Hyena-LI at the shapes of c2 / c3
@@ -54,7 +55,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
                     choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "c1_shards",
-                             "c2_shards", "c3_shards", "copy"] + list(YARDSTICKS),
+                             "c2_shards", "c3_shards", "c3_bwd_shards", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "
@@ -103,9 +104,9 @@ class Workload:
 
     def __init__(self, name, nsets, torch, pkg, synth, seq_len=0, depth=0):
         self.name, self.torch, self.pkg = name, torch, pkg
-        self.bwd = name.endswith("_bwd")
         self.shards = 4 if name.endswith("_shards") else 0
         name = name[:-7] if self.shards else name
+        self.bwd = name.endswith("_bwd")
         self.strip, self.ywaves, ydepth = YARDSTICKS.get(name, (None, 0, 0))
         depth = depth or ydepth
         name = name[:-4] if self.bwd else name
@@ -136,9 +137,25 @@ class Workload:
                 grads = torch.empty((3,) + tuple(d["q"].shape), dtype=d["q"].dtype, device="cuda")
                 d["dq"], d["dk"], d["dv"] = grads[0], grads[1], grads[2]
                 d["dh"] = torch.empty_like(d["h"])
-                self.main.append(pkg.plan_bwd("hyena_se_bwd" if c["kind"] == "se" else "hyena_mr_bwd", d["dy"], d["q"],
-                                              d["k"], d["v"], d["h"], c["group"],
-                                              out=(d["dq"], d["dk"], d["dv"], d["dh"])))
+                if self.shards:
+                    # the sequence as consecutive shard calls: lh - 1 rows of k, v before and of dy, q behind each
+                    # shard; every call leaves its share of dh in a buffer of its own
+                    entry = "hyena_se_bwd_shard" if c["kind"] == "se" else "hyena_mr_bwd_shard"
+                    n = c["L"] // self.shards
+                    d["dh_parts"] = [torch.empty_like(d["h"]) for _ in range(self.shards)]
+                    plans = []
+                    for i in range(self.shards):
+                        w = slice(i * n, (i + 1) * n)
+                        plans.append(pkg.plan_bwd_shard(entry, d["dy"][:, w], d["q"][:, w], d["k"][:, w], d["v"][:, w],
+                                                        d["h"], c["group"], min(i * n, c["lh"] - 1),
+                                                        min(c["L"] - (i + 1) * n, c["lh"] - 1),
+                                                        out=(d["dq"][:, w], d["dk"][:, w], d["dv"][:, w],
+                                                             d["dh_parts"][i])))
+                    self.main.append(lambda plans=plans: [p() for p in plans])
+                else:
+                    self.main.append(pkg.plan_bwd("hyena_se_bwd" if c["kind"] == "se" else "hyena_mr_bwd", d["dy"], d["q"],
+                                                  d["k"], d["v"], d["h"], c["group"],
+                                                  out=(d["dq"], d["dk"], d["dv"], d["dh"])))
             elif self.strip is not None:
                 self.main.append(pkg.plan_stream_gate(d["q"], d["k"], d["v"], self.strip, 0, depth, self.ywaves,
                                                       out=d["y"]))
@@ -307,9 +324,11 @@ def entry_point(wl):
         return "hyena_stream_gate (strip_channels=%d, waves=%d)" % (wl.strip, wl.ywaves or wl.strip // 16)
     name = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd",
             "li": "hyena_li_fwd (both passes of the scan)"}[wl.cfg["kind"]]
+    if wl.bwd:
+        name = name.replace("_fwd", "_bwd")
     if wl.shards:
-        return "%s_shard x %d (the sequence in consecutive shards, one launch each)" % (name, wl.shards)
-    return name.replace("_fwd", "_bwd (all launches of the entry point)") if wl.bwd else name
+        return "%s_shard x %d (the sequence in consecutive shards, one call each)" % (name, wl.shards)
+    return name + " (all launches of the entry point)" if wl.bwd else name
 
 
 def measure(name, args, torch, pkg, synth, steps, warmup, settle=0):
