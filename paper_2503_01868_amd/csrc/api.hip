@@ -488,6 +488,7 @@ int64_t hyena_bwd_shard_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t
     s.shard_call = true;
     if (bwd_stencil_supported(s)) return bwd_stencil_workspace_bytes(s);
     if (mr_bwd_supported(s)) return mr_bwd_workspace_bytes(s);
+    if (cp4_bwd_supported(s)) return cp4_bwd_workspace_bytes(s);
     return 0;
 }
 

@@ -19,6 +19,12 @@
 // filter gradient of the tile, written out contiguously and reduced over tiles (and the channels of a group) by
 // dh_reduce_kernel, the two-pass structure of App. A.4.
 //
+// A shard of a longer sequence (Sec. 4) is one more cut of the same kind: a call whose dy, q go on behind row
+// L - 1 and whose k, v begin before row 0 counts the pair (t, j) when step t - (j mod 4) is one of its own, reads
+// up to 3 of the rows behind it and up to lh - 1 of the rows in front, and the shares of all shards add up to the
+// full gradient.  Where the call's last step is not the last step of a 4-step group, the entries of A that belong
+// to the steps behind it are masked out (their g is real data there, not zeros).
+//
 // Data movement: 8 waves per 128 channels; per iteration of 64 steps every lane loads two rows x 8 channels of
 // dy, q, k, v (16-byte pieces, one iteration ahead), forms g and u, rounds them to bf16 and writes them
 // transposed into per-channel [time] lines in LDS (rings of 4 x 64 steps); the products of an iteration run one
@@ -40,6 +46,8 @@ struct Cp4DhArgs {
     const uint16_t* v;
     float* partial;  // [B * tiles_per_seq][D][lh]
     int64_t L, D;
+    int64_t skv, sgq;  // elements between batch items in k, v / in dy, q
+    int32_t hist, fut;  // rows of k, v in front of row 0 / of dy, q behind row L - 1 that hold data
     int32_t lh;
     int32_t rows;           // time steps per workgroup, multiple of 64
     int32_t tiles_per_seq;  // ceil(L / rows)
@@ -53,7 +61,7 @@ constexpr int kRing = 256;  // ring length in steps (4 slots)
 constexpr int kLine = 544;  // bytes per ring line: 256 steps, 4 steps of wrap-around copy, padding (8 banks per channel)
 
 // NA = lag blocks of 16 = ceil(lh / 16)
-template <int NA>
+template <int NA, bool kShard>
 __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
     constexpr int PPR = kC / 8;  // 16-byte pieces per row
     static_assert(kNW * 64 == PPR * (kT / 2), "one lane per (row pair, piece)");
@@ -76,7 +84,9 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
 
     const uint32_t D32 = (uint32_t)a.D;
     const int64_t cblock0 = (int64_t)cb * kC;
-    const int64_t seq0 = b * a.L * a.D;
+    const int64_t seq0kv = b * a.skv, seq0gq = b * a.sgq;
+    const int t_old = kShard ? -a.hist : 0;       // oldest step of k, v that holds data
+    const int t_end = kShard ? L32 + a.fut : L32;  // one past the newest step of dy, q that holds data
     auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
 
     // ---- row layout: rows 2 rp, 2 rp + 1 of an iteration, channels 8 lp .. 8 lp + 7 of the block
@@ -85,11 +95,16 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
     char* const u_lines = uring + line_off(8 * lp, kLine) + 4 * rp;
     char* const g_lines = gring + line_off(8 * lp, kLine) + 4 * rp;
 
-    // rows are clamped into the sequence; what lies outside it is zeroed when it is written to LDS
-    auto row_addr = [&](int t) {
+    // rows are clamped into what holds data; what lies outside it is zeroed when it is written to LDS
+    auto row_kv = [&](int t) {
         t = t < L32 ? t : L32 - 1;
+        t = t > t_old ? t : t_old;
+        return seq0kv + ((int64_t)t * (int64_t)D32 + ld_off);
+    };
+    auto row_gq = [&](int t) {
+        t = t < t_end ? t : t_end - 1;
         t = t > 0 ? t : 0;
-        return seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off);
+        return seq0gq + ((int64_t)t * (int64_t)D32 + ld_off);
     };
     // x = a*b of 2 rows x 8 channels, transposed: one dword (2 steps) per channel at ring position `pos` + 2 rp
     auto write_prod = [&](char* lines, const Words<4> (&aa)[2], const Words<4> (&bb)[2], bool keep0, bool keep1, int pos) {
@@ -109,16 +124,16 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
         const int t0 = ts32 + (it - 1) * kT + 2 * rp;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            const int64_t off = row_addr(t0 + r);
-            yw[r] = load_words_nt<4>(a.dy + off);
-            qw[r] = load_words_nt<4>(a.q + off);
+            const int64_t off = row_kv(t0 + r), offg = row_gq(t0 + r);
+            yw[r] = load_words_nt<4>(a.dy + offg);
+            qw[r] = load_words_nt<4>(a.q + offg);
             kw[r] = load_words_nt<4>(a.k + off);
             vw[r] = load_words_nt<4>(a.v + off);
         }
     };
 
     // ---- history of u: the steps ts32 - 128 .. ts32 - 1 go to ring slots 3 and 0 (iteration it uses slot it & 3);
-    // steps before the sequence are zeros
+    // steps before the oldest row that holds data are zeros
     {
         Words<4> kh[2][2], vh[2][2];
 #pragma unroll
@@ -126,7 +141,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
             const int t0 = ts32 - 2 * kT + hb * kT + 2 * rp;
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
-                const int64_t off = row_addr(t0 + r);
+                const int64_t off = row_kv(t0 + r);
                 kh[hb][r] = load_words_nt<4>(a.k + off);
                 vh[hb][r] = load_words_nt<4>(a.v + off);
             }
@@ -135,7 +150,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb) {
             const int t0 = ts32 - 2 * kT + hb * kT + 2 * rp;
-            write_prod(u_lines, kh[hb], vh[hb], t0 >= 0, t0 + 1 >= 0, hb == 0 ? 3 * kT : 0);
+            write_prod(u_lines, kh[hb], vh[hb], t0 >= t_old, t0 + 1 >= t_old, hb == 0 ? 3 * kT : 0);
         }
     }
 
@@ -154,8 +169,9 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
 #pragma unroll
     for (int x = 0; x < NA; ++x) acc[x] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // products of the iteration whose first step sits at ring position WB (a compile-time constant)
-    auto products = [&](auto wb_c) {
+    // products of the iteration whose first step sits at ring position WB (a compile-time constant); `left` = steps
+    // from there to the end of the tile (only a shard's last tile can end inside a group with real g behind it)
+    auto products = [&](auto wb_c, int left) {
         constexpr int WB = decltype(wb_c)::value;
 #pragma unroll
         for (int n = 0; n < kT / 4; ++n) {
@@ -168,6 +184,11 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
             Words<2> aw;
             aw.w[0] = odd ? __builtin_amdgcn_alignbit(d1, d0, 16) : d0;
             aw.w[1] = odd ? __builtin_amdgcn_alignbit(d2, d1, 16) : d1;
+            if constexpr (kShard) {  // column k of A belongs to step T + k: keep it while that step is the tile's
+                const int rem = left - 4 * n;
+                aw.w[0] &= rem >= 2 ? 0xffffffffu : (rem == 1 ? 0x0000ffffu : 0u);
+                aw.w[1] &= rem >= 4 ? 0xffffffffu : (rem == 3 ? 0x0000ffffu : 0u);
+            }
             const s16x4_t av = __builtin_bit_cast(s16x4_t, aw);
 #pragma unroll
             for (int x = 0; x < NA; ++x) {
@@ -193,14 +214,14 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
         {
             const int t = ts32 + (it - 1) * kT + 2 * rp;
             write_prod(u_lines, kw, vw, t < L32, t + 1 < L32, WB);
-            write_prod(g_lines, yw, qw, t < L32, t + 1 < L32, WB);
+            write_prod(g_lines, yw, qw, t < t_end, t + 1 < t_end, WB);
             if constexpr (SL == 0) {  // positions 0..3 once more behind position 255 (read windows do not wrap)
-                if (rp < 2) write_prod(g_lines, yw, qw, t < L32, t + 1 < L32, kRing);
+                if (rp < 2) write_prod(g_lines, yw, qw, t < t_end, t + 1 < t_end, kRing);
             }
         }
         if (it <= nit) load_rows(it + 1);
         __syncthreads();
-        if (it >= 2) products(std::integral_constant<int, kT * ((SL + 3) & 3)>{});
+        if (it >= 2) products(std::integral_constant<int, kT * ((SL + 3) & 3)>{}, te32 - (ts32 + (it - 2) * kT));
         __syncthreads();
     };
     using std::integral_constant;
@@ -237,7 +258,7 @@ int64_t dh_rows(const BwdShape& s) {
     return rows > cap ? cap : rows;
 }
 
-template <int NA>
+template <int NA, bool kShard>
 hy_status launch_dh_na(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st) {
     Cp4DhArgs a;
     a.dy = static_cast<const uint16_t*>(p.dy);
@@ -247,6 +268,10 @@ hy_status launch_dh_na(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_
     a.partial = static_cast<float*>(ws);
     a.L = s.L;
     a.D = s.D;
+    a.skv = s.stride_kv();
+    a.sgq = s.stride_gq();
+    a.hist = s.history;
+    a.fut = s.future;
     a.lh = s.lh;
     a.ncb = (int32_t)(s.D / kC);
     a.rows = (int32_t)dh_rows(s);
@@ -254,7 +279,7 @@ hy_status launch_dh_na(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_
     const int64_t nsets = s.B * a.tiles_per_seq;
     const int64_t nb = nsets * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    hy_status rc = launch_kernel((cp4_dh_kernel<NA>), dim3((uint32_t)nb), dim3(kNW * 64), st, a);
+    hy_status rc = launch_kernel((cp4_dh_kernel<NA, kShard>), dim3((uint32_t)nb), dim3(kNW * 64), st, a);
     if (rc != HY_OK) return rc;
     return launch_dh_reduce(static_cast<const float*>(ws), p.dh, nsets, s.D, s.lh, s.group, st);
 }
@@ -262,7 +287,7 @@ hy_status launch_dh_na(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_
 }  // namespace
 
 bool cp4_bwd_supported(const BwdShape& s) {
-    return !s.sharded() && s.dtype == HY_BF16 && s.D % 128 == 0 && s.lh > 8 && s.lh <= 129 && s.L <= 0x7fff0000LL && s.D <= 0x7fff0000LL;
+    return s.dtype == HY_BF16 && s.D % 128 == 0 && s.lh > 8 && s.lh <= 129 && s.L <= 0x7fff0000LL && s.D <= 0x7fff0000LL;
 }
 
 int64_t cp4_bwd_workspace_bytes(const BwdShape& s) {
@@ -274,8 +299,19 @@ int64_t cp4_bwd_workspace_bytes(const BwdShape& s) {
 hy_status launch_cp4_bwd(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t st) {
     if (!cp4_bwd_supported(s)) return HY_ERR_UNSUPPORTED;
     // dq: the forward operator on (dy, k, v); dk, dv: the operator towards the past on g = dy*q, gated by v and by k
+    // (a shard: dq reaches back into the rows in front of k and v, dk and dv forward into the rows behind dy and q)
     ConvShape fwd{s.B, s.L, s.D, s.lh, s.group, s.dtype, true, false};
     ConvShape rev{s.B, s.L, s.D, s.lh, s.group, s.dtype, true, true};
+    if (s.sharded()) {
+        fwd.bstride_kv = s.stride_kv();
+        fwd.bstride_qy = s.stride_gq();
+        fwd.bstride_y = s.stride_out();
+        fwd.history = s.history;
+        rev.bstride_kv = s.stride_gq();
+        rev.bstride_qy = s.stride_kv();
+        rev.bstride_y = s.stride_out();
+        rev.history = s.future;
+    }
     hy_status rc = launch_cp4(ConvPtrs{p.dy, p.k, p.v, p.h, p.dq}, fwd, st);
     if (rc != HY_OK) return rc;
     if (cp4_dual_supported(rev)) {
@@ -289,9 +325,14 @@ hy_status launch_cp4_bwd(const BwdPtrs& p, const BwdShape& s, void* ws, hipStrea
         if (rc != HY_OK) return rc;
     }
     const int na = (s.lh + 15) / 16;
-    if (na <= 3) return launch_dh_na<3>(p, s, ws, st);
-    if (na <= 5) return launch_dh_na<5>(p, s, ws, st);
-    return launch_dh_na<9>(p, s, ws, st);
+    if (s.sharded()) {
+        if (na <= 3) return launch_dh_na<3, true>(p, s, ws, st);
+        if (na <= 5) return launch_dh_na<5, true>(p, s, ws, st);
+        return launch_dh_na<9, true>(p, s, ws, st);
+    }
+    if (na <= 3) return launch_dh_na<3, false>(p, s, ws, st);
+    if (na <= 5) return launch_dh_na<5, false>(p, s, ws, st);
+    return launch_dh_na<9, false>(p, s, ws, st);
 }
 
 }  // namespace hy

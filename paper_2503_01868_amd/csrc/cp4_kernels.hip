@@ -49,9 +49,9 @@ struct Cp4Args {
     int32_t ncb;            // channel blocks = D / (16 NW)
     int32_t rev;            // 1: step t of the kernel is row L - 1 - t of the tensors (the convolution then runs
                             // towards the past: the transposed operator of the backward pass)
-    int64_t bstride_kv, bstride_qy;  // elements between batch items in k, v / in q, y (and q2, y2)
-    int32_t hist;           // rows of k and v in front of row 0 that hold data (a sequence shard's left halo;
-                            // forward direction only)
+    int64_t bstride_kv, bstride_qy, bstride_y;  // elements between batch items in k, v / in q (and q2) / in y (and y2)
+    int32_t hist;           // steps of k and v before step 0 that hold data (a sequence shard's halo: rows in front
+                            // of row 0, in reversed time rows behind row L - 1)
 };
 
 constexpr int kT = 64;    // steps per iteration
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
     const int64_t D = a.D;
     const uint32_t D32 = (uint32_t)D;
     const int64_t cblock0 = (int64_t)cb * C;
-    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv;
+    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv, seq0y = b * a.bstride_y;
     const int t_old = -a.hist;  // oldest row that holds data; what lies before it counts as zeros
 
     auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
@@ -251,8 +251,8 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void cp4_kernel(Cp4Args 
                 row1.w[p] = (yc[2 * p] >> 16) | (yc[2 * p + 1] & 0xffff0000u);
             }
             const int t = ts + 2 * rp;
-            if (t < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t) * D32 + ld_off), row0);
-            if (t + 1 < te32) store_words_nt<4>(a.y + seq0 + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
+            if (t < te32) store_words_nt<4>(a.y + seq0y + ((uint64_t)phys(t) * D32 + ld_off), row0);
+            if (t + 1 < te32) store_words_nt<4>(a.y + seq0y + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
         }
     };
 
@@ -316,7 +316,7 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
 
     const uint32_t D32 = (uint32_t)a.D;
     const int64_t cblock0 = (int64_t)cb * C;
-    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv;
+    const int64_t seq0 = b * a.bstride_qy, seq0kv = b * a.bstride_kv, seq0y = b * a.bstride_y;
     const int t_old = -a.hist;  // oldest row that holds data; what lies before it counts as zeros
     auto line_off = [](int c, int stride) { return c * stride + (c >> 3) * 8; };
     const int rxor = a.rev ? -1 : 0, radd = a.rev ? (int)a.L : 0;  // step -> row, see cp4_kernel
@@ -481,8 +481,8 @@ __global__ __launch_bounds__((kWM + kWV) * 64, 3) void cp4ws_kernel(Cp4Args a) {
                     row1.w[p] = (yc[2 * p] >> 16) | (yc[2 * p + 1] & 0xffff0000u);
                 }
                 const int t = ts32 + (it - 1) * kT + 32 * hf + 2 * rp;
-                if (t < te32) store_words_nt<4>(dst + seq0 + ((uint64_t)phys(t) * D32 + ld_off), row0);
-                if (t + 1 < te32) store_words_nt<4>(dst + seq0 + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
+                if (t < te32) store_words_nt<4>(dst + seq0y + ((uint64_t)phys(t) * D32 + ld_off), row0);
+                if (t + 1 < te32) store_words_nt<4>(dst + seq0y + ((uint64_t)phys(t + 1) * D32 + ld_off), row1);
             }
         };
         auto store_y = [&](int it, int sl) {
@@ -565,6 +565,7 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.rev = s.reversed ? 1 : 0;
     a.bstride_kv = s.stride_kv();
     a.bstride_qy = s.stride_qy();
+    a.bstride_y = s.stride_y();
     a.hist = s.history;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
@@ -601,6 +602,7 @@ hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.rev = s.reversed ? 1 : 0;
     a.bstride_kv = s.stride_kv();
     a.bstride_qy = s.stride_qy();
+    a.bstride_y = s.stride_y();
     a.hist = s.history;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
@@ -640,7 +642,7 @@ hy_status launch_cp4_nbk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) 
 bool cp4_dual_supported(const ConvShape& s) { return cp4_supported(s) && (s.lh + 2) / 4 + 1 > 17; }
 
 bool cp4_supported(const ConvShape& s) {
-    return !(s.sharded() && s.reversed) && s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh >= 1 && s.lh <= 129 && s.L <= 0x7fff0000LL &&
+    return s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh >= 1 && s.lh <= 129 && s.L <= 0x7fff0000LL &&
            s.D <= 0x7fff0000LL;
 }
 

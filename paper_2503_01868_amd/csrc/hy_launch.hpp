@@ -34,12 +34,15 @@ struct ConvShape {
     // `bstride_kv` elements apart in k and v and `bstride_qy` in q and y (0: L * D, dense), and `history` rows of
     // k and v in front of row 0 hold the steps that precede the shard (the left neighbour's last rows); what lies
     // before them is zero.  Implemented by launch_stencil, launch_se_walk (history 0 or >= 8), launch_mr_mfma,
-    // launch_cp4 (forward direction) and launch_direct.
+    // launch_cp4 and launch_direct.  In reversed time the history rows lie BEHIND row L - 1.  `bstride_y` (0: as
+    // q) gives y a batch stride of its own; only launch_cp4 takes it.
     int64_t bstride_kv = 0, bstride_qy = 0;
     int32_t history = 0;
+    int64_t bstride_y = 0;
     int64_t stride_kv() const { return bstride_kv > 0 ? bstride_kv : L * D; }
     int64_t stride_qy() const { return bstride_qy > 0 ? bstride_qy : L * D; }
-    bool sharded() const { return history != 0 || stride_kv() != L * D || stride_qy() != L * D; }
+    int64_t stride_y() const { return bstride_y > 0 ? bstride_y : stride_qy(); }
+    bool sharded() const { return history != 0 || stride_kv() != L * D || stride_qy() != L * D || stride_y() != L * D; }
 };
 
 // The operator chain: featurize q, k, v (filters hq, hk, hv), then the gated medium convolution with h.
@@ -87,7 +90,7 @@ struct BwdShape {
     // One rank's share of a sequence-sharded backward call: `history` rows of k and v in front of row 0 and `future`
     // rows of dy and q behind row L - 1 hold the neighbours' steps (zeros beyond them); batch items are
     // `bstride_kv` / `bstride_gq` / `bstride_out` elements apart in k, v / dy, q / dq, dk, dv (0: L * D, dense).
-    // Implemented by launch_bwd_stencil, launch_mr_bwd and launch_bwd_direct.
+    // Implemented by launch_bwd_stencil, launch_mr_bwd, launch_cp4_bwd and launch_bwd_direct.
     int64_t bstride_kv = 0, bstride_gq = 0, bstride_out = 0;
     int32_t history = 0, future = 0;
     bool shard_call = false;  // came in through a shard entry point: only the paths above, whatever the values

@@ -331,7 +331,8 @@ def test_backward_shard_entry_points_reject_bad_layouts(entry):
     assert call(dq=Q[0] + 8 * 16 * 2) == 4      # an output inside the future rows behind dy
     assert call(dh=Q[1] + 9 * 16 * 2) == 4      # the filter gradient inside q's future rows
     assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 256, 7, 1, 1) > 0
-    assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 128, 100, 1, 1) == 0    # ungrouped medium: general kernels
+    assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 128, 100, 1, 1) > 0     # ungrouped medium: 4x4x4 kernels
+    assert lib.hyena_bwd_shard_workspace_bytes(1, 4096, 96, 100, 1, 1) == 0     # ... at D % 128 != 0: general kernels
     assert lib.hyena_bwd_shard_workspace_bytes(1, 64, 30, 3, 4, 1) == -1
 
 

@@ -134,7 +134,12 @@ BWD_CASES = [
     ("hyena_mr_bwd_shard", 3, 700, 64, 33, 32, "bf16", (128, 129), {}),
     ("hyena_mr_bwd_shard", 2, 800, 48, 100, 1, "bf16", (333,), {}),                 # general kernels (ungrouped)
     ("hyena_mr_bwd_shard", 1, 600, 128, 128, 16, "f32", (200, 400), {}),            # general kernels (fp32)
-    ("hyena_mr_bwd_shard", 1, 640, 128, 100, 1, "bf16", (320,), {}),                # ungrouped at D % 128 == 0
+    ("hyena_mr_bwd_shard", 1, 640, 128, 100, 1, "bf16", (320,), {}),                # chunk-parallel 4x4x4 kernels
+    ("hyena_mr_bwd_shard", 2, 1000, 128, 128, 1, "bf16", (300, 301, 640), {}),      # ... two post-gates; shard lengths
+                                                                                    # 300, 1, 339, 360
+    ("hyena_mr_bwd_shard", 1, 777, 256, 33, 2, "bf16", (130, 391), {}),             # ... 16-wave kernel, groups of 2
+    ("hyena_mr_bwd_shard", 1, 1100, 128, 65, 4, "bf16", (7, 550, 1098), {"mr_rows": 256}),  # ... short halos, tiles
+    ("hyena_mr_bwd_shard", 2, 515, 128, 9, 1, "bf16", (258,), {}),                  # ... shortest filter; 258 % 4 = 2
 ]
 
 
@@ -149,7 +154,7 @@ def test_sharded_backward_equals_the_whole_sequence(case):
         binding.set_option(name, value)
     got = run_bwd_sharded(entry, dev(dy), dev(q), dev(k), dev(v), dev(h), group, cuts, lh)
     ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
-    on_matrix_cores = dtype == "bf16" and 8 < lh <= 129 and group % 16 == 0 and D % 64 == 0
+    on_matrix_cores = dtype == "bf16" and 8 < lh <= 129 and ((group % 16 == 0 and D % 64 == 0) or D % 128 == 0)
     for name, g, want, tol in zip(("dq", "dk", "dv", "dh"), got, ref,
                                   (TOL[dtype],) * 3 + (1e-2 if on_matrix_cores else TOL["f32"],)):
         gh = host(g)
@@ -159,6 +164,40 @@ def test_sharded_backward_equals_the_whole_sequence(case):
 
 
 # ------------------------------------------------------------------------------------------------ fused chain
+@pytest.mark.parametrize("entry,lh,group", [("hyena_se_bwd_shard", 7, 1), ("hyena_mr_bwd_shard", 128, 16),
+                                            ("hyena_mr_bwd_shard", 100, 1), ("hyena_mr_bwd_shard", 40, 2)])
+def test_backward_shards_with_their_own_halo_buffers(entry, lh, group):
+    """The layout ranks would really hold: k and v as [B, history + L, D] buffers (first rows received from the left
+    neighbour), dy and q as [B, L + future, D] buffers (last rows received from the right neighbour), dq, dk, dv
+    dense: three different batch strides.  Two ranks; the shares of dh add up."""
+    B, Ltot, D, cut = 2, 900, 128, 500
+    say("%s lh=%d group=%d, buffers with halos, B=%d L=%d+%d D=%d" % (entry, lh, group, B, cut, Ltot - cut, D))
+    rng = np.random.Generator(np.random.PCG64(4600 + lh))
+    dy, q, k, v = (synth.normal_tensor(rng, (B, Ltot, D), "bf16") for _ in range(4))
+    h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
+    hd = dev(h)
+    parts, dh = [], torch.zeros_like(hd, dtype=torch.float64)
+    for t0, t1 in ((0, cut), (cut, Ltot)):
+        L = t1 - t0
+        hist, fut = min(t0, lh - 1), min(Ltot - t1, lh - 1)
+        kbuf, vbuf = (dev(x[:, t0 - hist:t1].contiguous()) for x in (k, v))
+        gbuf, qbuf = (dev(x[:, t0:t1 + fut].contiguous()) for x in (dy, q))
+        guard = torch.full((3, B * L * D + 4096), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+        outs = tuple(guard[i, 2048:2048 + B * L * D].view(B, L, D) for i in range(3))
+        res = getattr(binding, entry)(gbuf[:, :L], qbuf[:, :L], kbuf[:, hist:], vbuf[:, hist:], hd, group, hist, fut,
+                                      out=outs + (torch.empty_like(hd),))
+        torch.cuda.synchronize()
+        assert torch.isnan(guard[:, :2048]).all() and torch.isnan(guard[:, 2048 + B * L * D:]).all()
+        parts.append([host(o) for o in outs])
+        dh += res[3].double()
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for i, name in enumerate(("dq", "dk", "dv")):
+        got = np.concatenate([parts[0][i], parts[1][i]], axis=1)
+        assert np.isfinite(got).all(), name
+        assert oracle.rel_err(got, ref[i]) <= TOL["bf16"], name
+    assert oracle.rel_err(host(dh), ref[3]) <= (1e-2 if lh > 8 else TOL["f32"])
+
+
 @pytest.mark.parametrize("case", [
     # B, L, D, lf, lh, group, cuts, mr_rows
     (2, 1500, 128, 7, 128, 16, (400, 1000), 0),
