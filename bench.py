@@ -55,7 +55,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
                     choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "c1_shards",
-                             "c2_shards", "c3_shards", "c3_bwd_shards", "copy"] + list(YARDSTICKS),
+                             "c2_shards", "c3_shards", "c1_bwd_shards", "c3_bwd_shards", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "

@@ -295,10 +295,9 @@ int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, i
  * batch_stride_kv for k and v (>= (L + history) * D), batch_stride_gq for dy and q (>= (L + future) * D) and
  * batch_stride_out for dq, dk, dv (>= L * D); ignored when B = 1; multiples of 16 bytes (HY_ERR_ALIGN), too
  * small: HY_ERR_SHAPE.  The overlap rules apply to the memory really touched.
- * workspace: hyena_bwd_shard_workspace_bytes(...) bytes (the shard calls take the short-filter stencil, the
- * one-pass grouped matrix-core kernel, the chunk-parallel kernels for single channels and small groups or the
- * general kernels, never the short-filter tile walker, which does not know shards, so their size can differ from
- * hyena_bwd_workspace_bytes).
+ * workspace: hyena_bwd_shard_workspace_bytes(...) bytes, for the shard's own B, L, D (every kernel that serves
+ * hyena_se_bwd / hyena_mr_bwd also takes shards; the size is the one hyena_bwd_workspace_bytes gives for the same
+ * arguments, asked through this function so that the pairing stays explicit).
  */
 hy_status hyena_se_bwd_shard(const void *dy, const void *q, const void *k, const void *v, const float *h, void *dq,
                              void *dk, void *dv, float *dh, void *workspace, int64_t workspace_bytes, int64_t B,

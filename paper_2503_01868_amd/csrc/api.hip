@@ -486,7 +486,7 @@ int64_t hyena_bwd_shard_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t
     if (empty(B, L, D)) return 0;
     BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
     s.shard_call = true;
-    if (bwd_stencil_supported(s)) return bwd_stencil_workspace_bytes(s);
+    if (bwd_stencil_supported(s)) return bwd_walk_preferred(s) ? bwd_walk_workspace_bytes(s) : bwd_stencil_workspace_bytes(s);
     if (mr_bwd_supported(s)) return mr_bwd_workspace_bytes(s);
     if (cp4_bwd_supported(s)) return cp4_bwd_workspace_bytes(s);
     return 0;

@@ -13,7 +13,10 @@
 // one rounding per stored element.  At the end the 16 lanes that share a channel quartet add their partial filter
 // gradients through LDS in row order; the tile's partial goes to the workspace as [tile][D][lh] and dh_reduce_kernel
 // sums tiles and the channels of a group (two passes, App. A.4).
-// A tile reads lh-1 <= 8 rows of k, v before its start and of dy, q after its end.
+// A tile reads lh-1 <= 8 rows of k, v before its start and of dy, q after its end.  A shard of a longer sequence
+// (Sec. 4) is the same thing one level up: its first tile finds those rows of k, v in front of row 0, its last tile
+// those of dy, q behind row L - 1 (as many as the call says hold data), and a product g[t] u[t-j] is counted by the
+// call that owns step t, which is also the rule of the stencil kernel.
 #include "hy_common.hpp"
 #include "hy_launch.hpp"
 
@@ -31,6 +34,8 @@ struct BwdWalkArgs {
     uint16_t* dv;
     float* partial;  // [B * tiles_per_seq][D][lh]
     int64_t L, D;
+    int64_t skv, sgq, sout;  // elements between batch items in k, v / dy, q / dq, dk, dv
+    int32_t hist, fut;       // rows of k, v in front of row 0 / of dy, q behind row L - 1 that hold data
     int32_t lh, group;
     int32_t rows, tiles_per_seq, ncb;
 };
@@ -42,7 +47,7 @@ constexpr int kLook = 8;     // look-back (u) / look-ahead (g) rows kept beside 
 constexpr int kRowB = kCh * 4;                      // bytes per staged fp32 row
 constexpr int kSlot = (kRowsC + kLook) * kRowB;     // bytes per ring slot
 
-template <int LH, int PF>
+template <int LH, int PF, bool kShard>
 __global__ __launch_bounds__(kWaves * 64, 4) void bwd_walk_kernel(BwdWalkArgs a) {
     static_assert(LH >= 1 && LH - 1 <= kLook, "the extra rows must cover the filter");
     // u slot: rows 0..7 = the 8 rows before the chunk, rows 8..23 = the chunk; g slot: rows 0..15 = the chunk,
@@ -61,33 +66,35 @@ __global__ __launch_bounds__(kWaves * 64, 4) void bwd_walk_kernel(BwdWalkArgs a)
     const int te32 = (ts32 + a.rows < a.L) ? ts32 + a.rows : L32;
     // one chunk in front of a tile that does not start the sequence (k, v of its last rows), one more chunk behind
     // the tile (dy, q of its first rows; also the iteration that finishes du of the last chunk)
-    const bool warm = ts32 > 0;
+    const int t_old = kShard ? -a.hist : 0;        // oldest row of k, v that holds data
+    const int t_end = kShard ? L32 + a.fut : L32;  // one past the newest row of dy, q that holds data
+    const bool warm = ts32 > t_old;
     const int tb32 = warm ? ts32 - kRowsC : 0;
     const int nch = (te32 - tb32 + kRowsC - 1) / kRowsC + 1;
 
     const uint32_t D32 = (uint32_t)a.D;
     const int64_t cblock0 = (int64_t)cb * kCh;
-    const int64_t seq0 = b * a.L * a.D;
+    const int64_t seq0kv = b * a.skv, seq0gq = b * a.sgq, seq0out = b * a.sout;
     const int lr = tid >> 6, lp = tid & 63;          // row of the chunk, quartet of channels
     const uint32_t ld_off = (uint32_t)(cblock0 + 4 * lp);
     const int col = lp * 16;                          // byte offset of this lane's 4 fp32 values in a staged row
 
     // rows whose values are never used load one 8-byte location per workgroup instead (one cache line per wave)
-    const uint64_t idle_off = (uint64_t)(uint32_t)(te32 - 1) * D32 + (uint32_t)cblock0;
+    const int64_t idle_off = (int64_t)((uint64_t)(uint32_t)(te32 - 1) * D32 + (uint32_t)cblock0);
     auto row_of = [&](int ci) { return tb32 + ci * kRowsC + lr; };
     auto load_kv = [&](int ci, Words<2>& kk, Words<2>& vv) {
         const int t = row_of(ci);
-        const bool used = ci < nch && t >= ts32 - (LH - 1) && t >= 0 && t < te32;
-        const uint64_t off = used ? (uint64_t)(uint32_t)t * D32 + ld_off : idle_off;
-        kk = load_words_nt<2>(a.k + seq0 + off);
-        vv = load_words_nt<2>(a.v + seq0 + off);
+        const bool used = ci < nch && t >= ts32 - (LH - 1) && t >= t_old && t < te32;
+        const int64_t off = used ? (int64_t)t * (int64_t)D32 + ld_off : idle_off;  // t < 0: a shard's rows in front
+        kk = load_words_nt<2>(a.k + seq0kv + off);
+        vv = load_words_nt<2>(a.v + seq0kv + off);
     };
     auto load_g = [&](int ci, Words<2>& yy, Words<2>& qq) {
         const int t = row_of(ci);
-        const bool used = ci < nch && t >= ts32 && t < te32 + (LH - 1) && t < L32;
-        const uint64_t off = used ? (uint64_t)(uint32_t)t * D32 + ld_off : idle_off;
-        yy = load_words_nt<2>(a.dy + seq0 + off);
-        qq = load_words_nt<2>(a.q + seq0 + off);
+        const bool used = ci < nch && t >= ts32 && t < te32 + (LH - 1) && t < t_end;
+        const int64_t off = used ? (int64_t)t * (int64_t)D32 + ld_off : idle_off;
+        yy = load_words_nt<2>(a.dy + seq0gq + off);
+        qq = load_words_nt<2>(a.q + seq0gq + off);
     };
 
     Words<2> kpre[PF], vpre[PF], ypre[PF], qpre[PF];
@@ -128,8 +135,8 @@ __global__ __launch_bounds__(kWaves * 64, 4) void bwd_walk_kernel(BwdWalkArgs a)
             Pack<BF16, 4>::unpack(ypre[sgi], yf);
             Pack<BF16, 4>::unpack(qpre[sgi], qf);
             // what lies outside the sequence, or outside what this tile may use, is zero
-            const bool u_ok = ci < nch && t >= 0 && t < te32;
-            const bool g_ok = ci < nch && t >= ts32 && t < L32;
+            const bool u_ok = ci < nch && t >= t_old && t < te32;
+            const bool g_ok = ci < nch && t >= ts32 && t < t_end;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 uf[c] = u_ok ? kf[c] * vf[c] : 0.0f;
@@ -172,7 +179,7 @@ __global__ __launch_bounds__(kWaves * 64, 4) void bwd_walk_kernel(BwdWalkArgs a)
                 float o[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) o[c] = yf[c] * z[c];
-                store_words_nt<2>(a.dq + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), Pack<BF16, 4>::pack(o));
+                store_words_nt<2>(a.dq + seq0out + ((uint64_t)(uint32_t)t * D32 + ld_off), Pack<BF16, 4>::pack(o));
             }
             // du, dk, dv of the previous chunk's row: its g rows and the 8 after them are in the previous slot now
             const int tp = t - kRowsC;
@@ -198,8 +205,8 @@ __global__ __launch_bounds__(kWaves * 64, 4) void bwd_walk_kernel(BwdWalkArgs a)
                     o2[c] = du[c] * kprev[c];
                 }
                 const uint64_t off = (uint64_t)(uint32_t)tp * D32 + ld_off;
-                store_words_nt<2>(a.dk + seq0 + off, Pack<BF16, 4>::pack(o1));
-                store_words_nt<2>(a.dv + seq0 + off, Pack<BF16, 4>::pack(o2));
+                store_words_nt<2>(a.dk + seq0out + off, Pack<BF16, 4>::pack(o1));
+                store_words_nt<2>(a.dv + seq0out + off, Pack<BF16, 4>::pack(o2));
             }
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -257,6 +264,11 @@ hy_status launch_walk_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipStrea
     a.partial = static_cast<float*>(ws);
     a.L = s.L;
     a.D = s.D;
+    a.skv = s.stride_kv();
+    a.sgq = s.stride_gq();
+    a.sout = s.stride_out();
+    a.hist = s.history;
+    a.fut = s.future;
     a.lh = s.lh;
     a.group = s.group;
     a.ncb = (int32_t)(s.D / kCh);
@@ -265,7 +277,9 @@ hy_status launch_walk_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipStrea
     const int64_t nsets = s.B * a.tiles_per_seq;
     const int64_t nb = nsets * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    const hy_status rc = launch_kernel((bwd_walk_kernel<LH, PF>), dim3((uint32_t)nb), dim3(kWaves * 64), st, a);
+    const hy_status rc = s.sharded()
+        ? launch_kernel((bwd_walk_kernel<LH, PF, true>), dim3((uint32_t)nb), dim3(kWaves * 64), st, a)
+        : launch_kernel((bwd_walk_kernel<LH, PF, false>), dim3((uint32_t)nb), dim3(kWaves * 64), st, a);
     if (rc != HY_OK) return rc;
     return launch_dh_reduce(static_cast<const float*>(ws), p.dh, nsets, s.D, s.lh, s.group, st);
 }
@@ -275,7 +289,7 @@ hy_status launch_walk_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipStrea
 // bf16, lh <= 7 (eight taps do not fit 128 registers beside two chunks of loads), whole 256-channel blocks, and a
 // stretch of at least 256 steps per workgroup to walk
 bool bwd_walk_preferred(const BwdShape& s) {
-    if (s.sharded() || s.dtype != HY_BF16 || s.lh < 1 || s.lh > 7 || s.D % kCh != 0) return false;
+    if (s.dtype != HY_BF16 || s.lh < 1 || s.lh > 7 || s.D % kCh != 0) return false;
     if (s.L > 0x7fff0000LL || s.D > 0x7fff0000LL) return false;
     const int force = tuning().se_walk;
     if (force == 1) return true;

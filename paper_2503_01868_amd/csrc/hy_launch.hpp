@@ -90,10 +90,10 @@ struct BwdShape {
     // One rank's share of a sequence-sharded backward call: `history` rows of k and v in front of row 0 and `future`
     // rows of dy and q behind row L - 1 hold the neighbours' steps (zeros beyond them); batch items are
     // `bstride_kv` / `bstride_gq` / `bstride_out` elements apart in k, v / dy, q / dq, dk, dv (0: L * D, dense).
-    // Implemented by launch_bwd_stencil, launch_mr_bwd, launch_cp4_bwd and launch_bwd_direct.
+    // Implemented by every backward launcher.
     int64_t bstride_kv = 0, bstride_gq = 0, bstride_out = 0;
     int32_t history = 0, future = 0;
-    bool shard_call = false;  // came in through a shard entry point: only the paths above, whatever the values
+    bool shard_call = false;  // came in through a shard entry point: the kernels' shard variants, whatever the values
     int64_t stride_kv() const { return bstride_kv > 0 ? bstride_kv : L * D; }
     int64_t stride_gq() const { return bstride_gq > 0 ? bstride_gq : L * D; }
     int64_t stride_out() const { return bstride_out > 0 ? bstride_out : L * D; }

@@ -129,6 +129,9 @@ BWD_CASES = [
     ("hyena_se_bwd_shard", 2, 1000, 256, 7, 1, "bf16", (300, 301, 640), {}),        # stencil; a one-step shard
     ("hyena_se_bwd_shard", 1, 900, 64, 4, 2, "f32", (3, 500, 898), {}),             # halos shorter than lh - 1
     ("hyena_se_bwd_shard", 2, 700, 128, 8, 4, "bf16", (350,), {"se_rows": 64}),
+    ("hyena_se_bwd_shard", 2, 1000, 256, 7, 1, "bf16", (300, 301, 640), {"se_walk": 1}),   # tile walker
+    ("hyena_se_bwd_shard", 1, 1500, 512, 4, 2, "bf16", (3, 700, 1497), {"se_walk": 1, "se_rows": 64}),  # ... short halos
+    ("hyena_se_bwd_shard", 1, 2100, 256, 7, 1, "bf16", (1000,), {"se_walk": 1, "se_rows": 256}),  # ... several tiles
     ("hyena_mr_bwd_shard", 2, 1500, 128, 128, 16, "bf16", (400, 1000), {}),         # one-pass matrix-core kernel
     ("hyena_mr_bwd_shard", 1, 2000, 64, 128, 16, "bf16", (50, 90, 1024, 1950), {"mr_rows": 256}),  # partial halo chunks
     ("hyena_mr_bwd_shard", 3, 700, 64, 33, 32, "bf16", (128, 129), {}),
@@ -164,14 +167,16 @@ def test_sharded_backward_equals_the_whole_sequence(case):
 
 
 # ------------------------------------------------------------------------------------------------ fused chain
-@pytest.mark.parametrize("entry,lh,group", [("hyena_se_bwd_shard", 7, 1), ("hyena_mr_bwd_shard", 128, 16),
-                                            ("hyena_mr_bwd_shard", 100, 1), ("hyena_mr_bwd_shard", 40, 2)])
-def test_backward_shards_with_their_own_halo_buffers(entry, lh, group):
+@pytest.mark.parametrize("entry,lh,group,D,walk", [
+    ("hyena_se_bwd_shard", 7, 1, 128, 0), ("hyena_se_bwd_shard", 7, 1, 256, 1), ("hyena_mr_bwd_shard", 128, 16, 128, 0),
+    ("hyena_mr_bwd_shard", 100, 1, 128, 0), ("hyena_mr_bwd_shard", 40, 2, 128, 0)])
+def test_backward_shards_with_their_own_halo_buffers(entry, lh, group, D, walk):
     """The layout ranks would really hold: k and v as [B, history + L, D] buffers (first rows received from the left
     neighbour), dy and q as [B, L + future, D] buffers (last rows received from the right neighbour), dq, dk, dv
     dense: three different batch strides.  Two ranks; the shares of dh add up."""
-    B, Ltot, D, cut = 2, 900, 128, 500
+    B, Ltot, cut = 2, 900, 500
     say("%s lh=%d group=%d, buffers with halos, B=%d L=%d+%d D=%d" % (entry, lh, group, B, cut, Ltot - cut, D))
+    binding.set_option("se_walk", walk)   # 1: the short-filter tile walker whatever the length
     rng = np.random.Generator(np.random.PCG64(4600 + lh))
     dy, q, k, v = (synth.normal_tensor(rng, (B, Ltot, D), "bf16") for _ in range(4))
     h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
