@@ -193,10 +193,13 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
 // second pass: dh[g][j] = sum over partial sets and over the channels of group g.  A workgroup owns 64 outputs;
 // its four waves each sum a contiguous quarter of the terms (fixed order: set, then channel of the group), wave 0
 // adds the four quarters in order.  Deterministic, no atomics.  The sums run in fp64 (the adds are a negligible
-// part of this kernel), so the reduction adds no rounding of its own to the fp32 partials.
-constexpr int kRedOut = 64, kRedParts = kBlock / kRedOut;
+// part of this kernel), so the reduction adds no rounding of its own to the fp32 partials.  With few terms per
+// output (up to 8: single channels and a handful of tiles) a lane sums all of them for one of 256 outputs instead:
+// a quarter of the workgroups, all loads of a lane in flight at once, no exchange.
+template <int kRedParts>
 __global__ __launch_bounds__(kBlock) void dh_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dh,
                                                            int64_t nsets, int64_t D, int32_t lh, int32_t group) {
+    constexpr int kRedOut = kBlock / kRedParts;
     __shared__ double red[kRedParts][kRedOut];
     const int o = threadIdx.x % kRedOut, part = threadIdx.x / kRedOut;
     const int64_t idx = (int64_t)blockIdx.x * kRedOut + o;  // (g, j)
@@ -232,6 +235,10 @@ __global__ __launch_bounds__(kBlock) void dh_reduce_kernel(const float* __restri
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             if (x0 + i < hi) s += (double)v[i];
+    }
+    if constexpr (kRedParts == 1) {
+        if (idx < n) dh[idx] = (float)s;
+        return;
     }
     red[part][o] = s;
     __syncthreads();
@@ -421,8 +428,7 @@ hy_status launch_stencil_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipSt
     if (rc != HY_OK) return rc;
     const int64_t nsets = s.B * a.tiles_per_seq;
     const int64_t nout = (s.D / s.group) * s.lh;
-    return launch_kernel(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), st,
-                         a.partial, p.dh, nsets, s.D, s.lh, s.group);
+    return launch_dh_reduce(a.partial, p.dh, nsets, s.D, s.lh, s.group, st);
 }
 
 template <typename T>
@@ -483,8 +489,11 @@ hy_status launch_dh_reduce(const float* partial, float* dh, int64_t nsets, int64
                            hipStream_t st) {
     const int64_t nout = (n_rows / group) * lh;
     if (nout == 0) return HY_OK;
-    return launch_kernel(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), st, partial, dh,
-                       nsets, n_rows, lh, group);
+    if (nsets * group <= 8)
+        return launch_kernel(dh_reduce_kernel<1>, dim3((uint32_t)((nout + kBlock - 1) / kBlock)), dim3(kBlock), st, partial,
+                             dh, nsets, n_rows, lh, group);
+    return launch_kernel(dh_reduce_kernel<4>, dim3((uint32_t)((nout + kBlock / 4 - 1) / (kBlock / 4))), dim3(kBlock), st,
+                         partial, dh, nsets, n_rows, lh, group);
 }
 
 hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hipStream_t st) {
@@ -492,7 +501,7 @@ hy_status launch_bwd_zero_dh(float* dh, int64_t D, int32_t lh, int32_t group, hi
     if (nout == 0) return HY_OK;
     // a reduction over zero partial sets writes zeros (a fill kernel, not a memset, so that callers may
     // capture the call in a HIP graph)
-    return launch_kernel(dh_reduce_kernel, dim3((uint32_t)((nout + kRedOut - 1) / kRedOut)), dim3(kBlock), st,
+    return launch_kernel(dh_reduce_kernel<1>, dim3((uint32_t)((nout + kBlock - 1) / kBlock)), dim3(kBlock), st,
                          static_cast<const float*>(dh), dh, (int64_t)0, D, lh, group);
 }
 

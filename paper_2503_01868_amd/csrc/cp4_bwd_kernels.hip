@@ -11,7 +11,10 @@
 //     D_a[i][r] += sum_k A[i][k] * B_a[k][r],   A[i][k] = g[T + i + k],   B_a[k][r] = u[T + k - 4 r - 16 a],
 // so that entry (i, r) of accumulator a collects g[t] u[t - j] for the lag j = 16 a + 4 r + i over all t = T+i+k.
 // B_a is four aligned 4-step pieces of the channel's u line (one 8-byte LDS read per lane, as in the forward
-// kernel); A is a Hankel block of g whose rows start at consecutive steps, read as three aligned dwords and
+// kernel), and B_a of the group at T is B_0 of the group at T - 16 a: every operand is read from LDS once, as B_0
+// of its group, and then stays in a register window of the last 4 (NA - 1) + 1 groups until its last lag block has
+// used it (reading all NA operands per group from LDS made the LDS pipe the limit of this kernel).  A is a Hankel
+// block of g whose rows start at consecutive steps, read as three aligned dwords and
 // shifted by 16 bits in the odd rows.  Every (t, j) pair is produced exactly once, row i of a tile covering the
 // steps [t0, t1) of T + k taking the g of [t0 + i, t1 + i): tiles partition the sum and need 3 steps of dy, q past
 // their end and lh - 1 steps of k, v before their start.  The accumulators (4 registers per lag block) stay in
@@ -26,9 +29,10 @@
 // to the steps behind it are masked out (their g is real data there, not zeros).
 //
 // Data movement: 8 waves per 128 channels; per iteration of 64 steps every lane loads two rows x 8 channels of
-// dy, q, k, v (16-byte pieces, one iteration ahead), forms g and u, rounds them to bf16 and writes them
-// transposed into per-channel [time] lines in LDS (rings of 4 x 64 steps); the products of an iteration run one
-// iteration late, when the 3 look-ahead steps of g are there.
+// dy, q, k, v (16-byte pieces, one iteration ahead; two ahead do not fit the registers beside the operand
+// window), forms g and u, rounds them to bf16 and writes them transposed into per-channel [time] lines in LDS
+// (rings of 4 x 64 steps); the products of an iteration run one iteration late, when the 3 look-ahead steps of g
+// are there.
 #include <type_traits>
 
 #include "hy_common.hpp"
@@ -62,7 +66,7 @@ constexpr int kLine = 544;  // bytes per ring line: 256 steps, 4 steps of wrap-a
 
 // NA = lag blocks of 16 = ceil(lh / 16)
 template <int NA, bool kShard>
-__global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
+__global__ __launch_bounds__(kNW * 64, 1) void cp4_dh_kernel(Cp4DhArgs a) {
     constexpr int PPR = kC / 8;  // 16-byte pieces per row
     static_assert(kNW * 64 == PPR * (kT / 2), "one lane per (row pair, piece)");
     static_assert(16 * NA + 12 <= kRing - kT, "the lags must fit the ring behind the current slot");
@@ -119,16 +123,18 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
         }
     };
 
-    Words<4> yw[2], qw[2], kw[2], vw[2];
-    auto load_rows = [&](int it) {  // iteration it >= 1; one past the last iteration only its first rows matter
+    constexpr int PF = 1;  // iterations of loads in flight; register stage it % PF holds the rows of iteration it
+    Words<4> yw[PF][2], qw[PF][2], kw[PF][2], vw[PF][2];
+    auto load_rows = [&](auto st_c, int it) {  // iteration it >= 1; one past the last iteration only its first rows matter
+        constexpr int ST = decltype(st_c)::value;
         const int t0 = ts32 + (it - 1) * kT + 2 * rp;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int64_t off = row_kv(t0 + r), offg = row_gq(t0 + r);
-            yw[r] = load_words_nt<4>(a.dy + offg);
-            qw[r] = load_words_nt<4>(a.q + offg);
-            kw[r] = load_words_nt<4>(a.k + off);
-            vw[r] = load_words_nt<4>(a.v + off);
+            yw[ST][r] = load_words_nt<4>(a.dy + offg);
+            qw[ST][r] = load_words_nt<4>(a.q + offg);
+            kw[ST][r] = load_words_nt<4>(a.k + off);
+            vw[ST][r] = load_words_nt<4>(a.v + off);
         }
     };
 
@@ -146,7 +152,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
                 vh[hb][r] = load_words_nt<4>(a.v + off);
             }
         }
-        load_rows(1);
+        load_rows(std::integral_constant<int, 1 % PF>{}, 1);
+        if constexpr (PF == 2) load_rows(std::integral_constant<int, 0>{}, 2);
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb) {
             const int t0 = ts32 - 2 * kT + hb * kT + 2 * rp;
@@ -169,58 +176,76 @@ __global__ __launch_bounds__(kNW * 64, 2) void cp4_dh_kernel(Cp4DhArgs a) {
 #pragma unroll
     for (int x = 0; x < NA; ++x) acc[x] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // products of the iteration whose first step sits at ring position WB (a compile-time constant); `left` = steps
-    // from there to the end of the tile (only a shard's last tile can end inside a group with real g behind it)
+    // B_0 of the group at ring position 4 i sits in win[i]; all indices are compile-time constants, an entry is
+    // dead 4 (NA - 1) groups after it was read
+    constexpr int kWin = kRing / 4;
+    s16x4_t win[kWin];
+    auto read_b0 = [&](int c0) {  // ring position of column 0, a constant after unrolling
+        const char* p;
+        if (c0 >= 12) p = u_lane + 2 * c0;
+        else if (c0 == 0) p = u_mix0;
+        else if (c0 == 4) p = u_mix4;
+        else p = u_mix8;
+        const uint2 bw = *reinterpret_cast<const uint2*>(p);
+        Words<2> bb;
+        bb.w[0] = bw.x; bb.w[1] = bw.y;
+        win[c0 / 4] = __builtin_bit_cast(s16x4_t, bb);
+    };
+    // the 4 (NA - 1) groups before ring position kT (the first iteration's), for its first products
+    auto fill_history = [&]() {
+        static_assert(4 * (NA - 1) <= 2 * (kT / 4), "the history lies in the two slots before the first iteration's");
+#pragma unroll
+        for (int i = 0; i < 4 * (NA - 1); ++i) read_b0((kT - 4 * (i + 1) + kRing) % kRing);
+    };
+
+    // one group of 4 steps whose first step sits at ring position P (a constant after unrolling); `rem` = steps from
+    // there to the end of the tile (only a shard's last tile can end inside a group with real g behind it)
+    auto group = [&](int P, int rem) {
+        read_b0(P);
+        // A: g[T + l4 .. T + l4 + 3], T at position P; the line carries a copy of positions 0..3 behind position 255,
+        // so the window never wraps
+        const char* gp = gl + 2 * P;
+        const uint32_t d0 = *reinterpret_cast<const uint32_t*>(gp);
+        const uint32_t d1 = *reinterpret_cast<const uint32_t*>(gp + 4);
+        const uint32_t d2 = *reinterpret_cast<const uint32_t*>(gp + 8);
+        Words<2> aw;
+        aw.w[0] = odd ? __builtin_amdgcn_alignbit(d1, d0, 16) : d0;
+        aw.w[1] = odd ? __builtin_amdgcn_alignbit(d2, d1, 16) : d1;
+        if constexpr (kShard) {  // column k of A belongs to step T + k: keep it while that step is the tile's
+            aw.w[0] &= rem >= 2 ? 0xffffffffu : (rem == 1 ? 0x0000ffffu : 0u);
+            aw.w[1] &= rem >= 4 ? 0xffffffffu : (rem == 3 ? 0x0000ffffu : 0u);
+        }
+        const s16x4_t av = __builtin_bit_cast(s16x4_t, aw);
+#pragma unroll
+        for (int x = 0; x < NA; ++x)
+            acc[x] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(av, win[((P - 16 * x + 4 * kRing) % kRing) / 4], acc[x], 0, 0, 0);
+    };
+
+    // products of the iteration whose first step sits at ring position WB; `left` = steps from there to the tile's end
     auto products = [&](auto wb_c, int left) {
         constexpr int WB = decltype(wb_c)::value;
 #pragma unroll
-        for (int n = 0; n < kT / 4; ++n) {
-            // A: g[T + l4 .. T + l4 + 3], T at position WB + 4 n; the line carries a copy of positions 0..3 behind
-            // position 255, so the window never wraps
-            const char* gp = gl + 2 * (WB + 4 * n);
-            const uint32_t d0 = *reinterpret_cast<const uint32_t*>(gp);
-            const uint32_t d1 = *reinterpret_cast<const uint32_t*>(gp + 4);
-            const uint32_t d2 = *reinterpret_cast<const uint32_t*>(gp + 8);
-            Words<2> aw;
-            aw.w[0] = odd ? __builtin_amdgcn_alignbit(d1, d0, 16) : d0;
-            aw.w[1] = odd ? __builtin_amdgcn_alignbit(d2, d1, 16) : d1;
-            if constexpr (kShard) {  // column k of A belongs to step T + k: keep it while that step is the tile's
-                const int rem = left - 4 * n;
-                aw.w[0] &= rem >= 2 ? 0xffffffffu : (rem == 1 ? 0x0000ffffu : 0u);
-                aw.w[1] &= rem >= 4 ? 0xffffffffu : (rem == 3 ? 0x0000ffffu : 0u);
-            }
-            const s16x4_t av = __builtin_bit_cast(s16x4_t, aw);
-#pragma unroll
-            for (int x = 0; x < NA; ++x) {
-                constexpr int kWrap = 4 * kRing;
-                const int c0 = (WB + 4 * n - 16 * x + kWrap) % kRing;  // position of column 0, constant after unrolling
-                const char* p;
-                if (c0 >= 12) p = u_lane + 2 * c0;
-                else if (c0 == 0) p = u_mix0;
-                else if (c0 == 4) p = u_mix4;
-                else p = u_mix8;
-                const uint2 bw = *reinterpret_cast<const uint2*>(p);
-                Words<2> bb;
-                bb.w[0] = bw.x; bb.w[1] = bw.y;
-                acc[x] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(av, __builtin_bit_cast(s16x4_t, bb), acc[x], 0, 0, 0);
-            }
-        }
+        for (int n = 0; n < kT / 4; ++n) group(WB + 4 * n, left - 4 * n);
     };
 
     // iteration `it` (1 .. nit + 1): its rows go to ring slot it & 3; then the products of iteration it - 1
     auto step = [&](auto slot_c, int it) {
         constexpr int SL = decltype(slot_c)::value;  // it & 3
         constexpr int WB = kT * SL;
+        constexpr int ST = SL % PF;
         {
             const int t = ts32 + (it - 1) * kT + 2 * rp;
-            write_prod(u_lines, kw, vw, t < L32, t + 1 < L32, WB);
-            write_prod(g_lines, yw, qw, t < t_end, t + 1 < t_end, WB);
+            write_prod(u_lines, kw[ST], vw[ST], t < L32, t + 1 < L32, WB);
+            write_prod(g_lines, yw[ST], qw[ST], t < t_end, t + 1 < t_end, WB);
             if constexpr (SL == 0) {  // positions 0..3 once more behind position 255 (read windows do not wrap)
-                if (rp < 2) write_prod(g_lines, yw, qw, t < t_end, t + 1 < t_end, kRing);
+                if (rp < 2) write_prod(g_lines, yw[ST], qw[ST], t < t_end, t + 1 < t_end, kRing);
             }
         }
-        if (it <= nit) load_rows(it + 1);
+        if (it + PF - 1 <= nit) load_rows(std::integral_constant<int, ST>{}, it + PF);
         __syncthreads();
+        if constexpr (SL == 2) {
+            if (it == 2) fill_history();  // the first products: iteration 1, ring slot 1
+        }
         if (it >= 2) products(std::integral_constant<int, kT * ((SL + 3) & 3)>{}, te32 - (ts32 + (it - 2) * kT));
         __syncthreads();
     };
