@@ -116,6 +116,44 @@ def test_backward_entry_points_replay_from_a_graph():
     replay_and_compare(g, plans, eager, refill)
 
 
+def test_shard_entry_points_replay_from_a_graph():
+    say("graph: forward and backward shard calls (windows of full tensors, halos on both sides)")
+    B, L, D, t0, t1 = 2, 900, 128, 300, 700
+    rng = np.random.Generator(np.random.PCG64(93))
+    dy, q, k, v = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(4))
+    h_se = dev(synth.short_filter(rng, D, 7))
+    h_mr = dev(synth.decay_filter(rng, D // 16, 128))
+    h_un = dev(synth.decay_filter(rng, D, 100))
+    w = slice(t0, t1)
+    cases = [("se", h_se, 1, 6), ("mr", h_mr, 16, 127), ("mr", h_un, 1, 99)]
+
+    def build(stream):
+        plans = []
+        for kind, h, group, halo in cases:
+            plans.append(binding.plan_gated_shard("hyena_%s_fwd_shard" % kind, q[:, w], k[:, w], v[:, w], h, group, halo,
+                                                  out=torch.empty_like(q)[:, w], stream=stream))
+            plans.append(binding.plan_bwd_shard("hyena_%s_bwd_shard" % kind, dy[:, w], q[:, w], k[:, w], v[:, w], h, group,
+                                                halo, halo, stream=stream))
+        return plans
+
+    g, plans = capture(build)
+
+    def eager():
+        out = []
+        for kind, h, group, halo in cases:
+            out.append(getattr(binding, "hyena_%s_fwd_shard" % kind)(q[:, w], k[:, w], v[:, w], h, group, halo,
+                                                                     out=torch.empty_like(q)[:, w]))
+            out += list(getattr(binding, "hyena_%s_bwd_shard" % kind)(dy[:, w], q[:, w], k[:, w], v[:, w], h, group,
+                                                                      halo, halo))
+        return out
+
+    def refill(it):
+        for t in (dy, q, k, v):
+            t.copy_(dev(synth.normal_tensor(rng, (B, L, D), "bf16")))
+
+    replay_and_compare(g, plans, eager, refill)
+
+
 def test_entry_points_run_concurrently_on_separate_streams():
     """Two streams issue different entry points back to back (each call with its own outputs and workspace); the
     results must equal those of the same calls issued one after the other on the default stream."""
