@@ -74,6 +74,7 @@ def _load():
         lib.oracle_gated_conv_points.argtypes = [vp, vp, vp, vp, vp, i64, vp] + [i64] * 5 + [ci, ci]
         lib.oracle_chain_points.argtypes = [vp] * 8 + [i64, vp] + [i64] * 7 + [ci, ci]
         lib.oracle_gated_conv_bwd.argtypes = [vp] * 9 + [i64] * 5 + [ci, ci]
+        lib.oracle_causal_conv_bwd.argtypes = [vp] * 5 + [i64] * 5 + [ci, ci]
         lib.oracle_li_recurrent.argtypes = [vp] * 7 + [i64] * 5 + [ci, ci]
         _lib = lib
     return _lib
@@ -234,6 +235,23 @@ def gated_conv_bwd(dy, q, k, v, h, group: int = 1):
     _ok(_load().oracle_gated_conv_bwd(_ptr(ga), _ptr(qa), _ptr(ka), _ptr(va), _ptr(ha), _ptr(dq), _ptr(dk), _ptr(dv),
                                       _ptr(dh), B, L, D, ha.shape[1], group, xd, hd), "oracle_gated_conv_bwd")
     return dq, dk, dv, dh
+
+
+def causal_conv_bwd(dy, x, h, group: int = 1):
+    """Gradients of ``causal_conv`` (the featurizers of Eq. 1) w.r.t. x ([B, L, D]) and h ([D // group, l_h]) given
+    dy: the chain rule of Eq. 2 written out in fp64.  Returns (dx, dh)."""
+    ga, gd = _arr(dy)
+    xa, xd = _arr(x)
+    cd = _same(gd, xd)
+    if ga.shape != xa.shape or xa.ndim != 3:
+        raise ValueError("dy and x must share one [B, L, D] shape")
+    B, L, D = xa.shape
+    ha, hd = _filt(h, D // group if group > 0 and D % group == 0 else -1)
+    dx = np.empty((B, L, D), dtype=np.float64)
+    dh = np.empty(ha.shape, dtype=np.float64)
+    _ok(_load().oracle_causal_conv_bwd(_ptr(ga), _ptr(xa), _ptr(ha), _ptr(dx), _ptr(dh), B, L, D, ha.shape[1], group,
+                                       cd, hd), "oracle_causal_conv_bwd")
+    return dx, dh
 
 
 def li_filter(R, lam, L: int) -> np.ndarray:

@@ -270,6 +270,49 @@ int oracle_gated_conv_bwd(const void *dy, const void *q, const void *k, const vo
 }
 
 /*
+ * Backward of oracle_causal_conv, the featurizer convolutions of Eq. 1 (x' = h * x with Eq. 2, no gates): the
+ * chain rule of that definition, given dy = dLoss/dx', term by term in fp64:
+ *     dx[s]     = sum_{j<lh, s+j<L} h[j] * dy[s+j]            (the transposed, anti-causal convolution)
+ *     dh[g', j] = sum_b sum_{c in group g'} sum_{t>=j} dy[b,t,c] * x[b,t-j,c]
+ * dx: [B,L,D] fp64; dh: [D/dg, lh] fp64.
+ */
+int oracle_causal_conv_bwd(const void *dy, const void *x, const void *h, double *dx, double *dh, int64_t B,
+                           int64_t L, int64_t D, int64_t lh, int64_t dg, int x_dtype, int h_dtype)
+{
+    int rc = orc_check(dy, x, h, B, L, D, lh, dg, x_dtype, h_dtype);
+    if (rc)
+        return rc;
+    if (!dx || !dh)
+        return 1;
+    int64_t rows = B * L;
+    int64_t G = D / dg;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        int64_t b = r / L, s = r % L;
+        for (int64_t c = 0; c < D; ++c) {
+            int64_t g = c / dg;
+            double acc = 0.0;
+            for (int64_t j = 0; j < lh && s + j < L; ++j)
+                acc += orc_load(h, h_dtype, (size_t)(g * lh + j)) * orc_load(dy, x_dtype, (size_t)((b * L + (s + j)) * D + c));
+            dx[(size_t)(r * D + c)] = acc;
+        }
+    }
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t g = 0; g < G; ++g) {
+        for (int64_t j = 0; j < lh; ++j) {
+            double acc = 0.0;
+            for (int64_t b = 0; b < B; ++b)
+                for (int64_t c = g * dg; c < (g + 1) * dg; ++c)
+                    for (int64_t t = j; t < L; ++t)
+                        acc += orc_load(dy, x_dtype, (size_t)((b * L + t) * D + c)) *
+                               orc_load(x, x_dtype, (size_t)((b * L + (t - j)) * D + c));
+            dh[(size_t)(g * lh + j)] = acc;
+        }
+    }
+    return 0;
+}
+
+/*
  * Hyena-LI in its recurrent form (Sec. 2.1: the long implicit filter is a sum of real exponentials,
  * h_t = sum_n R_n lambda_n^(t-1), t from 1, and the operator can be evaluated as a recurrence).  Per channel c with
  * group g = c / dg and u = k (.) v:

@@ -125,3 +125,88 @@ def test_batch_and_group_sums_in_filter_gradient():
     np.testing.assert_allclose(dh, per_item, rtol=0, atol=1e-12)
     per_chan = oracle.gated_conv_bwd(dy, q, k, v, np.repeat(h, group, axis=0), group=1)[3]
     np.testing.assert_allclose(dh, per_chan.reshape(D // group, group, lh).sum(axis=1), rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------- featurizer backward
+@pytest.mark.parametrize("B,L,D,lh,group", [(1, 6, 2, 3, 1), (2, 7, 4, 4, 2), (1, 5, 4, 8, 4), (2, 4, 2, 1, 1)])
+def test_featurizer_backward_is_the_adjoint_of_the_forward_on_every_basis_vector(B, L, D, lh, group):
+    """The forward x -> h * x is linear in x and in h, so its gradient given dy is fixed element by element:
+    dx[i] = <dy, h * e_i> and dh[m] = <dy, e_m * x>, computed here with the pinned forward oracle on unit inputs."""
+    r = rng(700 + L + lh)
+    x, dy = r.standard_normal((B, L, D)), r.standard_normal((B, L, D))
+    h = r.standard_normal((D // group, lh))
+    dx, dh = oracle.causal_conv_bwd(dy, x, h, group=group)
+    want_dx = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        e = np.zeros_like(x)
+        e[idx] = 1.0
+        want_dx[idx] = np.sum(dy * oracle.causal_conv(e, h, group=group))
+    want_dh = np.zeros_like(h)
+    for idx in np.ndindex(*h.shape):
+        e = np.zeros_like(h)
+        e[idx] = 1.0
+        want_dh[idx] = np.sum(dy * oracle.causal_conv(x, e, group=group))
+    np.testing.assert_allclose(dx, want_dx, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dh, want_dh, rtol=0, atol=1e-12)
+
+
+def test_featurizer_backward_against_numpy_correlations():
+    """Per channel: dx is dy correlated with h (np.correlate, taps reaching forward in time), dh[j] the lag-j
+    correlation of dy with x, summed over the batch and the channels of a group."""
+    r = rng(711)
+    B, L, D, lh, group = 2, 40, 6, 7, 3
+    x, dy = r.standard_normal((B, L, D)), r.standard_normal((B, L, D))
+    h = r.standard_normal((D // group, lh))
+    dx, dh = oracle.causal_conv_bwd(dy, x, h, group=group)
+    want_dh = np.zeros_like(h)
+    for b in range(B):
+        for c in range(D):
+            g = c // group
+            full = np.correlate(np.concatenate([dy[b, :, c], np.zeros(lh - 1)]), h[g], mode="valid")
+            np.testing.assert_allclose(dx[b, :, c], full, rtol=0, atol=1e-12)
+            for j in range(lh):
+                want_dh[g, j] += np.dot(dy[b, j:, c], x[b, :L - j, c])
+    np.testing.assert_allclose(dh, want_dh, rtol=0, atol=1e-11)
+
+
+def test_featurizer_backward_is_the_gated_backward_with_unit_gates():
+    """With q = v = 1 the gated operator is the featurizer of k, so dk and dh of the (separately pinned) gated
+    backward are dx and dh."""
+    r = rng(712)
+    B, L, D, lh, group = 2, 30, 8, 5, 2
+    x, dy = r.standard_normal((B, L, D)), r.standard_normal((B, L, D))
+    h = r.standard_normal((D // group, lh))
+    one = np.ones_like(x)
+    _, dk, _, dh_g = oracle.gated_conv_bwd(dy, one, x, one, h, group=group)
+    dx, dh = oracle.causal_conv_bwd(dy, x, h, group=group)
+    np.testing.assert_allclose(dx, dk, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dh, dh_g, rtol=0, atol=1e-12)
+
+
+def test_featurizer_backward_closed_forms():
+    """A filter that is one tap at lag j0 shifts: dx[s] = dy[s + j0] (zero past the end); with dy = x = 1 the filter
+    gradient counts the terms: dh[g, j] = B * group * (L - j), zero once the lag reaches L."""
+    B, L, D, lh, group, j0 = 2, 9, 4, 12, 2, 3
+    r = rng(713)
+    dy = r.standard_normal((B, L, D))
+    h = np.zeros((D // group, lh))
+    h[:, j0] = 1.0
+    dx, _ = oracle.causal_conv_bwd(dy, np.zeros_like(dy), h, group=group)
+    want = np.zeros_like(dy)
+    want[:, :L - j0] = dy[:, j0:]
+    np.testing.assert_array_equal(dx, want)
+    one = np.ones((B, L, D))
+    _, dh = oracle.causal_conv_bwd(one, one, h, group=group)
+    np.testing.assert_array_equal(dh, np.tile(np.maximum(L - np.arange(lh), 0) * B * group, (D // group, 1)).astype(float))
+
+
+def test_featurizer_backward_reads_bf16_and_fp32_inputs_exactly():
+    r = rng(714)
+    B, L, D, lh = 1, 20, 4, 4
+    x32 = r.standard_normal((B, L, D)).astype(np.float32)
+    dy32 = r.standard_normal((B, L, D)).astype(np.float32)
+    h = r.standard_normal((D, lh)).astype(np.float32)
+    a = oracle.causal_conv_bwd(dy32, x32, h)
+    b = oracle.causal_conv_bwd(dy32.astype(np.float64), x32.astype(np.float64), h.astype(np.float64))
+    for u, w in zip(a, b):
+        np.testing.assert_array_equal(u, w)

@@ -28,6 +28,11 @@ MUTATIONS = [
     ("dk and dv swapped", "dk[at] = du * orc_load(v, x_dtype, at);", "dk[at] = du * orc_load(k, x_dtype, at);", 1),
     ("dh lag sign", "size_t src = (size_t)((b * L + (t - j)) * D + c);\n                        s +=", "size_t src = (size_t)((b * L + (t - j)) * D + c); src = (size_t)((b * L + (L - 1 - t + j)) * D + c);\n                        s +=", 1),
     ("dq misses the upstream gradient", "dq[at] = orc_load(dy, x_dtype, at) * z;", "dq[at] = z;", 1),
+    ("featurizer dx reaches back instead of forward", "(b * L + (s + j)) * D + c", "(b * L + (s - j >= 0 ? s - j : s)) * D + c", 1),
+    ("featurizer dx one tap short", "j < lh && s + j < L", "j < lh - 1 && s + j < L", 1),
+    ("featurizer dx clipped at the sequence start like the forward", "j < lh && s + j < L; ++j)", "j < lh && s + j < L && j <= s; ++j)", 1),
+    ("featurizer dh starts at lag 0 rows", "for (int64_t t = j; t < L; ++t)\n                        acc +=", "for (int64_t t = j + 1; t < L; ++t)\n                        acc +=", 1),
+    ("featurizer dh forgets the group's channels", "for (int64_t c = g * dg; c < (g + 1) * dg; ++c)\n                    for (int64_t t = j; t < L; ++t)\n                        acc +=", "for (int64_t c = g * dg; c < g * dg + 1; ++c)\n                    for (int64_t t = j; t < L; ++t)\n                        acc +=", 1),
 ]
 
 
@@ -40,6 +45,7 @@ def build(src_text, tmp_path, tag):
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.oracle_gated_conv.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci, ci]
     lib.oracle_gated_conv_bwd.argtypes = [vp] * 9 + [i64] * 5 + [ci, ci]
+    lib.oracle_causal_conv_bwd.argtypes = [vp] * 5 + [i64] * 5 + [ci, ci]
     return lib
 
 
@@ -74,6 +80,16 @@ def disagreements(lib):
             bad += not np.allclose(dv[b, :, c], du * k[b, :, c], atol=1e-10)
             dh_ref[c // dg] += np.correlate(g, u, mode="full")[L - 1:L - 1 + lh]
     bad += not np.allclose(dh, dh_ref, atol=1e-9)
+    # featurizer backward: dx and dh of x -> h * x
+    dx = np.empty((B, L, D))
+    dhf = np.empty((D // dg, lh))
+    assert lib.oracle_causal_conv_bwd(ptr(dy), ptr(k), ptr(h), ptr(dx), ptr(dhf), B, L, D, lh, dg, 0, 0) == 0
+    dhf_ref = np.zeros_like(dhf)
+    for b in range(B):
+        for c in range(D):
+            bad += not np.allclose(dx[b, :, c], np.convolve(dy[b, ::-1, c], h[c // dg])[:L][::-1], atol=1e-10)
+            dhf_ref[c // dg] += np.correlate(dy[b, :, c], k[b, :, c], mode="full")[L - 1:L - 1 + lh]
+    bad += not np.allclose(dhf, dhf_ref, atol=1e-9)
     return bad
 
 
