@@ -254,6 +254,19 @@ def causal_conv_bwd(dy, x, h, group: int = 1):
     return dx, dh
 
 
+def chain_bwd(dy, q, k, v, hq, hk, hv, h, group: int = 1, feat_group: int = 1):
+    """Gradients of ``chain`` w.r.t. q, k, v and the four filters given dy: the chain rule of Eq. 1 through the two
+    backward functions above, intermediates in fp64.  Returns (dq, dk, dv, dhq, dhk, dhv, dh)."""
+    qf = causal_conv(q, hq, feat_group)
+    kf = causal_conv(k, hk, feat_group)
+    vf = causal_conv(v, hv, feat_group)
+    dqf, dkf, dvf, dh = gated_conv_bwd(_wide(dy), qf, kf, vf, h, group)
+    dq, dhq = causal_conv_bwd(dqf, _wide(q), hq, feat_group)
+    dk, dhk = causal_conv_bwd(dkf, _wide(k), hk, feat_group)
+    dv, dhv = causal_conv_bwd(dvf, _wide(v), hv, feat_group)
+    return dq, dk, dv, dhq, dhk, dhv, dh
+
+
 def li_filter(R, lam, L: int) -> np.ndarray:
     """Hyena-LI inner filter (Sec. 2.1, "long implicit"): a sum of real exponentials per filter group,
     ``h[g, j] = sum_n R[g, n] * lam[g, n] ** j`` for j = 0 .. L-1, i.e. the paper's ``h_t = sum_n R_n lambda_n^(t-1)``

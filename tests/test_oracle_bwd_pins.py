@@ -210,3 +210,50 @@ def test_featurizer_backward_reads_bf16_and_fp32_inputs_exactly():
     b = oracle.causal_conv_bwd(dy32.astype(np.float64), x32.astype(np.float64), h.astype(np.float64))
     for u, w in zip(a, b):
         np.testing.assert_array_equal(u, w)
+
+
+# ---------------------------------------------------------------------------------------- chain backward
+@pytest.mark.parametrize("B,L,D,lf,fg,lh,group", [(1, 8, 2, 3, 1, 4, 1), (2, 9, 4, 2, 2, 6, 4), (1, 6, 4, 4, 1, 9, 2)])
+def test_chain_backward_matches_central_finite_differences_of_the_chain(B, L, D, lf, fg, lh, group):
+    """The chain is linear in each of q, k, v, hq, hk, hv, h separately, so a central difference of the (pinned)
+    forward chain in one argument is exact up to rounding."""
+    r = rng(900 + L + lh)
+    q, k, v, w = (r.standard_normal((B, L, D)) for _ in range(4))
+    hq, hk, hv = (r.standard_normal((D // fg, lf)) for _ in range(3))
+    h = r.standard_normal((D // group, lh))
+    grads = oracle.chain_bwd(w, q, k, v, hq, hk, hv, h, group=group, feat_group=fg)
+    args = [q, k, v, hq, hk, hv, h]
+    eps = 1e-3
+
+    def f():
+        return float(np.sum(w * oracle.chain(*args, group=group, feat_group=fg)))
+
+    for name, arr, grad in zip(("q", "k", "v", "hq", "hk", "hv", "h"), args, grads):
+        num = np.zeros_like(arr)
+        for idx in np.ndindex(*arr.shape):
+            old = arr[idx]
+            arr[idx] = old + eps
+            lp = f()
+            arr[idx] = old - eps
+            lm = f()
+            arr[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        np.testing.assert_allclose(grad, num, rtol=0, atol=1e-8, err_msg=name)
+
+
+def test_chain_backward_with_identity_featurizers_is_the_gated_backward():
+    """Featurizers that are a single unit tap at lag 0 leave q, k, v unchanged: dq, dk, dv and dh are those of the
+    gated operator, and the featurizer gradients at tap 0 are <dq, q>, <dk, k>, <dv, v> per channel."""
+    r = rng(950)
+    B, L, D, lf, lh, group = 2, 12, 4, 3, 5, 2
+    q, k, v, dy = (r.standard_normal((B, L, D)) for _ in range(4))
+    h = r.standard_normal((D // group, lh))
+    ident = np.zeros((D, lf))
+    ident[:, 0] = 1.0
+    dq, dk, dv, dhq, dhk, dhv, dh = oracle.chain_bwd(dy, q, k, v, ident, ident, ident, h, group=group, feat_group=1)
+    want = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for a, b in zip((dq, dk, dv, dh), want):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dhq[:, 0], np.sum(want[0] * q, axis=(0, 1)), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dhk[:, 0], np.sum(want[1] * k, axis=(0, 1)), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dhv[:, 0], np.sum(want[2] * v, axis=(0, 1)), rtol=0, atol=1e-11)
