@@ -9,7 +9,8 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c3  Hyena-MR  bf16 B1 L131072 D4096 lh128 group16  hyena_mr_fwd
   c4  chain     bf16 B4 L32768  D4096                hyena_chain_fwd (featurizers + MR in one kernel)
   c1_bwd / c2_bwd / c3_bwd / c2u_bwd: the backward entry points (hyena_se_bwd / hyena_mr_bwd) on the shapes of
-      c1 / c2 / c3 / c2u
+      c1 / c2 / c3 / c2u; c4_bwd: hyena_chain_bwd on c4's shape (featurizers recomputed, inner backward, three
+      featurizer backward calls; 6 tensors of workspace)
   c1_shards / c2_shards / c3_shards: c1 / c2 / c3 computed as four consecutive sequence shards (hyena_se_fwd_shard /
       hyena_mr_fwd_shard: each call sees its quarter of the steps plus the lh - 1 rows of k and v before it), the
       compute half of a sequence-sharded run on one GPU; a step is the four launches.  c3_bwd_shards: the same for
@@ -55,7 +56,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
                     choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "c1_shards",
-                             "c2_shards", "c3_shards", "c1_bwd_shards", "c3_bwd_shards", "copy"] + list(YARDSTICKS),
+                             "c2_shards", "c3_shards", "c1_bwd_shards", "c3_bwd_shards", "c4_bwd", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "
@@ -137,7 +138,12 @@ class Workload:
                 grads = torch.empty((3,) + tuple(d["q"].shape), dtype=d["q"].dtype, device="cuda")
                 d["dq"], d["dk"], d["dv"] = grads[0], grads[1], grads[2]
                 d["dh"] = torch.empty_like(d["h"])
-                if self.shards:
+                if c["kind"] == "chain":
+                    d["dhf"] = [torch.empty_like(d["hq"]) for _ in range(3)]
+                    self.main.append(pkg.plan_chain_bwd(d["dy"], d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"], d["h"],
+                                                        c["group"], c["feat_group"],
+                                                        out=(d["dq"], d["dk"], d["dv"]) + tuple(d["dhf"]) + (d["dh"],)))
+                elif self.shards:
                     # the sequence as consecutive shard calls: lh - 1 rows of k, v before and of dy, q behind each
                     # shard; every call leaves its share of dh in a buffer of its own
                     entry = "hyena_se_bwd_shard" if c["kind"] == "se" else "hyena_mr_bwd_shard"
@@ -240,7 +246,10 @@ class Workload:
             return (4.0 * self.cfg["order"] + 2.0) * self.n_out
         f = 2.0 * self.cfg["lh"] + 2.0
         if self.bwd:
-            return (3 * 2.0 * self.cfg["lh"] + 5.0) * self.n_out  # z, du, dh contractions + five gates
+            f = 3 * 2.0 * self.cfg["lh"] + 5.0  # z, du, dh contractions + five gates
+            if self.cfg["kind"] == "chain":
+                f += 3 * 3 * 2.0 * self.cfg["lf"]  # per featurizer: the recomputed forward, dx and its filter gradient
+            return f * self.n_out
         if self.cfg["kind"] == "chain":
             f += 3 * 2.0 * self.cfg["lf"]
         return f * self.n_out
@@ -258,7 +267,12 @@ def cpu_baseline(wl, target_s, np, oracle):
         if wl.bwd:
             # dq[t] only looks at the past, so the first rows of the slice's dq equal those of the full problem
             dy = w["dy"][:1, :rows].contiguous()
-            y = oracle.gated_conv_bwd(dy, q, k, v, w["h"], group=c["group"])[0]
+            if c["kind"] == "chain":
+                # ... except for the last lf - 1 rows, which the featurizer's transpose reaches past
+                y = oracle.chain_bwd(dy, q, k, v, w["hq"], w["hk"], w["hv"], w["h"], group=c["group"],
+                                     feat_group=c["feat_group"])[0][:, :max(rows - (c["lf"] - 1), 1)]
+            else:
+                y = oracle.gated_conv_bwd(dy, q, k, v, w["h"], group=c["group"])[0]
         elif c["kind"] == "li":
             y = oracle.li_conv(q, k, v, w["R"], w["lam"], group=c["group"])
         elif c["kind"] == "chain":
@@ -419,7 +433,7 @@ def main():
         wl.i = 0
         wl.step()
         torch.cuda.synchronize()
-        got = (d["dq"] if wl.bwd else d["y"])[:1, :rows].float().cpu().numpy().astype(np.float64)
+        got = (d["dq"] if wl.bwd else d["y"])[:1, :y_ref.shape[1]].float().cpu().numpy().astype(np.float64)
         out["parity_rel_err"] = oracle.rel_err(got, y_ref)
 
     if args.workload == "c1" and args.also and args.seq_len <= 0:

@@ -282,6 +282,43 @@ hy_status hyena_mr_bwd(const void *dy, const void *q, const void *k, const void 
 int64_t hyena_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype);
 
 /*
+ * Backward of hyena_featurize_fwd: the featurizer convolutions of Eq. 1 (x' = h * x with Eq. 2, no gates) under
+ * the chain rule, with the two-pass filter gradient of App. A.4.  Given dy = dLoss/dx':
+ *     dx[b,s,c] = sum_{j<lh, s+j<L} h[c/group, j] * dy[b,s+j,c]
+ *     dh[g, j]  = sum_b sum_{c in group g} sum_{t>=j} dy[b,t,c] * x[b,t-j,c]
+ * dy, x, dx: device, [B, L, D] row-major of `dtype`, 16-byte aligned, dx distinct from dy and x; h, dh: device,
+ * fp32 [D/group, lh], dh distinct from everything else (overlaps: HY_ERR_ALIGN).  Arithmetic as in
+ * hyena_se_bwd: fp32 FMA chains in ascending tap order, one rounding per stored element of dx, fp32 partial filter
+ * gradients per tile summed in fp64.  Filters of up to 8 taps run one fused streaming pass and need
+ * hyena_featurize_bwd_workspace_bytes(...) bytes of device workspace (16-byte aligned, not overlapping any
+ * argument; too small: HY_ERR_SHAPE); longer filters take the general kernels and need none.  An empty problem
+ * (B, L or D zero) writes a zero dh and nothing else.  Asynchronous on hip_stream; never allocates.
+ */
+hy_status hyena_featurize_bwd(const void *dy, const void *x, const float *h, void *dx, float *dh, void *workspace,
+                              int64_t workspace_bytes, int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group,
+                              int32_t dtype, void *hip_stream);
+int64_t hyena_featurize_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype);
+
+/*
+ * Backward of hyena_chain_fwd (Eq. 1 as a whole: q' = hq * q, k' = hk * k, v' = hv * v, y = q' (.) (h * (k' (.) v')))
+ * by the chain rule, as a composition of the calls above on the caller's stream: hyena_featurize3_fwd recomputes
+ * q', k', v'; hyena_mr_bwd gives dq', dk', dv' and dh; hyena_featurize_bwd, once per tensor, gives dq, dk, dv and
+ * dhq, dhk, dhv.  The intermediate tensors live in the workspace in the activations' dtype (for bf16 they are
+ * rounded to bf16 between the steps, as the forward's two-kernel path rounds q', k', v').
+ * dy, q, k, v, dq, dk, dv: device, [B, L, D] of `dtype`; hq, hk, hv, dhq, dhk, dhv: fp32 [D/feat_group, lf];
+ * h, dh: fp32 [D/group, lh]; the usual alignment and overlap rules (every gradient distinct from everything else).
+ * workspace: hyena_chain_bwd_workspace_bytes(...) bytes (six tensors plus what the inner calls need), 16-byte
+ * aligned, disjoint from every argument; too small: HY_ERR_SHAPE.  An empty problem writes zero filter gradients.
+ */
+hy_status hyena_chain_bwd(const void *dy, const void *q, const void *k, const void *v, const float *hq,
+                          const float *hk, const float *hv, const float *h, void *dq, void *dk, void *dv,
+                          float *dhq, float *dhk, float *dhv, float *dh, void *workspace, int64_t workspace_bytes,
+                          int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh,
+                          int32_t group, int32_t dtype, void *hip_stream);
+int64_t hyena_chain_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh,
+                                        int32_t group, int32_t dtype);
+
+/*
  * One rank's share of a sequence-sharded backward call (Sec. 4, point-to-point scheme; App. A.4).  Same
  * gradients as hyena_se_bwd / hyena_mr_bwd on the shard's L steps, with the neighbours' steps where the chain
  * rule reaches across the cuts: dq needs k and v of the `history` rows in front of row 0 (as the forward shard

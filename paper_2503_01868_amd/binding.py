@@ -56,6 +56,12 @@ def lib() -> ctypes.CDLL:
         L.hyena_mr_bwd_shard.argtypes = bwd_shard_args
         L.hyena_bwd_shard_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_bwd_shard_workspace_bytes.restype = i64
+        L.hyena_featurize_bwd.argtypes = [vp] * 6 + [i64, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_featurize_bwd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
+        L.hyena_featurize_bwd_workspace_bytes.restype = i64
+        L.hyena_chain_bwd.argtypes = [vp] * 16 + [i64, i64, i64, i64, i32, i32, i32, i32, ci, vp]
+        L.hyena_chain_bwd_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, i32, i32, ci]
+        L.hyena_chain_bwd_workspace_bytes.restype = i64
         L.hyena_li_fwd.argtypes = [vp] * 7 + [i64, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_li_fwd_static.argtypes = [vp] * 6 + [i64, i64, i64, i32, i32, ci, vp]
         L.hyena_li_fwd_carry.argtypes = [vp] * 9 + [i64, i64, i64, i64, i32, i32, ci, vp]
@@ -68,7 +74,8 @@ def lib() -> ctypes.CDLL:
         L.hyena_set_option.argtypes = [ctypes.c_char_p, i32]
         for name in ("hyena_se_fwd", "hyena_mr_fwd", "hyena_se_fwd_shard", "hyena_mr_fwd_shard", "hyena_featurize_fwd",
                      "hyena_featurize3_fwd",
-                     "hyena_chain_fwd", "hyena_chain_fwd_shard", "hyena_se_bwd", "hyena_mr_bwd", "hyena_se_bwd_shard", "hyena_mr_bwd_shard", "hyena_li_fwd",
+                     "hyena_chain_fwd", "hyena_chain_fwd_shard", "hyena_se_bwd", "hyena_mr_bwd", "hyena_se_bwd_shard",
+                     "hyena_mr_bwd_shard", "hyena_featurize_bwd", "hyena_chain_bwd", "hyena_li_fwd",
                      "hyena_li_fwd_static", "hyena_li_fwd_carry",
                      "hyena_stream_copy", "hyena_stream_gate", "hyena_set_option"):
             getattr(L, name).restype = ci
@@ -473,6 +480,78 @@ def hyena_se_bwd(dy, q, k, v, h, group: int = 1, workspace=None, stream=None):
 def hyena_mr_bwd(dy, q, k, v, h, group: int = 16, workspace=None, stream=None):
     """(dq, dk, dv, dh) of ``hyena_mr_fwd``; see ``hyena_mr_bwd`` in hyena.h."""
     return _bwd("hyena_mr_bwd", dy, q, k, v, h, group, workspace, stream)
+
+
+def plan_featurize_bwd(dy, x, h, group: int = 1, out=None, workspace=None, stream=None) -> Plan:
+    """Marshal one ``hyena_featurize_bwd`` call for repeated issue; ``out`` = (dx, dh)."""
+    _check_act("dy", dy)
+    _check_act("x", x, dy)
+    lh = _check_filter("h", h, dy, group)
+    B, L, D = dy.shape
+    code = _dtype_code(dy)
+    need = int(lib().hyena_featurize_bwd_workspace_bytes(B, L, D, lh, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid backward problem")
+    if need > 0 and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dy.device)  # device memory from PyTorch
+    if out is None:
+        out = (torch.empty_like(dy), torch.empty_like(h))
+    _check_act("dx", out[0], dy)
+    _check_filter("dh", out[1], dy, group)
+    c = ctypes
+    ws_ptr = workspace.data_ptr() if need > 0 else None
+    ws_bytes = workspace.numel() * workspace.element_size() if need > 0 else 0
+    args = tuple(c.c_void_p(t.data_ptr()) for t in (dy, x, h) + tuple(out)) + (
+        c.c_void_p(ws_ptr), c.c_int64(ws_bytes), c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lh),
+        c.c_int32(int(group)), c.c_int(code), c.c_void_p(_stream(dy, stream)))
+    return Plan(lib().hyena_featurize_bwd, args, "hyena_featurize_bwd", (dy, x, h, workspace) + tuple(out), tuple(out))
+
+
+def hyena_featurize_bwd(dy, x, h, group: int = 1, workspace=None, stream=None):
+    """(dx, dh) of ``hyena_featurize_fwd``; see ``hyena_featurize_bwd`` in hyena.h."""
+    with torch.cuda.device(dy.device):
+        return plan_featurize_bwd(dy, x, h, group, None, workspace, stream)()
+
+
+def plan_chain_bwd(dy, q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, out=None, workspace=None,
+                   stream=None) -> Plan:
+    """Marshal one ``hyena_chain_bwd`` call for repeated issue; ``out`` = (dq, dk, dv, dhq, dhk, dhv, dh)."""
+    _check_act("dy", dy)
+    _check_act("q", q, dy)
+    _check_act("k", k, dy)
+    _check_act("v", v, dy)
+    lf = _check_filter("hq", hq, dy, feat_group)
+    if _check_filter("hk", hk, dy, feat_group) != lf or _check_filter("hv", hv, dy, feat_group) != lf:
+        raise ValueError("the three featurizer filters must share one length")
+    lh = _check_filter("h", h, dy, group)
+    B, L, D = dy.shape
+    code = _dtype_code(dy)
+    need = int(lib().hyena_chain_bwd_workspace_bytes(B, L, D, lf, int(feat_group), lh, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid chain problem")
+    if need > 0 and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dy.device)  # device memory from PyTorch
+    if out is None:
+        out = tuple(torch.empty_like(dy) for _ in range(3)) + tuple(torch.empty_like(f) for f in (hq, hk, hv, h))
+    for name, o in zip(("dq", "dk", "dv"), out[:3]):
+        _check_act(name, o, dy)
+    for name, o in zip(("dhq", "dhk", "dhv"), out[3:6]):
+        _check_filter(name, o, dy, feat_group)
+    _check_filter("dh", out[6], dy, group)
+    c = ctypes
+    ws_ptr = workspace.data_ptr() if need > 0 else None
+    ws_bytes = workspace.numel() * workspace.element_size() if need > 0 else 0
+    args = tuple(c.c_void_p(t.data_ptr()) for t in (dy, q, k, v, hq, hk, hv, h) + tuple(out)) + (
+        c.c_void_p(ws_ptr), c.c_int64(ws_bytes), c.c_int64(B), c.c_int64(L), c.c_int64(D), c.c_int32(lf),
+        c.c_int32(int(feat_group)), c.c_int32(lh), c.c_int32(int(group)), c.c_int(code), c.c_void_p(_stream(dy, stream)))
+    return Plan(lib().hyena_chain_bwd, args, "hyena_chain_bwd", (dy, q, k, v, hq, hk, hv, h, workspace) + tuple(out),
+                tuple(out))
+
+
+def hyena_chain_bwd(dy, q, k, v, hq, hk, hv, h, group: int = 16, feat_group: int = 1, workspace=None, stream=None):
+    """(dq, dk, dv, dhq, dhk, dhv, dh) of ``hyena_chain_fwd``; see ``hyena_chain_bwd`` in hyena.h."""
+    with torch.cuda.device(dy.device):
+        return plan_chain_bwd(dy, q, k, v, hq, hk, hv, h, group, feat_group, None, workspace, stream)()
 
 
 def plan_li(q, k, v, R, lam, group: int = 16, out=None, workspace=None, stream=None) -> Plan:

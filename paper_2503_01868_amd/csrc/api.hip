@@ -12,14 +12,19 @@ namespace {
 std::mutex g_tuning_mu;
 Tuning g_tuning;                   // process-wide options, guarded by g_tuning_mu
 thread_local Tuning t_tuning;      // what the entry point running on this thread sees
+thread_local int t_depth = 0;      // entry points on this thread's stack (one that is composed of others nests)
 }  // namespace
 
 const Tuning& tuning() { return t_tuning; }
 
+// Only the outermost entry point copies: the calls it is composed of see the options it saw.
 TuningSnapshot::TuningSnapshot() {
-    std::lock_guard<std::mutex> lock(g_tuning_mu);
-    t_tuning = g_tuning;
+    if (t_depth++ == 0) {
+        std::lock_guard<std::mutex> lock(g_tuning_mu);
+        t_tuning = g_tuning;
+    }
 }
+TuningSnapshot::~TuningSnapshot() { --t_depth; }
 
 namespace {
 
@@ -102,7 +107,7 @@ hy_status validate(const void* const* ins, int n_in, void* const* outs, int n_ou
     if (B > 0 && L > 0 && D > 0) {
         if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > INT64_MAX / esz) return HY_ERR_SHAPE;
         const int64_t bytes = B * L * D * esz;
-        Range rd[8], wr[4];
+        Range rd[16], wr[4];
         int n_rd = 0;
         for (int i = 0; i < n_in; ++i) rd[n_rd++] = Range{ins[i], bytes};
         for (int i = 0; i < n_h; ++i)
@@ -591,6 +596,129 @@ hy_status hyena_mr_bwd(const void* dy, const void* q, const void* k, const void*
                        void* dv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D,
                        int32_t lh, int32_t group, int32_t dtype, void* hip_stream) {
     return gated_bwd(dy, q, k, v, h, dq, dk, dv, dh, workspace, workspace_bytes, B, L, D, lh, group, dtype, hip_stream);
+}
+
+int64_t hyena_featurize_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group, int32_t dtype) {
+    TuningSnapshot snap;
+    if (B < 0 || L < 0 || D < 0 || lh < 1 || group < 1 || D % group != 0) return -1;
+    if (dtype != HY_F32 && dtype != HY_BF16) return -1;
+    if (empty(B, L, D)) return 0;
+    BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
+    s.gated = false;
+    return bwd_stencil_supported(s) ? bwd_stencil_workspace_bytes(s) : 0;
+}
+
+hy_status hyena_featurize_bwd(const void* dy, const void* x, const float* h, void* dx, float* dh, void* workspace,
+                              int64_t workspace_bytes, int64_t B, int64_t L, int64_t D, int32_t lh, int32_t group,
+                              int32_t dtype, void* hip_stream) {
+    TuningSnapshot snap;
+    const void* ins[2] = {dy, x};
+    void* outs[1] = {dx};
+    const FilterArg hs[2] = {{h, group, lh}, {dh, group, lh}};
+    hy_status rc = validate(ins, 2, outs, 1, hs, 2, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (workspace_bytes < 0) return HY_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t nh = filter_bytes(D, group, lh);
+    const int64_t bytes = B * L * D * (dtype == HY_F32 ? 4 : 2);
+    // dh is written: disjoint from the filter and from every activation, read or written
+    const Range reads[4] = {{h, nh}, {dy, bytes}, {x, bytes}, {dx, bytes}};
+    const Range dh_range{dh, nh};
+    if (check_disjoint(reads, 4, &dh_range, 1) != HY_OK) return HY_ERR_ALIGN;
+    if (empty(B, L, D)) return launch_bwd_zero_dh(dh, D, lh, group, st);
+    BwdPtrs p{dy, nullptr, x, nullptr, h, nullptr, dx, nullptr, dh};
+    BwdShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype)};
+    s.gated = false;
+    if (bwd_stencil_supported(s)) {
+        const Range others[5] = {{dy, bytes}, {x, bytes}, {dx, bytes}, {h, nh}, {dh, nh}};
+        rc = check_workspace(workspace, workspace_bytes, bwd_stencil_workspace_bytes(s), others, 5);
+        if (rc != HY_OK) return rc;
+        return launch_bwd_stencil(p, s, workspace, st);
+    }
+    return launch_bwd_direct(p, s, st);
+}
+
+// The operator chain's backward as a composition of the calls above, through the caller's workspace:
+// [q', k', v' | dq', dk', dv' | workspace of the inner calls].
+namespace {
+int64_t align256(int64_t n) { return (n + 255) / 256 * 256; }
+int64_t chain_bwd_inner_ws(int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh, int32_t group,
+                           int32_t dtype) {
+    const int64_t a = hyena_bwd_workspace_bytes(B, L, D, lh, group, dtype);
+    const int64_t b = hyena_featurize_bwd_workspace_bytes(B, L, D, lf, feat_group, dtype);
+    if (a < 0 || b < 0) return -1;
+    return a > b ? a : b;
+}
+}  // namespace
+
+int64_t hyena_chain_bwd_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t lf, int32_t feat_group, int32_t lh,
+                                        int32_t group, int32_t dtype) {
+    TuningSnapshot snap;
+    if (B < 0 || L < 0 || D < 0 || lf < 1 || lh < 1 || feat_group < 1 || group < 1) return -1;
+    if (D % group != 0 || D % feat_group != 0) return -1;
+    if (dtype != HY_F32 && dtype != HY_BF16) return -1;
+    if (empty(B, L, D)) return 0;
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    if (L > INT64_MAX / D || B > INT64_MAX / (L * D) || B * L * D > (INT64_MAX / 8) / esz) return -1;
+    const int64_t inner = chain_bwd_inner_ws(B, L, D, lf, feat_group, lh, group, dtype);
+    if (inner < 0) return -1;
+    return 6 * align256(B * L * D * esz) + inner;
+}
+
+hy_status hyena_chain_bwd(const void* dy, const void* q, const void* k, const void* v, const float* hq, const float* hk,
+                          const float* hv, const float* h, void* dq, void* dk, void* dv, float* dhq, float* dhk,
+                          float* dhv, float* dh, void* workspace, int64_t workspace_bytes, int64_t B, int64_t L,
+                          int64_t D, int32_t lf, int32_t feat_group, int32_t lh, int32_t group, int32_t dtype,
+                          void* hip_stream) {
+    TuningSnapshot snap;
+    const void* ins[4] = {dy, q, k, v};
+    void* outs[3] = {dq, dk, dv};
+    const FilterArg hs[8] = {{hq, feat_group, lf}, {hk, feat_group, lf}, {hv, feat_group, lf}, {h, group, lh},
+                             {dhq, feat_group, lf}, {dhk, feat_group, lf}, {dhv, feat_group, lf}, {dh, group, lh}};
+    hy_status rc = validate(ins, 4, outs, 3, hs, 8, B, L, D, lh, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (lf < 1 || feat_group < 1 || D % feat_group != 0 || workspace_bytes < 0) return HY_ERR_SHAPE;
+    const int64_t nf = filter_bytes(D, feat_group, lf), nh = filter_bytes(D, group, lh);
+    const int64_t esz = dtype == HY_F32 ? 4 : 2;
+    if (!empty(B, L, D) && B * L * D > (INT64_MAX / 8) / esz) return HY_ERR_SHAPE;
+    const int64_t bytes = B * L * D * esz;
+    // every filter gradient is written: disjoint from everything else the call touches
+    const Range all[15] = {{dy, bytes}, {q, bytes}, {k, bytes}, {v, bytes}, {dq, bytes}, {dk, bytes}, {dv, bytes},
+                           {hq, nf}, {hk, nf}, {hv, nf}, {h, nh}, {dhq, nf}, {dhk, nf}, {dhv, nf}, {dh, nh}};
+    for (int i = 11; i < 15; ++i) {
+        Range rest[14];
+        int n = 0;
+        for (int j = 0; j < 15; ++j)
+            if (j != i) rest[n++] = all[j];
+        if (check_disjoint(rest, n, &all[i], 1) != HY_OK) return HY_ERR_ALIGN;
+    }
+    if (empty(B, L, D)) {
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        float* const fg[3] = {dhq, dhk, dhv};
+        for (float* g : fg) {
+            rc = launch_bwd_zero_dh(g, D, lf, feat_group, st);
+            if (rc != HY_OK) return rc;
+        }
+        return launch_bwd_zero_dh(dh, D, lh, group, st);
+    }
+    const int64_t inner = chain_bwd_inner_ws(B, L, D, lf, feat_group, lh, group, dtype);
+    if (inner < 0) return HY_ERR_SHAPE;
+    const int64_t slot = align256(bytes);
+    rc = check_workspace(workspace, workspace_bytes, 6 * slot + inner, all, 15);
+    if (rc != HY_OK) return rc;
+    char* const ws = static_cast<char*>(workspace);
+    void* const qf = ws, * const kf = ws + slot, * const vf = ws + 2 * slot;               // q', k', v'
+    void* const gq = ws + 3 * slot, * const gk = ws + 4 * slot, * const gv = ws + 5 * slot;  // dq', dk', dv'
+    void* const iw = inner > 0 ? ws + 6 * slot : nullptr;
+    rc = hyena_featurize3_fwd(q, k, v, hq, hk, hv, qf, kf, vf, B, L, D, lf, feat_group, dtype, hip_stream);
+    if (rc != HY_OK) return rc;
+    rc = hyena_mr_bwd(dy, qf, kf, vf, h, gq, gk, gv, dh, iw, inner, B, L, D, lh, group, dtype, hip_stream);
+    if (rc != HY_OK) return rc;
+    rc = hyena_featurize_bwd(gq, q, hq, dq, dhq, iw, inner, B, L, D, lf, feat_group, dtype, hip_stream);
+    if (rc != HY_OK) return rc;
+    rc = hyena_featurize_bwd(gk, k, hk, dk, dhk, iw, inner, B, L, D, lf, feat_group, dtype, hip_stream);
+    if (rc != HY_OK) return rc;
+    return hyena_featurize_bwd(gv, v, hv, dv, dhv, iw, inner, B, L, D, lf, feat_group, dtype, hip_stream);
 }
 
 hy_status hyena_se_bwd_shard(const void* dy, const void* q, const void* k, const void* v, const float* h, void* dq,

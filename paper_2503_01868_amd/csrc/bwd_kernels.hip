@@ -15,6 +15,10 @@
 //    arrived), a delay line of k and v for that lag, and VEC*lh partial sums for dh.  A tile reads lh-1
 //    halo rows of k, v before its start and lh-1 halo rows of dy, q after its end.
 //  * bwd_direct_kernel / dh_direct_kernel: any lh, any group, both dtypes.  Correctness path.
+//
+// kGated = false turns both paths into the backward of the featurizer convolutions of Eq. 1 (x' = h * x, no
+// gates): u = x (the k pointer), g = dy, the only activation gradient is dx = du (the dk pointer); q, v, dq, dv are
+// neither read nor written.
 #include "hy_common.hpp"
 #include "hy_launch.hpp"
 
@@ -34,7 +38,7 @@ struct BwdStencilArgs {
 
 constexpr int kBlock = 256;
 
-template <typename T, int VEC, int LH, int R>
+template <typename T, int VEC, int LH, int R, bool kGated>
 __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
     using P = Pack<T, VEC>;
     using Raw = typename P::Raw;
@@ -77,7 +81,12 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
         if (t >= -(int64_t)a.hist) {
             const int64_t off = (seq0kv + t * D) * T::kBytes;
             P::unpack(P::load(kp + off), kf);
-            P::unpack(P::load(vp + off), vf);
+            if constexpr (kGated) {
+                P::unpack(P::load(vp + off), vf);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) vf[e] = 1.0f;
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) kf[e] = vf[e] = 0.0f;
@@ -104,12 +113,12 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
             gr[r] = zero_words<P::kWords>();
             if (t + r < t_walk) {
                 const int64_t off = (seq0gq + (t + r) * D) * T::kBytes;
-                qr[r] = P::load_nt(qp + off);
+                if constexpr (kGated) qr[r] = P::load_nt(qp + off);
                 gr[r] = P::load_nt(dyp + off);
                 if (t + r < t1) {
                     const int64_t offkv = (seq0kv + (t + r) * D) * T::kBytes;
                     kr[r] = P::load_nt(kp + offkv);
-                    vr[r] = P::load_nt(vp + offkv);
+                    if constexpr (kGated) vr[r] = P::load_nt(vp + offkv);
                 }
             }
         }
@@ -132,9 +141,14 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
         for (int r = 0; r < R; ++r) {
             float kf[VEC], vf[VEC], qf[VEC], dyf[VEC];
             P::unpack(kc[r], kf);
-            P::unpack(vc[r], vf);
-            P::unpack(qc[r], qf);
             P::unpack(gc[r], dyf);
+            if constexpr (kGated) {
+                P::unpack(vc[r], vf);
+                P::unpack(qc[r], qf);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) vf[e] = qf[e] = 1.0f;
+            }
             const int64_t tt = t + r;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
@@ -147,14 +161,16 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
                 float dqv[VEC];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    float z = taps[e][0] * uw[e][LH - 1 + r];
+                    if constexpr (kGated) {
+                        float z = taps[e][0] * uw[e][LH - 1 + r];
 #pragma unroll
-                    for (int j = 1; j < LH; ++j) z = __builtin_fmaf(taps[e][j], uw[e][LH - 1 + r - j], z);
-                    dqv[e] = dyf[e] * z;
+                        for (int j = 1; j < LH; ++j) z = __builtin_fmaf(taps[e][j], uw[e][LH - 1 + r - j], z);
+                        dqv[e] = dyf[e] * z;
+                    }
 #pragma unroll
                     for (int j = 0; j < LH; ++j) dh[e][j] = __builtin_fmaf(gw[e][LH - 1 + r], uw[e][LH - 1 + r - j], dh[e][j]);
                 }
-                P::store_nt(dqp + (seq0 + tt * D) * T::kBytes, P::pack(dqv));
+                if constexpr (kGated) P::store_nt(dqp + (seq0 + tt * D) * T::kBytes, P::pack(dqv));
             }
             const int64_t s = tt - (LH - 1);  // the step whose du is complete now; window index r
             if (s >= t0 && s < t1) {
@@ -168,7 +184,7 @@ __global__ __launch_bounds__(kBlock) void bwd_stencil_kernel(BwdStencilArgs a) {
                     dvv[e] = du * kd[e][r];
                 }
                 P::store_nt(dkp + (seq0 + s * D) * T::kBytes, P::pack(dkv));
-                P::store_nt(dvp + (seq0 + s * D) * T::kBytes, P::pack(dvv));
+                if constexpr (kGated) P::store_nt(dvp + (seq0 + s * D) * T::kBytes, P::pack(dvv));
             }
         }
 #pragma unroll
@@ -265,7 +281,7 @@ struct BwdDirectArgs {
 
 // dq, dk, dv: one lane = one channel x kRows consecutive steps, sliding along the sources with the kRows
 // matching taps in registers (backwards in time for z, forwards for du).
-template <typename T>
+template <typename T, bool kGated>
 __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectArgs a) {
     using P = Pack<T, 1>;
     const int64_t b = blockIdx.z;
@@ -287,28 +303,29 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
         return f[0];
     };
 
-    float tw[kRows], acc[kRows];
-    // z[tf + r] = sum_s h[tf + r - s] u[s], s ascending
-    int64_t s = tf - (lh - 1);
-    if (s < -(int64_t)a.hist) s = -(int64_t)a.hist;
+    float tw[kRows], acc[kRows], zz[kRows];
+    if constexpr (kGated) {
+        // z[tf + r] = sum_s h[tf + r - s] u[s], s ascending
+        int64_t s = tf - (lh - 1);
+        if (s < -(int64_t)a.hist) s = -(int64_t)a.hist;
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        const int64_t j = tf + r - s;
-        tw[r] = (j >= 0 && j < lh) ? hp[j] : 0.0f;
-        acc[r] = 0.0f;
+        for (int r = 0; r < kRows; ++r) {
+            const int64_t j = tf + r - s;
+            tw[r] = (j >= 0 && j < lh) ? hp[j] : 0.0f;
+            acc[r] = 0.0f;
+        }
+        for (; s <= tl; ++s) {
+            const float u = ld(kp, seq0kv, s) * ld(vp, seq0kv, s);
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) acc[r] = __builtin_fmaf(tw[r], u, acc[r]);
+#pragma unroll
+            for (int r = kRows - 1; r > 0; --r) tw[r] = tw[r - 1];
+            const int64_t j0 = tf - (s + 1);
+            tw[0] = (j0 >= 0 && j0 < lh) ? hp[j0] : 0.0f;
+        }
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) zz[r] = acc[r];
     }
-    for (; s <= tl; ++s) {
-        const float u = ld(kp, seq0kv, s) * ld(vp, seq0kv, s);
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) acc[r] = __builtin_fmaf(tw[r], u, acc[r]);
-#pragma unroll
-        for (int r = kRows - 1; r > 0; --r) tw[r] = tw[r - 1];
-        const int64_t j0 = tf - (s + 1);
-        tw[0] = (j0 >= 0 && j0 < lh) ? hp[j0] : 0.0f;
-    }
-    float zz[kRows];
-#pragma unroll
-    for (int r = 0; r < kRows; ++r) zz[r] = acc[r];
 
     // du[tf + r] = sum_t h[t - tf - r] g[t], t ascending from tf to tl + lh - 1
     int64_t t = tf;
@@ -321,7 +338,7 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
         acc[r] = 0.0f;
     }
     for (; t <= t_last; ++t) {
-        const float g = ld(dyp, seq0gq, t) * ld(qp, seq0gq, t);
+        const float g = kGated ? ld(dyp, seq0gq, t) * ld(qp, seq0gq, t) : ld(dyp, seq0gq, t);
 #pragma unroll
         for (int r = 0; r < kRows; ++r) acc[r] = __builtin_fmaf(tw[r], g, acc[r]);
         // next source: every tap index grows by one
@@ -334,21 +351,26 @@ __global__ __launch_bounds__(kChan* kRowLanes) void bwd_direct_kernel(BwdDirectA
     for (int r = 0; r < kRows; ++r) {
         if (tf + r <= tl) {
             const int64_t off = (seq0 + (tf + r) * a.D) * T::kBytes;
-            const float kf = ld(kp, seq0kv, tf + r), vf = ld(vp, seq0kv, tf + r), dyf = ld(dyp, seq0gq, tf + r);
             float o[1];
-            o[0] = dyf * zz[r];
-            P::store(static_cast<char*>(a.p.dq) + off, P::pack(o));
-            o[0] = acc[r] * vf;
-            P::store(static_cast<char*>(a.p.dk) + off, P::pack(o));
-            o[0] = acc[r] * kf;
-            P::store(static_cast<char*>(a.p.dv) + off, P::pack(o));
+            if constexpr (kGated) {
+                const float kf = ld(kp, seq0kv, tf + r), vf = ld(vp, seq0kv, tf + r), dyf = ld(dyp, seq0gq, tf + r);
+                o[0] = dyf * zz[r];
+                P::store(static_cast<char*>(a.p.dq) + off, P::pack(o));
+                o[0] = acc[r] * vf;
+                P::store(static_cast<char*>(a.p.dk) + off, P::pack(o));
+                o[0] = acc[r] * kf;
+                P::store(static_cast<char*>(a.p.dv) + off, P::pack(o));
+            } else {
+                o[0] = acc[r];
+                P::store(static_cast<char*>(a.p.dk) + off, P::pack(o));
+            }
         }
     }
 }
 
 // dh[g][j]: one workgroup per (group, tap); lanes stride over (b, t, channel of the group), then a tree sum.
 // Products of fp32 factors and their sum are carried in fp64 (correctness path: the sum has B * L * group terms).
-template <typename T>
+template <typename T, bool kGated>
 __global__ __launch_bounds__(kBlock) void dh_direct_kernel(BwdDirectArgs a) {
     using P = Pack<T, 1>;
     __shared__ double red[kBlock];
@@ -374,7 +396,10 @@ __global__ __launch_bounds__(kBlock) void dh_direct_kernel(BwdDirectArgs a) {
             const int64_t t = t_first + i / group;
             const int64_t c = g * group + i % group;
             const int64_t at = b * a.sgq + t * D + c, src = b * a.skv + (t - j) * D + c;
-            s = __builtin_fma((double)ld(dyp, at) * (double)ld(qp, at), (double)ld(kp, src) * (double)ld(vp, src), s);
+            if constexpr (kGated)
+                s = __builtin_fma((double)ld(dyp, at) * (double)ld(qp, at), (double)ld(kp, src) * (double)ld(vp, src), s);
+            else
+                s = __builtin_fma((double)ld(dyp, at), (double)ld(kp, src), s);
         }
     }
     red[threadIdx.x] = s;
@@ -392,8 +417,11 @@ int stencil_rows(const BwdShape& s, int64_t nvec) {
         const int64_t waves_per_row = (nvec + kWave - 1) / kWave;
         // Measured on MI355X (L = 8192, D = 4096): 256-step tiles run 10% faster than 128-step ones (half the
         // halo rows and half the partial filter gradients), as long as four waves per CU are left.
+        // The featurizer variant holds half the loads and windows per lane and wants eight waves per CU (same
+        // shape: 48.5 us with 128-step tiles, 66 us with 256).
         rows = 256;
-        while (rows > 32 && s.B * ((s.L + rows - 1) / rows) * waves_per_row < 1024) rows >>= 1;
+        const int64_t want = s.gated ? 1024 : 2048;
+        while (rows > 32 && s.B * ((s.L + rows - 1) / rows) * waves_per_row < want) rows >>= 1;
     }
     if (rows > s.L) rows = (int)s.L;
     if (rows < 1) rows = 1;
@@ -424,7 +452,9 @@ hy_status launch_stencil_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipSt
     a.nitems = s.B * a.tiles_per_seq * a.nvec;
     const int64_t nb = (a.nitems + kBlock - 1) / kBlock;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    const hy_status rc = launch_kernel((bwd_stencil_kernel<T, VEC, LH, R>), dim3((uint32_t)nb), dim3(kBlock), st, a);
+    const hy_status rc = s.gated
+        ? launch_kernel((bwd_stencil_kernel<T, VEC, LH, R, true>), dim3((uint32_t)nb), dim3(kBlock), st, a)
+        : launch_kernel((bwd_stencil_kernel<T, VEC, LH, R, false>), dim3((uint32_t)nb), dim3(kBlock), st, a);
     if (rc != HY_OK) return rc;
     const int64_t nsets = s.B * a.tiles_per_seq;
     const int64_t nout = (s.D / s.group) * s.lh;
@@ -460,10 +490,15 @@ hy_status launch_direct_t(const BwdPtrs& p, const BwdShape& s, hipStream_t st) {
     const int64_t gy = (s.L + kRows * kRowLanes - 1) / (kRows * kRowLanes);
     const int64_t G = s.D / s.group;
     if (gx > 0x7fffffffLL || gy > 65535 || s.B > 65535 || G > 0x7fffffffLL || s.lh > 65535) return HY_ERR_UNSUPPORTED;
-    const hy_status rc = launch_kernel((bwd_direct_kernel<T>), dim3((uint32_t)gx, (uint32_t)gy, (uint32_t)s.B),
-                                       dim3(kChan * kRowLanes), st, a);
+    const dim3 grid((uint32_t)gx, (uint32_t)gy, (uint32_t)s.B), gridh((uint32_t)G, (uint32_t)s.lh);
+    if (s.gated) {
+        const hy_status rc = launch_kernel((bwd_direct_kernel<T, true>), grid, dim3(kChan * kRowLanes), st, a);
+        if (rc != HY_OK) return rc;
+        return launch_kernel((dh_direct_kernel<T, true>), gridh, dim3(kBlock), st, a);
+    }
+    const hy_status rc = launch_kernel((bwd_direct_kernel<T, false>), grid, dim3(kChan * kRowLanes), st, a);
     if (rc != HY_OK) return rc;
-    return launch_kernel((dh_direct_kernel<T>), dim3((uint32_t)G, (uint32_t)s.lh), dim3(kBlock), st, a);
+    return launch_kernel((dh_direct_kernel<T, false>), gridh, dim3(kBlock), st, a);
 }
 
 }  // namespace

@@ -289,7 +289,7 @@ hy_status launch_walk_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipStrea
 // bf16, lh <= 7 (eight taps do not fit 128 registers beside two chunks of loads), whole 256-channel blocks, and a
 // stretch of at least 256 steps per workgroup to walk
 bool bwd_walk_preferred(const BwdShape& s) {
-    if (s.dtype != HY_BF16 || s.lh < 1 || s.lh > 7 || s.D % kCh != 0) return false;
+    if (!s.gated || s.dtype != HY_BF16 || s.lh < 1 || s.lh > 7 || s.D % kCh != 0) return false;
     if (s.L > 0x7fff0000LL || s.D > 0x7fff0000LL) return false;
     const int force = tuning().se_walk;
     if (force == 1) return true;

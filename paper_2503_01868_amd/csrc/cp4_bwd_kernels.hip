@@ -312,7 +312,7 @@ hy_status launch_dh_na(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_
 }  // namespace
 
 bool cp4_bwd_supported(const BwdShape& s) {
-    return s.dtype == HY_BF16 && s.D % 128 == 0 && s.lh > 8 && s.lh <= 129 && s.L <= 0x7fff0000LL && s.D <= 0x7fff0000LL;
+    return s.gated && s.dtype == HY_BF16 && s.D % 128 == 0 && s.lh > 8 && s.lh <= 129 && s.L <= 0x7fff0000LL && s.D <= 0x7fff0000LL;
 }
 
 int64_t cp4_bwd_workspace_bytes(const BwdShape& s) {

@@ -93,6 +93,8 @@ struct BwdShape {
     // Implemented by every backward launcher.
     int64_t bstride_kv = 0, bstride_gq = 0, bstride_out = 0;
     int32_t history = 0, future = 0;
+    bool gated = true;        // false: backward of the ungated featurizer convolution (x = k, dx = dk; no q, v, dq, dv);
+                              // stencil and general kernels only
     bool shard_call = false;  // came in through a shard entry point: the kernels' shard variants, whatever the values
     int64_t stride_kv() const { return bstride_kv > 0 ? bstride_kv : L * D; }
     int64_t stride_gq() const { return bstride_gq > 0 ? bstride_gq : L * D; }
@@ -135,6 +137,9 @@ struct Tuning {
 const Tuning& tuning();
 struct TuningSnapshot {
     TuningSnapshot();
+    ~TuningSnapshot();
+    TuningSnapshot(const TuningSnapshot&) = delete;
+    TuningSnapshot& operator=(const TuningSnapshot&) = delete;
 };
 
 // Short-filter streaming stencil on the vector ALUs.  HY_ERR_UNSUPPORTED when lh is above its limit.

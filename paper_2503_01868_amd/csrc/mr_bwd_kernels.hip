@@ -414,7 +414,7 @@ hy_status launch_nkb(const BwdPtrs& p, const BwdShape& s, void* ws, hipStream_t 
 }  // namespace
 
 bool mr_bwd_supported(const BwdShape& s) {
-    return s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.lh > 8 && s.lh <= 129;
+    return s.gated && s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.lh > 8 && s.lh <= 129;
 }
 
 // time steps per workgroup: one workgroup per CU where the sequence allows it (same rule as the forward kernel)

@@ -193,6 +193,57 @@ def test_backward_entry_points_reject_bad_arguments_and_size_their_workspace():
     assert wb(0, 100, 64, 7, 1, 1) == 0 and wb(1, 100, 64, 0, 1, 1) == -1 and wb(1, 100, 64, 7, 5, 1) == -1
 
 
+def test_featurizer_backward_rejects_bad_arguments_and_sizes_its_workspace():
+    lib = binding.lib()
+    Q = [0x100000 * (i + 1) for i in range(7)]
+
+    def fb(**kw):
+        a = dict(dy=Q[0], x=Q[1], h=Q[2], dx=Q[3], dh=Q[4], ws=Q[5], wsb=1 << 19, B=1, L=8, D=16, lh=3, group=1, dtype=1)
+        a.update(kw)
+        return lib.hyena_featurize_bwd(*[a[n] for n in ("dy", "x", "h", "dx", "dh", "ws", "wsb", "B", "L", "D", "lh",
+                                                        "group", "dtype")], None)
+
+    for name in ("dy", "x", "h", "dx", "dh"):
+        assert fb(**{name: None}) == 1
+    assert fb(lh=0) == 2 and fb(group=3) == 2 and fb(dtype=4) == 3 and fb(wsb=-1) == 2 and fb(L=-1) == 2
+    assert fb(dx=Q[0]) == 4 and fb(dx=Q[1] + 16) == 4 and fb(dh=Q[2]) == 4 and fb(dx=Q[3] + 2) == 4
+    assert fb(dh=Q[3] + 64) == 4 and fb(h=Q[3] + 64) == 4      # filter tables inside the written tensor
+    assert fb(dh=Q[0] + 64) == 4                               # the filter gradient inside a tensor that is read
+    assert fb(ws=None) == 1 and fb(wsb=16) == 2 and fb(ws=Q[5] + 4) == 4 and fb(ws=Q[1]) == 4
+    wb = lib.hyena_featurize_bwd_workspace_bytes
+    assert wb(1, 8, 16, 3, 1, 1) == 16 * 3 * 4 and wb(1, 8, 16, 3, 1, 0) == 16 * 3 * 4
+    assert wb(2, 1000, 256, 7, 1, 1) == lib.hyena_bwd_shard_workspace_bytes(2, 1000, 256, 7, 1, 1)   # the stencil's tiles
+    assert wb(1, 100, 64, 20, 1, 1) == 0 and wb(0, 100, 64, 7, 1, 1) == 0
+    assert wb(1, 100, 64, 0, 1, 1) == -1 and wb(1, 100, 64, 7, 5, 1) == -1 and wb(1, 100, 64, 7, 1, 7) == -1
+
+
+def test_chain_backward_rejects_bad_arguments_and_sizes_its_workspace():
+    lib = binding.lib()
+    Q = [0x100000 * (i + 1) for i in range(17)]
+    names = ("dy", "q", "k", "v", "hq", "hk", "hv", "h", "dq", "dk", "dv", "dhq", "dhk", "dhv", "dh", "ws")
+
+    def cb(**kw):
+        a = dict(zip(names, Q))
+        a.update(wsb=1 << 19, B=1, L=8, D=16, lf=3, fg=1, lh=5, group=1, dtype=1)
+        a.update(kw)
+        return lib.hyena_chain_bwd(*[a[n] for n in names + ("wsb", "B", "L", "D", "lf", "fg", "lh", "group", "dtype")], None)
+
+    for name in names[:15]:
+        assert cb(**{name: None}) == 1
+    assert cb(lf=0) == 2 and cb(fg=3) == 2 and cb(lh=0) == 2 and cb(group=5) == 2 and cb(dtype=7) == 3 and cb(wsb=-1) == 2
+    assert cb(dq=Q[1]) == 4 and cb(dk=Q[8]) == 4 and cb(dv=Q[0] + 16) == 4        # activations
+    assert cb(dhq=Q[4]) == 4 and cb(dhk=Q[11]) == 4 and cb(dh=Q[7]) == 4 and cb(dhv=Q[9] + 64) == 4 and cb(dh=Q[2] + 32) == 4
+    need = lib.hyena_chain_bwd_workspace_bytes(1, 8, 16, 3, 1, 5, 1, 1)
+    assert need == 6 * 256 + max(lib.hyena_bwd_workspace_bytes(1, 8, 16, 5, 1, 1),
+                                 lib.hyena_featurize_bwd_workspace_bytes(1, 8, 16, 3, 1, 1))
+    assert cb(ws=None) == 1 and cb(wsb=need - 1) == 2 and cb(ws=Q[15] + 4) == 4 and cb(ws=Q[3]) == 4
+    wb = lib.hyena_chain_bwd_workspace_bytes
+    assert wb(0, 8, 16, 3, 1, 5, 1, 1) == 0 and wb(1, 8, 16, 0, 1, 5, 1, 1) == -1 and wb(1, 8, 16, 3, 5, 5, 1, 1) == -1
+    assert wb(1, 8, 16, 3, 1, 5, 1, 9) == -1
+    # six tensors of 2 GiB-ish each plus the inner calls' share
+    assert wb(4, 32768, 4096, 7, 1, 128, 16, 1) >= 6 * 4 * 32768 * 4096 * 2
+
+
 def li(q=P[0], k=P[1], v=P[2], R=P[3], lam=P[5], y=P[4], ws=P[6], ws_bytes=1 << 30, B=1, L=8, D=16, order=4, group=1,
        dtype=0):
     return binding.lib().hyena_li_fwd(q, k, v, R, lam, y, ws, ws_bytes, B, L, D, order, group, dtype, None)

@@ -308,3 +308,115 @@ def test_backward_at_the_long_context_shape_on_channel_slabs():
             err = oracle.rel_err(g, want)
             say("  channels %d..%d %s rel_err=%.3e" % (c0, c1 - 1, nm, err))
             assert err <= tol, (nm, err)
+
+
+# ---------------------------------------------------------------------------------------- featurizer backward
+FEAT_CASES = [
+    # B, L, D, lh, group, forced tile rows (0: the library's choice)
+    (1, 1024, 256, 7, 1, 0), (2, 777, 512, 7, 1, 0), (3, 100, 264, 4, 1, 0), (1, 5, 64, 7, 1, 0), (1, 1, 8, 3, 1, 0),
+    (2, 333, 96, 1, 1, 0), (2, 400, 128, 8, 4, 32), (1, 300, 100, 5, 2, 1), (2, 129, 64, 2, 64, 7),
+    (1, 200, 48, 20, 1, 0), (2, 150, 64, 64, 16, 0), (1, 90, 32, 128, 4, 0),     # general kernels
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", FEAT_CASES)
+def test_featurizer_backward_matches_oracle(case, dtype):
+    B, L, D, lh, group, rows = case
+    say("hyena_featurize_bwd B=%d L=%d D=%d lh=%d group=%d rows=%d %s" % (B, L, D, lh, group, rows, dtype))
+    rng = np.random.Generator(np.random.PCG64(8800 + L + lh))
+    dy, x = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(2))
+    h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
+    binding.set_option("se_rows", rows)
+    code = binding.HY_BF16 if dtype == "bf16" else binding.HY_F32
+    assert (binding.lib().hyena_featurize_bwd_workspace_bytes(B, L, D, lh, group, code) > 0) == (lh <= 8)
+    dx, dh = binding.hyena_featurize_bwd(dev(dy), dev(x), dev(h), group)
+    want_dx, want_dh = oracle.causal_conv_bwd(dy, x, h, group=group)
+    gx, gh = host(dx), host(dh)
+    assert np.isfinite(gx).all() and np.isfinite(gh).all()
+    assert oracle.rel_err(gx, want_dx) <= TOL[dtype]
+    assert oracle.rel_err(gh, want_dh) <= DH_TOL
+
+
+def test_featurizer_backward_is_bit_equal_to_the_gated_backward_with_unit_gates():
+    """Same kernels, same order of operations: with q = v = 1 the gated call's dk and dh are dx and dh exactly."""
+    B, L, D, lh, group = 2, 600, 128, 7, 1
+    rng = np.random.Generator(np.random.PCG64(8899))
+    dy, x = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(2))
+    h = dev(synth.short_filter(rng, D // group, lh))
+    one = torch.ones_like(x)
+    binding.set_option("se_walk", 2)   # the stencil, which is what the featurizer backward runs
+    binding.set_option("se_rows", 64)  # the same tiles for both (their own choices differ at large sizes)
+    _, dk, _, dh_g = binding.hyena_se_bwd(dy, one, x, one, h, group)
+    dx, dh = binding.hyena_featurize_bwd(dy, x, h, group)
+    assert torch.equal(dx, dk) and torch.equal(dh, dh_g)
+
+
+def test_featurizer_backward_of_an_empty_batch_writes_a_zero_filter_gradient():
+    h = dev(synth.short_filter(np.random.Generator(np.random.PCG64(1)), 16, 5))
+    dy, x, dx = (torch.zeros((1, 10, 16), dtype=torch.bfloat16, device="cuda:0") for _ in range(3))
+    dh = torch.full_like(h, 7.0)
+    rc = binding.lib().hyena_featurize_bwd(dy.data_ptr(), x.data_ptr(), h.data_ptr(), dx.data_ptr(), dh.data_ptr(), None, 0,
+                                           1, 0, 16, 5, 1, binding.HY_BF16, None)   # L = 0
+    torch.cuda.synchronize()
+    assert rc == 0 and torch.count_nonzero(dh) == 0
+
+
+# ---------------------------------------------------------------------------------------- chain backward
+CHAIN_BWD_CASES = [
+    # B, L, D, lf, feat_group, lh, group, dtype
+    (2, 700, 128, 7, 1, 128, 16, "bf16"),     # one-pass matrix-core kernel inside
+    (1, 900, 128, 7, 1, 64, 1, "bf16"),       # chunk-parallel kernels inside
+    (2, 500, 256, 4, 2, 7, 1, "bf16"),        # short inner filter: stencil / tile walker inside
+    (1, 300, 64, 4, 1, 20, 4, "f32"),         # general kernels, fp32 throughout
+    (2, 200, 48, 12, 1, 33, 2, "bf16"),       # long featurizers: general kernels for them
+]
+
+
+@pytest.mark.parametrize("case", CHAIN_BWD_CASES, ids=lambda c: "B%dL%dD%dlf%dfg%dlh%dg%d%s" % c)
+def test_chain_backward_matches_oracle(case):
+    B, L, D, lf, fg, lh, group, dtype = case
+    say("hyena_chain_bwd B=%d L=%d D=%d lf=%d feat_group=%d lh=%d group=%d %s" % case)
+    rng = np.random.Generator(np.random.PCG64(9100 + L + lh))
+    dy, q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(4))
+    hq, hk, hv = ((synth.short_filter if lf <= 8 else synth.decay_filter)(rng, D // fg, lf) for _ in range(3))
+    h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
+    got = binding.hyena_chain_bwd(*[dev(x) for x in (dy, q, k, v, hq, hk, hv, h)], group, fg)
+    ref = oracle.chain_bwd(dy, q, k, v, hq, hk, hv, h, group=group, feat_group=fg)
+    # bf16: q', k', v' and dq', dk', dv' pass through memory in bf16, so every filter gradient carries their
+    # rounding like the matrix-core backward's (the same recorded bar); fp32 stays at the fp32 bar
+    ftol = DH_TOL if dtype == "f32" else DH_TOL_MFMA
+    for name, g, want, tol in zip(("dq", "dk", "dv", "dhq", "dhk", "dhv", "dh"), got, ref, (TOL[dtype],) * 3 + (ftol,) * 4):
+        gh = host(g)
+        assert gh.shape == want.shape and np.isfinite(gh).all(), name
+        err = oracle.rel_err(gh, want)
+        say("  %s rel_err=%.3e" % (name, err))
+        assert err <= tol, (name, err)
+
+
+@pytest.mark.timeout(900)
+def test_chain_backward_at_the_chain_config_on_a_channel_slab():
+    """c4_bwd as bench.py times it (B=4, L=32768, D=4096, featurizers of 7 taps, lh=128, groups of 16): the whole
+    problem runs on the GPU; all seven gradients of the last 256 channels (whole filter groups and whole
+    featurizer channels: an exact sub-problem for the oracle, 100 663 296 activation-gradient elements with every
+    tile boundary of those channels) are compared element by element."""
+    w = synth.make("c4")
+    B, L, D, lh, group, lf, fg = (w[x] for x in ("B", "L", "D", "lh", "group", "lf", "feat_group"))
+    say("chain backward at c4's shape B=%d L=%d D=%d lf=%d lh=%d group=%d" % (B, L, D, lf, lh, group))
+    rng = np.random.Generator(np.random.PCG64(synth.seed_for("c4", 0) + 500000))
+    dy = synth.normal_tensor(rng, (B, L, D), w["dtype"])
+    outs = binding.hyena_chain_bwd(*[dev(x) for x in (dy, w["q"], w["k"], w["v"], w["hq"], w["hk"], w["hv"], w["h"])],
+                                   group, fg)
+    torch.cuda.synchronize()
+    c0, c1 = D - 256, D
+    sub = [x[:, :, c0:c1].contiguous() for x in (dy, w["q"], w["k"], w["v"])]
+    filt = [w[n][c0 // fg:c1 // fg] for n in ("hq", "hk", "hv")] + [w["h"][c0 // group:c1 // group]]
+    ref = oracle.chain_bwd(*sub, *filt, group=group, feat_group=fg)
+    got = ([host(o[:, :, c0:c1]) for o in outs[:3]] + [host(o[c0 // fg:c1 // fg]) for o in outs[3:6]] +
+           [host(outs[6][c0 // group:c1 // group])])
+    for nm, g, want, tol in zip(("dq", "dk", "dv", "dhq", "dhk", "dhv", "dh"), got, ref,
+                                (TOL["bf16"],) * 3 + (DH_TOL_MFMA,) * 4):
+        assert g.shape == want.shape and np.isfinite(g).all(), nm
+        err = oracle.rel_err(g, want)
+        say("  channels %d..%d %s rel_err=%.3e" % (c0, c1 - 1, nm, err))
+        assert err <= tol, (nm, err)

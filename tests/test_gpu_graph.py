@@ -88,7 +88,7 @@ def test_forward_entry_points_replay_from_a_graph():
 
 
 def test_backward_entry_points_replay_from_a_graph():
-    say("graph: se, mr (grouped and ungrouped) backward")
+    say("graph: se, mr (grouped and ungrouped) and featurizer backward")
     B, L, D = 2, 500, 128
     rng = np.random.Generator(np.random.PCG64(92))
     dy, q, k, v = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(4))
@@ -101,13 +101,15 @@ def test_backward_entry_points_replay_from_a_graph():
         return [pkg.plan_bwd("hyena_se_bwd", dy, q, k, v, h_se, 1, stream=stream),
                 pkg.plan_bwd("hyena_mr_bwd", dy, q, k, v, h_mr, 16, stream=stream),
                 pkg.plan_bwd("hyena_mr_bwd", dy, q, k, v, h_un, 1, stream=stream),
-                pkg.plan_bwd("hyena_mr_bwd", dy, q, k, v, h_us, 2, stream=stream)]
+                pkg.plan_bwd("hyena_mr_bwd", dy, q, k, v, h_us, 2, stream=stream),
+                pkg.plan_featurize_bwd(dy, k, h_se, 1, stream=stream)]
 
     g, plans = capture(build)
 
     def eager():
         return (list(binding.hyena_se_bwd(dy, q, k, v, h_se, 1)) + list(binding.hyena_mr_bwd(dy, q, k, v, h_mr, 16)) +
-                list(binding.hyena_mr_bwd(dy, q, k, v, h_un, 1)) + list(binding.hyena_mr_bwd(dy, q, k, v, h_us, 2)))
+                list(binding.hyena_mr_bwd(dy, q, k, v, h_un, 1)) + list(binding.hyena_mr_bwd(dy, q, k, v, h_us, 2)) +
+                list(binding.hyena_featurize_bwd(dy, k, h_se, 1)))
 
     def refill(it):
         for t in (dy, q, k, v):
