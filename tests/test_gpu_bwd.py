@@ -420,3 +420,15 @@ def test_chain_backward_at_the_chain_config_on_a_channel_slab():
         err = oracle.rel_err(g, want)
         say("  channels %d..%d %s rel_err=%.3e" % (c0, c1 - 1, nm, err))
         assert err <= tol, (nm, err)
+
+
+def test_chain_backward_of_an_empty_sequence_writes_zero_filter_gradients():
+    rng = np.random.Generator(np.random.PCG64(2))
+    hq, hk, hv = (dev(synth.short_filter(rng, 16, 5)) for _ in range(3))
+    h = dev(synth.decay_filter(rng, 4, 20))
+    t = [torch.zeros((1, 10, 16), dtype=torch.bfloat16, device="cuda:0") for _ in range(7)]
+    grads = [torch.full_like(f, 7.0) for f in (hq, hk, hv, h)]
+    ptrs = [x.data_ptr() for x in t[:4] + [hq, hk, hv, h] + t[4:] + grads]
+    rc = binding.lib().hyena_chain_bwd(*ptrs, None, 0, 1, 0, 16, 5, 1, 20, 4, binding.HY_BF16, None)   # L = 0
+    torch.cuda.synchronize()
+    assert rc == 0 and all(torch.count_nonzero(g) == 0 for g in grads)
