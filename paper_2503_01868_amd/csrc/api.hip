@@ -813,6 +813,6 @@ const char* hyena_status_string(int32_t status) {
     return "unknown status";
 }
 
-int32_t hyena_version(void) { return 300; }
+int32_t hyena_version(void) { return 310; }
 
 }  // extern "C"
