@@ -234,3 +234,56 @@ def test_sharded_operator_chain_equals_the_whole_sequence(case):
     assert np.isfinite(got).all() and oracle.rel_err(got, ref) <= TOL["bf16"]
     whole = binding.hyena_chain_fwd(dq, dk, dv, dhq, dhk, dhv, dh, group, 1)
     assert oracle.rel_err(got, host(whole)) <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------------------------------------ random cuts
+def _pick(rng, xs):
+    return xs[int(rng.integers(0, len(xs)))]
+
+
+def random_shard_cases(n, seed):
+    """Seeded random shapes, filter lengths, group sizes, options and cut positions (cuts may fall anywhere: next to
+    each other, within lh - 1 steps of either end, off every tile and chunk boundary)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        group = _pick(rng, [1, 1, 2, 4, 16, 16, 32])
+        D = _pick(rng, [64, 128, 128, 256, 256, 384, 512])
+        D = max(D - D % group, group)
+        lh = _pick(rng, [1, 3, 7, 8, 9, 20, 33, 64, 65, 66, 100, 128, 129])
+        L = int(rng.integers(2, 1600))
+        B = int(rng.integers(1, 3))
+        dtype = _pick(rng, ["bf16", "bf16", "bf16", "f32"])
+        ncut = int(rng.integers(1, 5))
+        cuts = tuple(sorted(set(int(c) for c in rng.integers(1, L, size=ncut))))
+        opts = {}
+        if rng.random() < 0.5:
+            opts["mr_rows"] = opts["se_rows"] = _pick(rng, [32, 64, 256, 512])
+        if lh <= 7 and rng.random() < 0.5:
+            opts["se_walk"] = 1
+        out.append((i, B, L, D, lh, group, dtype, cuts, opts))
+    return out
+
+
+@pytest.mark.parametrize("case", random_shard_cases(28, 777), ids=lambda c: "%d-B%dL%dD%dlh%dg%d%s" % c[:7])
+def test_random_cuts_forward_and_backward(case):
+    i, B, L, D, lh, group, dtype, cuts, opts = case
+    kind = "se" if lh <= 8 else "mr"
+    say("random shards %d: B=%d L=%d D=%d lh=%d group=%d %s cuts=%s opts=%s" % (i, B, L, D, lh, group, dtype, cuts, opts))
+    rng = np.random.Generator(np.random.PCG64(7000 + i))
+    dy, q, k, v = (synth.normal_tensor(rng, (B, L, D), dtype) for _ in range(4))
+    h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
+    for name, value in opts.items():
+        binding.set_option(name, value)
+    d = [dev(x) for x in (dy, q, k, v, h)]
+    y = run_sharded("hyena_%s_fwd_shard" % kind, d[1], d[2], d[3], d[4], group, cuts, lh)
+    assert oracle.rel_err(host(y), oracle.gated_conv(q, k, v, h, group=group)) <= TOL[dtype]
+    got = run_bwd_sharded("hyena_%s_bwd_shard" % kind, *d, group, cuts, lh)
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    on_matrix_cores = dtype == "bf16" and 8 < lh <= 129 and ((group % 16 == 0 and D % 64 == 0) or D % 128 == 0)
+    for name, g, want, tol in zip(("dq", "dk", "dv", "dh"), got, ref,
+                                  (TOL[dtype],) * 3 + (1e-2 if on_matrix_cores else TOL["f32"],)):
+        gh = host(g)
+        assert np.isfinite(gh).all(), name
+        err = oracle.rel_err(gh, want)
+        assert err <= tol, (name, err)
