@@ -14,7 +14,9 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c1_shards / c2_shards / c3_shards: c1 / c2 / c3 computed as four consecutive sequence shards (hyena_se_fwd_shard /
       hyena_mr_fwd_shard: each call sees its quarter of the steps plus the lh - 1 rows of k and v before it), the
       compute half of a sequence-sharded run on one GPU; a step is the four launches.  c3_bwd_shards: the same for
-      the backward pass (hyena_mr_bwd_shard: halos on both sides, every shard its share of the filter gradient)
+      the backward pass (hyena_mr_bwd_shard: halos on both sides, every shard its share of the filter gradient).
+      c3_overlap: c3_shards with every shard after the first split into the call that needs no neighbour data (all
+      but its first lh - 1 steps) and the call for those first steps, the split that lets a rank hide the exchange
 Successive steps rotate through several independent input/output sets so that every launch streams from
 HBM instead of re-hitting the 256 MB last-level cache (c1 and c2 move exactly 256 MiB per step).
   c2u c2 with one filter per channel; li2 / li3: Hyena-LI at the shapes of c2 / c3
@@ -56,7 +58,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
                     choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "c1_shards",
-                             "c2_shards", "c3_shards", "c1_bwd_shards", "c3_bwd_shards", "c4_bwd", "copy"] + list(YARDSTICKS),
+                             "c2_shards", "c3_shards", "c3_overlap", "c1_bwd_shards", "c3_bwd_shards", "c4_bwd", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "
@@ -105,6 +107,8 @@ class Workload:
 
     def __init__(self, name, nsets, torch, pkg, synth, seq_len=0, depth=0):
         self.name, self.torch, self.pkg = name, torch, pkg
+        self.overlap = name.endswith("_overlap")   # shards split into an interior call and a boundary call
+        name = name[:-8] + "_shards" if self.overlap else name
         self.shards = 4 if name.endswith("_shards") else 0
         name = name[:-7] if self.shards else name
         self.bwd = name.endswith("_bwd")
@@ -174,10 +178,20 @@ class Workload:
                 # the sequence as `shards` consecutive shard calls, each with the lh - 1 rows before it as history
                 entry = "hyena_se_fwd_shard" if c["kind"] == "se" else "hyena_mr_fwd_shard"
                 n = c["L"] // self.shards
-                plans = [pkg.plan_gated_shard(entry, d["q"][:, i * n:(i + 1) * n], d["k"][:, i * n:(i + 1) * n],
-                                              d["v"][:, i * n:(i + 1) * n], d["h"], c["group"],
-                                              min(i * n, c["lh"] - 1), out=d["y"][:, i * n:(i + 1) * n])
-                         for i in range(self.shards)]
+                def shard(t0, t1):
+                    w = slice(t0, t1)
+                    return pkg.plan_gated_shard(entry, d["q"][:, w], d["k"][:, w], d["v"][:, w], d["h"], c["group"],
+                                                min(t0, c["lh"] - 1), out=d["y"][:, w])
+
+                H = c["lh"] - 1
+                plans = []
+                for i in range(self.shards):
+                    if self.overlap and i > 0:
+                        # what a rank does to hide the exchange: the steps at least lh - 1 in first (their history is
+                        # the shard's own rows), the lh - 1 steps next to the cut once the halo is there
+                        plans += [shard(i * n + H, (i + 1) * n), shard(i * n, i * n + H)]
+                    else:
+                        plans.append(shard(i * n, (i + 1) * n))
                 self.main.append(lambda plans=plans: [p() for p in plans])
             else:
                 entry = "hyena_se_fwd" if c["kind"] == "se" else "hyena_mr_fwd"
@@ -341,6 +355,9 @@ def entry_point(wl):
     if wl.bwd:
         name = name.replace("_fwd", "_bwd")
     if wl.shards:
+        if wl.overlap:
+            return "%s_shard x %d (consecutive shards, each after the first as an interior and a boundary call)" % (
+                name, 2 * wl.shards - 1)
         return "%s_shard x %d (the sequence in consecutive shards, one call each)" % (name, wl.shards)
     return name + " (all launches of the entry point)" if wl.bwd else name
 

@@ -287,3 +287,71 @@ def test_random_cuts_forward_and_backward(case):
         assert np.isfinite(gh).all(), name
         err = oracle.rel_err(gh, want)
         assert err <= tol, (name, err)
+
+
+# ------------------------------------------------------------------------------------------------ overlap
+@pytest.mark.parametrize("kind,lh,group", [("se", 7, 1), ("mr", 128, 16), ("mr", 100, 1)])
+def test_interior_and_boundary_calls_hide_the_halo_exchange(kind, lh, group):
+    """How a rank overlaps the exchange with compute (Sec. 4, point-to-point scheme): the steps of its shard that lie
+    at least lh - 1 steps away from a cut need no neighbour data, because their halo is the shard's own rows, so
+    they are launched at once; a copy on a second stream (standing in for the receive) meanwhile fills the halo
+    rows in front of k, v and behind dy, q; the lh - 1 steps next to each cut follow when it has finished.  All of
+    these are ordinary shard calls; forward and backward, with the shares of dh adding up."""
+    B, Ltot, D, t0, n = 2, 1500, 128, 500, 700          # the rank owns steps t0 .. t0 + n - 1
+    H = lh - 1
+    say("overlap pattern %s lh=%d group=%d: rank owns %d..%d of %d" % (kind, lh, group, t0, t0 + n - 1, Ltot))
+    rng = np.random.Generator(np.random.PCG64(5200 + lh))
+    dy, q, k, v = (synth.normal_tensor(rng, (B, Ltot, D), "bf16") for _ in range(4))
+    h = synth.short_filter(rng, D // group, lh) if lh <= 8 else synth.decay_filter(rng, D // group, lh)
+    hd = dev(h)
+    full = [dev(x) for x in (dy, q, k, v)]
+    nan = float("nan")
+    # the rank's buffers: k, v with room for the left halo in front, dy, q with room for the right halo behind
+    kbuf, vbuf = (torch.full((B, H + n, D), nan, dtype=torch.bfloat16, device="cuda:0") for _ in range(2))
+    gbuf, qbuf = (torch.full((B, n + H, D), nan, dtype=torch.bfloat16, device="cuda:0") for _ in range(2))
+    kbuf[:, H:], vbuf[:, H:] = full[2][:, t0:t0 + n], full[3][:, t0:t0 + n]
+    gbuf[:, :n], qbuf[:, :n] = full[0][:, t0:t0 + n], full[1][:, t0:t0 + n]
+    dq, dk, dv = (torch.full((B, n, D), nan, dtype=torch.bfloat16, device="cuda:0") for _ in range(3))
+    y = torch.full((B, n + H, D), nan, dtype=torch.bfloat16, device="cuda:0")[:, :n]   # q's batch stride (the forward
+    #                                                                                    entry has one for q and y)
+    dh_parts = [torch.empty_like(hd) for _ in range(3)]
+    fwd = getattr(binding, "hyena_%s_fwd_shard" % kind)
+    bwd = getattr(binding, "hyena_%s_bwd_shard" % kind)
+    torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    arrived = torch.cuda.Event()
+    with torch.cuda.stream(side):   # the "receive": the neighbours' rows land in the halo regions
+        kbuf[:, :H].copy_(full[2][:, t0 - H:t0], non_blocking=True)
+        vbuf[:, :H].copy_(full[3][:, t0 - H:t0], non_blocking=True)
+        gbuf[:, n:].copy_(full[0][:, t0 + n:t0 + n + H], non_blocking=True)
+        qbuf[:, n:].copy_(full[1][:, t0 + n:t0 + n + H], non_blocking=True)
+        arrived.record(side)
+    kk, vv, gg, qq = kbuf[:, H:], vbuf[:, H:], gbuf[:, :n], qbuf[:, :n]    # the rank's own n steps
+    # interior, launched without waiting: forward needs H own rows of history, backward also H own rows of future
+    fwd(qq[:, H:], kk[:, H:], vv[:, H:], hd, group, H, out=y[:, H:])
+    inner = slice(H, n - H)
+    bwd(gg[:, inner], qq[:, inner], kk[:, inner], vv[:, inner], hd, group, H, H,
+        out=(dq[:, inner], dk[:, inner], dv[:, inner], dh_parts[0]))
+    torch.cuda.current_stream().wait_event(arrived)
+    # the steps next to the cuts
+    fwd(qq[:, :H], kk[:, :H], vv[:, :H], hd, group, H, out=y[:, :H])
+    first, last = slice(0, H), slice(n - H, n)
+    bwd(gg[:, first], qq[:, first], kk[:, first], vv[:, first], hd, group, H, H,
+        out=(dq[:, first], dk[:, first], dv[:, first], dh_parts[1]))
+    bwd(gg[:, last], qq[:, last], kk[:, last], vv[:, last], hd, group, H, H,
+        out=(dq[:, last], dk[:, last], dv[:, last], dh_parts[2]))
+    torch.cuda.synchronize()
+
+    ref_y = oracle.gated_conv(q, k, v, h, group=group)[:, t0:t0 + n]
+    assert oracle.rel_err(host(y), ref_y) <= TOL["bf16"]
+    ref = oracle.gated_conv_bwd(dy, q, k, v, h, group=group)
+    for name, got, want in zip(("dq", "dk", "dv"), (dq, dk, dv), ref[:3]):
+        g = host(got)
+        assert np.isfinite(g).all(), name
+        assert oracle.rel_err(g, want[:, t0:t0 + n]) <= TOL["bf16"], name
+    # the rank's share of dh in one unsplit shard call: the three shares of the split add up to it
+    _, _, _, dh_one = bwd(gg, qq, kk, vv, hd, group, H, H)
+    share = sum(p.double() for p in dh_parts)
+    scale = float(dh_one.abs().max())
+    assert float((share - dh_one.double()).abs().max()) <= (1e-2 if lh > 8 else 1e-5) * scale
