@@ -160,6 +160,32 @@ hy_status hyena_li_fwd_carry(const void *q, const void *k, const void *v, const 
 int64_t hyena_li_state_bytes(int64_t B, int64_t D);
 
 /*
+ * The two calls that let the stretches of a Hyena-LI sequence run at the same time (Sec. 4 applied to the recurrent
+ * form of Sec. 2.1: ranks exchange `order` running sums per channel instead of a halo).
+ *
+ * hyena_li_state: the running sums after the call's L steps, from k and v alone (no q, no y): what
+ * hyena_li_fwd_carry would leave in state_out, at the cost of one read of k and v.  state_in as there (NULL: the
+ * sequence starts here); L a multiple of 32; bf16, group % 16 == 0, D % 64 == 0, order <= 16
+ * (else HY_ERR_UNSUPPORTED).  workspace: hyena_li_state_workspace_bytes(...) bytes.
+ *
+ * hyena_li_state_fold: given the end states of n_states consecutive stretches of `steps` steps each, every one
+ * walked from a zero state (states: fp32 [n_states][B][D/16][64][4], the layout above), the state after all of
+ * them:  state_out = Lambda^(n_states * steps) state_in + sum_i Lambda^((n_states - 1 - i) * steps) states[i]
+ * (state_in NULL: zero; n_states = 0: state_out = state_in or zero).  Powers of the poles by repeated squaring in
+ * fp32.  A rank that holds stretch r of a sequence calls hyena_li_state on its k, v with a zero state, gathers
+ * everyone's result, folds those of stretches 0 .. r-1 and passes the outcome to hyena_li_fwd_carry as state_in.
+ * Both calls are asynchronous on hip_stream and allocate nothing; every written buffer must be disjoint from the
+ * others (HY_ERR_ALIGN).
+ */
+hy_status hyena_li_state(const void *k, const void *v, const float *lambda, const float *state_in, float *state_out,
+                         void *workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D, int32_t order,
+                         int32_t group, int32_t dtype, void *hip_stream);
+int64_t hyena_li_state_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype);
+hy_status hyena_li_state_fold(const float *states, int64_t n_states, int64_t steps, const float *lambda,
+                              const float *state_in, float *state_out, int64_t B, int64_t D, int32_t order,
+                              int32_t group, void *hip_stream);
+
+/*
  * hyena_li_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and bit-identical
  * results; the end-of-tile states of the scan go to a buffer of HYENA_LI_STATIC_SCRATCH_BYTES = 4 MiB that is

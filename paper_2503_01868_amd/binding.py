@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.hyena_li_fwd_carry.argtypes = [vp] * 9 + [i64, i64, i64, i64, i32, i32, ci, vp]
         L.hyena_li_state_bytes.argtypes = [i64, i64]
         L.hyena_li_state_bytes.restype = i64
+        L.hyena_li_state.argtypes = [vp] * 6 + [i64, i64, i64, i64, i32, i32, ci, vp]
+        L.hyena_li_state_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
+        L.hyena_li_state_workspace_bytes.restype = i64
+        L.hyena_li_state_fold.argtypes = [vp, i64, i64, vp, vp, vp, i64, i64, i32, i32, vp]
         L.hyena_li_workspace_bytes.argtypes = [i64, i64, i64, i32, i32, ci]
         L.hyena_li_workspace_bytes.restype = i64
         L.hyena_stream_copy.argtypes = [vp, vp, i64, vp]
@@ -76,7 +80,7 @@ def lib() -> ctypes.CDLL:
                      "hyena_featurize3_fwd",
                      "hyena_chain_fwd", "hyena_chain_fwd_shard", "hyena_se_bwd", "hyena_mr_bwd", "hyena_se_bwd_shard",
                      "hyena_mr_bwd_shard", "hyena_featurize_bwd", "hyena_chain_bwd", "hyena_li_fwd",
-                     "hyena_li_fwd_static", "hyena_li_fwd_carry",
+                     "hyena_li_fwd_static", "hyena_li_fwd_carry", "hyena_li_state", "hyena_li_state_fold",
                      "hyena_stream_copy", "hyena_stream_gate", "hyena_set_option"):
             getattr(L, name).restype = ci
         L.hyena_status_string.argtypes = [ci]
@@ -623,6 +627,69 @@ def hyena_li_fwd_carry(q, k, v, R, lam, group: int = 16, state_in=None, want_sta
     if rc != HY_OK:
         raise HyenaError(rc, "hyena_li_fwd_carry")
     return y, state_out
+
+
+def hyena_li_state(k, v, lam, group: int = 16, state_in=None, stream=None) -> torch.Tensor:
+    """The running sums after the steps of k, v (no q, no y): the state ``hyena_li_fwd_carry`` would return; see
+    ``hyena_li_state`` in hyena.h."""
+    _check_act("k", k)
+    _check_act("v", v, k)
+    order = _check_filter("lam", lam, k, group)
+    B, L, D = k.shape
+    code = _dtype_code(k)
+    nstate = int(lib().hyena_li_state_bytes(B, D))
+    if nstate < 0:
+        raise ValueError("D must be a multiple of 16")
+    if state_in is not None and (state_in.dtype != torch.float32 or state_in.numel() * 4 != nstate or
+                                 not state_in.is_contiguous() or state_in.device != k.device):
+        raise ValueError("state_in must be a float32 state of this shape")
+    state_out = torch.empty(nstate // 4, dtype=torch.float32, device=k.device)
+    need = int(lib().hyena_li_state_workspace_bytes(B, L, D, order, int(group), code))
+    if need < 0:
+        raise ValueError("not a valid Hyena-LI problem")
+    workspace = torch.empty(need, dtype=torch.uint8, device=k.device) if need > 0 else None   # device memory from PyTorch
+    c = ctypes
+    with torch.cuda.device(k.device):
+        rc = lib().hyena_li_state(
+            c.c_void_p(k.data_ptr()), c.c_void_p(v.data_ptr()), c.c_void_p(lam.data_ptr()),
+            c.c_void_p(state_in.data_ptr() if state_in is not None else None), c.c_void_p(state_out.data_ptr()),
+            c.c_void_p(workspace.data_ptr() if workspace is not None else None), c.c_int64(need), c.c_int64(B),
+            c.c_int64(L), c.c_int64(D), c.c_int32(order), c.c_int32(int(group)), c.c_int(code),
+            c.c_void_p(_stream(k, stream)))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_li_state")
+    return state_out
+
+
+def hyena_li_state_fold(states, steps: int, lam, B: int, D: int, group: int = 16, state_in=None, stream=None) -> torch.Tensor:
+    """The state after ``len(states)`` consecutive stretches of ``steps`` steps whose zero-start end states are given
+    (``states``: a float32 tensor [n, state floats] or a list of states); see ``hyena_li_state_fold`` in hyena.h."""
+    if isinstance(states, (list, tuple)):
+        states = torch.stack(list(states)) if len(states) > 0 else torch.empty((0, B * D * 16), dtype=torch.float32,
+                                                                              device=lam.device)
+    nstate = int(lib().hyena_li_state_bytes(B, D))
+    if nstate < 0:
+        raise ValueError("D must be a multiple of 16")
+    if (states.dtype != torch.float32 or states.dim() != 2 or states.shape[1] * 4 != nstate or not states.is_contiguous()
+            or states.device.type != "cuda"):
+        raise ValueError("states must be a contiguous float32 [n, B * D * 16] tensor on the GPU")
+    if lam.dtype != torch.float32 or lam.dim() != 2 or not lam.is_contiguous() or lam.shape[0] * int(group) != D:
+        raise ValueError("lam must be a contiguous float32 [D // group, order] tensor")
+    if state_in is not None and (state_in.dtype != torch.float32 or state_in.numel() * 4 != nstate or
+                                 not state_in.is_contiguous() or state_in.device != states.device):
+        raise ValueError("state_in must be a float32 state of this shape")
+    out = torch.empty(nstate // 4, dtype=torch.float32, device=states.device)
+    n = int(states.shape[0])
+    c = ctypes
+    with torch.cuda.device(states.device):
+        rc = lib().hyena_li_state_fold(
+            c.c_void_p(states.data_ptr() if n > 0 else None), c.c_int64(n), c.c_int64(int(steps)),
+            c.c_void_p(lam.data_ptr()), c.c_void_p(state_in.data_ptr() if state_in is not None else None),
+            c.c_void_p(out.data_ptr()), c.c_int64(B), c.c_int64(D), c.c_int32(int(lam.shape[1])), c.c_int32(int(group)),
+            c.c_void_p(_stream(states, stream)))
+    if rc != HY_OK:
+        raise HyenaError(rc, "hyena_li_state_fold")
+    return out
 
 
 def hyena_li_fwd_static(q, k, v, R, lam, group: int = 16, out=None, stream=None) -> torch.Tensor:

@@ -448,6 +448,62 @@ hy_status hyena_li_fwd_carry(const void* q, const void* k, const void* v, const 
 
 int64_t hyena_li_state_bytes(int64_t B, int64_t D) { return (B < 0 || D < 0 || D % 16 != 0) ? -1 : B * D * 64; }
 
+int64_t hyena_li_state_workspace_bytes(int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype) {
+    TuningSnapshot snap;
+    if (B < 0 || L < 0 || D < 0 || order < 1 || group < 1 || D % group != 0) return -1;
+    if (dtype != HY_F32 && dtype != HY_BF16) return -1;
+    LiShape s{B, L, D, order, group, static_cast<hy_dtype>(dtype)};
+    return li_state_workspace_bytes(s);
+}
+
+hy_status hyena_li_state(const void* k, const void* v, const float* lambda, const float* state_in, float* state_out,
+                         void* workspace, int64_t workspace_bytes, int64_t B, int64_t L, int64_t D, int32_t order,
+                         int32_t group, int32_t dtype, void* hip_stream) {
+    TuningSnapshot snap;
+    if (!state_out) return HY_ERR_NULL;
+    // validated like a forward call whose q is k, whose residues are the poles and whose only output is the state
+    const void* ins[2] = {k, v};
+    const FilterArg hs[1] = {{lambda, group, order}};
+    hy_status rc = validate(ins, 2, nullptr, 0, hs, 1, B, L, D, order, group, dtype);
+    if (rc != HY_OK) return rc;
+    if (workspace_bytes < 0) return HY_ERR_SHAPE;
+    if ((state_in && !aligned16(state_in)) || !aligned16(state_out)) return HY_ERR_ALIGN;
+    LiShape s{B, L, D, order, group, static_cast<hy_dtype>(dtype)};
+    if (!li_mfma_supported(s) || empty(B, L, D) || L % 32 != 0) return HY_ERR_UNSUPPORTED;
+    const int64_t bytes = B * L * D * 2;
+    const int64_t nf = filter_bytes(D, group, order);
+    const int64_t sb = B * D * 64;
+    const Range rd[4] = {{k, bytes}, {v, bytes}, {lambda, nf}, {state_in, state_in ? sb : 0}};
+    const Range wr[1] = {{state_out, sb}};
+    rc = check_disjoint(rd, 4, wr, 1);
+    if (rc != HY_OK) return rc;
+    const Range others[5] = {{k, bytes}, {v, bytes}, {lambda, nf}, {state_in, state_in ? sb : 0}, {state_out, sb}};
+    rc = check_workspace(workspace, workspace_bytes, li_state_workspace_bytes(s), others, 5);
+    if (rc != HY_OK) return rc;
+    LiPtrs p{nullptr, k, v, nullptr, lambda, nullptr, state_in, state_out};
+    return launch_li_state(p, s, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+hy_status hyena_li_state_fold(const float* states, int64_t n_states, int64_t steps, const float* lambda,
+                              const float* state_in, float* state_out, int64_t B, int64_t D, int32_t order,
+                              int32_t group, void* hip_stream) {
+    TuningSnapshot snap;
+    if (!lambda || !state_out || (n_states > 0 && !states)) return HY_ERR_NULL;
+    if (B < 0 || D < 0 || n_states < 0 || steps < 0 || order < 1 || group < 1 || D % group != 0) return HY_ERR_SHAPE;
+    if (D % 16 != 0 || order > 16) return HY_ERR_UNSUPPORTED;
+    if (!aligned16(states) || !aligned16(lambda) || !aligned16(state_out) || (state_in && !aligned16(state_in)))
+        return HY_ERR_ALIGN;
+    if (B == 0 || D == 0) return HY_OK;
+    if (B > (INT64_MAX / 64) / D || (n_states > 0 && n_states > INT64_MAX / (B * D * 64))) return HY_ERR_SHAPE;
+    const int64_t sb = B * D * 64;
+    const Range rd[3] = {{states, n_states * sb}, {lambda, filter_bytes(D, group, order)}, {state_in, state_in ? sb : 0}};
+    const Range wr[1] = {{state_out, sb}};
+    hy_status rc = check_disjoint(rd, 3, wr, 1);
+    if (rc != HY_OK) return rc;
+    return launch_li_state_fold(states, n_states, steps, lambda, state_in, state_out, B, D, order, group,
+                                static_cast<hipStream_t>(hip_stream));
+}
+
 hy_status hyena_li_fwd_static(const void* q, const void* k, const void* v, const float* R, const float* lambda,
                               void* y, int64_t B, int64_t L, int64_t D, int32_t order, int32_t group, int32_t dtype,
                               void* hip_stream) {

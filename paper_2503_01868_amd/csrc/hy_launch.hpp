@@ -169,6 +169,12 @@ hy_status launch_chain4(const ChainPtrs& p, const ChainShape& s, hipStream_t st)
 bool li_mfma_supported(const LiShape& s);
 int64_t li_workspace_bytes(const LiShape& s);
 hy_status launch_li_mfma(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st);
+// The running sums after the call's steps alone (k, v only; L % 32 == 0; matrix-core scan's domain), and the fold of
+// several stretches' zero-start end states [n][B][D/16][64][4] into the state after them.
+int64_t li_state_workspace_bytes(const LiShape& s);
+hy_status launch_li_state(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st);
+hy_status launch_li_state_fold(const float* states, int64_t n, int64_t steps, const float* lam, const float* state_in,
+                               float* state_out, int64_t B, int64_t D, int32_t order, int32_t group, hipStream_t st);
 hy_status launch_li_direct(const LiPtrs& p, const LiShape& s, hipStream_t st);
 // Backward, short filters: fused streaming pass + reduction of partial filter gradients held in `ws`.
 bool bwd_stencil_supported(const BwdShape& s);

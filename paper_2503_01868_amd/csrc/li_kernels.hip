@@ -341,6 +341,67 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void li_mfma_kernel(LiAr
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// Folding states: out = Lambda^(steps of all records) s_in + sum_i Lambda^(steps after record i) rec_i, where every
+// record is the end state of a stretch of `steps` steps walked from zero (`last_steps` for the last one).  This is
+// the Horner sum of pass 2's start state as a kernel of its own: it turns the tile records of a state-only walk
+// into the state after the walk, and the end states of several ranks' stretches into each rank's start state.
+// One lane per float4 of a state ([B][D/16][64 lanes][4]: lane (li, lq) of a 16-channel block holds exponentials
+// 4 lq .. 4 lq + 3 of channel li); records of one batch item are rec_stride_i floats apart, batch items rec_stride_b.
+__device__ __forceinline__ float powi64(float x, int64_t e) {  // x^e, e >= 0, by squaring
+    float r = 1.0f;
+    while (e > 0) {
+        if (e & 1) r *= x;
+        x *= x;
+        e >>= 1;
+    }
+    return r;
+}
+
+__global__ __launch_bounds__(256) void li_fold_kernel(const float* __restrict__ rec, int64_t n, int64_t rec_stride_b,
+                                                      int64_t rec_stride_i, const float* __restrict__ lam,
+                                                      const float* __restrict__ s_in, float* __restrict__ s_out, int64_t B,
+                                                      int64_t D, int32_t order, int32_t group, int64_t steps,
+                                                      int64_t last_steps) {
+    const int64_t per_b = (D / 16) * 64;  // float4s of one batch item's state
+    const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (x >= B * per_b) return;
+    const int64_t b = x / per_b, within = x % per_b;
+    const int lane = (int)(within % 64);
+    const int64_t channel = (within / 64) * 16 + lane % 16;
+    const float* lp = lam + (channel / group) * (int64_t)order;
+    float pw[4], pl[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int nn = 4 * (lane / 16) + r;
+        const float l = nn < order ? lp[nn] : 0.0f;
+        pw[r] = powi64(l, steps);
+        pl[r] = powi64(l, last_steps);
+    }
+    float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (s_in) s = *reinterpret_cast<const float4*>(s_in + x * 4);
+    const float* rp = rec + b * rec_stride_b + within * 4;
+    for (int64_t i0 = 0; i0 < n; i0 += 8) {
+        float4 st[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {  // the loads do not depend on the running sum; past the end the last record repeats
+            const int64_t ii = i0 + i < n ? i0 + i : n - 1;
+            st[i] = *reinterpret_cast<const float4*>(rp + ii * rec_stride_i);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (i0 + i < n) {
+                const bool last = i0 + i == n - 1;
+                s.x = (last ? pl[0] : pw[0]) * s.x + st[i].x;
+                s.y = (last ? pl[1] : pw[1]) * s.y + st[i].y;
+                s.z = (last ? pl[2] : pw[2]) * s.z + st[i].z;
+                s.w = (last ? pl[3] : pw[3]) * s.w + st[i].w;
+            }
+        }
+    }
+    *reinterpret_cast<float4*>(s_out + x * 4) = s;
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // General kernel: the recurrence itself, one lane per (batch item, channel).  Any dtype, any group, up to
 // kMaxOrderDirect exponentials; slow (B * D lanes in all), the correctness path for what the matrix-core kernel
 // does not take.  The running sums and the output sum are kept in fp64: a slow pole (lambda close to 1) carries
@@ -413,6 +474,49 @@ int li_waves(const LiShape& s) {
     return 4;
 }
 
+hy_status launch_fold(const float* rec, int64_t n, int64_t stride_b, int64_t stride_i, const float* lam, const float* s_in,
+                      float* s_out, int64_t B, int64_t D, int32_t order, int32_t group, int64_t steps, int64_t last_steps,
+                      hipStream_t st) {
+    const int64_t items = B * (D / 16) * 64;
+    const int64_t nb = (items + 255) / 256;
+    if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
+    return launch_kernel(li_fold_kernel, dim3((uint32_t)nb), dim3(256), st, rec, n, stride_b, stride_i, lam, s_in, s_out, B,
+                         D, order, group, steps, last_steps);
+}
+
+// State-only walk: pass 1 over EVERY tile (the kernel skips the last of `tiles_per_seq` tiles, so it is told of one
+// more than there are), then the fold of the tile records.
+template <int NW>
+hy_status launch_li_state_nw(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st) {
+    constexpr int PF = 2;
+    LiArgs a;
+    a.q = nullptr;
+    a.k = static_cast<const uint16_t*>(p.k);
+    a.v = static_cast<const uint16_t*>(p.v);
+    a.R = p.lam;  // the state does not depend on the residues; the kernel's set-up reads the table all the same
+    a.lam = p.lam;
+    a.y = nullptr;
+    a.ws = static_cast<float*>(ws);
+    a.s_in = nullptr;
+    a.s_out = nullptr;
+    a.L = s.L;
+    a.D = s.D;
+    a.order = s.order;
+    a.group = s.group;
+    a.ncb = (int32_t)(s.D / (16 * NW));
+    const int64_t rows = li_rows(s, NW);
+    a.rows = (int32_t)rows;
+    const int64_t tiles = (s.L + rows - 1) / rows;
+    a.tiles_per_seq = (int32_t)(tiles + 1);
+    const int64_t nb = s.B * tiles * a.ncb;
+    if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
+    const hy_status rc = launch_kernel((li_mfma_kernel<NW, PF, true>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
+    if (rc != HY_OK) return rc;
+    const int64_t ws_tile = (s.D / 16) * 256;
+    return launch_fold(a.ws, tiles, tiles * ws_tile, ws_tile, p.lam, p.state_in, p.state_out, s.B, s.D, s.order, s.group,
+                       rows, s.L - (tiles - 1) * rows, st);
+}
+
 template <int NW>
 hy_status launch_li_nw(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st) {
     constexpr int PF = 2;
@@ -467,6 +571,29 @@ hy_status launch_li_mfma(const LiPtrs& p, const LiShape& s, void* ws, hipStream_
         case 8: return launch_li_nw<8>(p, s, ws, st);
         default: return launch_li_nw<4>(p, s, ws, st);
     }
+}
+
+int64_t li_state_workspace_bytes(const LiShape& s) {
+    if (!li_mfma_supported(s) || s.B == 0 || s.L == 0 || s.D == 0) return 0;
+    const int64_t rows = li_rows(s, li_waves(s));
+    const int64_t tiles = (s.L + rows - 1) / rows;
+    return s.B * tiles * (s.D / 16) * 256 * (int64_t)sizeof(float);
+}
+
+hy_status launch_li_state(const LiPtrs& p, const LiShape& s, void* ws, hipStream_t st) {
+    if (!li_mfma_supported(s) || s.L % kChunk != 0 || !p.state_out) return HY_ERR_UNSUPPORTED;
+    switch (li_waves(s)) {
+        case 16: return launch_li_state_nw<16>(p, s, ws, st);
+        case 8: return launch_li_state_nw<8>(p, s, ws, st);
+        default: return launch_li_state_nw<4>(p, s, ws, st);
+    }
+}
+
+hy_status launch_li_state_fold(const float* states, int64_t n, int64_t steps, const float* lam, const float* state_in,
+                               float* state_out, int64_t B, int64_t D, int32_t order, int32_t group, hipStream_t st) {
+    if (D % 16 != 0 || order < 1 || order > kMaxOrder) return HY_ERR_UNSUPPORTED;
+    const int64_t per = (D / 16) * 256;  // floats of one batch item's state
+    return launch_fold(states, n, per, B * per, lam, state_in, state_out, B, D, order, group, steps, steps, st);
 }
 
 hy_status launch_li_direct(const LiPtrs& p, const LiShape& s, hipStream_t st) {

@@ -17,6 +17,9 @@ bool li_mfma_supported(const LiShape& s) { return s.dtype == HY_BF16 && s.group 
 int64_t li_workspace_bytes(const LiShape& s) { return li_mfma_supported(s) ? s.B * ((s.L + 511) / 512 - 1) * (s.D / 16) * 1024 : 0; }
 hy_status launch_li_mfma(const LiPtrs&, const LiShape&, void*, hipStream_t) { return HY_OK; }
 hy_status launch_li_direct(const LiPtrs&, const LiShape& s, hipStream_t) { return s.order <= 64 ? HY_OK : HY_ERR_UNSUPPORTED; }
+int64_t li_state_workspace_bytes(const LiShape& s) { return li_mfma_supported(s) ? s.B * ((s.L + 511) / 512) * (s.D / 16) * 1024 : 0; }
+hy_status launch_li_state(const LiPtrs&, const LiShape&, void*, hipStream_t) { return HY_OK; }
+hy_status launch_li_state_fold(const float*, int64_t, int64_t, const float*, const float*, float*, int64_t, int64_t, int32_t, int32_t, hipStream_t) { return HY_OK; }
 bool chain4_supported(const ChainShape& s) {
     return s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 128 == 0 && s.lh <= 129 && s.lf >= 1 && s.lf <= 9;
 }

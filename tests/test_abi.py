@@ -327,6 +327,35 @@ def test_options_are_snapshotted_per_call_and_safe_to_set_from_other_threads():
     assert seen <= {a, b}
 
 
+def test_long_implicit_state_entry_points_reject_bad_arguments():
+    lib = binding.lib()
+    Q = [0x100000 * (i + 1) for i in range(6)]
+
+    def st(k=Q[0], v=Q[1], lam=Q[2], s_in=None, s_out=Q[3], ws=Q[4], wsb=1 << 20, B=1, L=64, D=64, order=4, group=16,
+           dtype=1):
+        return lib.hyena_li_state(k, v, lam, s_in, s_out, ws, wsb, B, L, D, order, group, dtype, None)
+
+    assert st(k=None) == 1 and st(v=None) == 1 and st(lam=None) == 1 and st(s_out=None) == 1
+    assert st(order=0) == 2 and st(group=5) == 2 and st(dtype=3) == 3 and st(wsb=-1) == 2
+    assert st(s_out=Q[3] + 4) == 4 and st(s_in=Q[5] + 8) == 4 and st(s_out=Q[0]) == 4 and st(s_in=Q[3]) == 4
+    assert st(L=100) == 5 and st(dtype=0) == 5 and st(group=8) == 5 and st(order=17) == 5 and st(L=0) == 5
+    need = lib.hyena_li_state_workspace_bytes(1, 64, 64, 4, 16, 1)
+    assert need == 1 * 1 * (64 // 16) * 256 * 4            # one tile: one record per 16 channels
+    assert st(ws=None) == 1 and st(wsb=need - 1) == 2 and st(ws=Q[4] + 4) == 4 and st(ws=Q[1]) == 4
+    assert lib.hyena_li_state_workspace_bytes(1, 64, 64, 4, 16, 0) == 0 and lib.hyena_li_state_workspace_bytes(1, 64, 64, 0, 16, 1) == -1
+
+    def fold(states=Q[0], n=3, steps=512, lam=Q[2], s_in=None, s_out=Q[3], B=1, D=64, order=4, group=16):
+        return lib.hyena_li_state_fold(states, n, steps, lam, s_in, s_out, B, D, order, group, None)
+
+    assert fold(states=None) == 1 and fold(lam=None) == 1 and fold(s_out=None) == 1
+    assert fold(n=-1) == 2 and fold(steps=-1) == 2 and fold(order=0) == 2 and fold(group=5) == 2
+    assert fold(D=24, group=8) == 5 and fold(order=17) == 5
+    assert fold(states=Q[0] + 4) == 4 and fold(s_out=Q[3] + 8) == 4 and fold(s_in=Q[5] + 4) == 4
+    assert fold(s_out=Q[0] + 2 * 64 * 64) == 4      # the result inside the third state that is read
+    assert fold(s_out=Q[2]) == 4 and fold(s_in=Q[3]) == 4
+    assert fold(B=0) == 0 and fold(D=0, group=1) == 0
+
+
 @pytest.mark.parametrize("entry", ["hyena_se_fwd_shard", "hyena_mr_fwd_shard"])
 def test_shard_entry_points_reject_bad_layouts(entry):
     lib = binding.lib()

@@ -312,3 +312,68 @@ def test_carry_without_states_is_the_plain_call_and_bad_requests_are_refused():
         binding.hyena_li_fwd_carry(q[:, :100].contiguous(), k[:, :100].contiguous(), v[:, :100].contiguous(), R, lam, group)
     with pytest.raises(binding.HyenaError):   # the general kernel keeps no such state
         binding.hyena_li_fwd_carry(q.float(), k.float(), v.float(), R, lam, group)
+
+
+# ------------------------------------------------------------------ stretches that run at the same time
+@pytest.mark.parametrize("case", [
+    # B, L, D, order, group, number of equal stretches, mr_rows
+    (2, 2048, 128, 16, 16, 4, 0),
+    (1, 3072, 256, 7, 32, 3, 128),        # several tiles per stretch
+    (3, 256, 64, 16, 16, 8, 32),          # one-chunk stretches
+    (1, 8192, 512, 16, 16, 4, 0),
+])
+def test_stretches_from_zero_states_plus_a_fold_equal_the_whole_sequence(case):
+    """What ranks that hold consecutive stretches of one sequence do (Sec. 4 applied to the recurrent form):
+    hyena_li_state on every stretch from a zero state (independent of each other), hyena_li_state_fold of the
+    stretches before a rank into its start state, then hyena_li_fwd_carry from there, here in reverse order to show
+    that no stretch waits for another.  States and outputs against the oracle on the whole sequence."""
+    B, L, D, order, group, n, rows = case
+    say("li parallel stretches B=%d L=%d D=%d order=%d group=%d n=%d rows=%d" % case)
+    binding.set_option("mr_rows", rows)
+    rng = np.random.Generator(np.random.PCG64(650 + L + n))
+    q, k, v = (synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3))
+    R, lam = synth.li_params(rng, D // group, order)
+    dq, dk, dv, dR, dl = dev(q), dev(k), dev(v), dev(R), dev(lam)
+    T = L // n
+    cut = lambda x, i: x[:, i * T:(i + 1) * T].contiguous()
+    local = [binding.hyena_li_state(cut(dk, i), cut(dv, i), dl, group) for i in range(n)]
+    for i in (0, n - 1):   # a stretch's own end state is the definition's on that stretch alone
+        want = oracle.li_state(k[:, i * T:(i + 1) * T], v[:, i * T:(i + 1) * T], lam, group=group)
+        assert oracle.rel_err(_state_as_oracle(local[i], B, D, order), want) <= TOL["bf16"]
+    parts = [None] * n
+    for i in reversed(range(n)):
+        start = binding.hyena_li_state_fold(local[:i], T, dl, B, D, group)
+        want = oracle.li_state(k[:, :i * T], v[:, :i * T], lam, group=group) if i > 0 else np.zeros((B, D, order))
+        got = _state_as_oracle(start, B, D, order)
+        assert np.isfinite(got).all()
+        assert np.abs(got - want).max() <= TOL["bf16"] * max(np.abs(want).max(), 1e-30), i
+        parts[i], _ = binding.hyena_li_fwd_carry(cut(dq, i), cut(dk, i), cut(dv, i), dR, dl, group, state_in=start,
+                                                 want_state=False)
+    y = torch.cat(parts, dim=1)
+    ref = oracle.li_recurrent(q, k, v, R, lam, group=group)
+    assert oracle.rel_err(host(y), ref) <= TOL["bf16"]
+    assert oracle.rel_err(host(y), host(binding.hyena_li_fwd(dq, dk, dv, dR, dl, group))) <= TOL["bf16"]
+    # the state-only walk continues a sequence like the carry call does
+    chained = None
+    for i in range(n):
+        chained = binding.hyena_li_state(cut(dk, i), cut(dv, i), dl, group, state_in=chained)
+    want = oracle.li_state(k, v, lam, group=group)
+    assert oracle.rel_err(_state_as_oracle(chained, B, D, order), want) <= TOL["bf16"]
+    folded = binding.hyena_li_state_fold(local, T, dl, B, D, group)
+    assert oracle.rel_err(_state_as_oracle(folded, B, D, order), want) <= TOL["bf16"]
+
+
+def test_state_calls_refuse_what_they_cannot_do():
+    B, L, D, order, group = 1, 640, 128, 16, 16
+    rng = np.random.Generator(np.random.PCG64(612))
+    k, v = (dev(synth.normal_tensor(rng, (B, L, D), "bf16")) for _ in range(2))
+    _, lam = (dev(x) for x in synth.li_params(rng, D // group, order))
+    with pytest.raises(binding.HyenaError):   # a length that is no multiple of 32
+        binding.hyena_li_state(k[:, :100].contiguous(), v[:, :100].contiguous(), lam, group)
+    with pytest.raises(binding.HyenaError):   # fp32: the general kernel keeps no such state
+        binding.hyena_li_state(k.float(), v.float(), lam, group)
+    zero = binding.hyena_li_state_fold([], 512, lam, B, D, group)
+    assert torch.count_nonzero(zero) == 0
+    s = binding.hyena_li_state(k, v, lam, group)
+    same = binding.hyena_li_state_fold([], 512, lam, B, D, group, state_in=s)    # nothing to fold: the state itself
+    assert torch.equal(same, s)
