@@ -457,7 +457,6 @@ hy_status launch_stencil_lh(const BwdPtrs& p, const BwdShape& s, void* ws, hipSt
         : launch_kernel((bwd_stencil_kernel<T, VEC, LH, R, false>), dim3((uint32_t)nb), dim3(kBlock), st, a);
     if (rc != HY_OK) return rc;
     const int64_t nsets = s.B * a.tiles_per_seq;
-    const int64_t nout = (s.D / s.group) * s.lh;
     return launch_dh_reduce(a.partial, p.dh, nsets, s.D, s.lh, s.group, st);
 }
 
