@@ -469,6 +469,13 @@ int li_waves(const LiShape& s) {
     // (half as many tiles per sequence, twice as long): measured at B = 1, D = 4096: L = 2048 29.8 against 32.5 us,
     // L = 4096 45.8 against 48.6; from L = 8192 on the wide workgroup wins (76.2 against 79.2 us).
     if (tuning().mr_waves == 0 && tuning().mr_rows == 0 && s.D % 256 == 0 && li_rows(s, 16) < 512) return 8;
+    // A batch that fills the chip with narrower workgroups of ONE tile per sequence takes them: a single pass moves
+    // 8 bytes per output where the two-pass scan moves 12 (measured at L = 8192, D = 4096: B = 8 400 us with 8
+    // waves against 445 with 16, B = 4 197 us with 4 waves against 241; B = 16 fills it with 16 waves: 695 us, 77%).
+    if (tuning().mr_waves == 0 && tuning().mr_rows == 0 && s.D % 256 == 0 && li_rows(s, 16) < s.L) {
+        if (s.B * (s.D / 128) >= 256) return 8;
+        if (s.B * (s.D / 64) >= 256) return 4;
+    }
     if (nw == 16 && s.D % 256 == 0) return 16;
     if (nw >= 8 && s.D % 128 == 0) return 8;
     return 4;
