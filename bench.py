@@ -65,6 +65,7 @@ def parse():
                          "width 4096); the JSON line then names the changed shape and carries no stored traffic figure")
     ap.add_argument("--batch", type=int, default=0,
                     help="override B of the workload (like --seq-len: the line names the changed shape, no stored traffic)")
+    ap.add_argument("--width", type=int, default=0, help="override D of the workload (likewise)")
     ap.add_argument("--sets", type=int, default=0, help="independent buffer sets to rotate through (0 = auto)")
     ap.add_argument("--depth", type=int, default=0,
                     help="strip yardsticks only: chunks of loads in flight per lane (0 = the workload's own: 2 as in the operator kernels, 4 / 8 for strip256w8 / strip256w4)")
@@ -107,7 +108,7 @@ def upload(w, torch):
 class Workload:
     """Device-resident rotating buffer sets plus the pre-marshalled launches of one configuration."""
 
-    def __init__(self, name, nsets, torch, pkg, synth, seq_len=0, depth=0, batch=0):
+    def __init__(self, name, nsets, torch, pkg, synth, seq_len=0, depth=0, batch=0, width=0):
         self.name, self.torch, self.pkg = name, torch, pkg
         self.overlap = name.endswith("_overlap")   # shards split into an interior call and a boundary call
         name = name[:-8] + "_shards" if self.overlap else name
@@ -120,6 +121,8 @@ class Workload:
         over = {"L": seq_len} if seq_len > 0 else {}
         if batch > 0:
             over["B"] = batch
+        if width > 0:
+            over["D"] = width
         if self.strip is not None:
             name = "c1"  # the yardsticks run on c1's tensors (its filter is not used)
         self.cfg = synth.config(name, **over)
@@ -368,11 +371,11 @@ def entry_point(wl):
 
 def measure(name, args, torch, pkg, synth, steps, warmup, settle=0):
     """Times one workload; returns it with the figures every line and every "also" entry carries."""
-    wl = Workload(name, args.sets, torch, pkg, synth, args.seq_len, args.depth, args.batch)
+    wl = Workload(name, args.sets, torch, pkg, synth, args.seq_len, args.depth, args.batch, args.width)
     wall, kern_ms = wl.run(steps, warmup, settle)
     ms_step = 1e3 * wall / steps
     gbs = wl.algo_bytes() / (kern_ms * 1e-3) / 1e9
-    traffic, source = stored_traffic(name, args.seq_len if args.batch <= 0 else 1)
+    traffic, source = stored_traffic(name, args.seq_len if args.batch <= 0 and args.width <= 0 else 1)
     res = {
         "tokens_per_s": wl.tokens * steps / wall, "ms_per_step": ms_step, "steps": steps, "warmup": warmup,
         "settle_launches_before_warmup": settle, "buffer_sets": len(wl.sets),
@@ -457,7 +460,7 @@ def main():
         got = (d["dq"] if wl.bwd else d["y"])[:1, :y_ref.shape[1]].float().cpu().numpy().astype(np.float64)
         out["parity_rel_err"] = oracle.rel_err(got, y_ref)
 
-    if args.workload == "c1" and args.also and args.seq_len <= 0 and args.batch <= 0:
+    if args.workload == "c1" and args.also and args.seq_len <= 0 and args.batch <= 0 and args.width <= 0:
         del wl
         torch.cuda.empty_cache()
         out["also"] = {}
