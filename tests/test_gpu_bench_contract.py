@@ -64,6 +64,24 @@ def test_sharded_workload_times_the_shard_entry_point_and_keeps_parity():
     assert d["roofline"]["traffic"] is None and d["parity_rel_err"] <= 2e-2
 
 
+def test_shape_overrides_change_the_named_workload_and_drop_the_stored_traffic():
+    proc = run_bench("--workload", "li2", "--batch", "2", "--width", "2048", "--seq-len", "2048", "--steps", "5",
+                     "--warmup", "2", "--settle", "0", "--cpu-seconds", "1")
+    assert proc.returncode == 0, proc.stderr[-2000:]
+    d = json.loads(proc.stdout.strip())
+    assert "B=2 L=2048 D=2048" in d["config"]["workload"] and d["roofline"]["traffic"] is None
+    assert "also" not in d and d["parity_rel_err"] <= 2e-2
+    assert d["roofline"]["algorithmic_bytes_per_launch"] == 8.0 * 2 * 2048 * 2048
+
+
+def test_backward_of_the_chain_runs_as_a_workload_with_parity():
+    proc = run_bench("--workload", "c4_bwd", "--batch", "1", "--seq-len", "2048", "--steps", "3", "--warmup", "1",
+                     "--settle", "0", "--cpu-seconds", "1")
+    assert proc.returncode == 0, proc.stderr[-2000:]
+    d = json.loads(proc.stdout.strip())
+    assert "hyena_chain_bwd" in d["roofline"]["kernel"] and d["parity_rel_err"] <= 2e-2
+
+
 def test_more_than_one_gpu_is_refused_with_a_message():
     proc = run_bench("--gpus", "2")
     assert proc.returncode != 0
