@@ -202,7 +202,7 @@ hy_status gated_fwd(bool mr_first, const void* q, const void* k, const void* v, 
     rc = mr_first ? launch_mr_mfma(p, s, st) : HY_ERR_UNSUPPORTED;
     // short filters (that the grouped matrix-core path does not take) are the SE kernels' business
     if (rc == HY_ERR_UNSUPPORTED && (lh <= 8 || !mr_first)) {
-        if (se_walk_preferred(s)) return launch_se_walk(p, s, st);
+        if (se_walk_preferred(s)) return launch_se_walk(&p, 1, s, st);
         rc = launch_stencil(&p, 1, s, st);
     }
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_cp4(p, s, st);
@@ -270,6 +270,7 @@ hy_status hyena_featurize_fwd(const void* x, const float* h, void* y, int64_t B,
     ConvPtrs p{nullptr, x, nullptr, h, y};
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), false};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (se_walk_preferred(s, 1)) return launch_se_walk(&p, 1, s, st);  // long sequences: the tile walker
     rc = launch_stencil(&p, 1, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(&p, 1, s, st);
     return rc;
@@ -288,6 +289,7 @@ hy_status hyena_featurize3_fwd(const void* q, const void* k, const void* v, cons
     ConvPtrs p[3] = {{nullptr, q, nullptr, hq, qo}, {nullptr, k, nullptr, hk, ko}, {nullptr, v, nullptr, hv, vo}};
     ConvShape s{B, L, D, lh, group, static_cast<hy_dtype>(dtype), false};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (se_walk_preferred(s, 3)) return launch_se_walk(p, 3, s, st);
     rc = launch_stencil(p, 3, s, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(p, 3, s, st);
     return rc;
@@ -335,7 +337,7 @@ hy_status hyena_chain_fwd(const void* q, const void* k, const void* v, const flo
     char* ws = static_cast<char*>(workspace);
     ConvPtrs f[3] = {{nullptr, q, nullptr, hq, ws}, {nullptr, k, nullptr, hk, ws + bytes}, {nullptr, v, nullptr, hv, ws + 2 * bytes}};
     ConvShape fs{B, L, D, lf, feat_group, static_cast<hy_dtype>(dtype), false};
-    rc = launch_stencil(f, 3, fs, st);
+    rc = se_walk_preferred(fs, 3) ? launch_se_walk(f, 3, fs, st) : launch_stencil(f, 3, fs, st);
     if (rc == HY_ERR_UNSUPPORTED) rc = launch_direct(f, 3, fs, st);
     if (rc != HY_OK) return rc;
     ConvPtrs m{ws, ws + bytes, ws + 2 * bytes, h, y};

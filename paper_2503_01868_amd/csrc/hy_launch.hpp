@@ -146,8 +146,9 @@ struct TuningSnapshot {
 hy_status launch_stencil(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
 // Short-filter kernel for long sequences (bf16, gated, lh <= 8, D % 128 == 0) on the MR kernel's data-movement
 // skeleton; se_walk_preferred() says whether the dispatcher should take it for this shape.
-bool se_walk_preferred(const ConvShape& s);
-hy_status launch_se_walk(const ConvPtrs& p, const ConvShape& s, hipStream_t st);
+// Ungated (featurizer) calls may bring up to three problems that share the shape (as launch_stencil does).
+bool se_walk_preferred(const ConvShape& s, int nprob = 1);
+hy_status launch_se_walk(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
 // General fp32 direct convolution: any lh, any group, both dtypes.
 hy_status launch_direct(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st);
 // Block-Toeplitz contraction on bf16 MFMA.  HY_ERR_UNSUPPORTED outside its domain.

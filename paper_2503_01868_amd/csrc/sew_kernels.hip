@@ -14,6 +14,10 @@
 // its taps in registers, gates with the q piece it loaded itself and stores 16 bytes.  Three slots make the single
 // barrier per chunk sufficient: chunk c+1 writes slot (c+1)%3 and the look-back rows of slot (c+2)%3, never the
 // slot chunk c is still being read from.
+//
+// GATED = false is the featurizer convolution of Eq. 1 (x' = h * x, no gates) on the same skeleton: u is the input
+// itself (the k pointer), nothing is read for v and q, and blockIdx.y selects one of up to three independent
+// problems (q, k, v of the operator chain each with its own filter), so that the three featurizers are one launch.
 #include "hy_common.hpp"
 #include "hy_launch.hpp"
 
@@ -22,10 +26,10 @@ namespace {
 
 struct SewArgs {
     const uint16_t* q;
-    const uint16_t* k;
+    const uint16_t* k[3];  // per problem (gated: one problem)
     const uint16_t* v;
-    const float* h;
-    uint16_t* y;
+    const float* h[3];
+    uint16_t* y[3];
     int64_t L, D;
     int64_t bstride_kv, bstride_qy;  // elements between batch items in k, v / in q, y
     int32_t hist;           // rows of k and v in front of row 0 that hold data: 0 or >= kLook
@@ -38,7 +42,7 @@ struct SewArgs {
 constexpr int kChunk = 32;
 constexpr int kLook = 8;  // look-back rows per slot, >= lh - 1
 
-template <int LH, int NW, int kPrefetch>
+template <int LH, int NW, int kPrefetch, bool GATED>
 __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewArgs a) {
     static_assert(LH >= 1 && LH - 1 <= kLook, "the look-back rows must cover the filter");
     constexpr int PPR = 2 * NW;                 // 16-byte pieces of bf16 per row = lanes per row
@@ -48,6 +52,10 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
 
     const int tid = threadIdx.x;
     const uint32_t lb = blockIdx.x;
+    const int pi = GATED ? 0 : (int)blockIdx.y;
+    const uint16_t* const kp = a.k[pi];
+    const float* const hp0 = a.h[pi];
+    uint16_t* const yp = a.y[pi];
     const int cb = lb % a.ncb;
     const int64_t tile = lb / a.ncb;
     const int64_t b = tile / a.tiles_per_seq;
@@ -76,8 +84,8 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
         const bool used = ci < nchunks && t >= t_lo;
         t = t < te32 ? t : te32 - 1;
         const int64_t off = used ? (int64_t)t * (int64_t)D32 + ld_off : (int64_t)idle_off;
-        kk = load_words_nt<4>(a.k + seq0kv + off);
-        vv = load_words_nt<4>(a.v + seq0kv + off);
+        kk = load_words_nt<4>(kp + seq0kv + off);
+        if constexpr (GATED) vv = load_words_nt<4>(a.v + seq0kv + off);
     };
     auto load_q = [&](int ci, Words<4>& qq) {
         int t = tb32 + ci * kChunk + lr;
@@ -90,14 +98,14 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
 #pragma unroll
     for (int i = 0; i < kPrefetch; ++i) {
         load_kv(i, kpre[i], vpre[i]);
-        load_q(i, qpre[i]);
+        if constexpr (GATED) load_q(i, qpre[i]);
     }
 
     // taps of this lane's 8 channels
     float tap[8][LH];
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-        const float* hp = a.h + ((cblock0 + 8 * lp + c) / a.group) * (int64_t)LH;
+        const float* hp = hp0 + ((cblock0 + 8 * lp + c) / a.group) * (int64_t)LH;
 #pragma unroll
         for (int j = 0; j < LH; ++j) tap[c][j] = hp[j];
     }
@@ -121,9 +129,14 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
             {
                 float kf[8], vf[8];
                 Pack<BF16, 8>::unpack(kpre[sgi], kf);
-                Pack<BF16, 8>::unpack(vpre[sgi], vf);
+                if constexpr (GATED) {
+                    Pack<BF16, 8>::unpack(vpre[sgi], vf);
 #pragma unroll
-                for (int c = 0; c < 8; ++c) uf[c] = kf[c] * vf[c];
+                    for (int c = 0; c < 8; ++c) uf[c] = kf[c] * vf[c];
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) uf[c] = kf[c];
+                }
             }
             {
                 char* p = ring + slot * SLOT + (kLook + lr) * ROWB + lane_col;
@@ -158,26 +171,44 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
                     z[6] = __builtin_fmaf(tap[6][j], wb.z, z[6]);
                     z[7] = __builtin_fmaf(tap[7][j], wb.w, z[7]);
                 }
-                float qf[8];
-                Pack<BF16, 8>::unpack(qpre[sgi], qf);
+                if constexpr (GATED) {
+                    float qf[8];
+                    Pack<BF16, 8>::unpack(qpre[sgi], qf);
 #pragma unroll
-                for (int c = 0; c < 8; ++c) z[c] *= qf[c];
-                store_words_nt<4>(a.y + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), Pack<BF16, 8>::pack(z));
+                    for (int c = 0; c < 8; ++c) z[c] *= qf[c];
+                }
+                store_words_nt<4>(yp + seq0 + ((uint64_t)(uint32_t)t * D32 + ld_off), Pack<BF16, 8>::pack(z));
             }
-            load_q(ci + kPrefetch, qpre[sgi]);
+            if constexpr (GATED) load_q(ci + kPrefetch, qpre[sgi]);
         }
     }
 }
 
+// Tiles per sequence when `base` workgroups cover one tile of every batch item and problem: one workgroup per
+// compute unit; where that is not a whole number of rounds of 256 workgroups (three problems, odd batches) the
+// sequence is cut finer if that gives whole rounds (up to four) and a tile keeps 1024 steps (three featurizers at
+// B = 4: 192 workgroups on 256 compute units ran slower than the stencil, 768 run faster).
+int64_t walk_tiles(int64_t base, int64_t L) {
+    int64_t tiles = 256 / base;
+    if (tiles < 1) tiles = 1;
+    if ((base * tiles) % 256 == 0) return tiles;
+    for (int64_t t = tiles + 1; base * t <= 1024 && (L + t - 1) / t >= 1024; ++t)
+        if ((base * t) % 256 == 0) return t;
+    return tiles;  // no finer cut gives whole rounds
+}
+
 template <int LH, int NW>
-hy_status launch_sew_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
+hy_status launch_sew_nw(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st) {
     constexpr int PF = 2;
     SewArgs a;
-    a.q = static_cast<const uint16_t*>(p.q);
-    a.k = static_cast<const uint16_t*>(p.k);
-    a.v = static_cast<const uint16_t*>(p.v);
-    a.h = p.h;
-    a.y = static_cast<uint16_t*>(p.y);
+    a.q = static_cast<const uint16_t*>(p[0].q);
+    a.v = static_cast<const uint16_t*>(p[0].v);
+    for (int i = 0; i < 3; ++i) {
+        const ConvPtrs& pp = p[i < nprob ? i : 0];
+        a.k[i] = static_cast<const uint16_t*>(pp.k);
+        a.h[i] = pp.h;
+        a.y[i] = static_cast<uint16_t*>(pp.y);
+    }
     a.L = s.L;
     a.D = s.D;
     a.bstride_kv = s.stride_kv();
@@ -188,8 +219,7 @@ hy_status launch_sew_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.ncb = (int32_t)(s.D / (16 * NW));
     int64_t rows = tuning().se_rows;
     if (rows <= 0) {
-        int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
-        if (tiles < 1) tiles = 1;
+        const int64_t tiles = walk_tiles(nprob * s.B * a.ncb, s.L);
         rows = (s.L + tiles - 1) / tiles;
         if (rows < 8 * kChunk) rows = 8 * kChunk;
     }
@@ -198,20 +228,22 @@ hy_status launch_sew_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.tiles_per_seq = (int32_t)((s.L + rows - 1) / rows);
     const int64_t nb = s.B * a.tiles_per_seq * a.ncb;
     if (nb > 0x7fffffffLL) return HY_ERR_UNSUPPORTED;
-    return launch_kernel((se_walk_kernel<LH, NW, PF>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
+    if (s.gated) return launch_kernel((se_walk_kernel<LH, NW, PF, true>), dim3((uint32_t)nb), dim3(NW * 64), st, a);
+    return launch_kernel((se_walk_kernel<LH, NW, PF, false>), dim3((uint32_t)nb, (uint32_t)nprob), dim3(NW * 64), st, a);
 }
 
 template <int LH>
-hy_status launch_sew_lh(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
-    if (s.D % 256 == 0 && tuning().mr_waves != 8) return launch_sew_nw<LH, 16>(p, s, st);
-    return launch_sew_nw<LH, 8>(p, s, st);
+hy_status launch_sew_lh(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st) {
+    if (s.D % 256 == 0 && tuning().mr_waves != 8) return launch_sew_nw<LH, 16>(p, nprob, s, st);
+    return launch_sew_nw<LH, 8>(p, nprob, s, st);
 }
 
 }  // namespace
 
 // The walking kernel pays off once every workgroup has a long stretch of time to walk.
-bool se_walk_preferred(const ConvShape& s) {
-    if (s.dtype != HY_BF16 || !s.gated || s.lh < 1 || s.lh > 8 || s.D % 128 != 0) return false;
+bool se_walk_preferred(const ConvShape& s, int nprob) {
+    if (s.dtype != HY_BF16 || s.lh < 1 || s.lh > 8 || s.D % 128 != 0) return false;
+    if (nprob < 1 || nprob > 3 || (s.gated && nprob != 1)) return false;
     if (s.history != 0 && s.history < kLook) return false;  // a halo shorter than the look-back rows: the stencil's case
     if (s.L > 0x7fff0000LL || s.D > 0x7fff0000LL) return false;
     const int force = tuning().se_walk;
@@ -220,21 +252,21 @@ bool se_walk_preferred(const ConvShape& s) {
     // Measured at D = 4096, B = 1: the stencil wins at L = 8192 (512 steps per workgroup), the walker from
     // L = 16384 on (1024 steps per workgroup); short batch items never give a workgroup a long walk.
     const int nw = (s.D % 256 == 0 && tuning().mr_waves != 8) ? 16 : 8;
-    int64_t tiles = 256 / (s.B * (s.D / (16 * nw)));
-    if (tiles < 1) tiles = 1;
+    const int64_t tiles = walk_tiles(nprob * s.B * (s.D / (16 * nw)), s.L);
     return (s.L + tiles - 1) / tiles >= 1024;
 }
 
-hy_status launch_se_walk(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
+hy_status launch_se_walk(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st) {
+    if (nprob < 1 || nprob > 3 || (s.gated && nprob != 1)) return HY_ERR_UNSUPPORTED;
     switch (s.lh) {
-        case 1: return launch_sew_lh<1>(p, s, st);
-        case 2: return launch_sew_lh<2>(p, s, st);
-        case 3: return launch_sew_lh<3>(p, s, st);
-        case 4: return launch_sew_lh<4>(p, s, st);
-        case 5: return launch_sew_lh<5>(p, s, st);
-        case 6: return launch_sew_lh<6>(p, s, st);
-        case 7: return launch_sew_lh<7>(p, s, st);
-        case 8: return launch_sew_lh<8>(p, s, st);
+        case 1: return launch_sew_lh<1>(p, nprob, s, st);
+        case 2: return launch_sew_lh<2>(p, nprob, s, st);
+        case 3: return launch_sew_lh<3>(p, nprob, s, st);
+        case 4: return launch_sew_lh<4>(p, nprob, s, st);
+        case 5: return launch_sew_lh<5>(p, nprob, s, st);
+        case 6: return launch_sew_lh<6>(p, nprob, s, st);
+        case 7: return launch_sew_lh<7>(p, nprob, s, st);
+        case 8: return launch_sew_lh<8>(p, nprob, s, st);
         default: return HY_ERR_UNSUPPORTED;
     }
 }

@@ -7,8 +7,8 @@ hy_status launch_direct(const ConvPtrs*, int, const ConvShape&, hipStream_t) { r
 hy_status launch_mr_mfma(const ConvPtrs&, const ConvShape& s, hipStream_t) {
     return (s.dtype == HY_BF16 && s.group % 16 == 0 && s.D % 64 == 0 && s.lh <= 513) ? HY_OK : HY_ERR_UNSUPPORTED;
 }
-bool se_walk_preferred(const ConvShape&) { return false; }
-hy_status launch_se_walk(const ConvPtrs&, const ConvShape&, hipStream_t) { return HY_OK; }
+bool se_walk_preferred(const ConvShape&, int) { return false; }
+hy_status launch_se_walk(const ConvPtrs*, int, const ConvShape&, hipStream_t) { return HY_OK; }
 bool cp4_supported(const ConvShape& s) { return s.dtype == HY_BF16 && s.gated && s.D % 128 == 0 && s.lh <= 129; }
 hy_status launch_cp4(const ConvPtrs&, const ConvShape& s, hipStream_t) { return cp4_supported(s) ? HY_OK : HY_ERR_UNSUPPORTED; }
 bool cp_mfma_supported(const ConvShape& s) { return s.dtype == HY_BF16 && s.gated && s.D % 64 == 0 && s.lh <= 145; }

@@ -557,3 +557,48 @@ def test_bandwidth_yardstick_computes_the_elementwise_gate(case):
     assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + n:]).all()
     ref = oracle.gated_conv(q, k, v, np.ones((D, 1), dtype=np.float32), group=1)
     assert np.isfinite(y).all() and oracle.rel_err(y, ref) <= TOL["bf16"]
+
+
+# --------------------------------------------------------------------------------------- featurizer on the tile walker
+@pytest.mark.parametrize("case", SE_WALK_CASES)
+def test_featurizer_long_sequence_kernel_matches_oracle_and_the_stencil(case):
+    """The ungated variant of the long-sequence kernel (forced on small shapes), one tensor and three tensors per
+    launch, against the oracle and, bit for bit (same fp32 FMA chain in the same tap order), against the stencil."""
+    B, L, D, lh, group = case
+    say("featurizer walker B=%d L=%d D=%d lh=%d group=%d" % case)
+    rng = np.random.Generator(np.random.PCG64(2300 + L + D))
+    xs = [synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3)]
+    hs = [synth.short_filter(rng, D // group, lh) for _ in range(3)]
+    dx, dh = [dev(x) for x in xs], [dev(h) for h in hs]
+    binding.set_option("se_walk", 1)
+    one = binding.hyena_featurize_fwd(dx[0], dh[0], group)
+    three = binding.hyena_featurize3_fwd(*dx, *dh, group)
+    binding.set_option("se_walk", 2)
+    one_s = binding.hyena_featurize_fwd(dx[0], dh[0], group)
+    three_s = binding.hyena_featurize3_fwd(*dx, *dh, group)
+    torch.cuda.synchronize()
+    assert torch.equal(one, one_s) and torch.equal(one, three[0])
+    for x, h, o, o_s in zip(xs, hs, three, three_s):
+        assert torch.equal(o, o_s)
+        assert oracle.rel_err(host(o), oracle.causal_conv(x, h, group)) <= TOL["bf16"]
+
+
+def test_featurizer_long_sequence_kernel_guard_bands_and_chain_fallback():
+    """Three outputs between NaN guard bands, and the two-kernel chain (a shape the single-kernel chain does not
+    take: lh = 200) with the walker as its first kernel against the oracle."""
+    B, L, D, lh = 2, 301, 256, 7
+    say("guard bands featurizer walker")
+    binding.set_option("se_walk", 1)
+    rng = np.random.Generator(np.random.PCG64(2400))
+    xs = [synth.normal_tensor(rng, (B, L, D), "bf16") for _ in range(3)]
+    hs = [synth.short_filter(rng, D, lh) for _ in range(3)]
+    n, guard = B * L * D, 4096
+    buf = torch.full((3, n + 2 * guard), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    outs = tuple(buf[i, guard:guard + n].view(B, L, D) for i in range(3))
+    binding.hyena_featurize3_fwd(*[dev(x) for x in xs], *[dev(h) for h in hs], 1, out=outs)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:, :guard]).all() and torch.isnan(buf[:, guard + n:]).all() and not torch.isnan(buf[:, guard:guard + n]).any()
+    h = synth.decay_filter(rng, D // 16, 200)
+    y = binding.hyena_chain_fwd(*[dev(x) for x in xs], *[dev(f) for f in hs], dev(h), 16, 1)
+    ref = oracle.chain(*xs, *hs, h, group=16, feat_group=1)
+    assert oracle.rel_err(host(y), ref) <= TOL["bf16"]
