@@ -472,9 +472,12 @@ int li_waves(const LiShape& s) {
     // A batch that fills the chip with narrower workgroups of ONE tile per sequence takes them: a single pass moves
     // 8 bytes per output where the two-pass scan moves 12 (measured at L = 8192, D = 4096: B = 8 400 us with 8
     // waves against 445 with 16, B = 4 197 us with 4 waves against 241; B = 16 fills it with 16 waves: 695 us, 77%).
+    // "Fills" means that at least three quarters of the compute units are busy in every round of 256 workgroups
+    // (B = 6: 192 workgroups of 8 waves 309 us against 374; B = 3: 192 of 4 waves 165 us against 190).
     if (tuning().mr_waves == 0 && tuning().mr_rows == 0 && s.D % 256 == 0 && li_rows(s, 16) < s.L) {
-        if (s.B * (s.D / 128) >= 256) return 8;
-        if (s.B * (s.D / 64) >= 256) return 4;
+        auto fills = [](int64_t wg) { return 4 * wg >= 3 * ((wg + 255) / 256) * 256; };
+        if (fills(s.B * (s.D / 128))) return 8;
+        if (fills(s.B * (s.D / 64))) return 4;
     }
     if (nw == 16 && s.D % 256 == 0) return 16;
     if (nw >= 8 && s.D % 128 == 0) return 8;

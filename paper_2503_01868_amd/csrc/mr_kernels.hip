@@ -307,13 +307,16 @@ hy_status launch_nkb(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
             // compute units idle.  Take the widest workgroup that still gives every compute unit one (measured
             // at B = 1, D = 4096, lh = 128: L = 4096 28.9 us with 8 waves against 33.0 with 16; L = 2048 16.3 us
             // with 4 waves against 19.8 / 28.3; L = 512 11.9 against 14.3 / 22.5; from L = 8192 on 16 waves win).
+            // "Every" means three quarters of them: a batch of 3 gives 240 wide workgroups, which beat 192 narrow
+            // ones by far (B = 3, L = 8192: 161 us with 4 waves, the old choice at a threshold of 256).
+            constexpr int64_t kEnough = 192;
             int64_t wg = 0;
             const bool wide_ok = NKB <= 5 && s.D % 256 == 0;
             if (wide_ok) tile_rows<NKB>(s, 16, &wg);
-            if (!wide_ok || wg < 256) {
+            if (!wide_ok || wg < kEnough) {
                 nw = 8;
                 if (s.D % 128 == 0) tile_rows<NKB>(s, 8, &wg);
-                if (s.D % 128 != 0 || wg < 256) nw = 4;
+                if (s.D % 128 != 0 || wg < kEnough) nw = 4;
             }
         }
         if constexpr (NKB <= 5) {  // 16 waves only where the kernel fits 128 registers without spilling
