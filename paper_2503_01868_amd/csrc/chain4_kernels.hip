@@ -356,10 +356,9 @@ hy_status launch_chain4_nkb(const ChainPtrs& p, const ChainShape& s, hipStream_t
     a.ncb = (int32_t)(s.D / kC);
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
-        int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
-        if (tiles < 1) tiles = 1;
-        rows = (s.L + tiles - 1) / tiles;
         const int64_t min_rows = 8LL * kT * (NKB > 1 ? NKB - 1 : 1);
+        const int64_t tiles = tiles_filling_rounds(s.B * a.ncb, s.L, min_rows);  // one workgroup per CU
+        rows = (s.L + tiles - 1) / tiles;
         if (rows < min_rows) rows = min_rows;
     }
     rows = (rows + kT - 1) / kT * kT;

@@ -135,6 +135,21 @@ struct Tuning {
 // thread-local; all code below the ABI reads only that copy, so within one call the tile choice that sizes a
 // workspace and the one the launch uses cannot differ, whatever other threads set meanwhile.
 const Tuning& tuning();
+
+// Tiles per sequence when `base` workgroups cover one tile of every batch item (and problem): one workgroup per
+// compute unit.  Kernels whose workgroups are bound by what one compute unit can stream pay the full time of a
+// round of 256 workgroups that is partly empty, so where that choice leaves a round under 90% full (batches that
+// do not divide 256) they take the finer cut, up to four rounds, that fills its rounds best while a tile keeps
+// `min_rows` steps (measured: MR backward at B = 3 48% -> 53% of peak, three featurizers at B = 4 1192 -> 1040 us).
+inline int64_t tiles_filling_rounds(int64_t base, int64_t L, int64_t min_rows) {
+    int64_t tiles = 256 / base;
+    if (tiles < 1) tiles = 1;
+    auto fill = [&](int64_t t) { return (double)(base * t) / (double)(((base * t + 255) / 256) * 256); };
+    int64_t best = tiles;
+    for (int64_t t = tiles; fill(best) < 0.9 && base * t <= 1024 && (L + t - 1) / t >= min_rows; ++t)
+        if (fill(t) > fill(best) + 1e-9) best = t;
+    return best;
+}
 struct TuningSnapshot {
     TuningSnapshot();
     ~TuningSnapshot();

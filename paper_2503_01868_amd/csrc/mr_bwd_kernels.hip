@@ -425,16 +425,7 @@ int64_t mr_bwd_rows(const BwdShape& s) {
     if (rows <= 0) {
         const int64_t base = s.B * ncb;
         const int64_t min_rows = 4LL * kChunk * (nkb > 1 ? nkb - 1 : 1);
-        int64_t tiles = 256 / base;
-        if (tiles < 1) tiles = 1;
-        // These workgroups (one wave per SIMD) are bound by what one compute unit can stream, so a round of 256 that
-        // is partly empty costs its full time: where one workgroup per compute unit leaves a round under 90% full
-        // (batches that do not divide 256), take the finer cut, up to four rounds, that fills its rounds best.
-        auto fill = [&](int64_t t) { return (double)(base * t) / (double)(((base * t + 255) / 256) * 256); };
-        int64_t best = tiles;
-        for (int64_t t = tiles; fill(best) < 0.9 && base * t <= 1024 && (s.L + t - 1) / t >= min_rows; ++t)
-            if (fill(t) > fill(best) + 1e-9) best = t;
-        tiles = best;
+        const int64_t tiles = tiles_filling_rounds(base, s.L, min_rows);  // one wave per SIMD: per-CU bound
         rows = (s.L + tiles - 1) / tiles;
         if (rows < min_rows) rows = min_rows;
     }

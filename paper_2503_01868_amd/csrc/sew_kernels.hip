@@ -184,18 +184,9 @@ __global__ __launch_bounds__(NW * 64, NW == 16 ? 4 : 2) void se_walk_kernel(SewA
     }
 }
 
-// Tiles per sequence when `base` workgroups cover one tile of every batch item and problem: one workgroup per
-// compute unit; where that is not a whole number of rounds of 256 workgroups (three problems, odd batches) the
-// sequence is cut finer if that gives whole rounds (up to four) and a tile keeps 1024 steps (three featurizers at
-// B = 4: 192 workgroups on 256 compute units ran slower than the stencil, 768 run faster).
-int64_t walk_tiles(int64_t base, int64_t L) {
-    int64_t tiles = 256 / base;
-    if (tiles < 1) tiles = 1;
-    if ((base * tiles) % 256 == 0) return tiles;
-    for (int64_t t = tiles + 1; base * t <= 1024 && (L + t - 1) / t >= 1024; ++t)
-        if ((base * t) % 256 == 0) return t;
-    return tiles;  // no finer cut gives whole rounds
-}
+// Tiles per sequence: one workgroup per compute unit, rounds of 256 kept full (three featurizers at B = 4: 192
+// workgroups on 256 compute units ran slower than the stencil, 768 run faster); a tile keeps 1024 steps.
+int64_t walk_tiles(int64_t base, int64_t L) { return tiles_filling_rounds(base, L, 1024); }
 
 template <int LH, int NW>
 hy_status launch_sew_nw(const ConvPtrs* p, int nprob, const ConvShape& s, hipStream_t st) {
