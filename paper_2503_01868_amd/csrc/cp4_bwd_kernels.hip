@@ -273,8 +273,7 @@ int64_t dh_rows(const BwdShape& s) {
     const int64_t ncb = s.D / kC;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
-        int64_t tiles = 256 / (s.B * ncb);  // one workgroup per CU
-        if (tiles < 1) tiles = 1;
+        const int64_t tiles = tiles_filling_rounds(s.B * ncb, s.L, 4 * kT);  // one workgroup per CU
         rows = (s.L + tiles - 1) / tiles;
         if (rows < 4 * kT) rows = 4 * kT;
     }

@@ -569,8 +569,7 @@ hy_status launch_cp4_nw(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.hist = s.history;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
-        int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
-        if (tiles < 1) tiles = 1;
+        const int64_t tiles = tiles_filling_rounds(s.B * a.ncb, s.L, 4 * kT);  // one workgroup per CU
         rows = (s.L + tiles - 1) / tiles;
         if (rows < 4 * kT) rows = 4 * kT;
     }
@@ -606,8 +605,7 @@ hy_status launch_cp4_ws(const ConvPtrs& p, const ConvShape& s, hipStream_t st) {
     a.hist = s.history;
     int64_t rows = tuning().mr_rows;
     if (rows <= 0) {
-        int64_t tiles = 256 / (s.B * a.ncb);  // one workgroup per CU
-        if (tiles < 1) tiles = 1;
+        const int64_t tiles = tiles_filling_rounds(s.B * a.ncb, s.L, 4 * kT);  // one workgroup per CU
         rows = (s.L + tiles - 1) / tiles;
         if (rows < 4 * kT) rows = 4 * kT;
     }
