@@ -10,7 +10,8 @@ A step is one pass of the hot path over one synthetic batch that already sits in
   c4  chain     bf16 B4 L32768  D4096                hyena_chain_fwd (featurizers + MR in one kernel)
   c1_bwd / c2_bwd / c3_bwd / c2u_bwd: the backward entry points (hyena_se_bwd / hyena_mr_bwd) on the shapes of
       c1 / c2 / c3 / c2u; c4_bwd: hyena_chain_bwd on c4's shape (featurizers recomputed, inner backward, three
-      featurizer backward calls; 6 tensors of workspace)
+      featurizer backward calls; 6 tensors of workspace); c4_feat: the three featurizer convolutions of c4 alone
+      (hyena_featurize3_fwd, 12 bytes per element: three tensors read and written)
   c1_shards / c2_shards / c3_shards: c1 / c2 / c3 computed as four consecutive sequence shards (hyena_se_fwd_shard /
       hyena_mr_fwd_shard: each call sees its quarter of the steps plus the lh - 1 rows of k and v before it), the
       compute half of a sequence-sharded run on one GPU; a step is the four launches.  c3_bwd_shards: the same for
@@ -58,7 +59,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c1",
                     choices=["c1", "c2", "c3", "c4", "c2u", "li2", "li3", "c1_bwd", "c2_bwd", "c3_bwd", "c2u_bwd", "c1_shards",
-                             "c2_shards", "c3_shards", "c3_overlap", "c1_bwd_shards", "c3_bwd_shards", "c4_bwd", "copy"] + list(YARDSTICKS),
+                             "c2_shards", "c3_shards", "c3_overlap", "c1_bwd_shards", "c3_bwd_shards", "c4_bwd", "c4_feat", "copy"] + list(YARDSTICKS),
                     help="'copy' only issues the plain copy kernel used to calibrate hardware byte counters")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override L of the workload (the paper sweeps its operator benchmark over L at batch 1, "
@@ -115,6 +116,8 @@ class Workload:
         self.shards = 4 if name.endswith("_shards") else 0
         name = name[:-7] if self.shards else name
         self.bwd = name.endswith("_bwd")
+        self.feat = name.endswith("_feat")   # the three featurizer convolutions of the chain alone
+        name = name[:-5] if self.feat else name
         self.strip, self.ywaves, ydepth = YARDSTICKS.get(name, (None, 0, 0))
         depth = depth or ydepth
         name = name[:-4] if self.bwd else name
@@ -176,6 +179,10 @@ class Workload:
             elif self.strip is not None:
                 self.main.append(pkg.plan_stream_gate(d["q"], d["k"], d["v"], self.strip, 0, depth, self.ywaves,
                                                       out=d["y"]))
+            elif self.feat:
+                d["feat_out"] = tuple(torch.empty_like(d["q"]) for _ in range(3))
+                self.main.append(pkg.plan_featurize3(d["q"], d["k"], d["v"], d["hq"], d["hk"], d["hv"], c["feat_group"],
+                                                     out=d["feat_out"]))
             elif c["kind"] == "li":
                 self.main.append(pkg.plan_li(d["q"], d["k"], d["v"], d["R"], d["lam"], c["group"], out=d["y"]))
             elif c["kind"] == "chain":
@@ -257,6 +264,8 @@ class Workload:
 
     # algorithmic work of the dominant kernel per launch
     def algo_bytes(self):
+        if self.feat:
+            return 12.0 * self.n_out  # bf16: three tensors read once and written once
         if self.bwd:
             return 14.0 * self.n_out  # bf16: dy, q, k, v read once, dq, dk, dv written once
         return 8.0 * self.n_out  # bf16: q, k, v read once, y written once
@@ -265,6 +274,8 @@ class Workload:
         if self.cfg["kind"] == "li":
             # recurrent form: per exponential one FMA for the running sum and one for the output, plus two gates
             return (4.0 * self.cfg["order"] + 2.0) * self.n_out
+        if self.feat:
+            return 3 * 2.0 * self.cfg["lf"] * self.n_out
         f = 2.0 * self.cfg["lh"] + 2.0
         if self.bwd:
             f = 3 * 2.0 * self.cfg["lh"] + 5.0  # z, du, dh contractions + five gates
@@ -285,7 +296,9 @@ def cpu_baseline(wl, target_s, np, oracle):
     def run(rows):
         q, k, v = (w[key][:1, :rows].contiguous() for key in ("q", "k", "v"))
         t0 = time.perf_counter()
-        if wl.bwd:
+        if wl.feat:
+            y = oracle.causal_conv(q, w["hq"], c["feat_group"])
+        elif wl.bwd:
             # dq[t] only looks at the past, so the first rows of the slice's dq equal those of the full problem
             dy = w["dy"][:1, :rows].contiguous()
             if c["kind"] == "chain":
@@ -357,6 +370,8 @@ def stored_traffic(workload, seq_len):
 def entry_point(wl):
     if wl.strip is not None:
         return "hyena_stream_gate (strip_channels=%d, waves=%d)" % (wl.strip, wl.ywaves or wl.strip // 16)
+    if wl.feat:
+        return "hyena_featurize3_fwd"
     name = {"se": "hyena_se_fwd", "mr": "hyena_mr_fwd", "chain": "hyena_chain_fwd",
             "li": "hyena_li_fwd (both passes of the scan)"}[wl.cfg["kind"]]
     if wl.bwd:
@@ -385,7 +400,7 @@ def measure(name, args, torch, pkg, synth, steps, warmup, settle=0):
                      # the same fraction from the wall clock of the timed region (launch overhead included)
                      "frac_wall_clock": wl.algo_bytes() / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
-    if wl.cfg["kind"] != "se" and wl.strip is None:
+    if wl.cfg["kind"] != "se" and wl.strip is None and not wl.feat:
         tf = wl.algo_flops() / (kern_ms * 1e-3) / 1e12
         res["mfma"] = {"tflops_algorithmic": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                        "frac": tf / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops_per_launch": wl.algo_flops()}
@@ -429,7 +444,7 @@ def main():
 
     wl, res = measure(args.workload, args, torch, pkg, synth, args.steps, args.warmup, args.settle)
     cfg = wl.cfg
-    what = "bandwidth yardstick y=q*k*v," if wl.strip is not None else {
+    what = "bandwidth yardstick y=q*k*v," if wl.strip is not None else "three featurizer convolutions," if wl.feat else {
         "se": "Hyena-SE", "mr": "Hyena-MR", "chain": "featurizers + Hyena-MR, one kernel,", "li": "Hyena-LI"}[cfg["kind"]]
     out = {
         "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
@@ -437,8 +452,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %s%s bf16 B=%d L=%d D=%d %s=%d group=%d" % (
             args.workload, what, " backward" if wl.bwd else "",
-            cfg["B"], cfg["L"], cfg["D"], "order" if cfg["kind"] == "li" else "lh",
-            cfg["order"] if cfg["kind"] == "li" else cfg["lh"], cfg["group"]), "buffer_sets": res["buffer_sets"],
+            cfg["B"], cfg["L"], cfg["D"], "order" if cfg["kind"] == "li" else "lf" if wl.feat else "lh",
+            cfg["order"] if cfg["kind"] == "li" else cfg["lf"] if wl.feat else cfg["lh"],
+            cfg["feat_group"] if wl.feat else cfg["group"]), "buffer_sets": res["buffer_sets"],
             "settle_launches_before_warmup": args.settle},
         "roofline": res["roofline"],
     }
@@ -457,7 +473,8 @@ def main():
         wl.i = 0
         wl.step()
         torch.cuda.synchronize()
-        got = (d["dq"] if wl.bwd else d["y"])[:1, :y_ref.shape[1]].float().cpu().numpy().astype(np.float64)
+        out0 = d["feat_out"][0] if wl.feat else (d["dq"] if wl.bwd else d["y"])
+        got = out0[:1, :y_ref.shape[1]].float().cpu().numpy().astype(np.float64)
         out["parity_rel_err"] = oracle.rel_err(got, y_ref)
 
     if args.workload == "c1" and args.also and args.seq_len <= 0 and args.batch <= 0 and args.width <= 0:
