@@ -3,7 +3,8 @@
 // structure of App. A.4.  With u = k*v, g = dy*q:
 //     dq = dy (.) (h * u)                 the forward chunk-parallel kernel (cp4_kernels.hip) on (dy, k, v)
 //     dk = v (.) (h *' g), dv = k (.) (h *' g),  (h *' g)[s] = sum_j h[j] g[s+j]
-//                                         the same kernel walking time backwards, once per output
+//                                         the same kernel walking time backwards, once per output (filters of
+//                                         66 taps and more: once, with two post-gates and two outputs)
 //     dh[c, j] = sum_{b, t} g[b,t,c] u[b,t-j,c]        this file: a per-channel correlation
 //
 // The correlation as batched 4 x 4 x 4 products (v_mfma_f32_4x4x4_16B_bf16: 16 independent blocks per
